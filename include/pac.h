@@ -1,0 +1,197 @@
+/*
+ * libpac -- cached Parallel-Adapter training step on one MI355X (gfx950).
+ *
+ * The library implements the epoch >= 2 phase of PAC+ (arXiv 2408.10746):
+ * the frozen backbone's per-layer hidden states are stored once
+ * (pac_cache_fill; paper Sec. 4.2, "activation cache") and every later
+ * training step runs forward and backward through the side adapter network
+ * only (pac_adapter_step; paper Sec. 4.1 "Parallel Adapters", Sec. 5.2
+ * "data-parallel fine-tuning for Parallel Adapters").  No backbone forward or
+ * backward is ever executed here and no gradient flows into the cache.
+ *
+ * The network (linear down/up-projection adapters, Sec. 4.1; gate initialised
+ * to 0.5, Sec. 4.1; zero-initialised up-projection, Sec. 4.3), with L cached
+ * layers b_1..b_L, hidden size d, adapter width r, C classes:
+ *
+ *     s_0 = 0
+ *     x_l   = lambda_l * b_l + (1 - lambda_l) * s_{l-1}
+ *     pre_l = x_l W_down^l + c_down^l          h_l = GELU_erf(pre_l)
+ *     s_l   = s_{l-1} + h_l W_up^l + c_up^l
+ *     y = b_L + s_L ;  p = mean over valid tokens ;  z = p W_cls + c_cls
+ *     loss = mean over the batch of softmax cross-entropy(z, label)
+ *
+ * followed by the exact gradients and one AdamW update.
+ *
+ * CONVENTIONS
+ *  - Every pointer is marked HOST or DEVICE.  The caller allocates and frees
+ *    every device buffer; the library allocates only the host-side pac_ctx and
+ *    keeps no device pointer between calls.
+ *  - All device work is enqueued on the HIP stream passed in (`hip_stream` is
+ *    a hipStream_t cast to void*, NULL = the default stream).  No call blocks
+ *    on the device; outputs are valid once the caller synchronises the stream.
+ *  - Every entry point returns a pac_status.  Argument errors are detected on
+ *    the host before anything is launched and leave device memory untouched.
+ *    Nothing throws, aborts or prints.
+ *  - Arithmetic follows the cache dtype: a bf16 cache runs the contractions on
+ *    bf16 MFMA with fp32 accumulation (side state, gradients, optimizer and
+ *    master weights stay fp32); an fp32 cache runs everything in fp32.
+ *
+ * PARAMETER VECTOR (flat fp32, P = L*(2dr + r + d + 1) + dC + C entries)
+ *    per layer  [ W_down (d x r, r contiguous) | c_down (r) | W_up (r x d, d contiguous)
+ *                 | c_up (d) | lambda (1) ]
+ *    then       [ W_cls (d x C, C contiguous) | c_cls (C) ]
+ *
+ * CACHE (paper Sec. 5.2: tokens x hidden x layers elements per sequence)
+ *    sample s owns one block [layer][token][d], d contiguous, holding only its
+ *    len_s valid tokens; blocks are packed in fill order.  Element size is 2
+ *    (bf16, round-to-nearest-even at fill) or 4 (fp32, copied unchanged).
+ */
+#ifndef PAC_H
+#define PAC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pac_ctx pac_ctx; /* opaque host object; owns no device memory */
+
+typedef enum {
+    PAC_OK = 0,
+    PAC_ERR_NULL = 1,        /* a required pointer is NULL */
+    PAC_ERR_SHAPE = 2,       /* a dimension is non-positive or inconsistent */
+    PAC_ERR_RANGE = 3,       /* an index/length/count is outside its range */
+    PAC_ERR_ALIGN = 4,       /* a device pointer is not aligned as required */
+    PAC_ERR_UNSUPPORTED = 5, /* a valid shape this build has no kernel for */
+    PAC_ERR_WORKSPACE = 6,   /* workspace or cache buffer too small */
+    PAC_ERR_DEVICE = 7,      /* the HIP runtime reported an error */
+    PAC_ERR_STATE = 8        /* a sample that was never filled is referenced */
+} pac_status;
+
+typedef enum { PAC_BF16 = 0, PAC_F32 = 1 } pac_dtype;
+
+/*
+ * L      cached layers (>= 1)                d      hidden size (multiple of 32)
+ * n_max  longest sequence (>= 1)             r      adapter width (multiple of 32, <= d... any)
+ * C      classes (1..16)                     B_max  largest batch of one step (1..64)
+ * N      samples the cache can index (>= 1)  cache_dtype  PAC_BF16 or PAC_F32
+ */
+typedef struct {
+    int32_t L, d, n_max, r, C, B_max;
+    int64_t N;
+    int32_t cache_dtype;
+} pac_config;
+
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+} pac_adamw;
+
+/* Validates cfg and builds the host context.  No device work.
+ * PAC_ERR_NULL / PAC_ERR_SHAPE / PAC_ERR_UNSUPPORTED on bad input; *out untouched then. */
+pac_status pac_create(const pac_config *cfg /*HOST*/, pac_ctx **out /*HOST*/);
+void pac_destroy(pac_ctx *ctx); /* NULL is allowed */
+const char *pac_status_str(pac_status s);
+
+/* P, the length of the flat parameter vector (see layout above); -1 if ctx is NULL. */
+int64_t pac_param_count(const pac_ctx *ctx);
+
+/* Offsets (in elements) into the flat vector.  layer in [0, L): out[0..4] =
+ * W_down, c_down, W_up, c_up, lambda.  layer = -1: out[0..1] = W_cls, c_cls (out[2..4] = -1). */
+pac_status pac_param_offsets(const pac_ctx *ctx, int32_t layer, int64_t out[5] /*HOST*/);
+
+/* Bytes of cache needed for `count` samples with the given valid lengths
+ * (paper Sec. 5.2: len x d x L elements each).  lens HOST, count entries, or
+ * NULL = every sample has n_max tokens.  -1 on bad arguments. */
+int64_t pac_cache_bytes(const pac_ctx *ctx, const int32_t *lens /*HOST*/, int64_t count);
+
+/* Bytes of device workspace pac_adapter_step / pac_adapter_loss_grad need for
+ * a batch of up to B_max samples of up to n_max tokens.  -1 if ctx is NULL. */
+int64_t pac_workspace_bytes(const pac_ctx *ctx);
+
+/*
+ * Store one backbone forward's per-layer activations (paper Sec. 4.2: during
+ * the first epoch everything the adapters consume is cached).
+ *   cache       DEVICE, cache_bytes long, 256-byte aligned.
+ *   sample_ids  HOST, count entries in [0, N), no repeats within a call.
+ *   acts        DEVICE, [count][L][n_max][d] of acts_dtype, d contiguous, 16-byte aligned.
+ *   lens        HOST, count entries in [1, n_max], or NULL = n_max for all.
+ * A sample filled for the first time is appended after the blocks filled so
+ * far; a sample filled again must keep its length and is overwritten in
+ * place.  Rows t >= len of acts are never read.  bf16 storage rounds to
+ * nearest-even, NaN stays NaN, infinities pass through.
+ * Errors: NULL, RANGE (id/len/count), STATE (length changed), WORKSPACE (cache
+ * too small), ALIGN, DEVICE.  On error nothing is recorded or written.
+ */
+pac_status pac_cache_fill(pac_ctx *ctx, void *cache /*DEVICE*/, int64_t cache_bytes,
+                          const int64_t *sample_ids /*HOST*/, int32_t count,
+                          const void *acts /*DEVICE*/, int32_t acts_dtype,
+                          const int32_t *lens /*HOST*/, void *hip_stream);
+
+/* Where a filled sample lives: element offset of its block and its length.
+ * PAC_ERR_STATE if it was never filled. */
+pac_status pac_cache_lookup(const pac_ctx *ctx, int64_t sample_id,
+                            int64_t *offset_elems /*HOST*/, int32_t *len /*HOST*/);
+
+/*
+ * Loss and gradients of one batch read from the cache, without an update
+ * (same forward/backward as pac_adapter_step; used for evaluation and parity).
+ *   cache       DEVICE (const: the backbone is frozen, nothing is written to it)
+ *   sample_ids  HOST, B entries, each filled before; 1 <= B <= B_max
+ *   labels      DEVICE, int32[B], each in [0, C) (out-of-range labels give a NaN loss)
+ *   params      DEVICE, fp32[P]
+ *   workspace   DEVICE, >= pac_workspace_bytes(), 256-byte aligned; contents are scratch
+ *   loss_out    DEVICE, fp32[1]
+ *   logits_out  DEVICE, fp32[B][C], or NULL
+ *   grads_out   DEVICE, fp32[P], or NULL (then only the forward pass runs)
+ */
+pac_status pac_adapter_loss_grad(pac_ctx *ctx, const void *cache /*DEVICE*/,
+                                 const int64_t *sample_ids /*HOST*/, int32_t B,
+                                 const int32_t *labels /*DEVICE*/, const float *params /*DEVICE*/,
+                                 void *workspace /*DEVICE*/, int64_t workspace_bytes,
+                                 float *loss_out /*DEVICE*/, float *logits_out /*DEVICE*/,
+                                 float *grads_out /*DEVICE*/, void *hip_stream);
+
+/*
+ * One optimizer step driven by the cache (paper Sec. 5.2: after the first
+ * epoch only the adapters are trained, from cached activations): forward,
+ * loss, backward, AdamW (decoupled decay on W_down, W_up, W_cls; bias-corrected;
+ * eps added to the root of the corrected second moment).
+ *   params, m, v  DEVICE, fp32[P], updated in place
+ *   step          HOST, in/out: number of updates applied so far (incremented)
+ *   grads_out     DEVICE fp32[P] or NULL (then the gradient lives in the workspace)
+ * Other arguments as in pac_adapter_loss_grad.
+ */
+pac_status pac_adapter_step(pac_ctx *ctx, const void *cache /*DEVICE*/,
+                            const int64_t *sample_ids /*HOST*/, int32_t B,
+                            const int32_t *labels /*DEVICE*/,
+                            float *params /*DEVICE*/, float *m /*DEVICE*/, float *v /*DEVICE*/,
+                            int64_t *step /*HOST*/, const pac_adamw *hp /*HOST*/,
+                            void *workspace /*DEVICE*/, int64_t workspace_bytes,
+                            float *loss_out /*DEVICE*/, float *grads_out /*DEVICE*/,
+                            void *hip_stream);
+
+/*
+ * Measurement aid (not part of the training path): per-kernel timing with HIP
+ * events recorded on the caller's stream around every kernel the library
+ * launches, so the duration of each kernel class can be set against its
+ * roofline (HBM bytes for the cache stream, MFMA flops for the adapter
+ * contractions; paper Sec. 5.2 calls the cached phase lightweight, which makes
+ * it bandwidth- and latency-sensitive).
+ *   pac_profile_begin  starts recording for later calls on this context.
+ *   pac_profile_end    waits for the recorded events, adds up elapsed time and
+ *                      launch counts per kernel class into ms[]/launches[]
+ *                      (HOST, max_classes entries each), stores the number of
+ *                      classes in *n_classes and stops recording.
+ *   pac_profile_class_name  name of class i, NULL past the end.
+ * Errors: NULL, STATE (end without begin), WORKSPACE (max_classes too small), DEVICE.
+ */
+pac_status pac_profile_begin(pac_ctx *ctx);
+pac_status pac_profile_end(pac_ctx *ctx, int32_t max_classes, float *ms /*HOST*/,
+                           int32_t *launches /*HOST*/, int32_t *n_classes /*HOST*/);
+const char *pac_profile_class_name(int32_t cls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PAC_H */

@@ -1,0 +1,190 @@
+"""Thin ctypes binding of libpac.so: the same entry points as include/pac.h.
+
+Argument marshalling only -- every step of the path runs in the library's HIP
+kernels.  PyTorch is used by callers for device memory and streams; this module
+accepts raw integer addresses (tensor.data_ptr()) and a raw stream handle.
+There is no CPU fallback: if the library is missing the import of a symbol fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpac.so")
+
+PAC_OK = 0
+PAC_ERR_NULL, PAC_ERR_SHAPE, PAC_ERR_RANGE, PAC_ERR_ALIGN = 1, 2, 3, 4
+PAC_ERR_UNSUPPORTED, PAC_ERR_WORKSPACE, PAC_ERR_DEVICE, PAC_ERR_STATE = 5, 6, 7, 8
+PAC_BF16, PAC_F32 = 0, 1
+
+EXPORTS = [
+    "pac_create", "pac_destroy", "pac_status_str", "pac_param_count", "pac_param_offsets",
+    "pac_cache_bytes", "pac_workspace_bytes", "pac_cache_fill", "pac_cache_lookup",
+    "pac_adapter_loss_grad", "pac_adapter_step",
+    "pac_profile_begin", "pac_profile_end", "pac_profile_class_name",
+]
+
+
+class pac_config(C.Structure):
+    _fields_ = [("L", C.c_int32), ("d", C.c_int32), ("n_max", C.c_int32), ("r", C.c_int32),
+                ("C", C.c_int32), ("B_max", C.c_int32), ("N", C.c_int64), ("cache_dtype", C.c_int32)]
+
+
+class pac_adamw(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float)]
+
+
+class PacError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_str(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib():
+    """Load libpac.so (built beforehand by paper_2408_10746_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2408_10746_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        L.pac_create.restype = C.c_int
+        L.pac_create.argtypes = [C.POINTER(pac_config), C.POINTER(vp)]
+        L.pac_destroy.restype = None
+        L.pac_destroy.argtypes = [vp]
+        L.pac_status_str.restype = C.c_char_p
+        L.pac_status_str.argtypes = [C.c_int]
+        L.pac_param_count.restype = i64
+        L.pac_param_count.argtypes = [vp]
+        L.pac_param_offsets.restype = C.c_int
+        L.pac_param_offsets.argtypes = [vp, i32, C.POINTER(i64)]
+        L.pac_cache_bytes.restype = i64
+        L.pac_cache_bytes.argtypes = [vp, vp, i64]
+        L.pac_workspace_bytes.restype = i64
+        L.pac_workspace_bytes.argtypes = [vp]
+        L.pac_cache_fill.restype = C.c_int
+        L.pac_cache_fill.argtypes = [vp, vp, i64, vp, i32, vp, i32, vp, vp]
+        L.pac_cache_lookup.restype = C.c_int
+        L.pac_cache_lookup.argtypes = [vp, i64, C.POINTER(i64), C.POINTER(i32)]
+        L.pac_adapter_loss_grad.restype = C.c_int
+        L.pac_adapter_loss_grad.argtypes = [vp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp]
+        L.pac_adapter_step.restype = C.c_int
+        L.pac_adapter_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, C.POINTER(i64),
+                                       C.POINTER(pac_adamw), vp, i64, vp, vp, vp]
+        L.pac_profile_begin.restype = C.c_int
+        L.pac_profile_begin.argtypes = [vp]
+        L.pac_profile_end.restype = C.c_int
+        L.pac_profile_end.argtypes = [vp, i32, C.POINTER(C.c_float), C.POINTER(i32), C.POINTER(i32)]
+        L.pac_profile_class_name.restype = C.c_char_p
+        L.pac_profile_class_name.argtypes = [i32]
+        _lib = L
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().pac_status_str(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != PAC_OK:
+        raise PacError(status, where)
+
+
+def _host_i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def _host_i32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _hp(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+# ---- the C entry points, one to one ---------------------------------------
+def pac_create(L, d, n_max, r, C_, B_max, N, cache_dtype) -> int:
+    cfg = pac_config(L, d, n_max, r, C_, B_max, N, cache_dtype)
+    out = C.c_void_p()
+    _check(lib().pac_create(C.byref(cfg), C.byref(out)), "pac_create")
+    return out.value
+
+
+def pac_destroy(ctx) -> None:
+    lib().pac_destroy(ctx)
+
+
+def pac_param_count(ctx) -> int:
+    return int(lib().pac_param_count(ctx))
+
+
+def pac_param_offsets(ctx, layer: int):
+    out = (C.c_int64 * 5)()
+    _check(lib().pac_param_offsets(ctx, layer, out), "pac_param_offsets")
+    return list(out)
+
+
+def pac_cache_bytes(ctx, lens, count: int) -> int:
+    la = _host_i32(lens)
+    return int(lib().pac_cache_bytes(ctx, _hp(la), count))
+
+
+def pac_workspace_bytes(ctx) -> int:
+    return int(lib().pac_workspace_bytes(ctx))
+
+
+def pac_cache_fill(ctx, cache_ptr, cache_bytes, sample_ids, acts_ptr, acts_dtype, lens=None, stream=0) -> None:
+    ids = _host_i64(sample_ids)
+    la = _host_i32(lens)
+    _check(lib().pac_cache_fill(ctx, cache_ptr, cache_bytes, _hp(ids), ids.shape[0], acts_ptr, acts_dtype,
+                                _hp(la), stream), "pac_cache_fill")
+
+
+def pac_cache_lookup(ctx, sample_id: int):
+    off, ln = C.c_int64(), C.c_int32()
+    _check(lib().pac_cache_lookup(ctx, sample_id, C.byref(off), C.byref(ln)), "pac_cache_lookup")
+    return off.value, ln.value
+
+
+def pac_adapter_loss_grad(ctx, cache_ptr, sample_ids, labels_ptr, params_ptr, ws_ptr, ws_bytes, loss_ptr,
+                          logits_ptr=None, grads_ptr=None, stream=0) -> None:
+    ids = _host_i64(sample_ids)
+    _check(lib().pac_adapter_loss_grad(ctx, cache_ptr, _hp(ids), ids.shape[0], labels_ptr, params_ptr, ws_ptr,
+                                       ws_bytes, loss_ptr, logits_ptr, grads_ptr, stream),
+           "pac_adapter_loss_grad")
+
+
+def pac_adapter_step(ctx, cache_ptr, sample_ids, labels_ptr, params_ptr, m_ptr, v_ptr, step: int, hp: pac_adamw,
+                     ws_ptr, ws_bytes, loss_ptr, grads_ptr=None, stream=0) -> int:
+    """Returns the incremented step count."""
+    ids = _host_i64(sample_ids)
+    st = C.c_int64(step)
+    _check(lib().pac_adapter_step(ctx, cache_ptr, _hp(ids), ids.shape[0], labels_ptr, params_ptr, m_ptr, v_ptr,
+                                  C.byref(st), C.byref(hp), ws_ptr, ws_bytes, loss_ptr, grads_ptr, stream),
+           "pac_adapter_step")
+    return st.value
+
+
+def pac_profile_begin(ctx) -> None:
+    _check(lib().pac_profile_begin(ctx), "pac_profile_begin")
+
+
+def pac_profile_end(ctx):
+    """Returns {class name: (total ms, launches)} for the classes that ran."""
+    n = 32
+    ms = (C.c_float * n)()
+    launches = (C.c_int32 * n)()
+    k = C.c_int32(0)
+    _check(lib().pac_profile_end(ctx, n, ms, launches, C.byref(k)), "pac_profile_end")
+    out = {}
+    for i in range(k.value):
+        if launches[i]:
+            out[lib().pac_profile_class_name(i).decode()] = (float(ms[i]), int(launches[i]))
+    return out

@@ -119,8 +119,10 @@ def init_params(w: Workload, seed: int = SEED_PARAMS) -> np.ndarray:
     return p
 
 
-def random_params(w: Workload, seed: int = SEED_PARAMS, scale: float = 1.0) -> np.ndarray:
-    """A generic (non-initial) state: every entry non-zero, gates spread around 0.5."""
+def random_params(w: Workload, seed: int = SEED_PARAMS, scale: float = 1.0, up_scale: float = 1.0) -> np.ndarray:
+    """A generic (non-initial) state: every entry non-zero, gates spread around 0.5.
+
+    up_scale shrinks the up-projections (a partly trained network: they start at zero)."""
     rng = np.random.default_rng([seed, 2])
     p = np.zeros(w.P, dtype=np.float32)
     PL, d, r, C = w.layer_block, w.d, w.r, w.C
@@ -130,7 +132,7 @@ def random_params(w: Workload, seed: int = SEED_PARAMS, scale: float = 1.0) -> n
         o += d * r
         p[o:o + r] = rng.standard_normal(r, dtype=np.float32) * np.float32(0.1 * scale)
         o += r
-        p[o:o + r * d] = rng.standard_normal(r * d, dtype=np.float32) * np.float32(scale / np.sqrt(r))
+        p[o:o + r * d] = rng.standard_normal(r * d, dtype=np.float32) * np.float32(scale * up_scale / np.sqrt(r))
         o += r * d
         p[o:o + d] = rng.standard_normal(d, dtype=np.float32) * np.float32(0.1 * scale)
         o += d

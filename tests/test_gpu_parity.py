@@ -1,0 +1,325 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Tolerances (relative L2 error per tensor, |a-b|_2 / |b|_2, and relative error of the loss):
+  fp32 mode  1e-5      bf16 cache + bf16 MFMA operands with fp32 accumulation  2e-2
+Tensors the oracle says are exactly zero must be exactly zero.
+Integer/byte work (the cache contents) is bit-exact.
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2408_10746_amd import inputs
+from paper_2408_10746_amd.inputs import Workload
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def note(msg):
+    """Progress line that survives pytest's capture (long tests must not look hung)."""
+    sys.__stderr__.write(f"[{time.strftime('%H:%M:%S')}] {msg}\n")
+    sys.__stderr__.flush()
+
+
+def rel_err(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    nb = np.linalg.norm(b)
+    if nb == 0.0:
+        return 0.0 if np.max(np.abs(a), initial=0.0) <= 1e-30 else np.inf
+    return float(np.linalg.norm(a - b) / nb)
+
+
+def tensors(dims):
+    """Parameter tensors compared one by one.  The L gate scalars are compared as one L-vector:
+    a single gate gradient is a sum of tokens x d signed terms that can cancel to (nearly)
+    nothing, and then no finite-precision path has a meaningful relative error on it alone."""
+    out = {}
+    lam = []
+    for name, sl in orc.param_slices(dims).items():
+        if name.startswith("lambda"):
+            lam.append(sl.start)
+        else:
+            out[name] = sl
+    out["lambda[0:L]"] = np.array(lam)
+    return out
+
+
+def oracle_batch(w: Workload, acts, lens, labels, params, want_grads=True):
+    cache, off, lens_a = orc.cache_fill(acts, lens=lens, as_bf16=(w.cache_dtype == "bf16"))
+    dims = orc.Dims(w.L, w.d, w.r, w.C)
+    return dims, orc.loss_grad(dims, orc.widen(cache), off, lens_a, labels, params.astype(np.float64),
+                               want_grads=want_grads)
+
+
+def check_against_oracle(w, sess, ids, acts, lens, labels, params, tol, what=""):
+    note(f"{what}: oracle on {len(ids)} samples")
+    dims, ref = oracle_batch(w, acts, lens, labels, params)
+    note(f"{what}: HIP path")
+    lab_dev = torch.from_numpy(labels).to(sess.dev)
+    sess.set_params(params)
+    sess.loss_grad(ids, lab_dev)
+    torch.cuda.synchronize()
+    loss = float(sess.loss.item())
+    B = len(ids)
+    logits = sess.logits.cpu().numpy()[: B * w.C].reshape(B, w.C)
+    grads = sess.grads.cpu().numpy()
+    assert np.isfinite(loss), what
+    assert abs(loss - ref["loss"]) <= tol * max(abs(ref["loss"]), 1e-3), (what, loss, ref["loss"])
+    assert rel_err(logits, ref["logits"]) <= tol, (what, "logits", rel_err(logits, ref["logits"]))
+    worst = {}
+    for name, sl in tensors(dims).items():
+        e = rel_err(grads[sl], ref["grads"][sl])
+        worst[name] = e
+        assert e <= tol, (what, name, e)
+    note(f"{what}: loss {loss:.6f} vs {ref['loss']:.6f}; worst grad rel err {max(worst.values()):.2e} "
+         f"({max(worst, key=worst.get)})")
+    return ref, loss, grads, worst
+
+
+def make_session(w, lens=None):
+    from paper_2408_10746_amd.runtime import Session
+    return Session(w, lens=lens)
+
+
+# ---------------------------------------------------------------------------
+# a0: cache fill (bit-exact)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_cache_fill_bits_ragged_and_specials(dtype):
+    w = Workload("cf", L=3, d=96, n_max=21, B=4, r=32, C=2, N=9, cache_dtype=dtype)
+    rng = np.random.default_rng(3)
+    lens = rng.integers(1, w.n_max + 1, size=w.N).astype(np.int32)
+    lens[0] = w.n_max
+    lens[1] = 1
+    acts = inputs.batch_acts(w, range(w.N))
+    acts[2, 0, 0, :8] = [np.nan, np.inf, -np.inf, 0.0, -0.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 3.0e38]
+    acts[3, 1, 0, :4] = [1e-40, -1e-45, 65504.0, np.finfo(np.float32).max]
+    sess = make_session(w, lens=lens)
+    order = np.array([4, 0, 7, 2, 1, 8, 3, 6, 5])       # fill order != id order, two calls
+    sess.cache_fill(order[:5], acts[order[:5]], lens[order[:5]])
+    sess.cache_fill(order[5:], acts[order[5:]], lens[order[5:]])
+    torch.cuda.synchronize()
+    ref, off, _ = orc.cache_fill(acts[order], lens=lens[order], as_bf16=(dtype == "bf16"))
+    from paper_2408_10746_amd import binding as pb
+    for k, sid in enumerate(order):
+        o, ln = pb.pac_cache_lookup(sess.ctx, int(sid))
+        assert o == off[k] and ln == lens[sid]
+        got = sess.cache_block(int(sid))
+        exp = ref[off[k]: off[k] + w.L * ln * w.d].reshape(w.L, ln, w.d)
+        if dtype == "bf16":
+            np.testing.assert_array_equal(got, exp)
+        else:
+            np.testing.assert_array_equal(got.view(np.uint32), exp.view(np.uint32))
+    # refill in place with new values keeps the layout
+    acts2 = acts[[7]] * np.float32(0.5)
+    sess.cache_fill([7], acts2, lens[[7]])
+    torch.cuda.synchronize()
+    ref2, _, _ = orc.cache_fill(acts2, lens=lens[[7]], as_bf16=(dtype == "bf16"))
+    np.testing.assert_array_equal(sess.cache_block(7).ravel(), ref2)
+    # bf16 input activations
+    a16 = torch.from_numpy(acts[[5]]).to(torch.bfloat16).cuda()
+    sess.cache_fill([5], a16, lens[[5]])
+    torch.cuda.synchronize()
+    exp16, _, _ = orc.cache_fill(a16.float().cpu().numpy(), lens=lens[[5]], as_bf16=(dtype == "bf16"))
+    np.testing.assert_array_equal(sess.cache_block(5).ravel().view(np.uint16 if dtype == "bf16" else np.uint32),
+                                  exp16.view(np.uint16 if dtype == "bf16" else np.uint32))
+
+
+# ---------------------------------------------------------------------------
+# a1-a4: forward, head, loss, reverse pass
+# ---------------------------------------------------------------------------
+SMALL = [
+    # several 64-row tiles with a ragged tail, r and d spanning more than one 64-column tile
+    Workload("s1", L=3, d=160, n_max=37, B=5, r=96, C=3, N=5, cache_dtype="f32", len_lo=9),
+    Workload("s2", L=2, d=64, n_max=70, B=3, r=32, C=2, N=3, cache_dtype="f32"),
+    Workload("s3", L=3, d=160, n_max=37, B=5, r=96, C=3, N=5, cache_dtype="bf16", len_lo=9),
+    Workload("s4", L=4, d=256, n_max=64, B=8, r=32, C=4, N=8, cache_dtype="bf16"),
+    Workload("s5", L=1, d=32, n_max=1, B=1, r=32, C=1, N=1, cache_dtype="f32"),      # degenerate: one token
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=[w.name for w in SMALL])
+@pytest.mark.parametrize("state", ["init", "random"])
+def test_loss_grad_small(w, state):
+    lens = inputs.lengths(w)
+    ids = np.arange(w.B)
+    acts = inputs.batch_acts(w, ids)
+    labels = inputs.labels(w)[ids]
+    params = inputs.init_params(w) if state == "init" else inputs.random_params(w)
+    sess = make_session(w, lens=lens)
+    sess.cache_fill(ids, acts, lens)
+    ref, loss, grads, worst = check_against_oracle(w, sess, ids, acts, lens, labels, params, TOL[w.cache_dtype],
+                                                   what=f"{w.name}/{state}")
+    if state == "init":
+        dims = orc.Dims(w.L, w.d, w.r, w.C)
+        sl = orc.param_slices(dims)
+        for l in range(w.L):
+            for nm in (f"W_down{l}", f"c_down{l}", f"lambda{l}"):
+                assert np.all(ref["grads"][sl[nm]] == 0.0)
+                assert np.all(grads[sl[nm]] == 0.0), nm
+
+
+def test_outlier_channels_bf16():
+    w = Workload("out", L=3, d=512, n_max=40, B=4, r=64, C=4, N=4, cache_dtype="bf16", outlier_frac=0.01)
+    ids = np.arange(w.B)
+    acts = inputs.batch_acts(w, ids)
+    assert np.abs(acts).max() > 20.0
+    labels = inputs.labels(w)[ids]
+    sess = make_session(w)
+    sess.cache_fill(ids, acts)
+    check_against_oracle(w, sess, ids, acts, None, labels, inputs.random_params(w, up_scale=0.25), TOL["bf16"], "outliers")
+
+
+def test_subset_and_order_of_cached_samples():
+    """A step may address any filled samples in any order (batch gather)."""
+    w = Workload("gather", L=2, d=64, n_max=19, B=4, r=32, C=3, N=10, cache_dtype="f32", len_lo=5)
+    lens = inputs.lengths(w)
+    acts = inputs.batch_acts(w, range(w.N))
+    sess = make_session(w, lens=lens)
+    sess.cache_fill(np.arange(w.N), acts, lens)
+    ids = np.array([7, 2, 9, 0])
+    labels = inputs.labels(w)[ids]
+    check_against_oracle(w, sess, ids, acts[ids], lens[ids], labels, inputs.random_params(w), TOL["f32"], "gather")
+    # a smaller batch than B_max
+    ids = np.array([3, 8])
+    labels = inputs.labels(w)[ids]
+    check_against_oracle(w, sess, ids, acts[ids], lens[ids], labels, inputs.random_params(w), TOL["f32"], "gather2")
+
+
+def test_bitwise_reproducible():
+    w = SMALL[2]
+    lens = inputs.lengths(w)
+    ids = np.arange(w.B)
+    sess = make_session(w, lens=lens)
+    sess.cache_fill(ids, inputs.batch_acts(w, ids), lens)
+    sess.set_params(inputs.random_params(w))
+    lab = torch.from_numpy(inputs.labels(w)[ids]).cuda()
+    sess.loss_grad(ids, lab)
+    g1, l1 = sess.grads.clone(), sess.loss.clone()
+    sess.grads.zero_()
+    sess.loss_grad(ids, lab)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, sess.grads) and torch.equal(l1, sess.loss)
+
+
+# ---------------------------------------------------------------------------
+# a5 + whole step: the Tiny configuration end to end (fp32 mode)
+# ---------------------------------------------------------------------------
+def test_tiny_config_three_epochs():
+    w = inputs.WORKLOADS["tiny"]
+    tol = TOL["f32"]
+    dims = orc.Dims(w.L, w.d, w.r, w.C)
+    acts = inputs.batch_acts(w, range(w.N))
+    labels = inputs.labels(w)
+    cache, off, lens = orc.cache_fill(acts, as_bf16=False)
+    p = inputs.init_params(w).astype(np.float64)
+    m, v, t = np.zeros(dims.P), np.zeros(dims.P), 0
+    hp = orc.AdamW()
+    sess = make_session(w)
+    sess.cache_fill(np.arange(w.N), acts)
+    sess.set_params(inputs.init_params(w))
+    lab_all = torch.from_numpy(labels).cuda()
+    k = 0
+    for e in range(w.epochs):
+        order = inputs.epoch_order(w, e)
+        for b in range(w.N // w.B):
+            ids = order[b * w.B:(b + 1) * w.B]
+            loss_ref, g_ref, t = orc.step(dims, cache, off[ids], lens[ids], labels[ids], p, m, v, t, hp)
+            sess.step(ids, lab_all[torch.from_numpy(ids).cuda()].contiguous())
+            k += 1
+            loss = float(sess.loss.item())
+            assert abs(loss - loss_ref) <= tol * abs(loss_ref), (k, loss, loss_ref)
+            if k in (1, 2, 9, 24):
+                g = sess.grads.cpu().numpy()
+                for name, sl in tensors(dims).items():
+                    assert rel_err(g[sl], g_ref[sl]) <= 20 * tol, (k, name, rel_err(g[sl], g_ref[sl]))
+    assert k == 24 and sess.step_count == 24
+    pg = sess.params.cpu().numpy()
+    for name, sl in tensors(dims).items():
+        assert rel_err(pg[sl], p[sl]) <= 20 * tol, (name, rel_err(pg[sl], p[sl]))
+
+
+def test_adamw_single_step_and_resume():
+    """One update from the same state matches the oracle; saving and restoring (params, m, v, step)
+    continues bit-identically."""
+    w = SMALL[0]
+    dims = orc.Dims(w.L, w.d, w.r, w.C)
+    lens = inputs.lengths(w)
+    ids = np.arange(w.B)
+    acts = inputs.batch_acts(w, ids)
+    labels = inputs.labels(w)[ids]
+    lab = torch.from_numpy(labels).cuda()
+    sess = make_session(w, lens=lens)
+    sess.cache_fill(ids, acts, lens)
+    p0 = inputs.random_params(w)
+    cache, off, lens_a = orc.cache_fill(acts, lens=lens, as_bf16=False)
+    p, m, v = p0.astype(np.float64), np.zeros(dims.P), np.zeros(dims.P)
+    t = 0
+    sess.set_params(p0)
+    for _ in range(3):
+        _, _, t = orc.step(dims, cache, off, lens_a, labels, p, m, v, t, orc.AdamW())
+        sess.step(ids, lab)
+    pg, mg, vg = sess.params.cpu().numpy(), sess.m.cpu().numpy(), sess.v.cpu().numpy()
+    for name, sl in tensors(dims).items():
+        assert rel_err(pg[sl], p[sl]) <= 1e-5, name
+        assert rel_err(mg[sl], m[sl]) <= 1e-4, name
+        assert rel_err(vg[sl], v[sl]) <= 1e-4, name
+    saved = (sess.params.clone(), sess.m.clone(), sess.v.clone(), sess.step_count)
+    sess.step(ids, lab)
+    after = sess.params.clone()
+    sess.params.copy_(saved[0]); sess.m.copy_(saved[1]); sess.v.copy_(saved[2]); sess.step_count = saved[3]
+    sess.step(ids, lab)
+    torch.cuda.synchronize()
+    assert torch.equal(after, sess.params)
+
+
+# ---------------------------------------------------------------------------
+# full-size configurations
+# ---------------------------------------------------------------------------
+def _full_size(name, n_fill, B_check=None, steps_before=0):
+    w = inputs.WORKLOADS[name]
+    lens_all = inputs.lengths(w)
+    ids_fill = np.arange(n_fill)
+    from paper_2408_10746_amd.runtime import Session
+    sess = Session(w, cache_samples=n_fill, lens=lens_all[:n_fill] if w.len_lo else None)
+    note(f"{name}: filling {n_fill} samples")
+    for s in ids_fill:                                     # one sample at a time keeps host memory small
+        sess.cache_fill([int(s)], inputs.batch_acts(w, [s]), lens_all[[s]] if w.len_lo else None)
+    labels = inputs.labels(w)
+    lab_all = torch.from_numpy(labels).cuda()
+    sess.set_params(inputs.init_params(w))
+    for k in range(steps_before):                          # move away from the zero-initialised state
+        ids = np.roll(ids_fill, -k * w.B)[:w.B]
+        sess.step(ids, lab_all[torch.from_numpy(ids).cuda()].contiguous(), keep_grads=False)
+    torch.cuda.synchronize()
+    params = sess.params.cpu().numpy().copy()
+    ids = ids_fill[:w.B] if B_check is None else ids_fill[:B_check]
+    return w, sess, ids, lens_all, labels, params
+
+
+@pytest.mark.parametrize("steps_before", [0, 12])
+def test_t5base_full_batch(steps_before):
+    """The benchmark's configuration and launch shape (B=32 x 128 tokens, d=768, r=96, L=12)."""
+    w, sess, ids, lens_all, labels, params = _full_size("t5base", 64, steps_before=steps_before)
+    acts = inputs.batch_acts(w, ids)
+    if steps_before:
+        dims = orc.Dims(w.L, w.d, w.r, w.C)
+        sl = orc.param_slices(dims)
+        assert np.abs(params[sl["W_up0"]]).max() > 0
+    check_against_oracle(w, sess, ids, acts, None, labels[ids], params, TOL["bf16"], f"t5base/{steps_before}")
+
+
+@pytest.mark.timeout(600)
+def test_llama7b_shape_reduced_batch():
+    """d=4096, r=256, L=32, 256-token samples with outlier channels; batch cut to 2 samples so the
+    plain CPU oracle finishes in about a minute."""
+    w, sess, ids, lens_all, labels, params = _full_size("llama7b", 16, B_check=2, steps_before=2)
+    acts = inputs.batch_acts(w, ids)
+    check_against_oracle(w, sess, ids, acts, None, labels[ids], params, TOL["bf16"], "llama7b")
