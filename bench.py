@@ -30,6 +30,7 @@ def kernel_models(w, M):
     slab = M * d * 2                       # one layer of the batch's cache slice, bf16
     pre = M * r * 4
     PL = 2 * d * r + r + d + 1
+    pairs = L * (L - 1) // 2
     return {
         "fwd_down": (slab + pre, 2.0 * M * d * r),
         "fwd_up": (0, 2.0 * M * d * r),
@@ -43,8 +44,16 @@ def kernel_models(w, M):
         "head": (B * d * 4, 2.0 * B * d * C),
         "head_bwd": (0, 2.0 * B * d * C),
         "setup": (0, 0.0),
-        "fused_fwd": (L * (slab + pre), 4.0 * M * d * r * L),
-        "fused_bwd": (L * (slab + pre) + w.P * 4, 8.0 * M * d * r * L),
+        # Gram-matrix path: the two cache passes are g_proj (U = b W_down, all layers) and
+        # g_tokred (E = b^T dpre, all layers, plus the h^T dpre Gram matrix)
+        "g_prep": (w.P * 4, 0.0),
+        "g_proj": (L * (slab + pre), 2.0 * M * d * r * L + 2.0 * r * r * d * pairs),
+        "g_chain_fwd": (2 * L * pre + L * M * r * 2, 2.0 * M * r * r * pairs),
+        "g_head": (B * d * 4, 2.0 * B * (d + L * r) * C),
+        "g_chain_bwd": (L * pre + L * M * r * 2, 2.0 * M * r * r * pairs),
+        "g_tokred": (L * slab + 2 * L * M * r * 2, 2.0 * M * d * r * L + 2.0 * M * r * r * pairs),
+        "g_reduce": (0, 0.0),
+        "g_post": (w.P * 4, 4.0 * d * r * r * pairs),
     }
 
 

@@ -76,12 +76,18 @@ typedef enum { PAC_BF16 = 0, PAC_F32 = 1 } pac_dtype;
  * n_max  longest sequence (>= 1)             r      adapter width (multiple of 32, <= d... any)
  * C      classes (1..16)                     B_max  largest batch of one step (1..64)
  * N      samples the cache can index (>= 1)  cache_dtype  PAC_BF16 or PAC_F32
+ * flags  see PAC_FLAG_* below
  */
 typedef struct {
     int32_t L, d, n_max, r, C, B_max;
     int64_t N;
     int32_t cache_dtype;
+    int32_t flags; /* 0, or PAC_FLAG_* or-ed together */
 } pac_config;
+
+/* Run the step with the per-layer kernels even where the faster Gram-matrix
+ * formulation applies (same results up to rounding; kept for cross-checking). */
+#define PAC_FLAG_PER_LAYER 1
 
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay;

@@ -19,6 +19,7 @@ PAC_OK = 0
 PAC_ERR_NULL, PAC_ERR_SHAPE, PAC_ERR_RANGE, PAC_ERR_ALIGN = 1, 2, 3, 4
 PAC_ERR_UNSUPPORTED, PAC_ERR_WORKSPACE, PAC_ERR_DEVICE, PAC_ERR_STATE = 5, 6, 7, 8
 PAC_BF16, PAC_F32 = 0, 1
+PAC_FLAG_PER_LAYER = 1
 
 EXPORTS = [
     "pac_create", "pac_destroy", "pac_status_str", "pac_param_count", "pac_param_offsets",
@@ -30,7 +31,8 @@ EXPORTS = [
 
 class pac_config(C.Structure):
     _fields_ = [("L", C.c_int32), ("d", C.c_int32), ("n_max", C.c_int32), ("r", C.c_int32),
-                ("C", C.c_int32), ("B_max", C.c_int32), ("N", C.c_int64), ("cache_dtype", C.c_int32)]
+                ("C", C.c_int32), ("B_max", C.c_int32), ("N", C.c_int64), ("cache_dtype", C.c_int32),
+                ("flags", C.c_int32)]
 
 
 class pac_adamw(C.Structure):
@@ -110,8 +112,8 @@ def _hp(a):
 
 
 # ---- the C entry points, one to one ---------------------------------------
-def pac_create(L, d, n_max, r, C_, B_max, N, cache_dtype) -> int:
-    cfg = pac_config(L, d, n_max, r, C_, B_max, N, cache_dtype)
+def pac_create(L, d, n_max, r, C_, B_max, N, cache_dtype, flags=0) -> int:
+    cfg = pac_config(L, d, n_max, r, C_, B_max, N, cache_dtype, flags)
     out = C.c_void_p()
     _check(lib().pac_create(C.byref(cfg), C.byref(out)), "pac_create")
     return out.value

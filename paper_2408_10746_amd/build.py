@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libpac.so")
-SOURCES = ["pac_api.hip", "pac_kernels.hip"]
+SOURCES = ["pac_api.hip", "pac_kernels.hip", "pac_gram.hip"]
 HEADERS = ["pac_gemm.h", "pac_internal.h", os.path.join("..", "..", "include", "pac.h")]
 
 HIPCC_FLAGS = [

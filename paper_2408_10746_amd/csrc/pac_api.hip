@@ -22,7 +22,8 @@ struct pac_ctx {
 
 static const char *const kClassNames[KC_COUNT] = {
     "cache_fill", "setup", "shadows", "fwd_down", "fwd_up", "pool", "head", "head_bwd",
-    "bwd_dpre", "bwd_wgrad", "bwd_dx", "reduce", "adamw"};
+    "bwd_dpre", "bwd_wgrad", "bwd_dx", "reduce", "adamw",
+    "g_prep", "g_proj", "g_chain_fwd", "g_head", "g_chain_bwd", "g_tokred", "g_reduce", "g_post"};
 
 static void drop_events(Profiler &p)
 {
@@ -58,6 +59,7 @@ pac_status pac_create(const pac_config *cfg, pac_ctx **out)
     if (cfg->L < 1 || cfg->d < 1 || cfg->n_max < 1 || cfg->r < 1 || cfg->C < 1 || cfg->B_max < 1 || cfg->N < 1)
         return PAC_ERR_SHAPE;
     if (cfg->cache_dtype != PAC_BF16 && cfg->cache_dtype != PAC_F32) return PAC_ERR_SHAPE;
+    if (cfg->flags & ~PAC_FLAG_PER_LAYER) return PAC_ERR_SHAPE;
     if (cfg->d % 32 || cfg->r % 32) return PAC_ERR_UNSUPPORTED;
     if (cfg->C > kMaxClasses || cfg->B_max > kMaxBatch) return PAC_ERR_UNSUPPORTED;
     if ((int64_t)cfg->B_max * cfg->n_max > (int64_t)1 << 24) return PAC_ERR_UNSUPPORTED;
@@ -67,7 +69,7 @@ pac_status pac_create(const pac_config *cfg, pac_ctx **out)
     if (!c) return PAC_ERR_WORKSPACE;
     Dims &D = c->D;
     D.L = cfg->L; D.d = cfg->d; D.n_max = cfg->n_max; D.r = cfg->r; D.C = cfg->C; D.B_max = cfg->B_max;
-    D.N = cfg->N; D.cache_dtype = cfg->cache_dtype;
+    D.N = cfg->N; D.cache_dtype = cfg->cache_dtype; D.flags = cfg->flags;
     D.PL = 2 * (int64_t)D.d * D.r + D.r + D.d + 1;
     D.P = (int64_t)D.L * D.PL + (int64_t)D.d * D.C + D.C;
     D.Mmax = (int64_t)D.B_max * D.n_max;

@@ -1,14 +1,15 @@
-// LDS-tiled MFMA contraction core for gfx950, shared by the per-layer kernels.
+// LDS-tiled MFMA contraction core for gfx950, shared by all contraction kernels.
 //
-// One workgroup = 256 threads = 4 wavefronts (64 lanes each) arranged 2 x 2;
+// One workgroup = 256 threads = 4 wavefronts (64 lanes each) arranged WM x WN;
 // every wavefront owns WTM x WTN accumulator tiles of 32 x 32, so the
-// workgroup tile is (64*WTM) x (64*WTN).  Operands are staged through LDS in a
-// K-contiguous layout for both sides ("A[i][k]" and "B[j][k]"), 64 bytes of K
-// per row per step plus 16 bytes of padding, which is what the 32x32 MFMA
-// wants: lane (i = lane%32, g = lane/32) supplies KV consecutive K values of
-// row i (8 bf16, or 1 fp32), and the instruction contracts 2*KV of K.
-// Because both operands use the same (g, element) -> K assignment, the result
-// does not depend on how the hardware labels K inside an instruction.
+// workgroup tile is (32*WM*WTM) x (32*WN*WTN).  Operands are staged through
+// LDS in a K-contiguous layout for both sides ("A[i][k]" and "B[j][k]"),
+// KU*64 bytes of K per row per step plus 16 bytes of padding, which is what
+// the 32x32 MFMA wants: lane (i = lane%32, g = lane/32) supplies KV
+// consecutive K values of row i (8 bf16, or 1 fp32), and the instruction
+// contracts 2*KV of K.  Because both operands use the same (g, element) -> K
+// assignment, the result does not depend on how the hardware labels K inside
+// an instruction.
 //
 // Accumulator layout of the 32x32 MFMA (public CDNA ISA): register v of lane l
 // holds C[8*(v/4) + 4*(l/32) + v%4][l%32].
@@ -30,21 +31,23 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
-constexpr int kRowBytes = 64;   // bytes of K staged per row per step
-constexpr int kPitchBytes = 80; // LDS row pitch (64 + 16 padding)
 
 template <typename TC> struct Traits;
 template <> struct Traits<bf16_t> {
-    static constexpr int CE = 8;   // elements per 16-byte chunk
-    static constexpr int KV = 8;   // K values a lane feeds to one MFMA
-    static constexpr int BK = 32;  // K elements per step
-    static constexpr int LDP = 40; // LDS pitch in elements
+    static constexpr int CE = 8;  // elements per 16-byte chunk
+    static constexpr int KV = 8;  // K values a lane feeds to one MFMA
 };
 template <> struct Traits<float> {
     static constexpr int CE = 4;
     static constexpr int KV = 1;
-    static constexpr int BK = 16;
-    static constexpr int LDP = 20;
+};
+
+// Geometry of one staged K step: KU * 64 bytes of K per row.
+template <typename TC, int KU> struct Stage {
+    static constexpr int CE = Traits<TC>::CE;
+    static constexpr int BK = KU * 64 / (int)sizeof(TC);       // K elements per step
+    static constexpr int LDP = (KU * 64 + 16) / (int)sizeof(TC); // LDS pitch in elements
+    static constexpr int CPK = 4 * KU;                          // 16-byte chunks along K per row
 };
 
 // 16 bytes of compute-type elements
@@ -57,56 +60,75 @@ __device__ __forceinline__ float to_f32(float f) { return f; }
 
 // ---------------------------------------------------------------------------
 // Row-major loaders: operand[row][k] = src[row][k] (K contiguous in memory).
-// Thread t handles rows t/4 + 64u (u < WT) and the 16-byte K chunk t%4.
+// Chunk c = t + 256u covers row c / CPK and the 16-byte K chunk c % CPK.
 // ---------------------------------------------------------------------------
-template <typename TC, int WT> struct LoadRowsTC {
-    using T = Traits<TC>;
+template <typename TC, int ROWS, int KU> struct RowsGeom {
+    using S = Stage<TC, KU>;
+    static constexpr int TOTAL = ROWS * S::CPK;
+    static constexpr int NCH = (TOTAL + kThreads - 1) / kThreads;
+};
+
+template <typename TC, int ROWS, int KU> struct LoadRowsTC {
+    using S = Stage<TC, KU>;
+    using G = RowsGeom<TC, ROWS, KU>;
     const TC *src;
     int64_t ld;
     int nrows;
-    const TC *rp[WT];
-    uint4 reg[WT];
+    const TC *rp[G::NCH];
+    uint4 reg[G::NCH];
     __device__ void init(int row0)
     {
         const int t = threadIdx.x;
-        for (int u = 0; u < WT; ++u) {
-            int row = row0 + (t >> 2) + 64 * u;
-            rp[u] = row < nrows ? src + (int64_t)row * ld + (t & 3) * T::CE : nullptr;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            const int row = row0 + c / S::CPK;
+            rp[u] = (c < G::TOTAL && row < nrows) ? src + (int64_t)row * ld + (c % S::CPK) * S::CE : nullptr;
         }
     }
     __device__ void fetch(int k0)
     {
-        for (int u = 0; u < WT; ++u)
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u)
             reg[u] = rp[u] ? *reinterpret_cast<const uint4 *>(rp[u] + k0) : make_uint4(0, 0, 0, 0);
     }
     __device__ void store(TC *lds)
     {
         const int t = threadIdx.x;
-        for (int u = 0; u < WT; ++u)
-            *reinterpret_cast<uint4 *>(lds + ((t >> 2) + 64 * u) * T::LDP + (t & 3) * T::CE) = reg[u];
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            if (c < G::TOTAL)
+                *reinterpret_cast<uint4 *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * S::CE) = reg[u];
+        }
     }
 };
 
-template <typename TC, int WT> struct LoadRowsF32 {
-    using T = Traits<TC>;
+template <typename TC, int ROWS, int KU> struct LoadRowsF32 {
+    using S = Stage<TC, KU>;
+    using G = RowsGeom<TC, ROWS, KU>;
     const float *src;
     int64_t ld;
     int nrows;
-    const float *rp[WT];
-    Chunk<TC> reg[WT];
+    const float *rp[G::NCH];
+    Chunk<TC> reg[G::NCH];
     __device__ void init(int row0)
     {
         const int t = threadIdx.x;
-        for (int u = 0; u < WT; ++u) {
-            int row = row0 + (t >> 2) + 64 * u;
-            rp[u] = row < nrows ? src + (int64_t)row * ld + (t & 3) * T::CE : nullptr;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            const int row = row0 + c / S::CPK;
+            rp[u] = (c < G::TOTAL && row < nrows) ? src + (int64_t)row * ld + (c % S::CPK) * S::CE : nullptr;
         }
     }
     __device__ void fetch(int k0)
     {
-        for (int u = 0; u < WT; ++u) {
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
             if (rp[u]) {
-                for (int q = 0; q < T::CE / 4; ++q) {
+#pragma unroll
+                for (int q = 0; q < S::CE / 4; ++q) {
                     float4 f = *reinterpret_cast<const float4 *>(rp[u] + k0 + 4 * q);
                     reg[u].e[4 * q + 0] = to_tc(f.x, TC());
                     reg[u].e[4 * q + 1] = to_tc(f.y, TC());
@@ -114,15 +136,20 @@ template <typename TC, int WT> struct LoadRowsF32 {
                     reg[u].e[4 * q + 3] = to_tc(f.w, TC());
                 }
             } else {
-                for (int e = 0; e < T::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
+#pragma unroll
+                for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
             }
         }
     }
     __device__ void store(TC *lds)
     {
         const int t = threadIdx.x;
-        for (int u = 0; u < WT; ++u)
-            *reinterpret_cast<Chunk<TC> *>(lds + ((t >> 2) + 64 * u) * T::LDP + (t & 3) * T::CE) = reg[u];
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            if (c < G::TOTAL)
+                *reinterpret_cast<Chunk<TC> *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * S::CE) = reg[u];
+        }
     }
 };
 
@@ -134,26 +161,29 @@ struct RowMap {
     int M;
 };
 
-// x[m][k] = lam * b_l[m][k] + (1 - lam) * s_prev[m][k]   (s_prev == nullptr: s = 0)
-template <typename TC, int WT> struct LoadRowsX {
-    using T = Traits<TC>;
+// x[m][k] = lam * b_l[m][k] + (1 - lam) * s_prev[m][k]   (s_prev == nullptr: x = lam * b)
+template <typename TC, int ROWS, int KU> struct LoadRowsX {
+    using S = Stage<TC, KU>;
+    using G = RowsGeom<TC, ROWS, KU>;
     const TC *cache;
     RowMap map;
     int layer;
     const float *s_prev;
     int64_t ld_s;
     float lam;
-    const TC *bp[WT];
-    const float *sp[WT];
-    Chunk<TC> reg[WT];
+    const TC *bp[G::NCH];
+    const float *sp[G::NCH];
+    Chunk<TC> reg[G::NCH];
     __device__ void init(int row0)
     {
         const int t = threadIdx.x;
-        for (int u = 0; u < WT; ++u) {
-            int row = row0 + (t >> 2) + 64 * u;
-            if (row < map.M) {
-                bp[u] = cache + map.rowoff[row] + (int64_t)layer * map.rowstride[row] + (t & 3) * T::CE;
-                sp[u] = s_prev ? s_prev + (int64_t)row * ld_s + (t & 3) * T::CE : nullptr;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            const int row = row0 + c / S::CPK;
+            if (c < G::TOTAL && row < map.M) {
+                bp[u] = cache + map.rowoff[row] + (int64_t)layer * map.rowstride[row] + (c % S::CPK) * S::CE;
+                sp[u] = s_prev ? s_prev + (int64_t)row * ld_s + (c % S::CPK) * S::CE : nullptr;
             } else {
                 bp[u] = nullptr;
                 sp[u] = nullptr;
@@ -162,30 +192,40 @@ template <typename TC, int WT> struct LoadRowsX {
     }
     __device__ void fetch(int k0)
     {
-        for (int u = 0; u < WT; ++u) {
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
             if (bp[u]) {
                 Chunk<TC> b = *reinterpret_cast<const Chunk<TC> *>(bp[u] + k0);
                 if (sp[u]) {
-                    for (int q = 0; q < T::CE / 4; ++q) {
+#pragma unroll
+                    for (int q = 0; q < S::CE / 4; ++q) {
                         float4 s = *reinterpret_cast<const float4 *>(sp[u] + k0 + 4 * q);
                         reg[u].e[4 * q + 0] = to_tc(lam * to_f32(b.e[4 * q + 0]) + (1.f - lam) * s.x, TC());
                         reg[u].e[4 * q + 1] = to_tc(lam * to_f32(b.e[4 * q + 1]) + (1.f - lam) * s.y, TC());
                         reg[u].e[4 * q + 2] = to_tc(lam * to_f32(b.e[4 * q + 2]) + (1.f - lam) * s.z, TC());
                         reg[u].e[4 * q + 3] = to_tc(lam * to_f32(b.e[4 * q + 3]) + (1.f - lam) * s.w, TC());
                     }
+                } else if (lam == 1.f) {
+                    reg[u] = b;
                 } else {
-                    for (int e = 0; e < T::CE; ++e) reg[u].e[e] = to_tc(lam * to_f32(b.e[e]), TC());
+#pragma unroll
+                    for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(lam * to_f32(b.e[e]), TC());
                 }
             } else {
-                for (int e = 0; e < T::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
+#pragma unroll
+                for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
             }
         }
     }
     __device__ void store(TC *lds)
     {
         const int t = threadIdx.x;
-        for (int u = 0; u < WT; ++u)
-            *reinterpret_cast<Chunk<TC> *>(lds + ((t >> 2) + 64 * u) * T::LDP + (t & 3) * T::CE) = reg[u];
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            if (c < G::TOTAL)
+                *reinterpret_cast<Chunk<TC> *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * S::CE) = reg[u];
+        }
     }
 };
 
@@ -193,70 +233,78 @@ template <typename TC, int WT> struct LoadRowsX {
 // Transposed loaders for contractions over the token index:
 // operand[i][k] = src[k][i]  (i contiguous in memory, k = token row).
 // A step stages BK token rows.  Chunk c = t + 256u covers token row
-// c / CPR and the 16-byte i-chunk c % CPR, CPR = 64*WT / CE; the chunk is
+// c / CPR and the 16-byte i-chunk c % CPR, CPR = ROWS / CE; the chunk is
 // scattered into the K-contiguous LDS layout element by element.
 // Rows k >= kend are zero.  Optionally keeps per-thread column sums.
 // ---------------------------------------------------------------------------
-template <typename TC, int WT> struct ColsGeom {
-    using T = Traits<TC>;
-    static constexpr int CPR = 64 * WT / T::CE;      // chunks per token row
-    static constexpr int NCH = T::BK * CPR / kThreads; // chunks per thread
-    static_assert(T::BK * CPR % kThreads == 0, "tile/threads mismatch");
-    static_assert(kThreads % CPR == 0 || CPR % kThreads == 0, "column ownership must be fixed");
+template <typename TC, int ROWS, int KU> struct ColsGeom {
+    using S = Stage<TC, KU>;
+    static constexpr int CPR = ROWS / S::CE;             // chunks per token row
+    static constexpr int TOTAL = S::BK * CPR;
+    static constexpr int NCH = (TOTAL + kThreads - 1) / kThreads; // chunks per thread
+    static_assert(ROWS % S::CE == 0, "tile rows must be whole chunks");
 };
 
-template <typename TC, int WT, typename SRC, bool SUMS> struct LoadCols {
-    using T = Traits<TC>;
-    using G = ColsGeom<TC, WT>;
+template <typename TC, int ROWS, int KU, typename SRC, bool SUMS> struct LoadCols {
+    using S = Stage<TC, KU>;
+    using G = ColsGeom<TC, ROWS, KU>;
+    static_assert(!SUMS || kThreads % G::CPR == 0, "column sums need a fixed column per thread");
     const SRC *src; // [k][ld]
     int64_t ld;
     int ncols; // valid i
     int kend;
     int i0;
     Chunk<TC> reg[G::NCH];
-    float sums[SUMS ? G::NCH : 1][T::CE];
+    float sums[SUMS ? G::NCH : 1][S::CE];
     __device__ void init(int i0_)
     {
         i0 = i0_;
         if (SUMS)
             for (int u = 0; u < G::NCH; ++u)
-                for (int e = 0; e < T::CE; ++e) sums[u][e] = 0.f;
+                for (int e = 0; e < S::CE; ++e) sums[u][e] = 0.f;
     }
     __device__ void fetch(int k0)
     {
         const int t = threadIdx.x;
+#pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
-            int c = t + kThreads * u;
-            int k = k0 + c / G::CPR;
-            int i = i0 + (c % G::CPR) * T::CE;
-            if (k < kend && i < ncols) {
+            const int c = t + kThreads * u;
+            const int k = k0 + c / G::CPR;
+            const int i = i0 + (c % G::CPR) * S::CE;
+            if (c < G::TOTAL && k < kend && i < ncols) {
                 const SRC *p = src + (int64_t)k * ld + i;
-                for (int e = 0; e < T::CE; ++e) {
+#pragma unroll
+                for (int e = 0; e < S::CE; ++e) {
                     float f = to_f32(p[e]);
                     if (SUMS) sums[u][e] += f;
                     reg[u].e[e] = to_tc(f, TC());
                 }
             } else {
-                for (int e = 0; e < T::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
+#pragma unroll
+                for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
             }
         }
     }
     __device__ void store(TC *lds)
     {
         const int t = threadIdx.x;
+#pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
-            int c = t + kThreads * u;
-            int kk = c / G::CPR;
-            int ii = (c % G::CPR) * T::CE;
-            for (int e = 0; e < T::CE; ++e) lds[(ii + e) * T::LDP + kk] = reg[u].e[e];
+            const int c = t + kThreads * u;
+            if (c < G::TOTAL) {
+                const int kk = c / G::CPR;
+                const int ii = (c % G::CPR) * S::CE;
+#pragma unroll
+                for (int e = 0; e < S::CE; ++e) lds[(ii + e) * S::LDP + kk] = reg[u].e[e];
+            }
         }
     }
 };
 
 // operand[i][k] = x[k][i] = lam * b_l[k][i] + (1 - lam) * s_prev[k][i]
-template <typename TC, int WT> struct LoadColsX {
-    using T = Traits<TC>;
-    using G = ColsGeom<TC, WT>;
+template <typename TC, int ROWS, int KU> struct LoadColsX {
+    using S = Stage<TC, KU>;
+    using G = ColsGeom<TC, ROWS, KU>;
     const TC *cache;
     RowMap map;
     int layer;
@@ -271,33 +319,43 @@ template <typename TC, int WT> struct LoadColsX {
     __device__ void fetch(int k0)
     {
         const int t = threadIdx.x;
+#pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
-            int c = t + kThreads * u;
-            int k = k0 + c / G::CPR;
-            int i = i0 + (c % G::CPR) * T::CE;
-            if (k < kend && i < ncols) {
+            const int c = t + kThreads * u;
+            const int k = k0 + c / G::CPR;
+            const int i = i0 + (c % G::CPR) * S::CE;
+            if (c < G::TOTAL && k < kend && i < ncols) {
                 const TC *bp = cache + map.rowoff[k] + (int64_t)layer * map.rowstride[k] + i;
                 Chunk<TC> b = *reinterpret_cast<const Chunk<TC> *>(bp);
                 if (s_prev) {
                     const float *sp = s_prev + (int64_t)k * ld_s + i;
-                    for (int e = 0; e < T::CE; ++e)
+#pragma unroll
+                    for (int e = 0; e < S::CE; ++e)
                         reg[u].e[e] = to_tc(lam * to_f32(b.e[e]) + (1.f - lam) * sp[e], TC());
+                } else if (lam == 1.f) {
+                    reg[u] = b;
                 } else {
-                    for (int e = 0; e < T::CE; ++e) reg[u].e[e] = to_tc(lam * to_f32(b.e[e]), TC());
+#pragma unroll
+                    for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(lam * to_f32(b.e[e]), TC());
                 }
             } else {
-                for (int e = 0; e < T::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
+#pragma unroll
+                for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
             }
         }
     }
     __device__ void store(TC *lds)
     {
         const int t = threadIdx.x;
+#pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
-            int c = t + kThreads * u;
-            int kk = c / G::CPR;
-            int ii = (c % G::CPR) * T::CE;
-            for (int e = 0; e < T::CE; ++e) lds[(ii + e) * T::LDP + kk] = reg[u].e[e];
+            const int c = t + kThreads * u;
+            if (c < G::TOTAL) {
+                const int kk = c / G::CPR;
+                const int ii = (c % G::CPR) * S::CE;
+#pragma unroll
+                for (int e = 0; e < S::CE; ++e) lds[(ii + e) * S::LDP + kk] = reg[u].e[e];
+            }
         }
     }
 };
@@ -305,21 +363,21 @@ template <typename TC, int WT> struct LoadColsX {
 // ---------------------------------------------------------------------------
 // MFMA step on one staged K tile
 // ---------------------------------------------------------------------------
-template <int WTM, int WTN>
+template <int KU, int WTM, int WTN>
 __device__ __forceinline__ void mma_tile(const bf16_t *As, const bf16_t *Bs, f32x16 (&acc)[WTM][WTN],
-                                         int wm, int wn, int lane)
+                                         int arow0, int brow0, int lane)
 {
-    using T = Traits<bf16_t>;
+    using S = Stage<bf16_t, KU>;
     const int i = lane & 31, g = lane >> 5;
 #pragma unroll
-    for (int q = 0; q < T::BK / (2 * T::KV); ++q) {
+    for (int q = 0; q < S::BK / 16; ++q) {
         bf16x8 a[WTM], b[WTN];
 #pragma unroll
         for (int x = 0; x < WTM; ++x)
-            a[x] = *reinterpret_cast<const bf16x8 *>(As + ((wm * WTM + x) * 32 + i) * T::LDP + q * 16 + g * 8);
+            a[x] = *reinterpret_cast<const bf16x8 *>(As + (arow0 + x * 32 + i) * S::LDP + q * 16 + g * 8);
 #pragma unroll
         for (int y = 0; y < WTN; ++y)
-            b[y] = *reinterpret_cast<const bf16x8 *>(Bs + ((wn * WTN + y) * 32 + i) * T::LDP + q * 16 + g * 8);
+            b[y] = *reinterpret_cast<const bf16x8 *>(Bs + (brow0 + y * 32 + i) * S::LDP + q * 16 + g * 8);
 #pragma unroll
         for (int x = 0; x < WTM; ++x)
 #pragma unroll
@@ -328,19 +386,19 @@ __device__ __forceinline__ void mma_tile(const bf16_t *As, const bf16_t *Bs, f32
     }
 }
 
-template <int WTM, int WTN>
+template <int KU, int WTM, int WTN>
 __device__ __forceinline__ void mma_tile(const float *As, const float *Bs, f32x16 (&acc)[WTM][WTN],
-                                         int wm, int wn, int lane)
+                                         int arow0, int brow0, int lane)
 {
-    using T = Traits<float>;
+    using S = Stage<float, KU>;
     const int i = lane & 31, g = lane >> 5;
 #pragma unroll
-    for (int q = 0; q < T::BK / 2; ++q) {
+    for (int q = 0; q < S::BK / 2; ++q) {
         float a[WTM], b[WTN];
 #pragma unroll
-        for (int x = 0; x < WTM; ++x) a[x] = As[((wm * WTM + x) * 32 + i) * T::LDP + q * 2 + g];
+        for (int x = 0; x < WTM; ++x) a[x] = As[(arow0 + x * 32 + i) * S::LDP + q * 2 + g];
 #pragma unroll
-        for (int y = 0; y < WTN; ++y) b[y] = Bs[((wn * WTN + y) * 32 + i) * T::LDP + q * 2 + g];
+        for (int y = 0; y < WTN; ++y) b[y] = Bs[(brow0 + y * 32 + i) * S::LDP + q * 2 + g];
 #pragma unroll
         for (int x = 0; x < WTM; ++x)
 #pragma unroll
@@ -349,24 +407,37 @@ __device__ __forceinline__ void mma_tile(const float *As, const float *Bs, f32x1
     }
 }
 
+// Shape of a workgroup tile.
+template <int WM_, int WN_, int WTM_, int WTN_, int KU_> struct Tile {
+    static constexpr int WM = WM_, WN = WN_, WTM = WTM_, WTN = WTN_, KU = KU_;
+    static constexpr int BM = 32 * WM * WTM, BN = 32 * WN * WTN;
+    static_assert(WM * WN * 64 == kThreads, "four wavefronts per workgroup");
+};
+
 // C[row0.., col0..] = sum_{k in [kbegin, kend)} A[row][k] * B[col][k]; the
 // epilogue functor receives (row, col, value) for every element inside
 // (nrows, ncols).  kbegin must be a multiple of the K step.
-template <typename TC, int WTM, int WTN, class ALoad, class BLoad, class Epi>
-__device__ __forceinline__ void gemm_tile(ALoad &al, BLoad &bl, Epi &epi, int kbegin, int kend,
-                                          int row0, int col0, int nrows, int ncols)
+// LDS bytes one workgroup tile needs (both operands of one K step).
+template <typename TC, class TL> constexpr int tile_lds_bytes()
 {
-    using T = Traits<TC>;
-    constexpr int BM = 64 * WTM, BN = 64 * WTN;
-    __shared__ __attribute__((aligned(16))) TC As[BM * T::LDP];
-    __shared__ __attribute__((aligned(16))) TC Bs[BN * T::LDP];
+    return (TL::BM + TL::BN) * Stage<TC, TL::KU>::LDP * (int)sizeof(TC);
+}
+
+template <typename TC, class TL, class ALoad, class BLoad, class Epi>
+__device__ __forceinline__ void gemm_tile(void *lds /* tile_lds_bytes<TC, TL>(), 16-byte aligned */, ALoad &al,
+                                          BLoad &bl, Epi &epi, int kbegin, int kend, int row0, int col0,
+                                          int nrows, int ncols)
+{
+    using S = Stage<TC, TL::KU>;
+    TC *As = reinterpret_cast<TC *>(lds);
+    TC *Bs = As + TL::BM * S::LDP;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    f32x16 acc[WTM][WTN];
+    const int wm = wave / TL::WN, wn = wave % TL::WN;
+    f32x16 acc[TL::WTM][TL::WTN];
 #pragma unroll
-    for (int x = 0; x < WTM; ++x)
+    for (int x = 0; x < TL::WTM; ++x)
 #pragma unroll
-        for (int y = 0; y < WTN; ++y)
+        for (int y = 0; y < TL::WTN; ++y)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
 
@@ -376,33 +447,33 @@ __device__ __forceinline__ void gemm_tile(ALoad &al, BLoad &bl, Epi &epi, int kb
         al.fetch(kbegin);
         bl.fetch(kbegin);
     }
-    for (int k0 = kbegin; k0 < kend; k0 += T::BK) {
+    for (int k0 = kbegin; k0 < kend; k0 += S::BK) {
         al.store(As);
         bl.store(Bs);
         __syncthreads();
-        if (k0 + T::BK < kend) {
-            al.fetch(k0 + T::BK);
-            bl.fetch(k0 + T::BK);
+        if (k0 + S::BK < kend) {
+            al.fetch(k0 + S::BK);
+            bl.fetch(k0 + S::BK);
         }
-        mma_tile<WTM, WTN>(As, Bs, acc, wm, wn, lane);
+        mma_tile<TL::KU, TL::WTM, TL::WTN>(As, Bs, acc, wm * TL::WTM * 32, wn * TL::WTN * 32, lane);
         __syncthreads();
     }
     const int i = lane & 31, g = lane >> 5;
 #pragma unroll
-    for (int x = 0; x < WTM; ++x)
+    for (int x = 0; x < TL::WTM; ++x)
 #pragma unroll
-        for (int y = 0; y < WTN; ++y) {
-            const int col = col0 + (wn * WTN + y) * 32 + i;
+        for (int y = 0; y < TL::WTN; ++y) {
+            const int col = col0 + (wn * TL::WTN + y) * 32 + i;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = row0 + (wm * WTM + x) * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                const int row = row0 + (wm * TL::WTM + x) * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
                 if (row < nrows && col < ncols) epi(row, col, acc[x][y][v]);
             }
         }
 }
 
 // Sum of one float per thread over the workgroup; result valid in thread 0.
-__device__ __forceinline__ float block_sum(float v, float *scratch /* >= 4 floats of LDS */)
+__device__ __forceinline__ float block_sum(float v, float *scratch /* >= 16 floats of LDS */)
 {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);

@@ -1,0 +1,930 @@
+// Gram-matrix formulation of the cached Parallel-Adapter step (bf16 cache, adapter width <= 128).
+//
+// The side state is a sum of rank-r terms, s_{l-1} = sum_{k<l} (h_k W_up^k + c_up^k), and so is its
+// gradient, ds_l = ds_L + sum_{k>l} (1-lambda_k) dpre_k W_down^{kT}.  Substituting both into the
+// step removes every per-token d-wide intermediate except the cache itself:
+//
+//   forward   U_l   = b_l W_down^l                                  (streams the cache once, all layers at once)
+//             pre_l = lambda_l U_l + (1-lambda_l)(sum_{k<l} h_k Q_{kl} + chat_l) + c_down^l
+//                     Q_{kl} = W_up^k W_down^l (r x r), chat_l = (sum_{k<l} c_up^k) W_down^l
+//   head      logits from mean(b_L), per-sample sums of h_k and V = W_up^k W_cls
+//   backward  dh_l  = (dz V_l^T)/len + sum_{k>l} (1-lambda_k) dpre_k Q_{lk}^T ,  dpre_l = dh_l * GELU'(pre_l)
+//   tokens    E_l = b_l^T dpre_l (streams the cache a second time), G_{kl} = h_k^T dpre_l (k < l)
+//   grads     dW_down^l = lambda_l E_l + (1-lambda_l) F_l,  F_l = sum_{k<l} W_up^{kT} G_{kl} + cusum_l^T colsum(dpre_l)
+//             dW_up^l   = Z_l W_cls^T + sum_{k>l} (1-lambda_k) G_{lk} W_down^{kT},  Z_l = (sum_t h_l / len)^T dz
+//             dlambda_l = <E_l - F_l, W_down^l>, dc_down^l = colsum(dpre_l),
+//             dc_up^l   = (sum_s dz_s) W_cls^T + sum_{k>l} (1-lambda_k) W_down^k colsum(dpre_k)
+//
+// This is the same function as the per-layer kernels compute (the layer-by-layer definition is the
+// oracle's); only the order of the floating-point operations differs.  Every reduction is ordered.
+#include "pac_gemm.h"
+#include "pac_internal.h"
+
+namespace pac {
+
+#define PAC_LAUNCH(prof, st, cls, ...)                         \
+    do {                                                       \
+        if (prof) (prof)->mark((st), (cls), true);             \
+        hipLaunchKernelGGL(__VA_ARGS__);                       \
+        if (prof) (prof)->mark((st), (cls), false);            \
+    } while (0)
+
+static inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
+static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+constexpr int kChainRows = 32;   // token rows per chain workgroup
+constexpr int kChainPad = 8;     // bf16 elements of padding per LDS row
+constexpr int kMaxD = 4096;
+
+static int64_t chain_lds_bytes(const Dims &D) { return (int64_t)D.L * kChainRows * (D.r + kChainPad) * 2; }
+
+bool gram_path_fits(const Dims &D)
+{
+    if (D.cache_dtype != 0 || (D.flags & 1)) return false;
+    if (D.r > 128 || D.d > kMaxD || D.L > 128) return false;
+    return chain_lds_bytes(D) <= 128 * 1024;
+}
+
+void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
+{
+    auto take = [&](int64_t bytes) { int64_t at = o; o = align256(o + bytes); return at; };
+    const int64_t Lr = (int64_t)D.L * D.r;
+    W.use_gram = 1;
+    W.max_tiles = D.B_max * cdiv(D.n_max, kChainRows);
+    W.pairs = D.L * (D.L - 1) / 2;
+    const int e_tiles = D.L * cdiv(D.d, 128);
+    int se = cdiv(768, e_tiles);
+    const int max_by_rows = (int)((D.Mmax + 127) / 128);
+    if (se > max_by_rows) se = max_by_rows;
+    W.se = se < 1 ? 1 : (se > 16 ? 16 : se);
+    const int tg = cdiv(Lr, 64);
+    int sg = cdiv(768, (int64_t)tg * (tg + 1) / 2);
+    if (sg > max_by_rows) sg = max_by_rows;
+    W.sg = sg < 1 ? 1 : (sg > 16 ? 16 : sg);
+    W.g_tile_row0 = take(W.max_tiles * 4);
+    W.g_tile_rows = take(W.max_tiles * 4);
+    W.g_tile_samp = take(W.max_tiles * 4);
+    W.g_WuTs = take((int64_t)D.d * Lr * 2);
+    W.g_Wds = take((int64_t)D.d * Lr * 2);
+    W.g_cusum = take((int64_t)(D.L + 1) * D.d * 4);
+    W.g_chat = take(Lr * 4);
+    W.g_V = take(Lr * D.C * 4);
+    W.g_QpN = take((int64_t)(W.pairs + 1) * D.r * D.r * 2);
+    W.g_QpT = take((int64_t)(W.pairs + 1) * D.r * D.r * 2);
+    W.g_DP = take(D.Mmax * Lr * 2);
+    W.g_HSpart = take((int64_t)W.max_tiles * Lr * 4);
+    W.g_cspart = take((int64_t)W.max_tiles * Lr * 4);
+    W.g_ghat = take((int64_t)D.B_max * Lr * 4);
+    W.g_Z = take(Lr * D.C * 4);
+    W.g_dzsum = take(kMaxClasses * 4);
+    W.g_cs = take(Lr * 4);
+    W.g_Epart = take((int64_t)W.se * D.L * D.d * D.r * 4);
+    W.g_GGpart = take((int64_t)W.sg * Lr * Lr * 4);
+    W.g_GGT = take(Lr * Lr * 2);
+    W.g_GGsc = take(Lr * Lr * 2);
+    W.g_dlam_slots = cdiv(D.d, 64) * cdiv(D.r, 64);
+    W.g_dlam_part = take((int64_t)D.L * W.g_dlam_slots * 4);
+    W.g_counter = take((int64_t)(D.L + 1) * 4);
+    W.g_samp_tile0 = take((kMaxBatch + 1) * 4);
+    W.g_HSm = take((int64_t)D.B_max * Lr * 4);
+    W.g_loss_part = take(kMaxBatch * 4);
+}
+
+__device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float u)
+{
+    const float Phi = 0.5f * (1.f + erff(u * 0.70710678118654752f));
+    const float phi = 0.3989422804014327f * expf(-0.5f * u * u);
+    return Phi + u * phi;
+}
+__device__ __forceinline__ int pair_index(int k, int l) { return l * (l - 1) / 2 + k; } // k < l
+
+// ---------------------------------------------------------------------------
+// launch 1: batch gather, token tiles, projection copies, cusum/chat, V
+// ---------------------------------------------------------------------------
+struct PrepArgs {
+    BatchMeta meta;
+    const float *params;
+    int64_t PL;
+    int L, d, r, C;
+    int nb_setup, nb_shadow, nb_chat;
+    int64_t *rowoff;
+    int32_t *rowstride, *rowsamp, *samp_start, *samp_len;
+    int32_t *tile_row0, *tile_rows, *tile_samp, *samp_tile0;
+    bf16_t *WdT, *Wu, *WuTs, *Wds;
+    float *cusum, *chat, *V;
+    unsigned *counter;
+};
+
+__global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
+{
+    __shared__ float sh[kMaxD > 32 * 33 ? kMaxD : 32 * 33];
+    const int b = blockIdx.x, t = threadIdx.x;
+    const int L = a.L, d = a.d, r = a.r, C = a.C;
+    const int64_t Lr = (int64_t)L * r;
+    if (b < a.nb_setup) {
+        const BatchMeta &meta = a.meta;
+        if (b == 0) {
+            if (t <= meta.B) {
+                a.samp_start[t] = meta.tok_start[t];
+                if (t < meta.B) a.samp_len[t] = meta.len[t];
+            }
+            if (t <= L) a.counter[t] = 0u;
+            if (t == 0) {
+                int nt = 0;
+                for (int s = 0; s < meta.B; ++s) {
+                    a.samp_tile0[s] = nt;
+                    for (int t0 = 0; t0 < meta.len[s]; t0 += kChainRows) {
+                        a.tile_row0[nt] = meta.tok_start[s] + t0;
+                        a.tile_rows[nt] = min(kChainRows, meta.len[s] - t0);
+                        a.tile_samp[nt] = s;
+                        ++nt;
+                    }
+                }
+                a.samp_tile0[meta.B] = nt;
+            }
+        }
+        const int m = b * 256 + t;
+        if (m >= meta.M) return;
+        int s = 0;
+        while (s + 1 < meta.B && meta.tok_start[s + 1] <= m) ++s;
+        a.rowoff[m] = meta.off[s] + (int64_t)(m - meta.tok_start[s]) * d;
+        a.rowstride[m] = meta.len[s] * d;
+        a.rowsamp[m] = s;
+        return;
+    }
+    if (b < a.nb_setup + a.nb_shadow) {
+        // one 32 x 32 tile of W_down^k (which = 0, [d][r]) or W_up^k (which = 1, [r][d])
+        int idx = b - a.nb_setup;
+        const int per_mat = (d / 32) * (r / 32);
+        const int which = idx / (per_mat * L);
+        idx -= which * per_mat * L;
+        const int k = idx / per_mat;
+        idx -= k * per_mat;
+        const int rows = which == 0 ? d : r, cols = which == 0 ? r : d;
+        const int tiles_c = cols / 32;
+        const int tr = idx / tiles_c, tcx = idx % tiles_c;
+        const float *src = a.params + (int64_t)k * a.PL + (which == 0 ? 0 : (int64_t)d * r + r);
+        float(*tile)[33] = reinterpret_cast<float(*)[33]>(sh);
+        const int tx = t & 31, ty = t >> 5;
+        for (int y = ty; y < 32; y += 8) {
+            const int row = tr * 32 + y, col = tcx * 32 + tx;
+            const float f = src[(int64_t)row * cols + col];
+            tile[y][tx] = f;
+            if (which == 0) a.Wds[(int64_t)row * Lr + (int64_t)k * r + col] = static_cast<bf16_t>(f);
+            else a.Wu[((int64_t)k * r + row) * d + col] = static_cast<bf16_t>(f);
+        }
+        __syncthreads();
+        for (int y = ty; y < 32; y += 8) {
+            // element (row = tr*32 + tx, col = tcx*32 + y) written at the transposed position
+            const int row = tr * 32 + tx, col = tcx * 32 + y;
+            const bf16_t v = static_cast<bf16_t>(tile[tx][y]);
+            if (which == 0) a.WdT[((int64_t)k * r + col) * d + row] = v;
+            else a.WuTs[(int64_t)col * Lr + (int64_t)k * r + row] = v;
+        }
+        (void)rows;
+        return;
+    }
+    if (b < a.nb_setup + a.nb_shadow + a.nb_chat) {
+        // cusum_l = sum_{k<l} c_up^k ; chat_l = cusum_l W_down^l   (fp32 master weights)
+        const int l = b - a.nb_setup - a.nb_shadow; // 0..L
+        for (int j = t; j < d; j += 256) {
+            float acc = 0.f;
+            for (int k = 0; k < l; ++k) acc += a.params[(int64_t)k * a.PL + 2 * (int64_t)d * r + r + j];
+            sh[j] = acc;
+            a.cusum[(int64_t)l * d + j] = acc;
+        }
+        __syncthreads();
+        if (l < L) {
+            const float *Wd = a.params + (int64_t)l * a.PL;
+            for (int n = t; n < r; n += 256) {
+                float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+                for (int j = 0; j < d; j += 4) { // d is a multiple of 32
+                    acc0 += sh[j] * Wd[(int64_t)j * r + n];
+                    acc1 += sh[j + 1] * Wd[(int64_t)(j + 1) * r + n];
+                    acc2 += sh[j + 2] * Wd[(int64_t)(j + 2) * r + n];
+                    acc3 += sh[j + 3] * Wd[(int64_t)(j + 3) * r + n];
+                }
+                a.chat[(int64_t)l * r + n] = (acc0 + acc1) + (acc2 + acc3);
+            }
+        }
+        return;
+    }
+    {
+        // V[(k,a)][c] = sum_j W_up^k[a][j] W_cls[j][c]; one wavefront per row
+        const int row = (b - a.nb_setup - a.nb_shadow - a.nb_chat) * 4 + (t >> 6);
+        if (row >= Lr) return;
+        const int k = row / r, aa = row % r, lane = t & 63;
+        const float *wu = a.params + (int64_t)k * a.PL + (int64_t)d * r + r + (int64_t)aa * d;
+        const float *Wc = a.params + (int64_t)L * a.PL;
+        float acc[kMaxClasses];
+        for (int c = 0; c < kMaxClasses; ++c) acc[c] = 0.f;
+        for (int j = lane; j < d; j += 64) {
+            const float w = wu[j];
+            for (int c = 0; c < C; ++c) acc[c] += w * Wc[(int64_t)j * C + c];
+        }
+        for (int c = 0; c < C; ++c) {
+            float v = acc[c];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+            if (lane == 0) a.V[(int64_t)row * C + c] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launch 2: U_l = b_l W_down^l for every layer, Q_{kl} = W_up^k W_down^l, mean(b_L)
+// ---------------------------------------------------------------------------
+struct ProjArgs {
+    const bf16_t *cache;
+    RowMap map;
+    int L, d, r, B;
+    int nb_U, nb_Q, row_tiles;
+    const bf16_t *WdT, *Wu;
+    float *U;          // [L][M][r]
+    bf16_t *QpN, *QpT; // [pairs][r][r]
+    const int32_t *samp_start, *samp_len;
+    float *pb; // [B][d]
+};
+
+struct EpiStoreF32 {
+    float *out;
+    int64_t ld;
+    __device__ void operator()(int row, int col, float v) const { out[(int64_t)row * ld + col] = v; }
+};
+
+struct EpiQ {
+    bf16_t *qn, *qt;
+    int r;
+    __device__ void operator()(int row, int col, float v) const
+    {
+        const bf16_t h = static_cast<bf16_t>(v);
+        qn[(int64_t)row * r + col] = h;
+        qt[(int64_t)col * r + row] = h;
+    }
+};
+
+using T64 = Tile<2, 2, 1, 1, 1>;
+
+template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArgs a)
+{
+    using TU = Tile<4, 1, 1, NT, KU>;
+    constexpr int kLds = tile_lds_bytes<bf16_t, TU>() > tile_lds_bytes<bf16_t, T64>() ? tile_lds_bytes<bf16_t, TU>()
+                                                                                      : tile_lds_bytes<bf16_t, T64>();
+    __shared__ __attribute__((aligned(16))) char smem[kLds];
+    const int b = blockIdx.x;
+    if (b < a.nb_U) {
+        const int l = b / a.row_tiles, mt = b % a.row_tiles;
+        LoadRowsX<bf16_t, TU::BM, KU> al;
+        al.cache = a.cache; al.map = a.map; al.layer = l; al.s_prev = nullptr; al.ld_s = 0; al.lam = 1.f;
+        LoadRowsTC<bf16_t, TU::BN, KU> bl;
+        bl.src = a.WdT + (int64_t)l * a.r * a.d; bl.ld = a.d; bl.nrows = a.r;
+        EpiStoreF32 epi{a.U + (int64_t)l * a.map.M * a.r, a.r};
+        gemm_tile<bf16_t, TU>(smem, al, bl, epi, 0, a.d, mt * TU::BM, 0, a.map.M, a.r);
+        return;
+    }
+    if (b < a.nb_U + a.nb_Q) {
+        int idx = b - a.nb_U;
+        const int tq = (a.r + 63) / 64;
+        const int p = idx / (tq * tq);
+        idx -= p * tq * tq;
+        // pair p = (k, l), k < l
+        int l = 1;
+        while ((l + 1) * l / 2 <= p) ++l;
+        const int k = p - l * (l - 1) / 2;
+        LoadRowsTC<bf16_t, 64, 1> al;
+        al.src = a.Wu + (int64_t)k * a.r * a.d; al.ld = a.d; al.nrows = a.r;
+        LoadRowsTC<bf16_t, 64, 1> bl;
+        bl.src = a.WdT + (int64_t)l * a.r * a.d; bl.ld = a.d; bl.nrows = a.r;
+        EpiQ epi{a.QpN + (int64_t)p * a.r * a.r, a.QpT + (int64_t)p * a.r * a.r, a.r};
+        gemm_tile<bf16_t, T64>(smem, al, bl, epi, 0, a.d, (idx / tq) * 64, (idx % tq) * 64, a.r, a.r);
+        return;
+    }
+    {
+        // mean over the valid tokens of the last cached layer
+        int idx = b - a.nb_U - a.nb_Q;
+        const int jt = (a.d + 255) / 256;
+        const int s = idx / jt, j = (idx % jt) * 256 + threadIdx.x;
+        if (j >= a.d) return;
+        const int m0 = a.samp_start[s], len = a.samp_len[s];
+        float acc = 0.f;
+        for (int tkn = 0; tkn < len; ++tkn) {
+            const int m = m0 + tkn;
+            acc += to_f32(a.cache[a.map.rowoff[m] + (int64_t)(a.L - 1) * a.map.rowstride[m] + j]);
+        }
+        a.pb[(int64_t)s * a.d + j] = acc / (float)len;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launches 3 and 5: the r-wide chains over the layers, one 32-token tile per workgroup.
+// Wavefront w owns columns [32w, 32w+32) of the r-wide state; earlier layers' tiles stay in LDS.
+// ---------------------------------------------------------------------------
+struct ChainArgs {
+    int L, r, M;
+    const int32_t *tile_row0, *tile_rows, *tile_samp;
+    const float *params;
+    int64_t PL;
+    int d;
+    float *pre;          // [L][M][r]: holds U on entry of the forward chain, pre afterwards
+    const float *chat;   // [L][r]
+    const bf16_t *Q;     // forward: QpT ; backward: QpN
+    bf16_t *Hg;          // forward: H [M][L*r] ; backward: DP [M][L*r]
+    float *part;         // forward: HSpart ; backward: cspart   [tiles][L][r]
+    const float *ghat;   // backward: [B][L][r]
+};
+
+template <bool FWD, int NT> __global__ __launch_bounds__(64 * NT) void k_gchain(ChainArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char dyn_smem[];
+    bf16_t *Hs = reinterpret_cast<bf16_t *>(dyn_smem); // [L][32][r + pad]
+    constexpr int r = 32 * NT, RP = r + kChainPad, KQ = r / 16;
+    constexpr int GP = 4; // layer pairs whose operands are in flight together
+    const int L = a.L;
+    const int tile = blockIdx.x;
+    const int m0 = a.tile_row0[tile], nrows = a.tile_rows[tile], samp = a.tile_samp[tile];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, g = lane >> 5;
+    const int n = 32 * wave + i;
+    const int64_t Lr = (int64_t)L * r;
+    constexpr int64_t rr = (int64_t)r * r;
+    for (int step = 0; step < L; ++step) {
+        const int l = FWD ? step : L - 1 - step;
+        const float *pl = a.params + (int64_t)l * a.PL;
+        const float lam = pl[a.PL - 1];
+        // values the epilogue needs, requested before the contraction starts
+        float uval[16];
+        float cvec = 0.f, cdn = 0.f;
+        if (FWD) {
+            cvec = a.chat[(int64_t)l * r + n];
+            cdn = pl[(int64_t)a.d * r + n];
+        } else {
+            cvec = a.ghat[((int64_t)samp * L + l) * r + n];
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = 8 * (v >> 2) + 4 * g + (v & 3);
+            uval[v] = row < nrows ? a.pre[((int64_t)l * a.M + m0 + row) * r + n] : 0.f;
+        }
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        const int k0 = FWD ? 0 : l + 1, k1 = FWD ? l : L;
+        for (int kb = k0; kb < k1; kb += GP) {
+            bf16x8 bq[GP][KQ];
+#pragma unroll
+            for (int u = 0; u < GP; ++u) {
+                const int k = kb + u < k1 ? kb + u : k1 - 1;
+                const bf16_t *Qrow = a.Q + (FWD ? pair_index(k, l) : pair_index(l, k)) * rr + (int64_t)n * r;
+#pragma unroll
+                for (int q = 0; q < KQ; ++q) bq[u][q] = *reinterpret_cast<const bf16x8 *>(Qrow + 16 * q + 8 * g);
+            }
+#pragma unroll
+            for (int u = 0; u < GP; ++u) {
+                if (kb + u < k1) {
+                    const bf16_t *Hk = Hs + ((int64_t)(kb + u) * kChainRows + i) * RP;
+#pragma unroll
+                    for (int q = 0; q < KQ; ++q) {
+                        const bf16x8 av = *reinterpret_cast<const bf16x8 *>(Hk + 16 * q + 8 * g);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bq[u][q], acc, 0, 0, 0);
+                    }
+                }
+            }
+        }
+        float colsum = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = 8 * (v >> 2) + 4 * g + (v & 3);
+            const bool valid = row < nrows;
+            float keep = 0.f, out = 0.f;
+            if (FWD) {
+                const float pre = lam * uval[v] + (1.f - lam) * (acc[v] + cvec) + cdn;
+                if (valid) {
+                    a.pre[((int64_t)l * a.M + m0 + row) * r + n] = pre;
+                    out = gelu_f(pre);
+                }
+                keep = out;
+            } else {
+                if (valid) out = (cvec + acc[v]) * gelu_grad_f(uval[v]);
+                keep = (1.f - lam) * out;
+            }
+            if (valid) a.Hg[(int64_t)(m0 + row) * Lr + (int64_t)l * r + n] = static_cast<bf16_t>(out);
+            Hs[((int64_t)l * kChainRows + row) * RP + n] = static_cast<bf16_t>(keep);
+            colsum += out;
+        }
+        colsum += __shfl_xor(colsum, 32, 64);
+        if (g == 0) a.part[((int64_t)tile * L + l) * r + n] = colsum;
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launch 4: logits, loss, dz, and the small per-sample quantities of the backward pass
+// ---------------------------------------------------------------------------
+struct HeadArgs {
+    int B, L, d, r, C;
+    const float *params;
+    int64_t PL;
+    const float *pb, *cusum, *V, *HSpart;
+    const int32_t *samp_tile0, *samp_len, *labels;
+    float *logits_ws, *logits_out, *dz, *loss_out, *ghat, *HSm, *loss_part;
+    unsigned *counter; // one counter after the per-layer ones
+};
+
+// One workgroup per sample: logits, loss term, dz, ghat = (dz V^T)/len, and the token mean of h.
+__global__ __launch_bounds__(256) void k_ghead(HeadArgs a)
+{
+    __shared__ float red[4][kMaxClasses];
+    __shared__ float sdz[kMaxClasses];
+    __shared__ int is_last;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int s = blockIdx.x;
+    const int B = a.B, L = a.L, d = a.d, r = a.r, C = a.C;
+    const int64_t Lr = (int64_t)L * r;
+    const float *Wc = a.params + (int64_t)L * a.PL;
+    const float *cc = Wc + (int64_t)d * C;
+    const float *cusumL = a.cusum + (int64_t)L * d;
+    const int tl0 = a.samp_tile0[s], tl1 = a.samp_tile0[s + 1];
+    const float inv_len = 1.f / (float)a.samp_len[s];
+    float acc[kMaxClasses];
+#pragma unroll
+    for (int c = 0; c < kMaxClasses; ++c) acc[c] = 0.f;
+    for (int64_t kk = t; kk < Lr; kk += 256) {
+        float hs = 0.f;
+        for (int k = tl0; k < tl1; ++k) hs += a.HSpart[(int64_t)k * Lr + kk];
+        hs *= inv_len;
+        a.HSm[(int64_t)s * Lr + kk] = hs;
+        for (int c = 0; c < C; ++c) acc[c] += hs * a.V[kk * C + c];
+    }
+    for (int j = t; j < d; j += 256) {
+        const float p = a.pb[(int64_t)s * d + j] + cusumL[j];
+        for (int c = 0; c < C; ++c) acc[c] += p * Wc[(int64_t)j * C + c];
+    }
+    for (int c = 0; c < C; ++c) {
+        float v = acc[c];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+        if (lane == 0) red[wave][c] = v;
+    }
+    __syncthreads();
+    if (t == 0) {
+        float z[kMaxClasses];
+        float zmax = -INFINITY;
+        for (int c = 0; c < C; ++c) {
+            z[c] = red[0][c] + red[1][c] + red[2][c] + red[3][c] + cc[c];
+            zmax = fmaxf(zmax, z[c]);
+        }
+        float se = 0.f;
+        for (int c = 0; c < C; ++c) se += expf(z[c] - zmax);
+        const float lse = zmax + logf(se);
+        const int y = a.labels[s];
+        float lossv = NAN;
+        for (int c = 0; c < C; ++c) {
+            a.logits_ws[s * C + c] = z[c];
+            if (a.logits_out) a.logits_out[s * C + c] = z[c];
+            const float gz = (expf(z[c] - lse) - (c == y ? 1.f : 0.f)) / (float)B;
+            a.dz[s * C + c] = gz;
+            sdz[c] = gz;
+            if (c == y) lossv = lse - z[c];
+        }
+        a.loss_part[s] = lossv;
+        __threadfence();
+        const unsigned prev = atomicAdd(a.counter, 1u);
+        is_last = (prev == (unsigned)(B - 1));
+    }
+    __syncthreads();
+    for (int64_t kk = t; kk < Lr; kk += 256) {
+        float v = 0.f;
+        for (int c = 0; c < C; ++c) v += sdz[c] * a.V[kk * C + c];
+        a.ghat[(int64_t)s * Lr + kk] = v * inv_len;
+    }
+    if (is_last && t == 0) {
+        __threadfence();
+        float tot = 0.f;
+        for (int q = 0; q < B; ++q)
+            tot += __hip_atomic_load(&a.loss_part[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *a.loss_out = tot / (float)B;
+        *a.counter = 0u;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launch 6: contractions over the tokens.  E_l = b_l^T dpre_l ; GG = H^T DP (all layer pairs at once)
+// ---------------------------------------------------------------------------
+struct TokRedArgs {
+    const bf16_t *cache;
+    RowMap map;
+    int L, d, r;
+    int nb_E, e_tiles, se, sg, rows_per_se, rows_per_sg, tg;
+    const bf16_t *H, *DP; // [M][L*r]
+    float *Epart;         // [se][L][d][r]
+    float *GGpart;        // [sg][L*r][L*r]
+};
+
+template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
+{
+    using TE = Tile<4, 1, 1, NT, 1>;
+    constexpr int kLds = tile_lds_bytes<bf16_t, TE>() > tile_lds_bytes<bf16_t, T64>() ? tile_lds_bytes<bf16_t, TE>()
+                                                                                      : tile_lds_bytes<bf16_t, T64>();
+    __shared__ __attribute__((aligned(16))) char smem[kLds];
+    const int b = blockIdx.x;
+    const int M = a.map.M;
+    const int Lr = a.L * a.r;
+    if (b < a.nb_E) {
+        const int split = b % a.se;
+        const int it = (b / a.se) % a.e_tiles;
+        const int l = b / (a.se * a.e_tiles);
+        const int kbegin = split * a.rows_per_se;
+        const int kend = min(M, kbegin + a.rows_per_se);
+        LoadColsX<bf16_t, TE::BM, 1> al;
+        al.cache = a.cache; al.map = a.map; al.layer = l; al.s_prev = nullptr; al.ld_s = 0; al.lam = 1.f;
+        al.ncols = a.d; al.kend = kend;
+        LoadCols<bf16_t, TE::BN, 1, bf16_t, false> bl;
+        bl.src = a.DP + (int64_t)l * a.r; bl.ld = Lr; bl.ncols = a.r; bl.kend = kend;
+        EpiStoreF32 epi{a.Epart + ((int64_t)split * a.L + l) * a.d * a.r, a.r};
+        gemm_tile<bf16_t, TE>(smem, al, bl, epi, kbegin, kend, it * TE::BM, 0, a.d, a.r);
+        return;
+    }
+    {
+        int idx = b - a.nb_E;
+        const int split = idx % a.sg;
+        idx /= a.sg;
+        const int ti = idx / a.tg, tj = idx % a.tg;
+        // needed only where some row layer is below some column layer
+        const int kmin = (ti * 64) / a.r;
+        const int lmax = min(Lr - 1, tj * 64 + 63) / a.r;
+        if (kmin >= lmax) return;
+        const int kbegin = split * a.rows_per_sg;
+        const int kend = min(M, kbegin + a.rows_per_sg);
+        LoadCols<bf16_t, 64, 1, bf16_t, false> al;
+        al.src = a.H; al.ld = Lr; al.ncols = Lr; al.kend = kend;
+        LoadCols<bf16_t, 64, 1, bf16_t, false> bl;
+        bl.src = a.DP; bl.ld = Lr; bl.ncols = Lr; bl.kend = kend;
+        EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
+        gemm_tile<bf16_t, T64>(smem, al, bl, epi, kbegin, kend, ti * 64, tj * 64, Lr, Lr);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launch 7: ordered sums of the split partials; bf16 copies of GG for the last contractions
+// ---------------------------------------------------------------------------
+struct ReduceArgs {
+    int L, r, sg, ntiles, nb_GG, B, C;
+    const float *params;
+    int64_t PL;
+    const float *GGpart, *cspart, *HSm, *dz;
+    bf16_t *GGT, *GGsc;
+    float *cs, *Z, *dzsum;
+};
+
+__global__ __launch_bounds__(256) void k_greduce(ReduceArgs a)
+{
+    __shared__ float tile[32][33];
+    const int Lr = a.L * a.r;
+    const int b = blockIdx.x, t = threadIdx.x;
+    if (b < a.nb_GG) {
+        const int tg = Lr / 32;
+        const int tr = b / tg, tcx = b % tg;
+        // rows of layer k, columns of layer l: used only for k < l
+        if ((tr * 32) / a.r >= (tcx * 32 + 31) / a.r) return;
+        const int tx = t & 31, ty = t >> 5;
+        for (int y = ty; y < 32; y += 8) {
+            const int row = tr * 32 + y, col = tcx * 32 + tx;
+            float acc = 0.f;
+            for (int s = 0; s < a.sg; ++s) acc += a.GGpart[((int64_t)s * Lr + row) * Lr + col];
+            tile[y][tx] = acc;
+            const float lam = a.params[(int64_t)(col / a.r) * a.PL + a.PL - 1];
+            a.GGsc[(int64_t)row * Lr + col] = static_cast<bf16_t>((1.f - lam) * acc);
+        }
+        __syncthreads();
+        for (int y = ty; y < 32; y += 8)
+            a.GGT[(int64_t)(tcx * 32 + y) * Lr + tr * 32 + tx] = static_cast<bf16_t>(tile[tx][y]);
+        return;
+    }
+    const int idx = (b - a.nb_GG) * 256 + t;
+    if (idx < Lr) {
+        float acc = 0.f;
+        for (int k = 0; k < a.ntiles; ++k) acc += a.cspart[(int64_t)k * Lr + idx];
+        a.cs[idx] = acc;
+        // Z[kk][c] = sum_s mean_t(h)[s][kk] dz[s][c]
+        float zc[kMaxClasses];
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c) zc[c] = 0.f;
+        for (int s = 0; s < a.B; ++s) {
+            const float hs = a.HSm[(int64_t)s * Lr + idx];
+            for (int c = 0; c < a.C; ++c) zc[c] += hs * a.dz[s * a.C + c];
+        }
+        for (int c = 0; c < a.C; ++c) a.Z[(int64_t)idx * a.C + c] = zc[c];
+    }
+    if (b == a.nb_GG && t < a.C) {
+        float acc = 0.f;
+        for (int s = 0; s < a.B; ++s) acc += a.dz[s * a.C + t];
+        a.dzsum[t] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launch 8: the gradients
+// ---------------------------------------------------------------------------
+struct PostArgs {
+    int L, d, r, C, B, se;
+    int nb_F, nb_W, nb_vec;
+    const float *params;
+    int64_t PL;
+    const bf16_t *WuTs, *Wds, *GGT, *GGsc;
+    const float *Epart, *cusum, *cs, *Z, *dzsum, *dz, *pb;
+    float *grads;
+    float *dlam_part;
+    unsigned *counter;
+    int slots;
+};
+
+struct EpiF {
+    const float *Epart;
+    int se;
+    int64_t split_stride;
+    const float *cusum_l, *cs_l, *Wd_l;
+    float *gWd;
+    int r;
+    float lam;
+    float dlam;
+    __device__ void operator()(int row, int col, float v)
+    {
+        const int64_t o = (int64_t)row * r + col;
+        float E = 0.f;
+        for (int s = 0; s < se; ++s) E += Epart[(int64_t)s * split_stride + o];
+        const float F = v + cusum_l[row] * cs_l[col];
+        gWd[o] = lam * E + (1.f - lam) * F;
+        dlam += (E - F) * Wd_l[o];
+    }
+};
+
+struct EpiW {
+    const float *Z_l, *Wc;
+    float *gWu;
+    int d, C;
+    __device__ void operator()(int row, int col, float v) const
+    {
+        float acc = v;
+        for (int c = 0; c < C; ++c) acc += Z_l[(int64_t)row * C + c] * Wc[(int64_t)col * C + c];
+        gWu[(int64_t)row * d + col] = acc;
+    }
+};
+
+__global__ __launch_bounds__(256) void k_gpost(PostArgs a)
+{
+    constexpr int kVecLds = 256 * 4 + 256 * kMaxClasses * 4;
+    constexpr int kLds = tile_lds_bytes<bf16_t, T64>() > kVecLds ? tile_lds_bytes<bf16_t, T64>() : kVecLds;
+    __shared__ __attribute__((aligned(16))) char smem[kLds];
+    __shared__ float red[16];
+    __shared__ int is_last;
+    const int L = a.L, d = a.d, r = a.r, C = a.C;
+    const int Lr = L * r;
+    const int64_t dr = (int64_t)d * r;
+    const int b = blockIdx.x, t = threadIdx.x;
+    const int ti_d = (d + 63) / 64, ti_r = (r + 63) / 64;
+    if (b < a.nb_F) {
+        // F_l = sum_{k<l} W_up^{kT} G_{kl}   ([d] x [l*r] times [l*r] x [r])
+        const int l = b / (ti_d * ti_r);
+        const int slot = b % (ti_d * ti_r);
+        const int it = slot / ti_r, nt = slot % ti_r;
+        const float *pl = a.params + (int64_t)l * a.PL;
+        LoadRowsTC<bf16_t, 64, 1> al;
+        al.src = a.WuTs; al.ld = Lr; al.nrows = d;
+        LoadRowsTC<bf16_t, 64, 1> bl;
+        bl.src = a.GGT + (int64_t)l * r * Lr; bl.ld = Lr; bl.nrows = r;
+        EpiF epi{a.Epart + (int64_t)l * dr, a.se, (int64_t)L * dr, a.cusum + (int64_t)l * d, a.cs + (int64_t)l * r,
+                 pl, a.grads + (int64_t)l * a.PL, r, pl[a.PL - 1], 0.f};
+        gemm_tile<bf16_t, T64>(smem, al, bl, epi, 0, l * r, it * 64, nt * 64, d, r);
+        const float tot = block_sum(epi.dlam, red);
+        if (t == 0) {
+            a.dlam_part[(int64_t)l * a.slots + slot] = tot;
+            __threadfence();
+            const unsigned prev = atomicAdd(&a.counter[l], 1u);
+            is_last = (prev == (unsigned)(a.slots - 1));
+        }
+        __syncthreads();
+        if (is_last && t == 0) {
+            __threadfence();
+            float acc = 0.f;
+            for (int s = 0; s < a.slots; ++s)
+                acc += __hip_atomic_load(&a.dlam_part[(int64_t)l * a.slots + s], __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+            a.grads[(int64_t)l * a.PL + a.PL - 1] = acc;
+            a.counter[l] = 0u;
+        }
+        return;
+    }
+    if (b < a.nb_F + a.nb_W) {
+        // dW_up^l = Z_l W_cls^T + sum_{k>l} (1-lambda_k) G_{lk} W_down^{kT}
+        int idx = b - a.nb_F;
+        const int l = idx / (ti_d * ti_r);
+        idx %= ti_d * ti_r;
+        const int at = idx / ti_d, jt = idx % ti_d;
+        LoadRowsTC<bf16_t, 64, 1> al;
+        al.src = a.GGsc + (int64_t)l * r * Lr; al.ld = Lr; al.nrows = r;
+        LoadRowsTC<bf16_t, 64, 1> bl;
+        bl.src = a.Wds; bl.ld = Lr; bl.nrows = d;
+        EpiW epi{a.Z + (int64_t)l * r * C, a.params + (int64_t)L * a.PL,
+                 a.grads + (int64_t)l * a.PL + dr + r, d, C};
+        gemm_tile<bf16_t, T64>(smem, al, bl, epi, (l + 1) * r, Lr, at * 64, jt * 64, r, d);
+        return;
+    }
+    const int vb = b - a.nb_F - a.nb_W;
+    if (vb < a.nb_vec - 1) {
+        // thread (jj, k): hidden index j = vb * jpb + jj, layer k
+        float *tsh = reinterpret_cast<float *>(smem);          // [jpb][L]      (1-lambda_k) W_down^k[j] . cs_k
+        float *wsh = tsh + 256;                                // [jpb][L][C]   W_up^k[.][j] . Z_k
+        const int jpb = 256 / L;
+        const int jj = t / L, k = t % L;
+        const int j = vb * jpb + jj;
+        const bool act = jj < jpb && j < d;
+        const float *Wc = a.params + (int64_t)L * a.PL;
+        float wz[kMaxClasses];
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c) wz[c] = 0.f;
+        if (act) {
+            const bf16_t *wrow = a.Wds + (int64_t)j * Lr + (int64_t)k * r;
+            const bf16_t *urow = a.WuTs + (int64_t)j * Lr + (int64_t)k * r;
+            const float *csk = a.cs + (int64_t)k * r;
+            const float *Zk = a.Z + (int64_t)k * r * C;
+            float acc = 0.f;
+            for (int b0 = 0; b0 < r; b0 += 8) {
+                const Chunk<bf16_t> wv = *reinterpret_cast<const Chunk<bf16_t> *>(wrow + b0);
+                const Chunk<bf16_t> uv = *reinterpret_cast<const Chunk<bf16_t> *>(urow + b0);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    acc += csk[b0 + e] * to_f32(wv.e[e]);
+                    const float u = to_f32(uv.e[e]);
+                    for (int c = 0; c < C; ++c) wz[c] += u * Zk[(int64_t)(b0 + e) * C + c];
+                }
+            }
+            const float lam = a.params[(int64_t)k * a.PL + a.PL - 1];
+            tsh[jj * L + k] = (1.f - lam) * acc;
+            for (int c = 0; c < C; ++c) wsh[(jj * L + k) * C + c] = wz[c];
+        }
+        __syncthreads();
+        if (!act) return;
+        // dc_up^k[j] = (sum_s dz_s) W_cls^T [j] + sum_{k'>k} t[j][k']
+        float base = 0.f;
+        for (int c = 0; c < C; ++c) base += a.dzsum[c] * Wc[(int64_t)j * C + c];
+        for (int k2 = k + 1; k2 < L; ++k2) base += tsh[jj * L + k2];
+        a.grads[(int64_t)k * a.PL + 2 * dr + r + j] = base;
+        // dW_cls[j][c] = sum_s (pb[s][j] + cusum_L[j]) dz[s][c] + sum_k W_up^k[.][j] . Z_k[.][c]
+        for (int c = k; c < C; c += L) {
+            const float cl = a.cusum[(int64_t)L * d + j];
+            float acc = 0.f;
+            for (int s2 = 0; s2 < a.B; ++s2) acc += (a.pb[(int64_t)s2 * d + j] + cl) * a.dz[s2 * C + c];
+            for (int k2 = 0; k2 < L; ++k2) acc += wsh[(jj * L + k2) * C + c];
+            a.grads[(int64_t)L * a.PL + (int64_t)j * C + c] = acc;
+        }
+        return;
+    }
+    // dc_down^l = colsum(dpre_l) ; dc_cls = sum_s dz_s
+    for (int idx = t; idx < Lr; idx += 256) {
+        const int l = idx / r, nn = idx % r;
+        a.grads[(int64_t)l * a.PL + dr + nn] = a.cs[idx];
+    }
+    if (t < C) a.grads[(int64_t)L * a.PL + (int64_t)d * C + t] = a.dzsum[t];
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io)
+{
+    hipStream_t st = io.stream;
+    Profiler *prof = io.prof;
+    char *ws = io.ws;
+    const int L = D.L, d = D.d, r = D.r, C = D.C, M = meta.M, B = meta.B;
+    const int Lr = L * r;
+    int ntiles = 0;
+    for (int s = 0; s < B; ++s) ntiles += cdiv(meta.len[s], kChainRows);
+
+    int64_t *rowoff = (int64_t *)(ws + W.rowoff);
+    int32_t *rowstride = (int32_t *)(ws + W.rowstride);
+    int32_t *rowsamp = (int32_t *)(ws + W.rowsamp);
+    int32_t *samp_start = (int32_t *)(ws + W.samp_start);
+    int32_t *samp_len = (int32_t *)(ws + W.samp_len);
+    int32_t *tile_row0 = (int32_t *)(ws + W.g_tile_row0);
+    int32_t *tile_rows = (int32_t *)(ws + W.g_tile_rows);
+    int32_t *tile_samp = (int32_t *)(ws + W.g_tile_samp);
+    int32_t *samp_tile0 = (int32_t *)(ws + W.g_samp_tile0);
+    float *HSm = (float *)(ws + W.g_HSm), *loss_part = (float *)(ws + W.g_loss_part);
+    bf16_t *WdT = (bf16_t *)(ws + W.WdT), *Wu = (bf16_t *)(ws + W.Wu);
+    bf16_t *WuTs = (bf16_t *)(ws + W.g_WuTs), *Wds = (bf16_t *)(ws + W.g_Wds);
+    float *cusum = (float *)(ws + W.g_cusum), *chat = (float *)(ws + W.g_chat), *V = (float *)(ws + W.g_V);
+    bf16_t *QpN = (bf16_t *)(ws + W.g_QpN), *QpT = (bf16_t *)(ws + W.g_QpT);
+    float *pre = (float *)(ws + W.pre_all);
+    bf16_t *H = (bf16_t *)(ws + W.h_all), *DP = (bf16_t *)(ws + W.g_DP);
+    float *pb = (float *)(ws + W.pooled);
+    float *HSpart = (float *)(ws + W.g_HSpart), *cspart = (float *)(ws + W.g_cspart);
+    float *logits = (float *)(ws + W.logits), *dz = (float *)(ws + W.dz);
+    float *ghat = (float *)(ws + W.g_ghat), *Z = (float *)(ws + W.g_Z), *dzsum = (float *)(ws + W.g_dzsum);
+    float *cs = (float *)(ws + W.g_cs);
+    float *Epart = (float *)(ws + W.g_Epart), *GGpart = (float *)(ws + W.g_GGpart);
+    bf16_t *GGT = (bf16_t *)(ws + W.g_GGT), *GGsc = (bf16_t *)(ws + W.g_GGsc);
+    float *dlam_part = (float *)(ws + W.g_dlam_part);
+    unsigned *counter = (unsigned *)(ws + W.g_counter);
+    const RowMap map{rowoff, rowstride, M};
+    const bf16_t *cache = (const bf16_t *)io.cache;
+
+    {
+        PrepArgs a;
+        a.meta = meta; a.params = io.params; a.PL = D.PL; a.L = L; a.d = d; a.r = r; a.C = C;
+        a.nb_setup = cdiv(M, 256); a.nb_shadow = (d / 32) * (r / 32) * L * 2; a.nb_chat = L + 1;
+        a.rowoff = rowoff; a.rowstride = rowstride; a.rowsamp = rowsamp; a.samp_start = samp_start;
+        a.samp_len = samp_len; a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.tile_samp = tile_samp; a.samp_tile0 = samp_tile0;
+        a.WdT = WdT; a.Wu = Wu; a.WuTs = WuTs; a.Wds = Wds; a.cusum = cusum; a.chat = chat; a.V = V;
+        a.counter = counter;
+        const int nb = a.nb_setup + a.nb_shadow + a.nb_chat + cdiv(Lr, 4);
+        PAC_LAUNCH(prof, st, KC_G_PREP, k_gprep, dim3(nb), dim3(256), 0, st, a);
+    }
+    {
+        ProjArgs a;
+        a.cache = cache; a.map = map; a.L = L; a.d = d; a.r = r; a.B = B;
+        a.row_tiles = cdiv(M, 128); a.nb_U = a.row_tiles * L;
+        a.nb_Q = W.pairs * cdiv(r, 64) * cdiv(r, 64);
+        a.WdT = WdT; a.Wu = Wu; a.U = pre; a.QpN = QpN; a.QpT = QpT;
+        a.samp_start = samp_start; a.samp_len = samp_len; a.pb = pb;
+        const int nb = a.nb_U + a.nb_Q + B * cdiv(d, 256);
+        if (d % 64 == 0)
+            PAC_LAUNCH(prof, st, KC_G_PROJ, (k_gproj<NT, 2>), dim3(nb), dim3(256), 0, st, a);
+        else
+            PAC_LAUNCH(prof, st, KC_G_PROJ, (k_gproj<NT, 1>), dim3(nb), dim3(256), 0, st, a);
+    }
+    const size_t chain_lds = (size_t)L * kChainRows * (r + kChainPad) * 2;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<true, NT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<false, NT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    ChainArgs ca;
+    ca.L = L; ca.r = r; ca.M = M; ca.tile_row0 = tile_row0; ca.tile_rows = tile_rows; ca.tile_samp = tile_samp;
+    ca.params = io.params; ca.PL = D.PL; ca.d = d; ca.pre = pre; ca.chat = chat; ca.ghat = ghat;
+    {
+        ChainArgs a = ca;
+        a.Q = QpT; a.Hg = H; a.part = HSpart;
+        PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * NT), chain_lds, st, a);
+    }
+    {
+        HeadArgs a;
+        a.B = B; a.L = L; a.d = d; a.r = r; a.C = C; a.params = io.params; a.PL = D.PL;
+        a.pb = pb; a.cusum = cusum; a.V = V; a.HSpart = HSpart; a.samp_tile0 = samp_tile0; a.samp_len = samp_len;
+        a.labels = io.labels; a.logits_ws = logits; a.logits_out = io.logits_out; a.dz = dz;
+        a.loss_out = io.loss_out; a.ghat = ghat; a.HSm = HSm; a.loss_part = loss_part; a.counter = counter + L;
+        PAC_LAUNCH(prof, st, KC_G_HEAD, k_ghead, dim3(B), dim3(256), 0, st, a);
+    }
+    if (!io.grads) return hipGetLastError();
+    {
+        ChainArgs a = ca;
+        a.Q = QpN; a.Hg = DP; a.part = cspart;
+        PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, (k_gchain<false, NT>), dim3(ntiles), dim3(64 * NT), chain_lds, st, a);
+    }
+    {
+        TokRedArgs a;
+        a.cache = cache; a.map = map; a.L = L; a.d = d; a.r = r;
+        a.e_tiles = cdiv(d, 128);
+        a.rows_per_se = cdiv(cdiv(M, W.se), 32) * 32;
+        a.se = cdiv(M, a.rows_per_se);
+        a.rows_per_sg = cdiv(cdiv(M, W.sg), 32) * 32;
+        a.sg = cdiv(M, a.rows_per_sg);
+        a.tg = cdiv(Lr, 64);
+        a.nb_E = L * a.e_tiles * a.se;
+        a.H = H; a.DP = DP; a.Epart = Epart; a.GGpart = GGpart;
+        const int nb = a.nb_E + (L > 1 ? a.tg * a.tg * a.sg : 0);
+        PAC_LAUNCH(prof, st, KC_G_TOKRED, (k_gtokred<NT>), dim3(nb), dim3(256), 0, st, a);
+        ReduceArgs ra;
+        ra.L = L; ra.r = r; ra.sg = a.sg; ra.ntiles = ntiles; ra.nb_GG = L > 1 ? (Lr / 32) * (Lr / 32) : 0;
+        ra.params = io.params; ra.PL = D.PL; ra.GGpart = GGpart; ra.cspart = cspart; ra.GGT = GGT; ra.GGsc = GGsc;
+        ra.cs = cs; ra.B = B; ra.C = C; ra.HSm = HSm; ra.dz = dz; ra.Z = Z; ra.dzsum = dzsum;
+        PAC_LAUNCH(prof, st, KC_G_REDUCE, k_greduce, dim3(ra.nb_GG + cdiv(Lr, 256)), dim3(256), 0, st, ra);
+        PostArgs pa;
+        pa.L = L; pa.d = d; pa.r = r; pa.C = C; pa.B = B; pa.se = a.se;
+        pa.nb_F = L * cdiv(d, 64) * cdiv(r, 64); pa.nb_W = pa.nb_F; pa.nb_vec = cdiv(d, 256 / L) + 1;
+        pa.params = io.params; pa.PL = D.PL; pa.WuTs = WuTs; pa.Wds = Wds; pa.GGT = GGT; pa.GGsc = GGsc;
+        pa.Epart = Epart; pa.cusum = cusum; pa.cs = cs; pa.Z = Z; pa.dzsum = dzsum; pa.dz = dz; pa.pb = pb;
+        pa.grads = io.grads; pa.dlam_part = dlam_part; pa.counter = counter;
+        pa.slots = cdiv(d, 64) * cdiv(r, 64);
+        PAC_LAUNCH(prof, st, KC_G_POST, k_gpost, dim3(pa.nb_F + pa.nb_W + pa.nb_vec), dim3(256), 0, st, pa);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gram_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io)
+{
+    switch (D.r / 32) {
+    case 1: return run_gram<1>(D, W, meta, io);
+    case 2: return run_gram<2>(D, W, meta, io);
+    case 3: return run_gram<3>(D, W, meta, io);
+    case 4: return run_gram<4>(D, W, meta, io);
+    }
+    return hipErrorInvalidValue;
+}
+
+} // namespace pac

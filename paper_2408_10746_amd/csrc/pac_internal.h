@@ -31,12 +31,31 @@ struct WsLayout {
     int64_t total;
     int32_t splits;     // split count of the token reductions
     int32_t dlam_slots; // workgroups of the dx kernel at the largest batch
+
+    // ---- regions of the Gram-matrix path (bf16, small adapter widths) ----
+    int32_t use_gram;   // 1: the step runs on the Gram-matrix path
+    int32_t max_tiles;  // 32-row token tiles at the largest batch
+    int32_t pairs;      // L (L - 1) / 2 layer pairs k < l
+    int32_t se, sg;     // token splits of the E and Gram contractions
+    int64_t g_tile_row0, g_tile_rows, g_tile_samp;
+    int64_t g_WuTs, g_Wds;          // bf16 [d][L*r] stacked projection copies
+    int64_t g_cusum, g_chat, g_V;   // f32 [L+1][d], [L][r], [L*r][C]
+    int64_t g_QpN, g_QpT;           // bf16 [pairs][r][r], both orientations
+    int64_t g_DP;                   // bf16 [Mmax][L*r]
+    int64_t g_HSpart, g_cspart;     // f32 [max_tiles][L][r]
+    int64_t g_ghat, g_Z, g_dzsum, g_cs;
+    int64_t g_Epart, g_GGpart;      // f32 [se][L][d*r], [sg][L*r][L*r]
+    int64_t g_GGT, g_GGsc;          // bf16 [L*r][L*r]
+    int64_t g_dlam_part, g_counter; // f32 [L][slots], u32 [L + 1]
+    int64_t g_samp_tile0, g_HSm, g_loss_part;
+    int32_t g_dlam_slots;
 };
 
 struct Dims {
     int32_t L, d, n_max, r, C, B_max;
     int64_t N;
     int32_t cache_dtype; // 0 bf16, 1 f32
+    int32_t flags;       // PAC_FLAG_* of the configuration
     int64_t PL;          // per-layer parameter block
     int64_t P;
     int64_t Mmax;
@@ -45,7 +64,9 @@ struct Dims {
 // Kernel classes for per-kernel timing.
 enum KClass {
     KC_CACHE_FILL = 0, KC_SETUP, KC_SHADOWS, KC_FWD_DOWN, KC_FWD_UP, KC_POOL, KC_HEAD, KC_HEAD_BWD,
-    KC_BWD_DPRE, KC_BWD_WGRAD, KC_BWD_DX, KC_REDUCE, KC_ADAMW, KC_COUNT
+    KC_BWD_DPRE, KC_BWD_WGRAD, KC_BWD_DX, KC_REDUCE, KC_ADAMW,
+    KC_G_PREP, KC_G_PROJ, KC_G_CHAIN_FWD, KC_G_HEAD, KC_G_CHAIN_BWD, KC_G_TOKRED, KC_G_REDUCE, KC_G_POST,
+    KC_COUNT
 };
 
 // Optional recorder: a pair of events around each launch.
@@ -88,6 +109,9 @@ void plan_workspace(const Dims &D, WsLayout &W);
 hipError_t launch_cache_fill(const Dims &D, void *cache, const void *acts, int acts_dtype,
                              const BatchMeta &meta, hipStream_t st, Profiler *prof);
 hipError_t launch_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io);
+bool gram_path_fits(const Dims &D);
+void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &offset);
+hipError_t launch_gram_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io);
 hipError_t launch_adamw(const Dims &D, float *p, float *m, float *v, const float *g,
                         const AdamArgs &a, hipStream_t st, Profiler *prof);
 

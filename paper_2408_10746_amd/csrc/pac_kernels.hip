@@ -13,6 +13,8 @@
 
 namespace pac {
 
+using T64 = Tile<2, 2, 1, 1, 1>; // 64 x 64 workgroup tile, 64 bytes of K per step
+
 // launch, optionally bracketed by timing events of its kernel class
 #define PAC_LAUNCH(prof, st, cls, ...)                         \
     do {                                                       \
@@ -68,8 +70,11 @@ void plan_workspace(const Dims &D, WsLayout &W)
     W.splits = choose_splits(D);
     W.part = take((int64_t)W.splits * D.PL * 4);
     W.dlam_slots = cdiv(D.Mmax, 64) * cdiv(D.d, 64);
+    if (W.dlam_slots < D.B_max * D.r) W.dlam_slots = D.B_max * D.r; // also holds the top layer's dh [B][r]
     W.dlam_part = take((int64_t)W.dlam_slots * 4);
     W.grads = take(D.P * 4);
+    W.use_gram = 0;
+    if (gram_path_fits(D)) plan_gram_workspace(D, W, o);
     W.total = o;
 }
 
@@ -247,12 +252,13 @@ template <typename TC> struct EpiFwdDown {
 
 template <typename TC> __global__ __launch_bounds__(256) void k_fwd_down(FwdDownArgs<TC> a)
 {
-    LoadRowsX<TC, 1> al;
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
+    LoadRowsX<TC, 64, 1> al;
     al.cache = a.cache; al.map = a.map; al.layer = a.layer; al.s_prev = a.s_prev; al.ld_s = a.d; al.lam = *a.lam;
-    LoadRowsTC<TC, 1> bl;
+    LoadRowsTC<TC, 64, 1> bl;
     bl.src = a.WdT; bl.ld = a.d; bl.nrows = a.r;
     EpiFwdDown<TC> epi{a.c_down, a.pre, a.h, a.r};
-    gemm_tile<TC, 1, 1>(al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.r);
+    gemm_tile<TC, T64>(smem, al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.r);
 }
 
 template <typename TC> struct FwdUpArgs {
@@ -278,12 +284,13 @@ struct EpiFwdUp {
 
 template <typename TC> __global__ __launch_bounds__(256) void k_fwd_up(FwdUpArgs<TC> a)
 {
-    LoadRowsTC<TC, 1> al;
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
+    LoadRowsTC<TC, 64, 1> al;
     al.src = a.h; al.ld = a.r; al.nrows = a.M;
-    LoadRowsTC<TC, 1> bl;
+    LoadRowsTC<TC, 64, 1> bl;
     bl.src = a.WuT; bl.ld = a.r; bl.nrows = a.d;
     EpiFwdUp epi{a.c_up, a.s_prev, a.s_out, a.d};
-    gemm_tile<TC, 1, 1>(al, bl, epi, 0, a.r, blockIdx.x * 64, blockIdx.y * 64, a.M, a.d);
+    gemm_tile<TC, T64>(smem, al, bl, epi, 0, a.r, blockIdx.x * 64, blockIdx.y * 64, a.M, a.d);
 }
 
 // pooled[s][j] = mean_t ( b_L[t][j] + s_L[t][j] )
@@ -411,12 +418,46 @@ template <typename TC> struct EpiDpre {
 
 template <typename TC> __global__ __launch_bounds__(256) void k_bwd_dpre(BwdDpreArgs<TC> a)
 {
-    LoadRowsF32<TC, 1> al;
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
+    LoadRowsF32<TC, 64, 1> al;
     al.src = a.ds; al.ld = a.d; al.nrows = a.M;
-    LoadRowsTC<TC, 1> bl;
+    LoadRowsTC<TC, 64, 1> bl;
     bl.src = a.Wu; bl.ld = a.d; bl.nrows = a.r;
     EpiDpre<TC> epi{a.pre, a.dpre, a.r};
-    gemm_tile<TC, 1, 1>(al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.M, a.r);
+    gemm_tile<TC, T64>(smem, al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.M, a.r);
+}
+
+// Top layer: ds_L is the same vector for every token of a sample (dp_s / len_s), so
+// dh_L = ds_L W_up^{LT} is computed once per sample in fp32 instead of through the matrix cores
+// (rounding that vector to bf16 would put the same error on every token of the sample).
+__global__ __launch_bounds__(256) void k_dh_top(const float *__restrict__ dz, const float *__restrict__ Wcls,
+                                                const float *__restrict__ Wu /* [r][d] fp32 */,
+                                                const int32_t *__restrict__ samp_len, int B, int d, int r, int C,
+                                                float *__restrict__ dh /* [B][r] */)
+{
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= B * r) return;
+    const int s = row / r, k = row % r;
+    float acc = 0.f;
+    for (int j = lane; j < d; j += 64) {
+        float dp = 0.f;
+        for (int c = 0; c < C; ++c) dp += dz[s * C + c] * Wcls[(int64_t)j * C + c];
+        acc += dp * Wu[(int64_t)k * d + j];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
+    if (lane == 0) dh[row] = acc / (float)samp_len[s];
+}
+
+template <typename TC>
+__global__ __launch_bounds__(256) void k_dpre_top(const float *__restrict__ dh, const float *__restrict__ pre,
+                                                  const int32_t *__restrict__ rowsamp, int M, int r,
+                                                  TC *__restrict__ dpre)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)M * r) return;
+    const int m = (int)(idx / r), k = (int)(idx % r);
+    dpre[idx] = to_tc(dh[rowsamp[m] * r + k] * gelu_grad_f(pre[idx]), TC());
 }
 
 // Token reductions.  blockIdx.z = 0: dW_up[r][d] = h^T ds, dc_up = colsum(ds);
@@ -447,7 +488,7 @@ __device__ __forceinline__ void write_colsums(BL &bl, float *dst, int ncols, int
 {
     // every thread owns the columns of chunk (t % CPR); sum over the threads that share them
     using T = Traits<TC>;
-    using G = ColsGeom<TC, 1>;
+    using G = ColsGeom<TC, 64, 1>;
     __shared__ float red[kThreads * T::CE];
     float mine[T::CE];
     for (int e = 0; e < T::CE; ++e) {
@@ -467,6 +508,7 @@ __device__ __forceinline__ void write_colsums(BL &bl, float *dst, int ncols, int
 
 template <typename TC> __global__ __launch_bounds__(256) void k_bwd_wgrad(BwdWgradArgs<TC> a)
 {
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
     const int M = a.map.M;
     const int kbegin = blockIdx.y * a.rows_per_split;
     const int kend = min(M, kbegin + a.rows_per_split);
@@ -475,23 +517,23 @@ template <typename TC> __global__ __launch_bounds__(256) void k_bwd_wgrad(BwdWgr
     if (blockIdx.z == 0) {
         const int tj = a.d / 64 + (a.d % 64 ? 1 : 0);
         const int ti = blockIdx.x / tj, tjx = blockIdx.x % tj;
-        LoadCols<TC, 1, TC, false> al;
+        LoadCols<TC, 64, 1, TC, false> al;
         al.src = a.h; al.ld = a.r; al.ncols = a.r; al.kend = kend;
-        LoadCols<TC, 1, float, true> bl;
+        LoadCols<TC, 64, 1, float, true> bl;
         bl.src = a.ds; bl.ld = a.d; bl.ncols = a.d; bl.kend = kend;
         EpiStore epi{part + dr + a.r, a.d};
-        gemm_tile<TC, 1, 1>(al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.r, a.d);
+        gemm_tile<TC, T64>(smem, al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.r, a.d);
         if (ti == 0) write_colsums<TC>(bl, part + 2 * dr + a.r, a.d, tjx * 64);
     } else {
         const int tj = a.r / 64 + (a.r % 64 ? 1 : 0);
         const int ti = blockIdx.x / tj, tjx = blockIdx.x % tj;
-        LoadColsX<TC, 1> al;
+        LoadColsX<TC, 64, 1> al;
         al.cache = a.cache; al.map = a.map; al.layer = a.layer; al.s_prev = a.s_prev; al.ld_s = a.d;
         al.lam = *a.lam; al.ncols = a.d; al.kend = kend;
-        LoadCols<TC, 1, TC, true> bl;
+        LoadCols<TC, 64, 1, TC, true> bl;
         bl.src = a.dpre; bl.ld = a.r; bl.ncols = a.r; bl.kend = kend;
         EpiStore epi{part, a.r};
-        gemm_tile<TC, 1, 1>(al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.d, a.r);
+        gemm_tile<TC, T64>(smem, al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.d, a.r);
         if (ti == 0) write_colsums<TC>(bl, part + dr, a.r, tjx * 64);
     }
 }
@@ -529,13 +571,14 @@ template <typename TC> struct EpiDx {
 
 template <typename TC> __global__ __launch_bounds__(256) void k_bwd_dx(BwdDxArgs<TC> a)
 {
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
     __shared__ float red[4];
-    LoadRowsTC<TC, 1> al;
+    LoadRowsTC<TC, 64, 1> al;
     al.src = a.dpre; al.ld = a.r; al.nrows = a.map.M;
-    LoadRowsTC<TC, 1> bl;
+    LoadRowsTC<TC, 64, 1> bl;
     bl.src = a.Wd; bl.ld = a.r; bl.nrows = a.d;
     EpiDx<TC> epi{a.cache, a.map, a.layer, a.d, a.s_prev, *a.lam, a.ds, 0.f};
-    gemm_tile<TC, 1, 1>(al, bl, epi, 0, a.r, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.d);
+    gemm_tile<TC, T64>(smem, al, bl, epi, 0, a.r, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.d);
     const float tot = block_sum(epi.dlam, red);
     if (threadIdx.x == 0) a.dlam_part[blockIdx.y * gridDim.x + blockIdx.x] = tot;
 }
@@ -658,7 +701,7 @@ static hipError_t run_loss_grad(const Dims &D, const WsLayout &W, const BatchMet
                        meta.B, M, d, D.C, rowsamp, samp_len, grads + (int64_t)L * PL,
                        grads + (int64_t)L * PL + (int64_t)d * D.C, ds, rows_per_block);
 
-    const int kstep = Traits<TC>::BK;
+    const int kstep = Stage<TC, 1>::BK;
     int splits = W.splits;
     int rows_per_split = cdiv(cdiv(M, splits), kstep) * kstep;
     splits = cdiv(M, rows_per_split);
@@ -666,8 +709,16 @@ static hipError_t run_loss_grad(const Dims &D, const WsLayout &W, const BatchMet
     for (int l = L - 1; l >= 0; --l) {
         const float *pl = params + (int64_t)l * PL;
         const float *s_prev = l == 0 ? nullptr : s_all + (int64_t)(l - 1) * Md;
-        BwdDpreArgs<TC> ba{ds, Wu + (int64_t)l * dr, pre_all + (int64_t)l * Mr, dpre, M, d, r};
-        PAC_LAUNCH(prof, st, KC_BWD_DPRE, (k_bwd_dpre<TC>), g_rows_r, dim3(256), 0, st, ba);
+        if (l == L - 1) {
+            float *dh_top = dlam_part; // B*r floats; the dx kernel overwrites it afterwards
+            PAC_LAUNCH(prof, st, KC_BWD_DPRE, k_dh_top, dim3(cdiv((int64_t)meta.B * r, 4)), dim3(256), 0, st, dz, Wcls,
+                       pl + dr + r, samp_len, meta.B, d, r, D.C, dh_top);
+            PAC_LAUNCH(prof, st, KC_BWD_DPRE, (k_dpre_top<TC>), dim3(cdiv(Mr, 256)), dim3(256), 0, st, dh_top,
+                       pre_all + (int64_t)l * Mr, rowsamp, M, r, dpre);
+        } else {
+            BwdDpreArgs<TC> ba{ds, Wu + (int64_t)l * dr, pre_all + (int64_t)l * Mr, dpre, M, d, r};
+            PAC_LAUNCH(prof, st, KC_BWD_DPRE, (k_bwd_dpre<TC>), g_rows_r, dim3(256), 0, st, ba);
+        }
         BwdWgradArgs<TC> wa{cache, map, l, d, r, s_prev, pl + PL - 1, h_all + (int64_t)l * Mr, ds, dpre, part, PL,
                             rows_per_split};
         PAC_LAUNCH(prof, st, KC_BWD_WGRAD, (k_bwd_wgrad<TC>), dim3(wg_tiles, splits, 2), dim3(256), 0, st, wa);
@@ -681,6 +732,7 @@ static hipError_t run_loss_grad(const Dims &D, const WsLayout &W, const BatchMet
 
 hipError_t launch_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io)
 {
+    if (W.use_gram) return launch_gram_loss_grad(D, W, meta, io);
     if (D.cache_dtype == 0) return run_loss_grad<bf16_t>(D, W, meta, io);
     return run_loss_grad<float>(D, W, meta, io);
 }

@@ -19,13 +19,14 @@ def _stream_handle() -> int:
 class Session:
     """Owns the device buffers of one configuration (cache, workspace, params, optimizer state)."""
 
-    def __init__(self, w: Workload, cache_samples: int | None = None, lens=None, device: str = "cuda:0"):
+    def __init__(self, w: Workload, cache_samples: int | None = None, lens=None, device: str = "cuda:0",
+                 flags: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("libpac needs a GPU: no HIP device is visible")
         self.w = w
         self.dev = torch.device(device)
         self.dtype = pb.PAC_BF16 if w.cache_dtype == "bf16" else pb.PAC_F32
-        self.ctx = pb.pac_create(w.L, w.d, w.n_max, w.r, w.C, w.B, w.N, self.dtype)
+        self.ctx = pb.pac_create(w.L, w.d, w.n_max, w.r, w.C, w.B, w.N, self.dtype, flags)
         self.P = pb.pac_param_count(self.ctx)
         n = w.N if cache_samples is None else cache_samples
         self.cache_bytes = pb.pac_cache_bytes(self.ctx, lens, n)

@@ -83,9 +83,9 @@ def check_against_oracle(w, sess, ids, acts, lens, labels, params, tol, what="")
     return ref, loss, grads, worst
 
 
-def make_session(w, lens=None):
+def make_session(w, lens=None, flags=0):
     from paper_2408_10746_amd.runtime import Session
-    return Session(w, lens=lens)
+    return Session(w, lens=lens, flags=flags)
 
 
 # ---------------------------------------------------------------------------
@@ -164,6 +164,37 @@ def test_loss_grad_small(w, state):
             for nm in (f"W_down{l}", f"c_down{l}", f"lambda{l}"):
                 assert np.all(ref["grads"][sl[nm]] == 0.0)
                 assert np.all(grads[sl[nm]] == 0.0), nm
+
+
+# The bf16 configurations above run on the Gram-matrix formulation where it applies; the shapes
+# below exercise its tile variants (adapter width 32..128, one layer, ragged 32-token tiles,
+# hidden sizes that are not multiples of 64), and the per-layer kernels are forced for the same inputs.
+GRAM = [
+    Workload("g1", L=1, d=96, n_max=45, B=3, r=32, C=2, N=3, cache_dtype="bf16", len_lo=1),
+    Workload("g2", L=5, d=128, n_max=70, B=4, r=64, C=3, N=4, cache_dtype="bf16", len_lo=20),
+    Workload("g3", L=3, d=224, n_max=33, B=6, r=128, C=5, N=6, cache_dtype="bf16", len_lo=30),
+    Workload("g4", L=6, d=192, n_max=64, B=2, r=96, C=16, N=2, cache_dtype="bf16"),
+]
+
+
+@pytest.mark.parametrize("w", GRAM, ids=[w.name for w in GRAM])
+@pytest.mark.parametrize("flags", [0, 1], ids=["gram", "per_layer"])
+def test_bf16_paths(w, flags):
+    lens = inputs.lengths(w)
+    ids = np.arange(w.B)
+    acts = inputs.batch_acts(w, ids)
+    labels = inputs.labels(w)[ids]
+    sess = make_session(w, lens=lens, flags=flags)
+    sess.cache_fill(ids, acts, lens)
+    check_against_oracle(w, sess, ids, acts, lens, labels, inputs.random_params(w, up_scale=0.5), TOL["bf16"],
+                         what=f"{w.name}/flags{flags}")
+    ref, loss, grads, _ = check_against_oracle(w, sess, ids, acts, lens, labels, inputs.init_params(w), TOL["bf16"],
+                                               what=f"{w.name}/flags{flags}/init")
+    dims = orc.Dims(w.L, w.d, w.r, w.C)
+    sl = orc.param_slices(dims)
+    for l in range(w.L):
+        for nm in (f"W_down{l}", f"c_down{l}", f"lambda{l}"):
+            assert np.all(grads[sl[nm]] == 0.0), nm
 
 
 def test_outlier_channels_bf16():
