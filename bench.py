@@ -65,6 +65,7 @@ def main():
     ap.add_argument("--workload", default="t5base")
     ap.add_argument("--samples", type=int, default=0, help="resident samples (0 = the workload's N)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--flags", type=int, default=0, help="pac_config flags (1 per-layer kernels, 2 split launches)")
     ap.add_argument("--cpu-samples", type=int, default=8)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -84,7 +85,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     lens_all = inputs.lengths(w)[:N]
-    sess = Session(w, cache_samples=N, lens=lens_all if w.len_lo else None)
+    sess = Session(w, cache_samples=N, lens=lens_all if w.len_lo else None, flags=args.flags)
 
     # ---- fill the cache on the device: N(0,1), per-token layer norm, optional outlier channels
     gen = torch.Generator(device=dev)
@@ -145,7 +146,7 @@ def main():
     prof = pb.pac_profile_end(sess.ctx)
     M = int(lens_all[plan[0]].sum())
     models = kernel_models(w, M)
-    dom = max(prof, key=lambda c: prof[c][0])
+    dom = max((c for c in prof if c in models), key=lambda c: prof[c][0])
     dom_ms, dom_n = prof[dom]
     avg_s = dom_ms * 1e-3 / dom_n
     abytes, aflops = models[dom]

@@ -88,6 +88,9 @@ typedef struct {
 /* Run the step with the per-layer kernels even where the faster Gram-matrix
  * formulation applies (same results up to rounding; kept for cross-checking). */
 #define PAC_FLAG_PER_LAYER 1
+/* Measurement aid: launch every part of the fused multi-part launches on its own, so that
+ * pac_profile_end reports one class per part (slower; results unchanged). */
+#define PAC_FLAG_SPLIT_LAUNCH 2
 
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay;

@@ -20,6 +20,7 @@ PAC_ERR_NULL, PAC_ERR_SHAPE, PAC_ERR_RANGE, PAC_ERR_ALIGN = 1, 2, 3, 4
 PAC_ERR_UNSUPPORTED, PAC_ERR_WORKSPACE, PAC_ERR_DEVICE, PAC_ERR_STATE = 5, 6, 7, 8
 PAC_BF16, PAC_F32 = 0, 1
 PAC_FLAG_PER_LAYER = 1
+PAC_FLAG_SPLIT_LAUNCH = 2
 
 EXPORTS = [
     "pac_create", "pac_destroy", "pac_status_str", "pac_param_count", "pac_param_offsets",
@@ -180,7 +181,7 @@ def pac_profile_begin(ctx) -> None:
 
 def pac_profile_end(ctx):
     """Returns {class name: (total ms, launches)} for the classes that ran."""
-    n = 32
+    n = 128
     ms = (C.c_float * n)()
     launches = (C.c_int32 * n)()
     k = C.c_int32(0)

@@ -23,7 +23,9 @@ struct pac_ctx {
 static const char *const kClassNames[KC_COUNT] = {
     "cache_fill", "setup", "shadows", "fwd_down", "fwd_up", "pool", "head", "head_bwd",
     "bwd_dpre", "bwd_wgrad", "bwd_dx", "reduce", "adamw",
-    "g_prep", "g_proj", "g_chain_fwd", "g_head", "g_chain_bwd", "g_tokred", "g_reduce", "g_post"};
+    "g_prep", "g_proj", "g_chain_fwd", "g_head", "g_chain_bwd", "g_tokred", "g_reduce", "g_post", "g_finish",
+    "g_prep.setup", "g_prep.copy", "g_prep.chat", "g_prep.V", "g_proj.U", "g_proj.Q", "g_proj.pb",
+    "g_tokred.E", "g_tokred.G", "g_reduce.GG", "g_reduce.E", "g_reduce.vec", "g_post.F", "g_post.W", "g_post.vec"};
 
 static void drop_events(Profiler &p)
 {
@@ -59,7 +61,7 @@ pac_status pac_create(const pac_config *cfg, pac_ctx **out)
     if (cfg->L < 1 || cfg->d < 1 || cfg->n_max < 1 || cfg->r < 1 || cfg->C < 1 || cfg->B_max < 1 || cfg->N < 1)
         return PAC_ERR_SHAPE;
     if (cfg->cache_dtype != PAC_BF16 && cfg->cache_dtype != PAC_F32) return PAC_ERR_SHAPE;
-    if (cfg->flags & ~PAC_FLAG_PER_LAYER) return PAC_ERR_SHAPE;
+    if (cfg->flags & ~(PAC_FLAG_PER_LAYER | PAC_FLAG_SPLIT_LAUNCH)) return PAC_ERR_SHAPE;
     if (cfg->d % 32 || cfg->r % 32) return PAC_ERR_UNSUPPORTED;
     if (cfg->C > kMaxClasses || cfg->B_max > kMaxBatch) return PAC_ERR_UNSUPPORTED;
     if ((int64_t)cfg->B_max * cfg->n_max > (int64_t)1 << 24) return PAC_ERR_UNSUPPORTED;

@@ -74,7 +74,9 @@ template <typename TC, int ROWS, int KU> struct LoadRowsTC {
     const TC *src;
     int64_t ld;
     int nrows;
+    int kmin = 0, klim = 0x7fffffff; // K outside [kmin, klim) reads as zero (whole 16-byte chunks)
     const TC *rp[G::NCH];
+    int kc[G::NCH];
     uint4 reg[G::NCH];
     __device__ void init(int row0)
     {
@@ -83,14 +85,18 @@ template <typename TC, int ROWS, int KU> struct LoadRowsTC {
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
             const int row = row0 + c / S::CPK;
-            rp[u] = (c < G::TOTAL && row < nrows) ? src + (int64_t)row * ld + (c % S::CPK) * S::CE : nullptr;
+            kc[u] = (c % S::CPK) * S::CE;
+            rp[u] = (c < G::TOTAL && row < nrows) ? src + (int64_t)row * ld + kc[u] : nullptr;
         }
     }
     __device__ void fetch(int k0)
     {
 #pragma unroll
-        for (int u = 0; u < G::NCH; ++u)
-            reg[u] = rp[u] ? *reinterpret_cast<const uint4 *>(rp[u] + k0) : make_uint4(0, 0, 0, 0);
+        for (int u = 0; u < G::NCH; ++u) {
+            const int k = k0 + kc[u];
+            reg[u] = (rp[u] && k >= kmin && k < klim) ? *reinterpret_cast<const uint4 *>(rp[u] + k0)
+                                                      : make_uint4(0, 0, 0, 0);
+        }
     }
     __device__ void store(TC *lds)
     {
@@ -232,36 +238,85 @@ template <typename TC, int ROWS, int KU> struct LoadRowsX {
 // ---------------------------------------------------------------------------
 // Transposed loaders for contractions over the token index:
 // operand[i][k] = src[k][i]  (i contiguous in memory, k = token row).
-// A step stages BK token rows.  Chunk c = t + 256u covers token row
-// c / CPR and the 16-byte i-chunk c % CPR, CPR = ROWS / CE; the chunk is
-// scattered into the K-contiguous LDS layout element by element.
-// Rows k >= kend are zero.  Optionally keeps per-thread column sums.
+// A thread owns CE x CE blocks (CE token rows x CE consecutive i): it loads CE
+// 16-byte chunks, transposes them in registers and writes CE 16-byte chunks
+// into the K-contiguous LDS layout.  Block c = t + 256u covers i-block c % IB
+// and token block c / IB.  Token rows >= kend and columns >= ncols are zero.
+// Optionally keeps per-thread column sums (fp32, before rounding).
 // ---------------------------------------------------------------------------
 template <typename TC, int ROWS, int KU> struct ColsGeom {
     using S = Stage<TC, KU>;
-    static constexpr int CPR = ROWS / S::CE;             // chunks per token row
-    static constexpr int TOTAL = S::BK * CPR;
-    static constexpr int NCH = (TOTAL + kThreads - 1) / kThreads; // chunks per thread
-    static_assert(ROWS % S::CE == 0, "tile rows must be whole chunks");
+    static constexpr int CE = S::CE;
+    static constexpr int IB = ROWS / CE;      // i-blocks per tile
+    static constexpr int KB = S::BK / CE;     // token blocks per step
+    static constexpr int TOTAL = IB * KB;
+    static constexpr int NCH = (TOTAL + kThreads - 1) / kThreads; // blocks per thread
+    static_assert(ROWS % CE == 0, "tile rows must be whole chunks");
+};
+
+__device__ __forceinline__ void transpose_block(const Chunk<bf16_t> (&in)[8], Chunk<bf16_t> (&out)[8])
+{
+    uint32_t a[8][4], o[8][4];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) __builtin_memcpy(a[k], &in[k], 16);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int w = i >> 1;
+#pragma unroll
+        for (int wp = 0; wp < 4; ++wp) {
+            const uint32_t x = a[2 * wp][w], y = a[2 * wp + 1][w]; // token rows 2wp, 2wp+1
+            o[i][wp] = (i & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) __builtin_memcpy(&out[i], o[i], 16);
+}
+
+__device__ __forceinline__ void transpose_block(const Chunk<float> (&in)[4], Chunk<float> (&out)[4])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) out[i].e[k] = in[k].e[i];
+}
+
+template <typename TC, int ROWS, int KU> struct ColsStore {
+    using S = Stage<TC, KU>;
+    using G = ColsGeom<TC, ROWS, KU>;
+    __device__ static void store(TC *lds, const Chunk<TC> (&reg)[G::NCH][G::CE])
+    {
+        const int t = threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            if (c < G::TOTAL) {
+                const int ib = c % G::IB, kb = c / G::IB;
+                Chunk<TC> tr[G::CE];
+                transpose_block(reg[u], tr);
+#pragma unroll
+                for (int e = 0; e < G::CE; ++e)
+                    *reinterpret_cast<Chunk<TC> *>(lds + (ib * G::CE + e) * S::LDP + kb * G::CE) = tr[e];
+            }
+        }
+    }
 };
 
 template <typename TC, int ROWS, int KU, typename SRC, bool SUMS> struct LoadCols {
     using S = Stage<TC, KU>;
     using G = ColsGeom<TC, ROWS, KU>;
-    static_assert(!SUMS || kThreads % G::CPR == 0, "column sums need a fixed column per thread");
+    static_assert(!SUMS || kThreads % G::IB == 0, "column sums need a fixed column block per thread");
     const SRC *src; // [k][ld]
     int64_t ld;
     int ncols; // valid i
     int kend;
     int i0;
-    Chunk<TC> reg[G::NCH];
-    float sums[SUMS ? G::NCH : 1][S::CE];
+    Chunk<TC> reg[G::NCH][G::CE];
+    float sums[SUMS ? G::CE : 1];
     __device__ void init(int i0_)
     {
         i0 = i0_;
         if (SUMS)
-            for (int u = 0; u < G::NCH; ++u)
-                for (int e = 0; e < S::CE; ++e) sums[u][e] = 0.f;
+            for (int e = 0; e < G::CE; ++e) sums[e] = 0.f;
     }
     __device__ void fetch(int k0)
     {
@@ -269,36 +324,30 @@ template <typename TC, int ROWS, int KU, typename SRC, bool SUMS> struct LoadCol
 #pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
-            const int k = k0 + c / G::CPR;
-            const int i = i0 + (c % G::CPR) * S::CE;
-            if (c < G::TOTAL && k < kend && i < ncols) {
-                const SRC *p = src + (int64_t)k * ld + i;
+            const int i = i0 + (c % G::IB) * G::CE;
+            const int kb = k0 + (c / G::IB) * G::CE;
 #pragma unroll
-                for (int e = 0; e < S::CE; ++e) {
-                    float f = to_f32(p[e]);
-                    if (SUMS) sums[u][e] += f;
-                    reg[u].e[e] = to_tc(f, TC());
+            for (int kk = 0; kk < G::CE; ++kk) {
+                if (c < G::TOTAL && kb + kk < kend && i < ncols) {
+                    const SRC *p = src + (int64_t)(kb + kk) * ld + i;
+                    if (sizeof(SRC) == sizeof(TC) && !SUMS) {
+                        reg[u][kk] = *reinterpret_cast<const Chunk<TC> *>(p);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < G::CE; ++e) {
+                            const float f = to_f32(p[e]);
+                            if (SUMS) sums[e] += f;
+                            reg[u][kk].e[e] = to_tc(f, TC());
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < G::CE; ++e) reg[u][kk].e[e] = to_tc(0.f, TC());
                 }
-            } else {
-#pragma unroll
-                for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
             }
         }
     }
-    __device__ void store(TC *lds)
-    {
-        const int t = threadIdx.x;
-#pragma unroll
-        for (int u = 0; u < G::NCH; ++u) {
-            const int c = t + kThreads * u;
-            if (c < G::TOTAL) {
-                const int kk = c / G::CPR;
-                const int ii = (c % G::CPR) * S::CE;
-#pragma unroll
-                for (int e = 0; e < S::CE; ++e) lds[(ii + e) * S::LDP + kk] = reg[u].e[e];
-            }
-        }
-    }
+    __device__ void store(TC *lds) { ColsStore<TC, ROWS, KU>::store(lds, reg); }
 };
 
 // operand[i][k] = x[k][i] = lam * b_l[k][i] + (1 - lam) * s_prev[k][i]
@@ -314,7 +363,7 @@ template <typename TC, int ROWS, int KU> struct LoadColsX {
     int ncols;
     int kend;
     int i0;
-    Chunk<TC> reg[G::NCH];
+    Chunk<TC> reg[G::NCH][G::CE];
     __device__ void init(int i0_) { i0 = i0_; }
     __device__ void fetch(int k0)
     {
@@ -322,42 +371,33 @@ template <typename TC, int ROWS, int KU> struct LoadColsX {
 #pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
-            const int k = k0 + c / G::CPR;
-            const int i = i0 + (c % G::CPR) * S::CE;
-            if (c < G::TOTAL && k < kend && i < ncols) {
-                const TC *bp = cache + map.rowoff[k] + (int64_t)layer * map.rowstride[k] + i;
-                Chunk<TC> b = *reinterpret_cast<const Chunk<TC> *>(bp);
-                if (s_prev) {
-                    const float *sp = s_prev + (int64_t)k * ld_s + i;
+            const int i = i0 + (c % G::IB) * G::CE;
+            const int kb = k0 + (c / G::IB) * G::CE;
 #pragma unroll
-                    for (int e = 0; e < S::CE; ++e)
-                        reg[u].e[e] = to_tc(lam * to_f32(b.e[e]) + (1.f - lam) * sp[e], TC());
-                } else if (lam == 1.f) {
-                    reg[u] = b;
+            for (int kk = 0; kk < G::CE; ++kk) {
+                const int k = kb + kk;
+                if (c < G::TOTAL && k < kend && i < ncols) {
+                    const TC *bp = cache + map.rowoff[k] + (int64_t)layer * map.rowstride[k] + i;
+                    const Chunk<TC> b = *reinterpret_cast<const Chunk<TC> *>(bp);
+                    if (s_prev) {
+                        const float *sp = s_prev + (int64_t)k * ld_s + i;
+#pragma unroll
+                        for (int e = 0; e < G::CE; ++e)
+                            reg[u][kk].e[e] = to_tc(lam * to_f32(b.e[e]) + (1.f - lam) * sp[e], TC());
+                    } else if (lam == 1.f) {
+                        reg[u][kk] = b;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < G::CE; ++e) reg[u][kk].e[e] = to_tc(lam * to_f32(b.e[e]), TC());
+                    }
                 } else {
 #pragma unroll
-                    for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(lam * to_f32(b.e[e]), TC());
+                    for (int e = 0; e < G::CE; ++e) reg[u][kk].e[e] = to_tc(0.f, TC());
                 }
-            } else {
-#pragma unroll
-                for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
             }
         }
     }
-    __device__ void store(TC *lds)
-    {
-        const int t = threadIdx.x;
-#pragma unroll
-        for (int u = 0; u < G::NCH; ++u) {
-            const int c = t + kThreads * u;
-            if (c < G::TOTAL) {
-                const int kk = c / G::CPR;
-                const int ii = (c % G::CPR) * S::CE;
-#pragma unroll
-                for (int e = 0; e < S::CE; ++e) lds[(ii + e) * S::LDP + kk] = reg[u].e[e];
-            }
-        }
-    }
+    __device__ void store(TC *lds) { ColsStore<TC, ROWS, KU>::store(lds, reg); }
 };
 
 // ---------------------------------------------------------------------------

@@ -19,6 +19,7 @@
 // oracle's); only the order of the floating-point operations differs.  Every reduction is ordered.
 #include "pac_gemm.h"
 #include "pac_internal.h"
+#include <type_traits>
 
 namespace pac {
 
@@ -36,13 +37,18 @@ constexpr int kChainRows = 32;   // token rows per chain workgroup
 constexpr int kChainPad = 8;     // bf16 elements of padding per LDS row
 constexpr int kMaxD = 4096;
 
-static int64_t chain_lds_bytes(const Dims &D) { return (int64_t)D.L * kChainRows * (D.r + kChainPad) * 2; }
+static int64_t chain_lds_bytes(const Dims &D)
+{
+    // the forward chain's LDS (see chain_lds below): operand tiles of every layer, the input ring, vectors
+    return (int64_t)D.L * kChainRows * (D.r + kChainPad) * 2 + 4 * (int64_t)kChainRows * D.r * 4 +
+           (int64_t)D.L * D.r * 8 + (int64_t)(D.L + 4) * 4;
+}
 
 bool gram_path_fits(const Dims &D)
 {
-    if (D.cache_dtype != 0 || (D.flags & 1)) return false;
+    if (D.cache_dtype != 0 || (D.flags & 1)) return false; // PAC_FLAG_PER_LAYER
     if (D.r > 128 || D.d > kMaxD || D.L > 128) return false;
-    return chain_lds_bytes(D) <= 128 * 1024;
+    return chain_lds_bytes(D) <= 160 * 1024;
 }
 
 void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
@@ -72,6 +78,7 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.g_QpN = take((int64_t)(W.pairs + 1) * D.r * D.r * 2);
     W.g_QpT = take((int64_t)(W.pairs + 1) * D.r * D.r * 2);
     W.g_DP = take(D.Mmax * Lr * 2);
+    W.g_Gp = take(D.Mmax * Lr * 2);
     W.g_HSpart = take((int64_t)W.max_tiles * Lr * 4);
     W.g_cspart = take((int64_t)W.max_tiles * Lr * 4);
     W.g_ghat = take((int64_t)D.B_max * Lr * 4);
@@ -88,6 +95,7 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.g_samp_tile0 = take((kMaxBatch + 1) * 4);
     W.g_HSm = take((int64_t)D.B_max * Lr * 4);
     W.g_loss_part = take(kMaxBatch * 4);
+    W.g_E = take((int64_t)D.L * D.d * D.r * 4);
 }
 
 __device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }
@@ -103,6 +111,7 @@ __device__ __forceinline__ int pair_index(int k, int l) { return l * (l - 1) / 2
 // launch 1: batch gather, token tiles, projection copies, cusum/chat, V
 // ---------------------------------------------------------------------------
 struct PrepArgs {
+    int blk_off; // first block of this launch (parts may be launched separately for timing)
     BatchMeta meta;
     const float *params;
     int64_t PL;
@@ -112,14 +121,14 @@ struct PrepArgs {
     int32_t *rowstride, *rowsamp, *samp_start, *samp_len;
     int32_t *tile_row0, *tile_rows, *tile_samp, *samp_tile0;
     bf16_t *WdT, *Wu, *WuTs, *Wds;
-    float *cusum, *chat, *V;
+    float *cusum, *V;
     unsigned *counter;
 };
 
 __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
 {
-    __shared__ float sh[kMaxD > 32 * 33 ? kMaxD : 32 * 33];
-    const int b = blockIdx.x, t = threadIdx.x;
+    __shared__ float sh[32 * 33];
+    const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
     const int L = a.L, d = a.d, r = a.r, C = a.C;
     const int64_t Lr = (int64_t)L * r;
     if (b < a.nb_setup) {
@@ -130,24 +139,28 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
                 if (t < meta.B) a.samp_len[t] = meta.len[t];
             }
             if (t <= L) a.counter[t] = 0u;
-            if (t == 0) {
+            if (t < meta.B) {
+                // tiles of sample t start after the tiles of the samples before it
                 int nt = 0;
-                for (int s = 0; s < meta.B; ++s) {
-                    a.samp_tile0[s] = nt;
-                    for (int t0 = 0; t0 < meta.len[s]; t0 += kChainRows) {
-                        a.tile_row0[nt] = meta.tok_start[s] + t0;
-                        a.tile_rows[nt] = min(kChainRows, meta.len[s] - t0);
-                        a.tile_samp[nt] = s;
-                        ++nt;
-                    }
+                for (int q = 0; q < t; ++q) nt += (meta.len[q] + kChainRows - 1) / kChainRows;
+                a.samp_tile0[t] = nt;
+                for (int t0 = 0; t0 < meta.len[t]; t0 += kChainRows) {
+                    a.tile_row0[nt] = meta.tok_start[t] + t0;
+                    a.tile_rows[nt] = min(kChainRows, meta.len[t] - t0);
+                    a.tile_samp[nt] = t;
+                    ++nt;
                 }
-                a.samp_tile0[meta.B] = nt;
+                if (t == meta.B - 1) a.samp_tile0[meta.B] = nt;
             }
         }
         const int m = b * 256 + t;
         if (m >= meta.M) return;
-        int s = 0;
-        while (s + 1 < meta.B && meta.tok_start[s + 1] <= m) ++s;
+        int lo = 0, hi = meta.B - 1; // last sample whose first row is <= m
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (meta.tok_start[mid] <= m) lo = mid; else hi = mid - 1;
+        }
+        const int s = lo;
         a.rowoff[m] = meta.off[s] + (int64_t)(m - meta.tok_start[s]) * d;
         a.rowstride[m] = meta.len[s] * d;
         a.rowsamp[m] = s;
@@ -186,27 +199,14 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
         return;
     }
     if (b < a.nb_setup + a.nb_shadow + a.nb_chat) {
-        // cusum_l = sum_{k<l} c_up^k ; chat_l = cusum_l W_down^l   (fp32 master weights)
-        const int l = b - a.nb_setup - a.nb_shadow; // 0..L
-        for (int j = t; j < d; j += 256) {
-            float acc = 0.f;
-            for (int k = 0; k < l; ++k) acc += a.params[(int64_t)k * a.PL + 2 * (int64_t)d * r + r + j];
-            sh[j] = acc;
+        // cusum_l = sum_{k<l} c_up^k for l = 0..L (fp32 master values)
+        const int j = (b - a.nb_setup - a.nb_shadow) * 256 + t;
+        if (j >= d) return;
+        float acc = 0.f;
+        a.cusum[j] = 0.f;
+        for (int l = 1; l <= L; ++l) {
+            acc += a.params[(int64_t)(l - 1) * a.PL + 2 * (int64_t)d * r + r + j];
             a.cusum[(int64_t)l * d + j] = acc;
-        }
-        __syncthreads();
-        if (l < L) {
-            const float *Wd = a.params + (int64_t)l * a.PL;
-            for (int n = t; n < r; n += 256) {
-                float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-                for (int j = 0; j < d; j += 4) { // d is a multiple of 32
-                    acc0 += sh[j] * Wd[(int64_t)j * r + n];
-                    acc1 += sh[j + 1] * Wd[(int64_t)(j + 1) * r + n];
-                    acc2 += sh[j + 2] * Wd[(int64_t)(j + 2) * r + n];
-                    acc3 += sh[j + 3] * Wd[(int64_t)(j + 3) * r + n];
-                }
-                a.chat[(int64_t)l * r + n] = (acc0 + acc1) + (acc2 + acc3);
-            }
         }
         return;
     }
@@ -236,11 +236,16 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
 // launch 2: U_l = b_l W_down^l for every layer, Q_{kl} = W_up^k W_down^l, mean(b_L)
 // ---------------------------------------------------------------------------
 struct ProjArgs {
+    int blk_off; // first block of this launch (parts may be launched separately for timing)
     const bf16_t *cache;
     RowMap map;
     int L, d, r, B;
-    int nb_U, nb_Q, row_tiles;
+    int nb_U, nb_Q, nb_C, row_tiles;
     const bf16_t *WdT, *Wu;
+    const float *cusum; // [L+1][d]
+    float *chat;        // [L][r]
+    const float *params;
+    int64_t PL;
     float *U;          // [L][M][r]
     bf16_t *QpN, *QpT; // [pairs][r][r]
     const int32_t *samp_start, *samp_len;
@@ -256,23 +261,34 @@ struct EpiStoreF32 {
 struct EpiQ {
     bf16_t *qn, *qt;
     int r;
+    float one_minus_lam; // of the later layer of the pair: the backward chain uses (1-lambda_l) Q_{kl}
     __device__ void operator()(int row, int col, float v) const
     {
-        const bf16_t h = static_cast<bf16_t>(v);
-        qn[(int64_t)row * r + col] = h;
-        qt[(int64_t)col * r + row] = h;
+        qn[(int64_t)row * r + col] = static_cast<bf16_t>(one_minus_lam * v);
+        qt[(int64_t)col * r + row] = static_cast<bf16_t>(v);
+    }
+};
+
+struct EpiChat {
+    float *chat_l;
+    __device__ void operator()(int row, int col, float v) const
+    {
+        if (row == 0) chat_l[col] = v;
     }
 };
 
 using T64 = Tile<2, 2, 1, 1, 1>;
+using T64K = Tile<2, 2, 1, 1, 4>; // 128-token K step for the token contractions
 
 template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArgs a)
 {
     using TU = Tile<4, 1, 1, NT, KU>;
-    constexpr int kLds = tile_lds_bytes<bf16_t, TU>() > tile_lds_bytes<bf16_t, T64>() ? tile_lds_bytes<bf16_t, TU>()
-                                                                                      : tile_lds_bytes<bf16_t, T64>();
+    using TQ = Tile<2, 2, 1, 1, KU>;
+    constexpr int kLds = tile_lds_bytes<bf16_t, TU>() > tile_lds_bytes<bf16_t, TQ>() ? tile_lds_bytes<bf16_t, TU>()
+                                                                                     : tile_lds_bytes<bf16_t, TQ>();
+    static_assert(kLds >= 8 * 256 * 4, "pooling scratch must fit");
     __shared__ __attribute__((aligned(16))) char smem[kLds];
-    const int b = blockIdx.x;
+    const int b = blockIdx.x + a.blk_off;
     if (b < a.nb_U) {
         const int l = b / a.row_tiles, mt = b % a.row_tiles;
         LoadRowsX<bf16_t, TU::BM, KU> al;
@@ -283,36 +299,65 @@ template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArg
         gemm_tile<bf16_t, TU>(smem, al, bl, epi, 0, a.d, mt * TU::BM, 0, a.map.M, a.r);
         return;
     }
+    const int tq = (a.r + 63) / 64;
     if (b < a.nb_U + a.nb_Q) {
         int idx = b - a.nb_U;
-        const int tq = (a.r + 63) / 64;
         const int p = idx / (tq * tq);
         idx -= p * tq * tq;
         // pair p = (k, l), k < l
         int l = 1;
         while ((l + 1) * l / 2 <= p) ++l;
         const int k = p - l * (l - 1) / 2;
-        LoadRowsTC<bf16_t, 64, 1> al;
+        LoadRowsTC<bf16_t, 64, KU> al;
         al.src = a.Wu + (int64_t)k * a.r * a.d; al.ld = a.d; al.nrows = a.r;
-        LoadRowsTC<bf16_t, 64, 1> bl;
+        LoadRowsTC<bf16_t, 64, KU> bl;
         bl.src = a.WdT + (int64_t)l * a.r * a.d; bl.ld = a.d; bl.nrows = a.r;
-        EpiQ epi{a.QpN + (int64_t)p * a.r * a.r, a.QpT + (int64_t)p * a.r * a.r, a.r};
-        gemm_tile<bf16_t, T64>(smem, al, bl, epi, 0, a.d, (idx / tq) * 64, (idx % tq) * 64, a.r, a.r);
+        EpiQ epi{a.QpN + (int64_t)p * a.r * a.r, a.QpT + (int64_t)p * a.r * a.r, a.r,
+                 1.f - a.params[(int64_t)l * a.PL + a.PL - 1]};
+        gemm_tile<bf16_t, TQ>(smem, al, bl, epi, 0, a.d, (idx / tq) * 64, (idx % tq) * 64, a.r, a.r);
+        return;
+    }
+    if (b < a.nb_U + a.nb_Q + a.nb_C) {
+        // chat_l = cusum_l W_down^l: a one-row contraction on the same tile code
+        const int idx = b - a.nb_U - a.nb_Q;
+        const int l = idx / tq, nt = idx % tq;
+        LoadRowsF32<bf16_t, 64, KU> al;
+        al.src = a.cusum + (int64_t)l * a.d; al.ld = a.d; al.nrows = 1;
+        LoadRowsTC<bf16_t, 64, KU> bl;
+        bl.src = a.WdT + (int64_t)l * a.r * a.d; bl.ld = a.d; bl.nrows = a.r;
+        EpiChat epi{a.chat + (int64_t)l * a.r};
+        gemm_tile<bf16_t, TQ>(smem, al, bl, epi, 0, a.d, 0, nt * 64, 1, a.r);
         return;
     }
     {
-        // mean over the valid tokens of the last cached layer
-        int idx = b - a.nb_U - a.nb_Q;
+        // mean over the valid tokens of the last cached layer: 8 token groups x 32 column chunks
+        int idx = b - a.nb_U - a.nb_Q - a.nb_C;
         const int jt = (a.d + 255) / 256;
-        const int s = idx / jt, j = (idx % jt) * 256 + threadIdx.x;
-        if (j >= a.d) return;
+        const int s = idx / jt, j0 = (idx % jt) * 256;
+        const int t = threadIdx.x, tg = t >> 5, j = j0 + (t & 31) * 8;
         const int m0 = a.samp_start[s], len = a.samp_len[s];
-        float acc = 0.f;
-        for (int tkn = 0; tkn < len; ++tkn) {
-            const int m = m0 + tkn;
-            acc += to_f32(a.cache[a.map.rowoff[m] + (int64_t)(a.L - 1) * a.map.rowstride[m] + j]);
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        if (j < a.d) {
+            for (int tkn = tg; tkn < len; tkn += 8) {
+                const int m = m0 + tkn;
+                const Chunk<bf16_t> c = *reinterpret_cast<const Chunk<bf16_t> *>(
+                    a.cache + a.map.rowoff[m] + (int64_t)(a.L - 1) * a.map.rowstride[m] + j);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += to_f32(c.e[e]);
+            }
         }
-        a.pb[(int64_t)s * a.d + j] = acc / (float)len;
+        float *red = reinterpret_cast<float *>(smem); // [8][256]
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[tg * 256 + (t & 31) * 8 + e] = acc[e];
+        __syncthreads();
+        if (j0 + t < a.d) {
+            float tot = 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) tot += red[q * 256 + t];
+            a.pb[(int64_t)s * a.d + j0 + t] = tot / (float)len;
+        }
     }
 }
 
@@ -326,96 +371,195 @@ struct ChainArgs {
     const float *params;
     int64_t PL;
     int d;
-    float *pre;          // [L][M][r]: holds U on entry of the forward chain, pre afterwards
+    const float *U;      // forward: [L][M][r] fp32
+    bf16_t *Gp;          // GELU'(pre) as bf16 [L][M][r]: written by the forward chain, read by the backward chain
     const float *chat;   // [L][r]
-    const bf16_t *Q;     // forward: QpT ; backward: QpN
+    const bf16_t *Q;     // forward: QpT ; backward: QpN scaled by (1 - lambda) of the later layer
     bf16_t *Hg;          // forward: H [M][L*r] ; backward: DP [M][L*r]
     float *part;         // forward: HSpart ; backward: cspart   [tiles][L][r]
     const float *ghat;   // backward: [B][L][r]
 };
 
-template <bool FWD, int NT> __global__ __launch_bounds__(64 * NT) void k_gchain(ChainArgs a)
+constexpr int kRing = 4; // layers of per-token inputs staged ahead in LDS
+
+// LDS of the chain kernels:
+//   Hs   [L][32][r+pad] bf16   h (forward) or dpre (backward) of every layer: the contraction operand
+//   ring [kRing][32][r]        per-token inputs of the coming layers: U (fp32, forward) or GELU' (bf16, backward)
+//   vecS [L][r] fp32           per-layer vector: (1-lambda) chat + c_down (forward), ghat of the sample (backward)
+//   lamS [L] fp32, Cs [L][r] fp32 column sums
+// Wavefronts 0..NT-1 contract and apply the nonlinearity; one more wavefront only moves the
+// per-token inputs of later layers from global memory into the ring, so that no contracting
+// wavefront ever waits on those loads.
+static size_t chain_lds(int L, int r, bool fwd)
+{
+    const size_t hs = (size_t)L * kChainRows * (r + kChainPad) * 2;
+    const size_t ring = (size_t)kRing * kChainRows * r * (fwd ? 4 : 2);
+    return hs + ring + (size_t)L * r * 4 * 2 + (size_t)((L + 3) / 4 * 4) * 4;
+}
+
+// GELU(u) and GELU'(u) from one exponential: erf by the five-term rational approximation of
+// Abramowitz & Stegun 7.1.26 (absolute error below 1.5e-7), whose exp(-x^2) with x = |u|/sqrt(2)
+// is the exp(-u^2/2) of the normal density.
+__device__ __forceinline__ void gelu_pair(float u, float &h, float &gp)
+{
+    const float x = fabsf(u) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(1.f + 0.3275911f * x);
+    const float ex = __expf(-0.5f * u * u);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float erf_abs = 1.f - poly * ex;
+    const float Phi = 0.5f * (1.f + copysignf(erf_abs, u));
+    h = u * Phi;
+    gp = Phi + u * 0.3989422804014327f * ex;
+}
+
+template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_gchain(ChainArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char dyn_smem[];
-    bf16_t *Hs = reinterpret_cast<bf16_t *>(dyn_smem); // [L][32][r + pad]
     constexpr int r = 32 * NT, RP = r + kChainPad, KQ = r / 16;
-    constexpr int GP = 4; // layer pairs whose operands are in flight together
+    constexpr int GP = 4; // layer pairs whose operands are requested together
+    using RingT = typename std::conditional<FWD, float, bf16_t>::type;
+    constexpr int kTileBytes = kChainRows * r * (int)sizeof(RingT);
+    constexpr int kChunksPerLane = kTileBytes / 16 / 64; // 16-byte chunks each helper lane moves per layer
+    static_assert(kTileBytes % (16 * 64) == 0, "ring tile must split evenly over the helper wavefront");
     const int L = a.L;
+    bf16_t *Hs = reinterpret_cast<bf16_t *>(dyn_smem);                                      // [L][32][RP]
+    RingT *ring = reinterpret_cast<RingT *>(Hs + (size_t)L * kChainRows * RP);              // [kRing][32][r]
+    float *vecS = reinterpret_cast<float *>(ring + (size_t)kRing * kChainRows * r);         // [L][r]
+    float *Cs = vecS + (size_t)L * r;                                                       // [L][r]
+    float *lamS = Cs + (size_t)L * r;                                                       // [L]
     const int tile = blockIdx.x;
     const int m0 = a.tile_row0[tile], nrows = a.tile_rows[tile], samp = a.tile_samp[tile];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i = lane & 31, g = lane >> 5;
-    const int n = 32 * wave + i;
     const int64_t Lr = (int64_t)L * r;
     constexpr int64_t rr = (int64_t)r * r;
-    for (int step = 0; step < L; ++step) {
-        const int l = FWD ? step : L - 1 - step;
-        const float *pl = a.params + (int64_t)l * a.PL;
-        const float lam = pl[a.PL - 1];
-        // values the epilogue needs, requested before the contraction starts
-        float uval[16];
-        float cvec = 0.f, cdn = 0.f;
+    const int nthreads = 64 * (NT + 1);
+    auto layer_at = [&](int step) { return FWD ? step : L - 1 - step; };
+
+    // per-layer vectors
+    for (int c = threadIdx.x; c < L * r; c += nthreads) {
+        const int l = c / r, nn = c % r;
         if (FWD) {
-            cvec = a.chat[(int64_t)l * r + n];
-            cdn = pl[(int64_t)a.d * r + n];
+            const float *pl = a.params + (int64_t)l * a.PL;
+            vecS[c] = (1.f - pl[a.PL - 1]) * a.chat[c] + pl[(int64_t)a.d * r + nn];
         } else {
-            cvec = a.ghat[((int64_t)samp * L + l) * r + n];
+            vecS[c] = a.ghat[(int64_t)samp * Lr + c];
         }
+    }
+    for (int l = threadIdx.x; l < L; l += nthreads) lamS[l] = a.params[(int64_t)l * a.PL + a.PL - 1];
+
+    if (wave == NT) {
+        // ---- helper wavefront: keep the ring filled three layers ahead ----
+        const RingT *src = FWD ? reinterpret_cast<const RingT *>(a.U) : reinterpret_cast<const RingT *>(a.Gp);
+        constexpr int EPC = 16 / (int)sizeof(RingT); // elements per chunk
+        auto fetch = [&](int step, uint4(&reg)[kChunksPerLane]) {
+            if (step >= L) return;
+            const RingT *base = src + ((int64_t)layer_at(step) * a.M + m0) * r;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = 8 * (v >> 2) + 4 * g + (v & 3);
-            uval[v] = row < nrows ? a.pre[((int64_t)l * a.M + m0 + row) * r + n] : 0.f;
-        }
-        f32x16 acc;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-        const int k0 = FWD ? 0 : l + 1, k1 = FWD ? l : L;
-        for (int kb = k0; kb < k1; kb += GP) {
-            bf16x8 bq[GP][KQ];
-#pragma unroll
-            for (int u = 0; u < GP; ++u) {
-                const int k = kb + u < k1 ? kb + u : k1 - 1;
-                const bf16_t *Qrow = a.Q + (FWD ? pair_index(k, l) : pair_index(l, k)) * rr + (int64_t)n * r;
-#pragma unroll
-                for (int q = 0; q < KQ; ++q) bq[u][q] = *reinterpret_cast<const bf16x8 *>(Qrow + 16 * q + 8 * g);
+            for (int q = 0; q < kChunksPerLane; ++q) {
+                const int e = (lane + 64 * q) * EPC;
+                reg[q] = e < nrows * r ? *reinterpret_cast<const uint4 *>(base + e) : make_uint4(0, 0, 0, 0);
             }
+        };
+        auto put = [&](int step, const uint4(&reg)[kChunksPerLane]) {
+            if (step >= L) return;
+            RingT *dst = ring + (size_t)(step % kRing) * kChainRows * r;
 #pragma unroll
-            for (int u = 0; u < GP; ++u) {
-                if (kb + u < k1) {
-                    const bf16_t *Hk = Hs + ((int64_t)(kb + u) * kChainRows + i) * RP;
+            for (int q = 0; q < kChunksPerLane; ++q) *reinterpret_cast<uint4 *>(dst + (lane + 64 * q) * EPC) = reg[q];
+        };
+        uint4 ra[kChunksPerLane], rb[kChunksPerLane], rc[kChunksPerLane];
+        fetch(0, ra);
+        fetch(1, rb);
+        fetch(2, rc);
+        put(0, ra);
+        __syncthreads();
+        // before the barrier that ends step s the tile of step s+1 must be in the ring
+        for (int s = 0; s < L; s += 3) {
+            fetch(s + 3, ra);
+            put(s + 1, rb);
+            __syncthreads();
+            if (s + 1 < L) {
+                fetch(s + 4, rb);
+                put(s + 2, rc);
+                __syncthreads();
+            }
+            if (s + 2 < L) {
+                fetch(s + 5, rc);
+                put(s + 3, ra);
+                __syncthreads();
+            }
+        }
+    } else {
+        // ---- contracting wavefronts ----
+        const int i = lane & 31, g = lane >> 5;
+        const int n = 32 * wave + i;
+        __syncthreads();
+        for (int step = 0; step < L; ++step) {
+            const int l = layer_at(step);
+            f32x16 acc;
 #pragma unroll
-                    for (int q = 0; q < KQ; ++q) {
-                        const bf16x8 av = *reinterpret_cast<const bf16x8 *>(Hk + 16 * q + 8 * g);
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bq[u][q], acc, 0, 0, 0);
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            const int k0 = FWD ? 0 : l + 1, k1 = FWD ? l : L;
+            for (int kb = k0; kb < k1; kb += GP) {
+                bf16x8 bq[GP][KQ];
+#pragma unroll
+                for (int u = 0; u < GP; ++u) {
+                    const int k = kb + u < k1 ? kb + u : k1 - 1;
+                    const bf16_t *Qrow = a.Q + (FWD ? pair_index(k, l) : pair_index(l, k)) * rr + (int64_t)n * r;
+#pragma unroll
+                    for (int q = 0; q < KQ; ++q) bq[u][q] = *reinterpret_cast<const bf16x8 *>(Qrow + 16 * q + 8 * g);
+                }
+#pragma unroll
+                for (int u = 0; u < GP; ++u) {
+                    if (kb + u < k1) {
+                        const bf16_t *Hk = Hs + ((int64_t)(kb + u) * kChainRows + i) * RP;
+#pragma unroll
+                        for (int q = 0; q < KQ; ++q) {
+                            const bf16x8 av = *reinterpret_cast<const bf16x8 *>(Hk + 16 * q + 8 * g);
+                            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bq[u][q], acc, 0, 0, 0);
+                        }
                     }
                 }
             }
-        }
-        float colsum = 0.f;
+            const float lam = lamS[l];
+            const float cvec = vecS[l * r + n];
+            const RingT *rt = ring + (size_t)(step % kRing) * kChainRows * r;
+            float colsum = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = 8 * (v >> 2) + 4 * g + (v & 3);
-            const bool valid = row < nrows;
-            float keep = 0.f, out = 0.f;
-            if (FWD) {
-                const float pre = lam * uval[v] + (1.f - lam) * (acc[v] + cvec) + cdn;
-                if (valid) {
-                    a.pre[((int64_t)l * a.M + m0 + row) * r + n] = pre;
-                    out = gelu_f(pre);
+            for (int v = 0; v < 16; ++v) {
+                const int row = 8 * (v >> 2) + 4 * g + (v & 3);
+                const bool valid = row < nrows;
+                const float uin = to_f32(rt[row * r + n]);
+                float out = 0.f;
+                if (FWD) {
+                    const float pre = lam * uin + (1.f - lam) * acc[v] + cvec;
+                    float h, gp;
+                    gelu_pair(pre, h, gp);
+                    if (valid) {
+                        out = h;
+                        a.Gp[((int64_t)l * a.M + m0 + row) * r + n] = static_cast<bf16_t>(gp);
+                    }
+                } else {
+                    if (valid) out = (cvec + acc[v]) * uin;
                 }
-                keep = out;
-            } else {
-                if (valid) out = (cvec + acc[v]) * gelu_grad_f(uval[v]);
-                keep = (1.f - lam) * out;
+                Hs[((int64_t)l * kChainRows + row) * RP + n] = static_cast<bf16_t>(out);
+                colsum += out;
             }
-            if (valid) a.Hg[(int64_t)(m0 + row) * Lr + (int64_t)l * r + n] = static_cast<bf16_t>(out);
-            Hs[((int64_t)l * kChainRows + row) * RP + n] = static_cast<bf16_t>(keep);
-            colsum += out;
+            colsum += __shfl_xor(colsum, 32, 64);
+            if (g == 0) Cs[l * r + n] = colsum;
+            __syncthreads();
         }
-        colsum += __shfl_xor(colsum, 32, 64);
-        if (g == 0) a.part[((int64_t)tile * L + l) * r + n] = colsum;
-        __syncthreads();
     }
+    // flush: 16-byte chunks of the valid rows, then the column sums
+    const int chunks_per_row = r / 8;
+    for (int c = threadIdx.x; c < L * kChainRows * chunks_per_row; c += nthreads) {
+        const int l = c / (kChainRows * chunks_per_row);
+        const int rem = c - l * kChainRows * chunks_per_row;
+        const int row = rem / chunks_per_row, cc = rem % chunks_per_row;
+        if (row < nrows)
+            *reinterpret_cast<uint4 *>(a.Hg + (int64_t)(m0 + row) * Lr + (int64_t)l * r + cc * 8) =
+                *reinterpret_cast<const uint4 *>(Hs + ((int64_t)l * kChainRows + row) * RP + cc * 8);
+    }
+    for (int c = threadIdx.x; c < L * r; c += nthreads) a.part[(int64_t)tile * Lr + c] = Cs[c];
 }
 
 // ---------------------------------------------------------------------------
@@ -436,7 +580,6 @@ __global__ __launch_bounds__(256) void k_ghead(HeadArgs a)
 {
     __shared__ float red[4][kMaxClasses];
     __shared__ float sdz[kMaxClasses];
-    __shared__ int is_last;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int s = blockIdx.x;
     const int B = a.B, L = a.L, d = a.d, r = a.r, C = a.C;
@@ -487,10 +630,7 @@ __global__ __launch_bounds__(256) void k_ghead(HeadArgs a)
             sdz[c] = gz;
             if (c == y) lossv = lse - z[c];
         }
-        a.loss_part[s] = lossv;
-        __threadfence();
-        const unsigned prev = atomicAdd(a.counter, 1u);
-        is_last = (prev == (unsigned)(B - 1));
+        a.loss_part[s] = lossv; // summed in sample order by k_gfinish
     }
     __syncthreads();
     for (int64_t kk = t; kk < Lr; kk += 256) {
@@ -498,20 +638,13 @@ __global__ __launch_bounds__(256) void k_ghead(HeadArgs a)
         for (int c = 0; c < C; ++c) v += sdz[c] * a.V[kk * C + c];
         a.ghat[(int64_t)s * Lr + kk] = v * inv_len;
     }
-    if (is_last && t == 0) {
-        __threadfence();
-        float tot = 0.f;
-        for (int q = 0; q < B; ++q)
-            tot += __hip_atomic_load(&a.loss_part[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *a.loss_out = tot / (float)B;
-        *a.counter = 0u;
-    }
 }
 
 // ---------------------------------------------------------------------------
 // launch 6: contractions over the tokens.  E_l = b_l^T dpre_l ; GG = H^T DP (all layer pairs at once)
 // ---------------------------------------------------------------------------
 struct TokRedArgs {
+    int blk_off; // first block of this launch (parts may be launched separately for timing)
     const bf16_t *cache;
     RowMap map;
     int L, d, r;
@@ -523,11 +656,11 @@ struct TokRedArgs {
 
 template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
 {
-    using TE = Tile<4, 1, 1, NT, 1>;
-    constexpr int kLds = tile_lds_bytes<bf16_t, TE>() > tile_lds_bytes<bf16_t, T64>() ? tile_lds_bytes<bf16_t, TE>()
-                                                                                      : tile_lds_bytes<bf16_t, T64>();
+    using TE = Tile<4, 1, 1, NT, 4>;
+    constexpr int kLds = tile_lds_bytes<bf16_t, TE>() > tile_lds_bytes<bf16_t, T64K>() ? tile_lds_bytes<bf16_t, TE>()
+                                                                                       : tile_lds_bytes<bf16_t, T64K>();
     __shared__ __attribute__((aligned(16))) char smem[kLds];
-    const int b = blockIdx.x;
+    const int b = blockIdx.x + a.blk_off;
     const int M = a.map.M;
     const int Lr = a.L * a.r;
     if (b < a.nb_E) {
@@ -536,10 +669,10 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         const int l = b / (a.se * a.e_tiles);
         const int kbegin = split * a.rows_per_se;
         const int kend = min(M, kbegin + a.rows_per_se);
-        LoadColsX<bf16_t, TE::BM, 1> al;
+        LoadColsX<bf16_t, TE::BM, 4> al;
         al.cache = a.cache; al.map = a.map; al.layer = l; al.s_prev = nullptr; al.ld_s = 0; al.lam = 1.f;
         al.ncols = a.d; al.kend = kend;
-        LoadCols<bf16_t, TE::BN, 1, bf16_t, false> bl;
+        LoadCols<bf16_t, TE::BN, 4, bf16_t, false> bl;
         bl.src = a.DP + (int64_t)l * a.r; bl.ld = Lr; bl.ncols = a.r; bl.kend = kend;
         EpiStoreF32 epi{a.Epart + ((int64_t)split * a.L + l) * a.d * a.r, a.r};
         gemm_tile<bf16_t, TE>(smem, al, bl, epi, kbegin, kend, it * TE::BM, 0, a.d, a.r);
@@ -556,12 +689,12 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         if (kmin >= lmax) return;
         const int kbegin = split * a.rows_per_sg;
         const int kend = min(M, kbegin + a.rows_per_sg);
-        LoadCols<bf16_t, 64, 1, bf16_t, false> al;
+        LoadCols<bf16_t, 64, 4, bf16_t, false> al;
         al.src = a.H; al.ld = Lr; al.ncols = Lr; al.kend = kend;
-        LoadCols<bf16_t, 64, 1, bf16_t, false> bl;
+        LoadCols<bf16_t, 64, 4, bf16_t, false> bl;
         bl.src = a.DP; bl.ld = Lr; bl.ncols = Lr; bl.kend = kend;
         EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
-        gemm_tile<bf16_t, T64>(smem, al, bl, epi, kbegin, kend, ti * 64, tj * 64, Lr, Lr);
+        gemm_tile<bf16_t, T64K>(smem, al, bl, epi, kbegin, kend, ti * 64, tj * 64, Lr, Lr);
     }
 }
 
@@ -569,7 +702,11 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
 // launch 7: ordered sums of the split partials; bf16 copies of GG for the last contractions
 // ---------------------------------------------------------------------------
 struct ReduceArgs {
-    int L, r, sg, ntiles, nb_GG, B, C;
+    int blk_off; // first block of this launch (parts may be launched separately for timing)
+    int L, r, sg, ntiles, nb_GG, nb_Esum, B, C, se;
+    int64_t e_elems; // L * d * r
+    const float *Epart;
+    float *E;
     const float *params;
     int64_t PL;
     const float *GGpart, *cspart, *HSm, *dz;
@@ -581,7 +718,7 @@ __global__ __launch_bounds__(256) void k_greduce(ReduceArgs a)
 {
     __shared__ float tile[32][33];
     const int Lr = a.L * a.r;
-    const int b = blockIdx.x, t = threadIdx.x;
+    const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
     if (b < a.nb_GG) {
         const int tg = Lr / 32;
         const int tr = b / tg, tcx = b % tg;
@@ -601,25 +738,48 @@ __global__ __launch_bounds__(256) void k_greduce(ReduceArgs a)
             a.GGT[(int64_t)(tcx * 32 + y) * Lr + tr * 32 + tx] = static_cast<bf16_t>(tile[tx][y]);
         return;
     }
-    const int idx = (b - a.nb_GG) * 256 + t;
-    if (idx < Lr) {
-        float acc = 0.f;
-        for (int k = 0; k < a.ntiles; ++k) acc += a.cspart[(int64_t)k * Lr + idx];
-        a.cs[idx] = acc;
-        // Z[kk][c] = sum_s mean_t(h)[s][kk] dz[s][c]
-        float zc[kMaxClasses];
+    if (b < a.nb_GG + a.nb_Esum) {
+        const int64_t o = ((int64_t)(b - a.nb_GG) * 256 + t) * 4;
+        if (o < a.e_elems) { // e_elems is a multiple of 4
+            float4 acc = *reinterpret_cast<const float4 *>(a.Epart + o);
+            for (int s2 = 1; s2 < a.se; ++s2) {
+                const float4 v = *reinterpret_cast<const float4 *>(a.Epart + (int64_t)s2 * a.e_elems + o);
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+            *reinterpret_cast<float4 *>(a.E + o) = acc;
+        }
+        return;
+    }
+    // cs = ordered sum of the tiles' column sums; Z[kk][c] = sum_s mean_t(h)[s][kk] dz[s][c].
+    // 64 indices per block, the tiles / samples split over 4 thread groups, combined in group order.
+    float *red = &tile[0][0]; // 4 * 64 * (1 + C) floats needed
+    const int vb = b - a.nb_GG - a.nb_Esum;
+    const int idx = vb * 64 + (t & 63), grp = t >> 6;
+    float acc = 0.f;
+    float zc[kMaxClasses];
 #pragma unroll
-        for (int c = 0; c < kMaxClasses; ++c) zc[c] = 0.f;
-        for (int s = 0; s < a.B; ++s) {
+    for (int c = 0; c < kMaxClasses; ++c) zc[c] = 0.f;
+    if (idx < Lr) {
+        for (int k = grp; k < a.ntiles; k += 4) acc += a.cspart[(int64_t)k * Lr + idx];
+        for (int s = grp; s < a.B; s += 4) {
             const float hs = a.HSm[(int64_t)s * Lr + idx];
             for (int c = 0; c < a.C; ++c) zc[c] += hs * a.dz[s * a.C + c];
         }
-        for (int c = 0; c < a.C; ++c) a.Z[(int64_t)idx * a.C + c] = zc[c];
     }
-    if (b == a.nb_GG && t < a.C) {
-        float acc = 0.f;
-        for (int s = 0; s < a.B; ++s) acc += a.dz[s * a.C + t];
-        a.dzsum[t] = acc;
+    __shared__ float zred[4 * 64 * kMaxClasses]; // [4][64][C]
+    red[grp * 64 + (t & 63)] = acc;
+    for (int c = 0; c < a.C; ++c) zred[(grp * 64 + (t & 63)) * kMaxClasses + c] = zc[c];
+    __syncthreads();
+    if (grp == 0 && idx < Lr) {
+        a.cs[idx] = (red[t] + red[64 + t]) + (red[128 + t] + red[192 + t]);
+        for (int c = 0; c < a.C; ++c)
+            a.Z[(int64_t)idx * a.C + c] = (zred[t * kMaxClasses + c] + zred[(64 + t) * kMaxClasses + c]) +
+                                          (zred[(128 + t) * kMaxClasses + c] + zred[(192 + t) * kMaxClasses + c]);
+    }
+    if (vb == 0 && t < a.C) {
+        float sum = 0.f;
+        for (int s = 0; s < a.B; ++s) sum += a.dz[s * a.C + t];
+        a.dzsum[t] = sum;
     }
 }
 
@@ -627,6 +787,7 @@ __global__ __launch_bounds__(256) void k_greduce(ReduceArgs a)
 // launch 8: the gradients
 // ---------------------------------------------------------------------------
 struct PostArgs {
+    int blk_off; // first block of this launch (parts may be launched separately for timing)
     int L, d, r, C, B, se;
     int nb_F, nb_W, nb_vec;
     const float *params;
@@ -674,14 +835,14 @@ struct EpiW {
 __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
 {
     constexpr int kVecLds = 256 * 4 + 256 * kMaxClasses * 4;
-    constexpr int kLds = tile_lds_bytes<bf16_t, T64>() > kVecLds ? tile_lds_bytes<bf16_t, T64>() : kVecLds;
+    constexpr int kLds = 56 * 1024;
+    static_assert(kLds >= tile_lds_bytes<bf16_t, T64K>() && kLds >= kVecLds, "LDS budget of the gradient kernel");
     __shared__ __attribute__((aligned(16))) char smem[kLds];
     __shared__ float red[16];
-    __shared__ int is_last;
     const int L = a.L, d = a.d, r = a.r, C = a.C;
     const int Lr = L * r;
     const int64_t dr = (int64_t)d * r;
-    const int b = blockIdx.x, t = threadIdx.x;
+    const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
     const int ti_d = (d + 63) / 64, ti_r = (r + 63) / 64;
     if (b < a.nb_F) {
         // F_l = sum_{k<l} W_up^{kT} G_{kl}   ([d] x [l*r] times [l*r] x [r])
@@ -689,30 +850,15 @@ __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
         const int slot = b % (ti_d * ti_r);
         const int it = slot / ti_r, nt = slot % ti_r;
         const float *pl = a.params + (int64_t)l * a.PL;
-        LoadRowsTC<bf16_t, 64, 1> al;
-        al.src = a.WuTs; al.ld = Lr; al.nrows = d;
-        LoadRowsTC<bf16_t, 64, 1> bl;
-        bl.src = a.GGT + (int64_t)l * r * Lr; bl.ld = Lr; bl.nrows = r;
+        LoadRowsTC<bf16_t, 64, 4> al;
+        al.src = a.WuTs; al.ld = Lr; al.nrows = d; al.klim = l * r;
+        LoadRowsTC<bf16_t, 64, 4> bl;
+        bl.src = a.GGT + (int64_t)l * r * Lr; bl.ld = Lr; bl.nrows = r; bl.klim = l * r;
         EpiF epi{a.Epart + (int64_t)l * dr, a.se, (int64_t)L * dr, a.cusum + (int64_t)l * d, a.cs + (int64_t)l * r,
                  pl, a.grads + (int64_t)l * a.PL, r, pl[a.PL - 1], 0.f};
-        gemm_tile<bf16_t, T64>(smem, al, bl, epi, 0, l * r, it * 64, nt * 64, d, r);
+        gemm_tile<bf16_t, T64K>(smem, al, bl, epi, 0, l * r, it * 64, nt * 64, d, r);
         const float tot = block_sum(epi.dlam, red);
-        if (t == 0) {
-            a.dlam_part[(int64_t)l * a.slots + slot] = tot;
-            __threadfence();
-            const unsigned prev = atomicAdd(&a.counter[l], 1u);
-            is_last = (prev == (unsigned)(a.slots - 1));
-        }
-        __syncthreads();
-        if (is_last && t == 0) {
-            __threadfence();
-            float acc = 0.f;
-            for (int s = 0; s < a.slots; ++s)
-                acc += __hip_atomic_load(&a.dlam_part[(int64_t)l * a.slots + s], __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
-            a.grads[(int64_t)l * a.PL + a.PL - 1] = acc;
-            a.counter[l] = 0u;
-        }
+        if (t == 0) a.dlam_part[(int64_t)l * a.slots + slot] = tot; // summed in slot order by k_gfinish
         return;
     }
     if (b < a.nb_F + a.nb_W) {
@@ -721,13 +867,13 @@ __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
         const int l = idx / (ti_d * ti_r);
         idx %= ti_d * ti_r;
         const int at = idx / ti_d, jt = idx % ti_d;
-        LoadRowsTC<bf16_t, 64, 1> al;
-        al.src = a.GGsc + (int64_t)l * r * Lr; al.ld = Lr; al.nrows = r;
-        LoadRowsTC<bf16_t, 64, 1> bl;
-        bl.src = a.Wds; bl.ld = Lr; bl.nrows = d;
+        LoadRowsTC<bf16_t, 64, 4> al;
+        al.src = a.GGsc + (int64_t)l * r * Lr; al.ld = Lr; al.nrows = r; al.kmin = (l + 1) * r; al.klim = Lr;
+        LoadRowsTC<bf16_t, 64, 4> bl;
+        bl.src = a.Wds; bl.ld = Lr; bl.nrows = d; bl.kmin = (l + 1) * r; bl.klim = Lr;
         EpiW epi{a.Z + (int64_t)l * r * C, a.params + (int64_t)L * a.PL,
                  a.grads + (int64_t)l * a.PL + dr + r, d, C};
-        gemm_tile<bf16_t, T64>(smem, al, bl, epi, (l + 1) * r, Lr, at * 64, jt * 64, r, d);
+        gemm_tile<bf16_t, T64K>(smem, al, bl, epi, ((l + 1) * r) / 128 * 128, Lr, at * 64, jt * 64, r, d);
         return;
     }
     const int vb = b - a.nb_F - a.nb_W;
@@ -740,14 +886,22 @@ __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
         const int j = vb * jpb + jj;
         const bool act = jj < jpb && j < d;
         const float *Wc = a.params + (int64_t)L * a.PL;
+        // cs and Z are read by every thread: stage them in LDS when they fit
+        float *stage = wsh + 256 * kMaxClasses;
+        const bool staged = (int64_t)Lr * (1 + C) * 4 + kVecLds <= kLds;
+        if (staged) {
+            for (int q = t; q < Lr; q += 256) stage[q] = a.cs[q];
+            for (int q = t; q < Lr * C; q += 256) stage[Lr + q] = a.Z[q];
+            __syncthreads();
+        }
         float wz[kMaxClasses];
 #pragma unroll
         for (int c = 0; c < kMaxClasses; ++c) wz[c] = 0.f;
         if (act) {
             const bf16_t *wrow = a.Wds + (int64_t)j * Lr + (int64_t)k * r;
             const bf16_t *urow = a.WuTs + (int64_t)j * Lr + (int64_t)k * r;
-            const float *csk = a.cs + (int64_t)k * r;
-            const float *Zk = a.Z + (int64_t)k * r * C;
+            const float *csk = staged ? stage + (int64_t)k * r : a.cs + (int64_t)k * r;
+            const float *Zk = staged ? stage + Lr + (int64_t)k * r * C : a.Z + (int64_t)k * r * C;
             float acc = 0.f;
             for (int b0 = 0; b0 < r; b0 += 8) {
                 const Chunk<bf16_t> wv = *reinterpret_cast<const Chunk<bf16_t> *>(wrow + b0);
@@ -788,9 +942,48 @@ __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
     if (t < C) a.grads[(int64_t)L * a.PL + (int64_t)d * C + t] = a.dzsum[t];
 }
 
+// last launch: the two scalar reductions whose inputs come from many workgroups, in a fixed order
+__global__ __launch_bounds__(64) void k_gfinish(const float *loss_part, int B, float *loss_out,
+                                                const float *dlam_part, int slots, int L, int64_t PL, float *grads)
+{
+    const int t = threadIdx.x;
+    if (t == 0 && loss_out) {
+        float tot = 0.f;
+        for (int s = 0; s < B; ++s) tot += loss_part[s];
+        *loss_out = tot / (float)B;
+    }
+    if (grads)
+        for (int l = t; l < L; l += 64) {
+            float acc = 0.f;
+            for (int s = 0; s < slots; ++s) acc += dlam_part[(int64_t)l * slots + s];
+            grads[(int64_t)l * PL + PL - 1] = acc;
+        }
+}
+
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
+// Launch a kernel whose block index selects one of several parts: in one go, or (for per-part
+// timing) one launch per part with its own profile class.
+template <class Args, class Kern>
+static void launch_parts(Profiler *prof, hipStream_t st, bool split, Kern kern, Args a, int nparts, const int *counts,
+                         const int *classes, int whole_class, unsigned threads)
+{
+    int total = 0;
+    for (int i = 0; i < nparts; ++i) total += counts[i];
+    if (!split) {
+        a.blk_off = 0;
+        if (total > 0) PAC_LAUNCH(prof, st, whole_class, kern, dim3(total), dim3(threads), 0, st, a);
+        return;
+    }
+    int off = 0;
+    for (int i = 0; i < nparts; ++i) {
+        a.blk_off = off;
+        if (counts[i] > 0) PAC_LAUNCH(prof, st, classes[i], kern, dim3(counts[i]), dim3(threads), 0, st, a);
+        off += counts[i];
+    }
+}
+
 template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io)
 {
     hipStream_t st = io.stream;
@@ -798,6 +991,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     char *ws = io.ws;
     const int L = D.L, d = D.d, r = D.r, C = D.C, M = meta.M, B = meta.B;
     const int Lr = L * r;
+    const bool split = (D.flags & 2) != 0;
     int ntiles = 0;
     for (int s = 0; s < B; ++s) ntiles += cdiv(meta.len[s], kChainRows);
 
@@ -832,45 +1026,49 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     {
         PrepArgs a;
         a.meta = meta; a.params = io.params; a.PL = D.PL; a.L = L; a.d = d; a.r = r; a.C = C;
-        a.nb_setup = cdiv(M, 256); a.nb_shadow = (d / 32) * (r / 32) * L * 2; a.nb_chat = L + 1;
+        a.nb_setup = cdiv(M, 256); a.nb_shadow = (d / 32) * (r / 32) * L * 2; a.nb_chat = cdiv(d, 256);
         a.rowoff = rowoff; a.rowstride = rowstride; a.rowsamp = rowsamp; a.samp_start = samp_start;
         a.samp_len = samp_len; a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.tile_samp = tile_samp; a.samp_tile0 = samp_tile0;
-        a.WdT = WdT; a.Wu = Wu; a.WuTs = WuTs; a.Wds = Wds; a.cusum = cusum; a.chat = chat; a.V = V;
+        a.WdT = WdT; a.Wu = Wu; a.WuTs = WuTs; a.Wds = Wds; a.cusum = cusum; a.V = V;
         a.counter = counter;
-        const int nb = a.nb_setup + a.nb_shadow + a.nb_chat + cdiv(Lr, 4);
-        PAC_LAUNCH(prof, st, KC_G_PREP, k_gprep, dim3(nb), dim3(256), 0, st, a);
+        const int counts[4] = {a.nb_setup, a.nb_shadow, a.nb_chat, cdiv(Lr, 4)};
+        const int classes[4] = {KC_G_PREP_SETUP, KC_G_PREP_COPY, KC_G_PREP_CHAT, KC_G_PREP_V};
+        launch_parts(prof, st, split, k_gprep, a, 4, counts, classes, KC_G_PREP, 256);
     }
     {
         ProjArgs a;
         a.cache = cache; a.map = map; a.L = L; a.d = d; a.r = r; a.B = B;
         a.row_tiles = cdiv(M, 128); a.nb_U = a.row_tiles * L;
         a.nb_Q = W.pairs * cdiv(r, 64) * cdiv(r, 64);
+        a.nb_C = L * cdiv(r, 64);
+        a.cusum = cusum; a.chat = chat; a.params = io.params; a.PL = D.PL;
         a.WdT = WdT; a.Wu = Wu; a.U = pre; a.QpN = QpN; a.QpT = QpT;
         a.samp_start = samp_start; a.samp_len = samp_len; a.pb = pb;
-        const int nb = a.nb_U + a.nb_Q + B * cdiv(d, 256);
-        if (d % 64 == 0)
-            PAC_LAUNCH(prof, st, KC_G_PROJ, (k_gproj<NT, 2>), dim3(nb), dim3(256), 0, st, a);
-        else
-            PAC_LAUNCH(prof, st, KC_G_PROJ, (k_gproj<NT, 1>), dim3(nb), dim3(256), 0, st, a);
+        const int counts[4] = {a.nb_U, a.nb_Q, a.nb_C, B * cdiv(d, 256)};
+        const int classes[4] = {KC_G_PROJ_U, KC_G_PROJ_Q, KC_G_PROJ_Q, KC_G_PROJ_PB};
+        if (d % 128 == 0) launch_parts(prof, st, split, k_gproj<NT, 4>, a, 4, counts, classes, KC_G_PROJ, 256);
+        else if (d % 64 == 0) launch_parts(prof, st, split, k_gproj<NT, 2>, a, 4, counts, classes, KC_G_PROJ, 256);
+        else launch_parts(prof, st, split, k_gproj<NT, 1>, a, 4, counts, classes, KC_G_PROJ, 256);
     }
-    const size_t chain_lds = (size_t)L * kChainRows * (r + kChainPad) * 2;
+    const size_t lds_fwd = chain_lds(L, r, true), lds_bwd = chain_lds(L, r, false);
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<true, NT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<false, NT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     ChainArgs ca;
     ca.L = L; ca.r = r; ca.M = M; ca.tile_row0 = tile_row0; ca.tile_rows = tile_rows; ca.tile_samp = tile_samp;
-    ca.params = io.params; ca.PL = D.PL; ca.d = d; ca.pre = pre; ca.chat = chat; ca.ghat = ghat;
+    ca.params = io.params; ca.PL = D.PL; ca.d = d; ca.U = pre; ca.Gp = (bf16_t *)(ws + W.g_Gp); ca.chat = chat;
+    ca.ghat = ghat;
     {
         ChainArgs a = ca;
         a.Q = QpT; a.Hg = H; a.part = HSpart;
-        PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * NT), chain_lds, st, a);
+        PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * (NT + 1)), lds_fwd, st, a);
     }
     {
         HeadArgs a;
@@ -880,38 +1078,57 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.loss_out = io.loss_out; a.ghat = ghat; a.HSm = HSm; a.loss_part = loss_part; a.counter = counter + L;
         PAC_LAUNCH(prof, st, KC_G_HEAD, k_ghead, dim3(B), dim3(256), 0, st, a);
     }
-    if (!io.grads) return hipGetLastError();
+    if (!io.grads) {
+        PAC_LAUNCH(prof, st, KC_G_FINISH, k_gfinish, dim3(1), dim3(64), 0, st, loss_part, B, io.loss_out, nullptr, 0, L,
+                   D.PL, nullptr);
+        return hipGetLastError();
+    }
     {
         ChainArgs a = ca;
         a.Q = QpN; a.Hg = DP; a.part = cspart;
-        PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, (k_gchain<false, NT>), dim3(ntiles), dim3(64 * NT), chain_lds, st, a);
+        PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, (k_gchain<false, NT>), dim3(ntiles), dim3(64 * (NT + 1)), lds_bwd, st, a);
     }
     {
         TokRedArgs a;
         a.cache = cache; a.map = map; a.L = L; a.d = d; a.r = r;
         a.e_tiles = cdiv(d, 128);
-        a.rows_per_se = cdiv(cdiv(M, W.se), 32) * 32;
+        a.rows_per_se = cdiv(cdiv(M, W.se), 128) * 128;
         a.se = cdiv(M, a.rows_per_se);
-        a.rows_per_sg = cdiv(cdiv(M, W.sg), 32) * 32;
+        a.rows_per_sg = cdiv(cdiv(M, W.sg), 128) * 128;
         a.sg = cdiv(M, a.rows_per_sg);
         a.tg = cdiv(Lr, 64);
         a.nb_E = L * a.e_tiles * a.se;
         a.H = H; a.DP = DP; a.Epart = Epart; a.GGpart = GGpart;
-        const int nb = a.nb_E + (L > 1 ? a.tg * a.tg * a.sg : 0);
-        PAC_LAUNCH(prof, st, KC_G_TOKRED, (k_gtokred<NT>), dim3(nb), dim3(256), 0, st, a);
+        {
+            const int counts[2] = {a.nb_E, L > 1 ? a.tg * a.tg * a.sg : 0};
+            const int classes[2] = {KC_G_TOKRED_E, KC_G_TOKRED_G};
+            launch_parts(prof, st, split, k_gtokred<NT>, a, 2, counts, classes, KC_G_TOKRED, 256);
+        }
         ReduceArgs ra;
         ra.L = L; ra.r = r; ra.sg = a.sg; ra.ntiles = ntiles; ra.nb_GG = L > 1 ? (Lr / 32) * (Lr / 32) : 0;
         ra.params = io.params; ra.PL = D.PL; ra.GGpart = GGpart; ra.cspart = cspart; ra.GGT = GGT; ra.GGsc = GGsc;
+        ra.e_elems = (int64_t)L * d * r; ra.nb_Esum = cdiv(ra.e_elems / 4, 256); ra.se = a.se; ra.Epart = Epart;
+        ra.E = (float *)(ws + W.g_E);
         ra.cs = cs; ra.B = B; ra.C = C; ra.HSm = HSm; ra.dz = dz; ra.Z = Z; ra.dzsum = dzsum;
-        PAC_LAUNCH(prof, st, KC_G_REDUCE, k_greduce, dim3(ra.nb_GG + cdiv(Lr, 256)), dim3(256), 0, st, ra);
+        {
+            const int counts[3] = {ra.nb_GG, ra.nb_Esum, cdiv(Lr, 64)};
+            const int classes[3] = {KC_G_REDUCE_GG, KC_G_REDUCE_E, KC_G_REDUCE_VEC};
+            launch_parts(prof, st, split, k_greduce, ra, 3, counts, classes, KC_G_REDUCE, 256);
+        }
         PostArgs pa;
-        pa.L = L; pa.d = d; pa.r = r; pa.C = C; pa.B = B; pa.se = a.se;
+        pa.L = L; pa.d = d; pa.r = r; pa.C = C; pa.B = B; pa.se = 1;
         pa.nb_F = L * cdiv(d, 64) * cdiv(r, 64); pa.nb_W = pa.nb_F; pa.nb_vec = cdiv(d, 256 / L) + 1;
         pa.params = io.params; pa.PL = D.PL; pa.WuTs = WuTs; pa.Wds = Wds; pa.GGT = GGT; pa.GGsc = GGsc;
-        pa.Epart = Epart; pa.cusum = cusum; pa.cs = cs; pa.Z = Z; pa.dzsum = dzsum; pa.dz = dz; pa.pb = pb;
+        pa.Epart = (const float *)(ws + W.g_E); pa.cusum = cusum; pa.cs = cs; pa.Z = Z; pa.dzsum = dzsum; pa.dz = dz; pa.pb = pb;
         pa.grads = io.grads; pa.dlam_part = dlam_part; pa.counter = counter;
         pa.slots = cdiv(d, 64) * cdiv(r, 64);
-        PAC_LAUNCH(prof, st, KC_G_POST, k_gpost, dim3(pa.nb_F + pa.nb_W + pa.nb_vec), dim3(256), 0, st, pa);
+        {
+            const int counts[3] = {pa.nb_F, pa.nb_W, pa.nb_vec};
+            const int classes[3] = {KC_G_POST_F, KC_G_POST_W, KC_G_POST_VEC};
+            launch_parts(prof, st, split, k_gpost, pa, 3, counts, classes, KC_G_POST, 256);
+        }
+        PAC_LAUNCH(prof, st, KC_G_FINISH, k_gfinish, dim3(1), dim3(64), 0, st, loss_part, B, io.loss_out, dlam_part,
+                   pa.slots, L, D.PL, io.grads);
     }
     return hipGetLastError();
 }

@@ -13,7 +13,8 @@
 
 namespace pac {
 
-using T64 = Tile<2, 2, 1, 1, 1>; // 64 x 64 workgroup tile, 64 bytes of K per step
+using T64 = Tile<2, 2, 1, 1, 1>;  // 64 x 64 workgroup tile, 64 bytes of K per step
+using T64K = Tile<2, 2, 1, 1, 4>; // same tile, 256 bytes of K per step (token reductions)
 
 // launch, optionally bracketed by timing events of its kernel class
 #define PAC_LAUNCH(prof, st, cls, ...)                         \
@@ -484,31 +485,27 @@ struct EpiStore {
 };
 
 template <typename TC, class BL>
-__device__ __forceinline__ void write_colsums(BL &bl, float *dst, int ncols, int j0)
+__device__ __forceinline__ void write_colsums(BL &bl, float *red /* 256 * CE floats of LDS */, float *dst,
+                                              int ncols, int j0)
 {
-    // every thread owns the columns of chunk (t % CPR); sum over the threads that share them
-    using T = Traits<TC>;
-    using G = ColsGeom<TC, 64, 1>;
-    __shared__ float red[kThreads * T::CE];
-    float mine[T::CE];
-    for (int e = 0; e < T::CE; ++e) {
-        mine[e] = 0.f;
-        for (int u = 0; u < G::NCH; ++u) mine[e] += bl.sums[u][e];
-    }
-    for (int e = 0; e < T::CE; ++e) red[threadIdx.x * T::CE + e] = mine[e];
+    // every thread owns the CE columns of i-block (t % IB); sum over the threads that share them
+    using G = ColsGeom<TC, 64, 4>;
+    __syncthreads();
+    for (int e = 0; e < G::CE; ++e) red[threadIdx.x * G::CE + e] = bl.sums[e];
     __syncthreads();
     if ((int)threadIdx.x < 64) {
         const int col = threadIdx.x; // column within the tile
-        const int chunk = col / T::CE, e = col % T::CE;
+        const int blk = col / G::CE, e = col % G::CE;
         float acc = 0.f;
-        for (int t = chunk; t < kThreads; t += G::CPR) acc += red[t * T::CE + e];
+        for (int t = blk; t < kThreads; t += G::IB) acc += red[t * G::CE + e];
         if (j0 + col < ncols) dst[j0 + col] = acc;
     }
 }
 
 template <typename TC> __global__ __launch_bounds__(256) void k_bwd_wgrad(BwdWgradArgs<TC> a)
 {
-    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64K>()];
+    static_assert(tile_lds_bytes<TC, T64K>() >= 256 * 8 * 4, "column-sum scratch must fit");
     const int M = a.map.M;
     const int kbegin = blockIdx.y * a.rows_per_split;
     const int kend = min(M, kbegin + a.rows_per_split);
@@ -517,24 +514,24 @@ template <typename TC> __global__ __launch_bounds__(256) void k_bwd_wgrad(BwdWgr
     if (blockIdx.z == 0) {
         const int tj = a.d / 64 + (a.d % 64 ? 1 : 0);
         const int ti = blockIdx.x / tj, tjx = blockIdx.x % tj;
-        LoadCols<TC, 64, 1, TC, false> al;
+        LoadCols<TC, 64, 4, TC, false> al;
         al.src = a.h; al.ld = a.r; al.ncols = a.r; al.kend = kend;
-        LoadCols<TC, 64, 1, float, true> bl;
+        LoadCols<TC, 64, 4, float, true> bl;
         bl.src = a.ds; bl.ld = a.d; bl.ncols = a.d; bl.kend = kend;
         EpiStore epi{part + dr + a.r, a.d};
-        gemm_tile<TC, T64>(smem, al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.r, a.d);
-        if (ti == 0) write_colsums<TC>(bl, part + 2 * dr + a.r, a.d, tjx * 64);
+        gemm_tile<TC, T64K>(smem, al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.r, a.d);
+        if (ti == 0) write_colsums<TC>(bl, reinterpret_cast<float *>(smem), part + 2 * dr + a.r, a.d, tjx * 64);
     } else {
         const int tj = a.r / 64 + (a.r % 64 ? 1 : 0);
         const int ti = blockIdx.x / tj, tjx = blockIdx.x % tj;
-        LoadColsX<TC, 64, 1> al;
+        LoadColsX<TC, 64, 4> al;
         al.cache = a.cache; al.map = a.map; al.layer = a.layer; al.s_prev = a.s_prev; al.ld_s = a.d;
         al.lam = *a.lam; al.ncols = a.d; al.kend = kend;
-        LoadCols<TC, 64, 1, TC, true> bl;
+        LoadCols<TC, 64, 4, TC, true> bl;
         bl.src = a.dpre; bl.ld = a.r; bl.ncols = a.r; bl.kend = kend;
         EpiStore epi{part, a.r};
-        gemm_tile<TC, T64>(smem, al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.d, a.r);
-        if (ti == 0) write_colsums<TC>(bl, part + dr, a.r, tjx * 64);
+        gemm_tile<TC, T64K>(smem, al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.d, a.r);
+        if (ti == 0) write_colsums<TC>(bl, reinterpret_cast<float *>(smem), part + dr, a.r, tjx * 64);
     }
 }
 
@@ -701,7 +698,7 @@ static hipError_t run_loss_grad(const Dims &D, const WsLayout &W, const BatchMet
                        meta.B, M, d, D.C, rowsamp, samp_len, grads + (int64_t)L * PL,
                        grads + (int64_t)L * PL + (int64_t)d * D.C, ds, rows_per_block);
 
-    const int kstep = Stage<TC, 1>::BK;
+    const int kstep = Stage<TC, 4>::BK;
     int splits = W.splits;
     int rows_per_split = cdiv(cdiv(M, splits), kstep) * kstep;
     splits = cdiv(M, rows_per_split);
