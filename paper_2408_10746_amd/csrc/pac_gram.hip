@@ -41,7 +41,7 @@ static int64_t chain_lds_bytes(const Dims &D)
 {
     // the forward chain's LDS (see chain_lds below): operand tiles of every layer, the input ring, vectors
     return (int64_t)D.L * kChainRows * (D.r + kChainPad) * 2 + 4 * (int64_t)kChainRows * D.r * 4 +
-           (int64_t)D.L * D.r * 8 + (int64_t)(D.L + 4) * 4;
+           2 * (int64_t)kChainRows * D.r * 2 + (int64_t)D.L * D.r * 8 + (int64_t)(D.L + 4) * 4;
 }
 
 bool gram_path_fits(const Dims &D)
@@ -258,14 +258,23 @@ struct EpiStoreF32 {
     __device__ void operator()(int row, int col, float v) const { out[(int64_t)row * ld + col] = v; }
 };
 
+// Q is stored twice, each time in the order the chain kernels' matrix instructions consume it
+// ("fragment-major"): for the contraction sum_kk A[.][kk] B[n][kk], element B[n][kk] sits at
+//   ((n/32 * r/16 + kk/16) * 64 + (n%32) + 32*((kk%16)/8)) * 8 + kk%8,
+// so that one wavefront load of a 32-column x 16-deep operand fragment reads 1 KB contiguously.
+__device__ __forceinline__ int64_t frag_index(int n, int kk, int r)
+{
+    return ((int64_t)((n >> 5) * (r >> 4) + (kk >> 4)) * 64 + (n & 31) + 32 * ((kk & 15) >> 3)) * 8 + (kk & 7);
+}
+
 struct EpiQ {
     bf16_t *qn, *qt;
     int r;
     float one_minus_lam; // of the later layer of the pair: the backward chain uses (1-lambda_l) Q_{kl}
     __device__ void operator()(int row, int col, float v) const
     {
-        qn[(int64_t)row * r + col] = static_cast<bf16_t>(one_minus_lam * v);
-        qt[(int64_t)col * r + row] = static_cast<bf16_t>(v);
+        qn[frag_index(row, col, r)] = static_cast<bf16_t>(one_minus_lam * v); // backward: B[n=row][kk=col]
+        qt[frag_index(col, row, r)] = static_cast<bf16_t>(v);                 // forward:  B[n=col][kk=row]
     }
 };
 
@@ -394,7 +403,8 @@ static size_t chain_lds(int L, int r, bool fwd)
 {
     const size_t hs = (size_t)L * kChainRows * (r + kChainPad) * 2;
     const size_t ring = (size_t)kRing * kChainRows * r * (fwd ? 4 : 2);
-    return hs + ring + (size_t)L * r * 4 * 2 + (size_t)((L + 3) / 4 * 4) * 4;
+    const size_t gstage = fwd ? (size_t)2 * kChainRows * r * 2 : 0;
+    return hs + ring + gstage + (size_t)L * r * 4 * 2 + (size_t)((L + 3) / 4 * 4) * 4;
 }
 
 // GELU(u) and GELU'(u) from one exponential: erf by the five-term rational approximation of
@@ -416,15 +426,17 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
 {
     extern __shared__ __attribute__((aligned(16))) char dyn_smem[];
     constexpr int r = 32 * NT, RP = r + kChainPad, KQ = r / 16;
-    constexpr int GP = 4; // layer pairs whose operands are requested together
+    constexpr int GP = 4; // layer pairs per operand group
     using RingT = typename std::conditional<FWD, float, bf16_t>::type;
     constexpr int kTileBytes = kChainRows * r * (int)sizeof(RingT);
     constexpr int kChunksPerLane = kTileBytes / 16 / 64; // 16-byte chunks each helper lane moves per layer
+    constexpr int kGChunks = kChainRows * r * 2 / 16 / 64; // same for a GELU' tile (bf16)
     static_assert(kTileBytes % (16 * 64) == 0, "ring tile must split evenly over the helper wavefront");
     const int L = a.L;
     bf16_t *Hs = reinterpret_cast<bf16_t *>(dyn_smem);                                      // [L][32][RP]
     RingT *ring = reinterpret_cast<RingT *>(Hs + (size_t)L * kChainRows * RP);              // [kRing][32][r]
-    float *vecS = reinterpret_cast<float *>(ring + (size_t)kRing * kChainRows * r);         // [L][r]
+    bf16_t *Gst = reinterpret_cast<bf16_t *>(ring + (size_t)kRing * kChainRows * r);        // [2][32][r] (forward)
+    float *vecS = reinterpret_cast<float *>(Gst + (FWD ? (size_t)2 * kChainRows * r : 0));  // [L][r]
     float *Cs = vecS + (size_t)L * r;                                                       // [L][r]
     float *lamS = Cs + (size_t)L * r;                                                       // [L]
     const int tile = blockIdx.x;
@@ -448,7 +460,9 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
     for (int l = threadIdx.x; l < L; l += nthreads) lamS[l] = a.params[(int64_t)l * a.PL + a.PL - 1];
 
     if (wave == NT) {
-        // ---- helper wavefront: keep the ring filled three layers ahead ----
+        // ---- helper wavefront: all global traffic of the per-token tiles.  It keeps the input ring
+        // filled three layers ahead and (forward) writes out the GELU' tile of the layer just finished,
+        // so the contracting wavefronts issue no global store and wait on no per-token load.
         const RingT *src = FWD ? reinterpret_cast<const RingT *>(a.U) : reinterpret_cast<const RingT *>(a.Gp);
         constexpr int EPC = 16 / (int)sizeof(RingT); // elements per chunk
         auto fetch = [&](int step, uint4(&reg)[kChunksPerLane]) {
@@ -466,6 +480,16 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
 #pragma unroll
             for (int q = 0; q < kChunksPerLane; ++q) *reinterpret_cast<uint4 *>(dst + (lane + 64 * q) * EPC) = reg[q];
         };
+        auto drain = [&](int step) { // GELU' tile of a finished step: LDS staging -> global
+            if (!FWD || step < 0 || step >= L) return;
+            const bf16_t *st = Gst + (size_t)(step & 1) * kChainRows * r;
+            bf16_t *dst = a.Gp + ((int64_t)layer_at(step) * a.M + m0) * r;
+#pragma unroll
+            for (int q = 0; q < kGChunks; ++q) {
+                const int e = (lane + 64 * q) * 8;
+                if (e < nrows * r) *reinterpret_cast<uint4 *>(dst + e) = *reinterpret_cast<const uint4 *>(st + e);
+            }
+        };
         uint4 ra[kChunksPerLane], rb[kChunksPerLane], rc[kChunksPerLane];
         fetch(0, ra);
         fetch(1, rb);
@@ -474,82 +498,125 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
         __syncthreads();
         // before the barrier that ends step s the tile of step s+1 must be in the ring
         for (int s = 0; s < L; s += 3) {
-            fetch(s + 3, ra);
+            // the tile consumed here was requested two steps ago; the new request goes out after it
+            // so that waiting for the old one never means waiting for the new one
             put(s + 1, rb);
+            drain(s - 1);
+            fetch(s + 3, ra);
             __syncthreads();
             if (s + 1 < L) {
-                fetch(s + 4, rb);
                 put(s + 2, rc);
+                drain(s);
+                fetch(s + 4, rb);
                 __syncthreads();
             }
             if (s + 2 < L) {
-                fetch(s + 5, rc);
                 put(s + 3, ra);
+                drain(s + 1);
+                fetch(s + 5, rc);
                 __syncthreads();
             }
         }
+        drain(L - 1);
     } else {
         // ---- contracting wavefronts ----
+        // The (k, l) layer pairs of the whole kernel form one sequence; their r x r operands do not
+        // depend on anything computed here, so they are requested kDepth pairs ahead of their use
+        // (across layer boundaries) into a register FIFO.
+        constexpr int kDepth = NT == 4 ? 4 : 8; // bounded by the register file at 320 threads per workgroup
         const int i = lane & 31, g = lane >> 5;
         const int n = 32 * wave + i;
-        __syncthreads();
-        for (int step = 0; step < L; ++step) {
-            const int l = layer_at(step);
-            f32x16 acc;
+        auto k_first = [&](int step) { return FWD ? 0 : layer_at(step) + 1; };
+        auto k_last = [&](int step) { return FWD ? layer_at(step) : L; };
+        int ls = 0, lk = 0; // next pair to request
+        while (ls < L && k_first(ls) >= k_last(ls)) ++ls;
+        if (ls < L) lk = k_first(ls);
+        auto issue = [&](bf16x8(&bq)[KQ]) {
+            if (ls >= L) return;
+            const int l = layer_at(ls);
+            const bf16_t *Qp = a.Q + (FWD ? pair_index(lk, l) : pair_index(l, lk)) * rr + (int64_t)wave * KQ * 512;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-            const int k0 = FWD ? 0 : l + 1, k1 = FWD ? l : L;
-            for (int kb = k0; kb < k1; kb += GP) {
-                bf16x8 bq[GP][KQ];
-#pragma unroll
-                for (int u = 0; u < GP; ++u) {
-                    const int k = kb + u < k1 ? kb + u : k1 - 1;
-                    const bf16_t *Qrow = a.Q + (FWD ? pair_index(k, l) : pair_index(l, k)) * rr + (int64_t)n * r;
-#pragma unroll
-                    for (int q = 0; q < KQ; ++q) bq[u][q] = *reinterpret_cast<const bf16x8 *>(Qrow + 16 * q + 8 * g);
-                }
-#pragma unroll
-                for (int u = 0; u < GP; ++u) {
-                    if (kb + u < k1) {
-                        const bf16_t *Hk = Hs + ((int64_t)(kb + u) * kChainRows + i) * RP;
-#pragma unroll
-                        for (int q = 0; q < KQ; ++q) {
-                            const bf16x8 av = *reinterpret_cast<const bf16x8 *>(Hk + 16 * q + 8 * g);
-                            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bq[u][q], acc, 0, 0, 0);
-                        }
-                    }
-                }
+            for (int q = 0; q < KQ; ++q) bq[q] = *reinterpret_cast<const bf16x8 *>(Qp + (q * 64 + lane) * 8);
+            if (++lk >= k_last(ls)) {
+                ++ls;
+                while (ls < L && k_first(ls) >= k_last(ls)) ++ls;
+                if (ls < L) lk = k_first(ls);
             }
+        };
+        bf16x8 fifo[kDepth][KQ];
+#pragma unroll
+        for (int slot = 0; slot < kDepth; ++slot) issue(fifo[slot]);
+        // two accumulators so that consecutive matrix instructions do not depend on each other
+        f32x16 acc0, acc1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            acc0[v] = 0.f;
+            acc1[v] = 0.f;
+        }
+        auto contract = [&](const bf16x8(&bq)[KQ], int k) {
+            const bf16_t *Hk = Hs + ((int64_t)k * kChainRows + i) * RP;
+            bf16x8 av[KQ];
+#pragma unroll
+            for (int q = 0; q < KQ; ++q) av[q] = *reinterpret_cast<const bf16x8 *>(Hk + 16 * q + 8 * g);
+#pragma unroll
+            for (int q = 0; q < KQ; q += 2) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[q], bq[q], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[q + 1], bq[q + 1], acc1, 0, 0, 0);
+            }
+        };
+        auto finish_layer = [&](int step) { // nonlinearity, tiles to LDS, barrier
+            const int l = layer_at(step);
             const float lam = lamS[l];
             const float cvec = vecS[l * r + n];
             const RingT *rt = ring + (size_t)(step % kRing) * kChainRows * r;
+            bf16_t *gst = Gst + (size_t)(step & 1) * kChainRows * r;
             float colsum = 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = 8 * (v >> 2) + 4 * g + (v & 3);
                 const bool valid = row < nrows;
                 const float uin = to_f32(rt[row * r + n]);
+                const float accv = acc0[v] + acc1[v];
                 float out = 0.f;
                 if (FWD) {
-                    const float pre = lam * uin + (1.f - lam) * acc[v] + cvec;
+                    const float pre = lam * uin + (1.f - lam) * accv + cvec;
                     float h, gp;
                     gelu_pair(pre, h, gp);
-                    if (valid) {
-                        out = h;
-                        a.Gp[((int64_t)l * a.M + m0 + row) * r + n] = static_cast<bf16_t>(gp);
-                    }
+                    if (valid) out = h;
+                    gst[row * r + n] = static_cast<bf16_t>(gp);
                 } else {
-                    if (valid) out = (cvec + acc[v]) * uin;
+                    if (valid) out = (cvec + accv) * uin;
                 }
                 Hs[((int64_t)l * kChainRows + row) * RP + n] = static_cast<bf16_t>(out);
                 colsum += out;
+                acc0[v] = 0.f;
+                acc1[v] = 0.f;
             }
             colsum += __shfl_xor(colsum, 32, 64);
             if (g == 0) Cs[l * r + n] = colsum;
             __syncthreads();
+        };
+        __syncthreads();
+        int cs = 0, ck = 0; // pair being contracted
+        while (cs < L && k_first(cs) >= k_last(cs)) finish_layer(cs++);
+        if (cs < L) ck = k_first(cs);
+        while (cs < L) {
+#pragma unroll
+            for (int slot = 0; slot < kDepth; ++slot) {
+                if (cs < L) {
+                    contract(fifo[slot], ck);
+                    issue(fifo[slot]);
+                    if (++ck >= k_last(cs)) {
+                        finish_layer(cs++);
+                        while (cs < L && k_first(cs) >= k_last(cs)) finish_layer(cs++);
+                        if (cs < L) ck = k_first(cs);
+                    }
+                }
+            }
         }
     }
     // flush: 16-byte chunks of the valid rows, then the column sums
+    __syncthreads();
     const int chunks_per_row = r / 8;
     for (int c = threadIdx.x; c < L * kChainRows * chunks_per_row; c += nthreads) {
         const int l = c / (kChainRows * chunks_per_row);
