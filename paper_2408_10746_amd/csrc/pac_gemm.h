@@ -69,6 +69,7 @@ template <typename TC, int ROWS, int KU> struct RowsGeom {
 };
 
 template <typename TC, int ROWS, int KU> struct LoadRowsTC {
+    static constexpr bool kSwizzled = false;
     using S = Stage<TC, KU>;
     using G = RowsGeom<TC, ROWS, KU>;
     const TC *src;
@@ -111,6 +112,7 @@ template <typename TC, int ROWS, int KU> struct LoadRowsTC {
 };
 
 template <typename TC, int ROWS, int KU> struct LoadRowsF32 {
+    static constexpr bool kSwizzled = false;
     using S = Stage<TC, KU>;
     using G = RowsGeom<TC, ROWS, KU>;
     const float *src;
@@ -169,6 +171,7 @@ struct RowMap {
 
 // x[m][k] = lam * b_l[m][k] + (1 - lam) * s_prev[m][k]   (s_prev == nullptr: x = lam * b)
 template <typename TC, int ROWS, int KU> struct LoadRowsX {
+    static constexpr bool kSwizzled = false;
     using S = Stage<TC, KU>;
     using G = RowsGeom<TC, ROWS, KU>;
     const TC *cache;
@@ -280,6 +283,14 @@ __device__ __forceinline__ void transpose_block(const Chunk<float> (&in)[4], Chu
         for (int k = 0; k < 4; ++k) out[i].e[k] = in[k].e[i];
 }
 
+// With 256-byte K rows of bf16 the transposed stores of one instruction hit rows 8 apart, i.e.
+// the same LDS banks; the 16-byte chunk index of row i is therefore XOR-ed with (i / 16) % 8
+// ("swizzle"), which spreads those stores over all banks.  The MFMA fragment reads apply the same XOR.
+template <typename TC, int KU> struct ColsSwizzle {
+    static constexpr bool value = sizeof(TC) == 2 && KU == 4;
+};
+__device__ __forceinline__ int swizzle_of_row(int row) { return (row >> 4) & 7; }
+
 template <typename TC, int ROWS, int KU> struct ColsStore {
     using S = Stage<TC, KU>;
     using G = ColsGeom<TC, ROWS, KU>;
@@ -294,14 +305,18 @@ template <typename TC, int ROWS, int KU> struct ColsStore {
                 Chunk<TC> tr[G::CE];
                 transpose_block(reg[u], tr);
 #pragma unroll
-                for (int e = 0; e < G::CE; ++e)
-                    *reinterpret_cast<Chunk<TC> *>(lds + (ib * G::CE + e) * S::LDP + kb * G::CE) = tr[e];
+                for (int e = 0; e < G::CE; ++e) {
+                    const int row = ib * G::CE + e;
+                    const int chunk = ColsSwizzle<TC, KU>::value ? (kb ^ swizzle_of_row(row)) : kb;
+                    *reinterpret_cast<Chunk<TC> *>(lds + row * S::LDP + chunk * G::CE) = tr[e];
+                }
             }
         }
     }
 };
 
 template <typename TC, int ROWS, int KU, typename SRC, bool SUMS> struct LoadCols {
+    static constexpr bool kSwizzled = ColsSwizzle<TC, KU>::value;
     using S = Stage<TC, KU>;
     using G = ColsGeom<TC, ROWS, KU>;
     static_assert(!SUMS || kThreads % G::IB == 0, "column sums need a fixed column block per thread");
@@ -352,6 +367,7 @@ template <typename TC, int ROWS, int KU, typename SRC, bool SUMS> struct LoadCol
 
 // operand[i][k] = x[k][i] = lam * b_l[k][i] + (1 - lam) * s_prev[k][i]
 template <typename TC, int ROWS, int KU> struct LoadColsX {
+    static constexpr bool kSwizzled = ColsSwizzle<TC, KU>::value;
     using S = Stage<TC, KU>;
     using G = ColsGeom<TC, ROWS, KU>;
     const TC *cache;
@@ -403,7 +419,7 @@ template <typename TC, int ROWS, int KU> struct LoadColsX {
 // ---------------------------------------------------------------------------
 // MFMA step on one staged K tile
 // ---------------------------------------------------------------------------
-template <int KU, int WTM, int WTN>
+template <int KU, int WTM, int WTN, bool SWA, bool SWB>
 __device__ __forceinline__ void mma_tile(const bf16_t *As, const bf16_t *Bs, f32x16 (&acc)[WTM][WTN],
                                          int arow0, int brow0, int lane)
 {
@@ -413,11 +429,17 @@ __device__ __forceinline__ void mma_tile(const bf16_t *As, const bf16_t *Bs, f32
     for (int q = 0; q < S::BK / 16; ++q) {
         bf16x8 a[WTM], b[WTN];
 #pragma unroll
-        for (int x = 0; x < WTM; ++x)
-            a[x] = *reinterpret_cast<const bf16x8 *>(As + (arow0 + x * 32 + i) * S::LDP + q * 16 + g * 8);
+        for (int x = 0; x < WTM; ++x) {
+            const int row = arow0 + x * 32 + i;
+            const int chunk = SWA ? ((2 * q + g) ^ swizzle_of_row(row)) : 2 * q + g;
+            a[x] = *reinterpret_cast<const bf16x8 *>(As + row * S::LDP + chunk * 8);
+        }
 #pragma unroll
-        for (int y = 0; y < WTN; ++y)
-            b[y] = *reinterpret_cast<const bf16x8 *>(Bs + (brow0 + y * 32 + i) * S::LDP + q * 16 + g * 8);
+        for (int y = 0; y < WTN; ++y) {
+            const int row = brow0 + y * 32 + i;
+            const int chunk = SWB ? ((2 * q + g) ^ swizzle_of_row(row)) : 2 * q + g;
+            b[y] = *reinterpret_cast<const bf16x8 *>(Bs + row * S::LDP + chunk * 8);
+        }
 #pragma unroll
         for (int x = 0; x < WTM; ++x)
 #pragma unroll
@@ -426,7 +448,7 @@ __device__ __forceinline__ void mma_tile(const bf16_t *As, const bf16_t *Bs, f32
     }
 }
 
-template <int KU, int WTM, int WTN>
+template <int KU, int WTM, int WTN, bool SWA, bool SWB>
 __device__ __forceinline__ void mma_tile(const float *As, const float *Bs, f32x16 (&acc)[WTM][WTN],
                                          int arow0, int brow0, int lane)
 {
@@ -495,7 +517,8 @@ __device__ __forceinline__ void gemm_tile(void *lds /* tile_lds_bytes<TC, TL>(),
             al.fetch(k0 + S::BK);
             bl.fetch(k0 + S::BK);
         }
-        mma_tile<TL::KU, TL::WTM, TL::WTN>(As, Bs, acc, wm * TL::WTM * 32, wn * TL::WTN * 32, lane);
+        mma_tile<TL::KU, TL::WTM, TL::WTN, ALoad::kSwizzled, BLoad::kSwizzled>(As, Bs, acc, wm * TL::WTM * 32,
+                                                                              wn * TL::WTN * 32, lane);
         __syncthreads();
     }
     const int i = lane & 31, g = lane >> 5;

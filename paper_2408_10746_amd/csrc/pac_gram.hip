@@ -59,12 +59,12 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.max_tiles = D.B_max * cdiv(D.n_max, kChainRows);
     W.pairs = D.L * (D.L - 1) / 2;
     const int e_tiles = D.L * cdiv(D.d, 128);
-    int se = cdiv(768, e_tiles);
+    int se = cdiv(288, e_tiles);
     const int max_by_rows = (int)((D.Mmax + 127) / 128);
     if (se > max_by_rows) se = max_by_rows;
     W.se = se < 1 ? 1 : (se > 16 ? 16 : se);
-    const int tg = cdiv(Lr, 64);
-    int sg = cdiv(768, (int64_t)tg * (tg + 1) / 2);
+    const int tg = cdiv(Lr, 128);
+    int sg = cdiv(256, (int64_t)tg * (tg + 1) / 2);
     if (sg > max_by_rows) sg = max_by_rows;
     W.sg = sg < 1 ? 1 : (sg > 16 ? 16 : sg);
     W.g_tile_row0 = take(W.max_tiles * 4);
@@ -288,6 +288,7 @@ struct EpiChat {
 
 using T64 = Tile<2, 2, 1, 1, 1>;
 using T64K = Tile<2, 2, 1, 1, 4>; // 128-token K step for the token contractions
+using TG = Tile<2, 2, 2, 2, 4>;   // 128 x 128 tile of the Gram matrix
 
 template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArgs a)
 {
@@ -470,8 +471,10 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
             const RingT *base = src + ((int64_t)layer_at(step) * a.M + m0) * r;
 #pragma unroll
             for (int q = 0; q < kChunksPerLane; ++q) {
-                const int e = (lane + 64 * q) * EPC;
-                reg[q] = e < nrows * r ? *reinterpret_cast<const uint4 *>(base + e) : make_uint4(0, 0, 0, 0);
+                // rows past the end of a short tile re-read the tile's last chunk (never used: the
+                // contracting wavefronts mask those rows); no branch, no register is zeroed
+                const int e = min((lane + 64 * q) * EPC, nrows * r - EPC);
+                reg[q] = *reinterpret_cast<const uint4 *>(base + e);
             }
         };
         auto put = [&](int step, const uint4(&reg)[kChunksPerLane]) {
@@ -528,19 +531,27 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
         const int n = 32 * wave + i;
         auto k_first = [&](int step) { return FWD ? 0 : layer_at(step) + 1; };
         auto k_last = [&](int step) { return FWD ? layer_at(step) : L; };
-        int ls = 0, lk = 0; // next pair to request
+        // next pair to request.  A request is issued for every FIFO slot on every path (once the
+        // sequence is exhausted the last pair is requested again and never used): the compiler can
+        // then count the loads in flight and wait only for the oldest ones.
+        int ls = 0, lk = 0;
         while (ls < L && k_first(ls) >= k_last(ls)) ++ls;
         if (ls < L) lk = k_first(ls);
+        const int total_pairs = L * (L - 1) / 2;
         auto issue = [&](bf16x8(&bq)[KQ]) {
-            if (ls >= L) return;
-            const int l = layer_at(ls);
-            const bf16_t *Qp = a.Q + (FWD ? pair_index(lk, l) : pair_index(l, lk)) * rr + (int64_t)wave * KQ * 512;
+            const int lsc = ls < L ? ls : L - 1;
+            const int l = layer_at(lsc);
+            int kq = lk;
+            if (total_pairs == 0) kq = 0;
+            const int pi = total_pairs == 0 ? 0 : (FWD ? pair_index(kq, l) : pair_index(l, kq));
+            const bf16_t *Qp = a.Q + pi * rr + (int64_t)wave * KQ * 512;
 #pragma unroll
             for (int q = 0; q < KQ; ++q) bq[q] = *reinterpret_cast<const bf16x8 *>(Qp + (q * 64 + lane) * 8);
-            if (++lk >= k_last(ls)) {
+            if (ls < L && ++lk >= k_last(ls)) {
                 ++ls;
                 while (ls < L && k_first(ls) >= k_last(ls)) ++ls;
                 if (ls < L) lk = k_first(ls);
+                else { ls = L; lk = FWD ? L - 2 : L - 1; } // stay on the last pair: (L-2, L-1) / (0, L-1)
             }
         };
         bf16x8 fifo[kDepth][KQ];
@@ -600,18 +611,18 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
         int cs = 0, ck = 0; // pair being contracted
         while (cs < L && k_first(cs) >= k_last(cs)) finish_layer(cs++);
         if (cs < L) ck = k_first(cs);
-        while (cs < L) {
+        for (int p0 = 0; p0 < total_pairs; p0 += kDepth) {
 #pragma unroll
             for (int slot = 0; slot < kDepth; ++slot) {
-                if (cs < L) {
+                if (p0 + slot < total_pairs) {
                     contract(fifo[slot], ck);
-                    issue(fifo[slot]);
                     if (++ck >= k_last(cs)) {
                         finish_layer(cs++);
                         while (cs < L && k_first(cs) >= k_last(cs)) finish_layer(cs++);
                         if (cs < L) ck = k_first(cs);
                     }
                 }
+                issue(fifo[slot]);
             }
         }
     }
@@ -724,8 +735,8 @@ struct TokRedArgs {
 template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
 {
     using TE = Tile<4, 1, 1, NT, 4>;
-    constexpr int kLds = tile_lds_bytes<bf16_t, TE>() > tile_lds_bytes<bf16_t, T64K>() ? tile_lds_bytes<bf16_t, TE>()
-                                                                                       : tile_lds_bytes<bf16_t, T64K>();
+    constexpr int kLds = tile_lds_bytes<bf16_t, TE>() > tile_lds_bytes<bf16_t, TG>() ? tile_lds_bytes<bf16_t, TE>()
+                                                                                     : tile_lds_bytes<bf16_t, TG>();
     __shared__ __attribute__((aligned(16))) char smem[kLds];
     const int b = blockIdx.x + a.blk_off;
     const int M = a.map.M;
@@ -751,17 +762,17 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         idx /= a.sg;
         const int ti = idx / a.tg, tj = idx % a.tg;
         // needed only where some row layer is below some column layer
-        const int kmin = (ti * 64) / a.r;
-        const int lmax = min(Lr - 1, tj * 64 + 63) / a.r;
+        const int kmin = (ti * TG::BM) / a.r;
+        const int lmax = min(Lr - 1, tj * TG::BN + TG::BN - 1) / a.r;
         if (kmin >= lmax) return;
         const int kbegin = split * a.rows_per_sg;
         const int kend = min(M, kbegin + a.rows_per_sg);
-        LoadCols<bf16_t, 64, 4, bf16_t, false> al;
+        LoadCols<bf16_t, TG::BM, 4, bf16_t, false> al;
         al.src = a.H; al.ld = Lr; al.ncols = Lr; al.kend = kend;
-        LoadCols<bf16_t, 64, 4, bf16_t, false> bl;
+        LoadCols<bf16_t, TG::BN, 4, bf16_t, false> bl;
         bl.src = a.DP; bl.ld = Lr; bl.ncols = Lr; bl.kend = kend;
         EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
-        gemm_tile<bf16_t, T64K>(smem, al, bl, epi, kbegin, kend, ti * 64, tj * 64, Lr, Lr);
+        gemm_tile<bf16_t, TG>(smem, al, bl, epi, kbegin, kend, ti * TG::BM, tj * TG::BN, Lr, Lr);
     }
 }
 
@@ -1163,7 +1174,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.se = cdiv(M, a.rows_per_se);
         a.rows_per_sg = cdiv(cdiv(M, W.sg), 128) * 128;
         a.sg = cdiv(M, a.rows_per_sg);
-        a.tg = cdiv(Lr, 64);
+        a.tg = cdiv(Lr, 128);
         a.nb_E = L * a.e_tiles * a.se;
         a.H = H; a.DP = DP; a.Epart = Epart; a.GGpart = GGpart;
         {
