@@ -29,6 +29,7 @@ typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4))); // 16 raw bytes held in registers
 
 constexpr int kThreads = 256;
 
@@ -59,9 +60,14 @@ __device__ __forceinline__ float to_f32(bf16_t h) { return static_cast<float>(h)
 __device__ __forceinline__ float to_f32(float f) { return f; }
 
 // ---------------------------------------------------------------------------
+// Loaders.  Every loader keeps two register slots so that two K steps can be in flight.
+// fetch<SLOT>(k0) issues its loads unconditionally, from addresses clamped into valid memory,
+// and store<SLOT>() applies the validity masks when it writes the LDS image: with no branch
+// around a load the compiler can count the loads in flight and wait only for the older slot.
+// ---------------------------------------------------------------------------
+
 // Row-major loaders: operand[row][k] = src[row][k] (K contiguous in memory).
 // Chunk c = t + 256u covers row c / CPK and the 16-byte K chunk c % CPK.
-// ---------------------------------------------------------------------------
 template <typename TC, int ROWS, int KU> struct RowsGeom {
     using S = Stage<TC, KU>;
     static constexpr int TOTAL = ROWS * S::CPK;
@@ -77,8 +83,9 @@ template <typename TC, int ROWS, int KU> struct LoadRowsTC {
     int nrows;
     int kmin = 0, klim = 0x7fffffff; // K outside [kmin, klim) reads as zero (whole 16-byte chunks)
     const TC *rp[G::NCH];
-    int kc[G::NCH];
-    uint4 reg[G::NCH];
+    bool ok[G::NCH];
+    int kpos[2];
+    u32x4 reg[2][G::NCH];
     __device__ void init(int row0)
     {
         const int t = threadIdx.x;
@@ -86,27 +93,33 @@ template <typename TC, int ROWS, int KU> struct LoadRowsTC {
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
             const int row = row0 + c / S::CPK;
-            kc[u] = (c % S::CPK) * S::CE;
-            rp[u] = (c < G::TOTAL && row < nrows) ? src + (int64_t)row * ld + kc[u] : nullptr;
+            ok[u] = c < G::TOTAL && row < nrows;
+            rp[u] = src + (ok[u] ? (int64_t)row * ld : 0) + (c % S::CPK) * S::CE;
         }
     }
-    __device__ void fetch(int k0)
+    template <int SLOT> __device__ void fetch(int k0)
     {
+        kpos[SLOT] = k0;
+        const int t = threadIdx.x;
 #pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
-            const int k = k0 + kc[u];
-            reg[u] = (rp[u] && k >= kmin && k < klim) ? *reinterpret_cast<const uint4 *>(rp[u] + k0)
-                                                      : make_uint4(0, 0, 0, 0);
+            const int kc = ((t + kThreads * u) % S::CPK) * S::CE;
+            const int k = k0 + kc;
+            // masked chunks re-read the start of their row
+            reg[SLOT][u] = *reinterpret_cast<const u32x4 *>(rp[u] + ((k >= kmin && k < klim) ? k0 : -kc));
         }
     }
-    __device__ void store(TC *lds)
+    template <int SLOT> __device__ void store(TC *lds, bool live)
     {
         const int t = threadIdx.x;
 #pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
+            const int k = kpos[SLOT] + (c % S::CPK) * S::CE;
+            const bool keep = ok[u] && k >= kmin && k < klim;
             if (c < G::TOTAL)
-                *reinterpret_cast<uint4 *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * S::CE) = reg[u];
+                *reinterpret_cast<u32x4 *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * S::CE) =
+                    keep ? reg[SLOT][u] : u32x4{0, 0, 0, 0};
         }
     }
 };
@@ -119,7 +132,8 @@ template <typename TC, int ROWS, int KU> struct LoadRowsF32 {
     int64_t ld;
     int nrows;
     const float *rp[G::NCH];
-    Chunk<TC> reg[G::NCH];
+    bool ok[G::NCH];
+    f32x4 reg[2][G::NCH][S::CE / 4];
     __device__ void init(int row0)
     {
         const int t = threadIdx.x;
@@ -127,36 +141,34 @@ template <typename TC, int ROWS, int KU> struct LoadRowsF32 {
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
             const int row = row0 + c / S::CPK;
-            rp[u] = (c < G::TOTAL && row < nrows) ? src + (int64_t)row * ld + (c % S::CPK) * S::CE : nullptr;
+            ok[u] = c < G::TOTAL && row < nrows;
+            rp[u] = src + (ok[u] ? (int64_t)row * ld : 0) + (c % S::CPK) * S::CE;
         }
     }
-    __device__ void fetch(int k0)
+    template <int SLOT> __device__ void fetch(int k0)
     {
 #pragma unroll
-        for (int u = 0; u < G::NCH; ++u) {
-            if (rp[u]) {
+        for (int u = 0; u < G::NCH; ++u)
 #pragma unroll
-                for (int q = 0; q < S::CE / 4; ++q) {
-                    float4 f = *reinterpret_cast<const float4 *>(rp[u] + k0 + 4 * q);
-                    reg[u].e[4 * q + 0] = to_tc(f.x, TC());
-                    reg[u].e[4 * q + 1] = to_tc(f.y, TC());
-                    reg[u].e[4 * q + 2] = to_tc(f.z, TC());
-                    reg[u].e[4 * q + 3] = to_tc(f.w, TC());
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
-            }
-        }
+            for (int q = 0; q < S::CE / 4; ++q) reg[SLOT][u][q] = *reinterpret_cast<const f32x4 *>(rp[u] + k0 + 4 * q);
     }
-    __device__ void store(TC *lds)
+    template <int SLOT> __device__ void store(TC *lds, bool live)
     {
         const int t = threadIdx.x;
 #pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
+            Chunk<TC> v;
+#pragma unroll
+            for (int q = 0; q < S::CE / 4; ++q) {
+                const f32x4 f = reg[SLOT][u][q];
+                v.e[4 * q + 0] = to_tc(ok[u] ? f.x : 0.f, TC());
+                v.e[4 * q + 1] = to_tc(ok[u] ? f.y : 0.f, TC());
+                v.e[4 * q + 2] = to_tc(ok[u] ? f.z : 0.f, TC());
+                v.e[4 * q + 3] = to_tc(ok[u] ? f.w : 0.f, TC());
+            }
             if (c < G::TOTAL)
-                *reinterpret_cast<Chunk<TC> *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * S::CE) = reg[u];
+                *reinterpret_cast<Chunk<TC> *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * S::CE) = v;
         }
     }
 };
@@ -169,8 +181,10 @@ struct RowMap {
     int M;
 };
 
-// x[m][k] = lam * b_l[m][k] + (1 - lam) * s_prev[m][k]   (s_prev == nullptr: x = lam * b)
-template <typename TC, int ROWS, int KU> struct LoadRowsX {
+// x[m][k] = lam * b_l[m][k] + (1 - lam) * s_prev[m][k]   (MIX == false: x = lam * b, s_prev unused)
+// Whether the previous side state takes part is a compile-time choice: a run-time branch around
+// some of the loads would bring back the conservative waits.
+template <typename TC, int ROWS, int KU, bool MIX> struct LoadRowsX {
     static constexpr bool kSwizzled = false;
     using S = Stage<TC, KU>;
     using G = RowsGeom<TC, ROWS, KU>;
@@ -181,8 +195,10 @@ template <typename TC, int ROWS, int KU> struct LoadRowsX {
     int64_t ld_s;
     float lam;
     const TC *bp[G::NCH];
-    const float *sp[G::NCH];
-    Chunk<TC> reg[G::NCH];
+    const float *sp[MIX ? G::NCH : 1];
+    bool ok[G::NCH];
+    u32x4 regb[2][G::NCH];
+    f32x4 regs[2][MIX ? G::NCH : 1][S::CE / 4];
     __device__ void init(int row0)
     {
         const int t = threadIdx.x;
@@ -190,50 +206,47 @@ template <typename TC, int ROWS, int KU> struct LoadRowsX {
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
             const int row = row0 + c / S::CPK;
-            if (c < G::TOTAL && row < map.M) {
-                bp[u] = cache + map.rowoff[row] + (int64_t)layer * map.rowstride[row] + (c % S::CPK) * S::CE;
-                sp[u] = s_prev ? s_prev + (int64_t)row * ld_s + (c % S::CPK) * S::CE : nullptr;
-            } else {
-                bp[u] = nullptr;
-                sp[u] = nullptr;
-            }
+            ok[u] = c < G::TOTAL && row < map.M;
+            const int rowc = ok[u] ? row : 0;
+            bp[u] = cache + map.rowoff[rowc] + (int64_t)layer * map.rowstride[rowc] + (c % S::CPK) * S::CE;
+            if (MIX) sp[u] = s_prev + (int64_t)rowc * ld_s + (c % S::CPK) * S::CE;
         }
     }
-    __device__ void fetch(int k0)
+    template <int SLOT> __device__ void fetch(int k0)
     {
 #pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
-            if (bp[u]) {
-                Chunk<TC> b = *reinterpret_cast<const Chunk<TC> *>(bp[u] + k0);
-                if (sp[u]) {
+            regb[SLOT][u] = *reinterpret_cast<const u32x4 *>(bp[u] + k0);
+            if (MIX) {
 #pragma unroll
-                    for (int q = 0; q < S::CE / 4; ++q) {
-                        float4 s = *reinterpret_cast<const float4 *>(sp[u] + k0 + 4 * q);
-                        reg[u].e[4 * q + 0] = to_tc(lam * to_f32(b.e[4 * q + 0]) + (1.f - lam) * s.x, TC());
-                        reg[u].e[4 * q + 1] = to_tc(lam * to_f32(b.e[4 * q + 1]) + (1.f - lam) * s.y, TC());
-                        reg[u].e[4 * q + 2] = to_tc(lam * to_f32(b.e[4 * q + 2]) + (1.f - lam) * s.z, TC());
-                        reg[u].e[4 * q + 3] = to_tc(lam * to_f32(b.e[4 * q + 3]) + (1.f - lam) * s.w, TC());
-                    }
-                } else if (lam == 1.f) {
-                    reg[u] = b;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(lam * to_f32(b.e[e]), TC());
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < S::CE; ++e) reg[u].e[e] = to_tc(0.f, TC());
+                for (int q = 0; q < S::CE / 4; ++q)
+                    regs[SLOT][u][q] = *reinterpret_cast<const f32x4 *>(sp[u] + k0 + 4 * q);
             }
         }
     }
-    __device__ void store(TC *lds)
+    template <int SLOT> __device__ void store(TC *lds, bool live)
     {
         const int t = threadIdx.x;
 #pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
-            if (c < G::TOTAL)
-                *reinterpret_cast<Chunk<TC> *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * S::CE) = reg[u];
+            u32x4 out = regb[SLOT][u];
+            if (MIX || lam != 1.f) {
+                Chunk<TC> b, v;
+                __builtin_memcpy(&b, &out, 16);
+#pragma unroll
+                for (int q = 0; q < S::CE / 4; ++q) {
+                    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+                    if (MIX) s = regs[SLOT][u][q];
+                    v.e[4 * q + 0] = to_tc(lam * to_f32(b.e[4 * q + 0]) + (1.f - lam) * s[0], TC());
+                    v.e[4 * q + 1] = to_tc(lam * to_f32(b.e[4 * q + 1]) + (1.f - lam) * s[1], TC());
+                    v.e[4 * q + 2] = to_tc(lam * to_f32(b.e[4 * q + 2]) + (1.f - lam) * s[2], TC());
+                    v.e[4 * q + 3] = to_tc(lam * to_f32(b.e[4 * q + 3]) + (1.f - lam) * s[3], TC());
+                }
+                __builtin_memcpy(&out, &v, 16);
+            }
+            if (!ok[u]) out = u32x4{0, 0, 0, 0};
+            if (c < G::TOTAL) *reinterpret_cast<u32x4 *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * S::CE) = out;
         }
     }
 };
@@ -291,41 +304,38 @@ template <typename TC, int KU> struct ColsSwizzle {
 };
 __device__ __forceinline__ int swizzle_of_row(int row) { return (row >> 4) & 7; }
 
-template <typename TC, int ROWS, int KU> struct ColsStore {
+// Writes one thread's transposed blocks; `blk` holds the (already masked) CE x CE block of slot u.
+template <typename TC, int ROWS, int KU>
+__device__ __forceinline__ void cols_store_block(TC *lds, int c, const Chunk<TC> (&blk)[Traits<TC>::CE])
+{
     using S = Stage<TC, KU>;
     using G = ColsGeom<TC, ROWS, KU>;
-    __device__ static void store(TC *lds, const Chunk<TC> (&reg)[G::NCH][G::CE])
-    {
-        const int t = threadIdx.x;
+    const int ib = c % G::IB, kb = c / G::IB;
+    Chunk<TC> tr[G::CE];
+    transpose_block(blk, tr);
 #pragma unroll
-        for (int u = 0; u < G::NCH; ++u) {
-            const int c = t + kThreads * u;
-            if (c < G::TOTAL) {
-                const int ib = c % G::IB, kb = c / G::IB;
-                Chunk<TC> tr[G::CE];
-                transpose_block(reg[u], tr);
-#pragma unroll
-                for (int e = 0; e < G::CE; ++e) {
-                    const int row = ib * G::CE + e;
-                    const int chunk = ColsSwizzle<TC, KU>::value ? (kb ^ swizzle_of_row(row)) : kb;
-                    *reinterpret_cast<Chunk<TC> *>(lds + row * S::LDP + chunk * G::CE) = tr[e];
-                }
-            }
-        }
+    for (int e = 0; e < G::CE; ++e) {
+        const int row = ib * G::CE + e;
+        const int chunk = ColsSwizzle<TC, KU>::value ? (kb ^ swizzle_of_row(row)) : kb;
+        *reinterpret_cast<Chunk<TC> *>(lds + row * S::LDP + chunk * G::CE) = tr[e];
     }
-};
+}
+
+template <typename SRC, int CE> struct alignas(16) SrcChunk { SRC e[CE]; };
 
 template <typename TC, int ROWS, int KU, typename SRC, bool SUMS> struct LoadCols {
     static constexpr bool kSwizzled = ColsSwizzle<TC, KU>::value;
     using S = Stage<TC, KU>;
     using G = ColsGeom<TC, ROWS, KU>;
+    static constexpr int NV = G::CE * (int)sizeof(SRC) / 16; // 16-byte registers per source chunk
     static_assert(!SUMS || kThreads % G::IB == 0, "column sums need a fixed column block per thread");
     const SRC *src; // [k][ld]
     int64_t ld;
     int ncols; // valid i
     int kend;
     int i0;
-    Chunk<TC> reg[G::NCH][G::CE];
+    int kpos[2];
+    u32x4 reg[2][G::NCH][G::CE][NV];
     float sums[SUMS ? G::CE : 1];
     __device__ void init(int i0_)
     {
@@ -333,43 +343,56 @@ template <typename TC, int ROWS, int KU, typename SRC, bool SUMS> struct LoadCol
         if (SUMS)
             for (int e = 0; e < G::CE; ++e) sums[e] = 0.f;
     }
-    __device__ void fetch(int k0)
+    template <int SLOT> __device__ void fetch(int k0)
+    {
+        kpos[SLOT] = k0;
+        const int t = threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = (t + kThreads * u) % G::TOTAL; // out-of-range blocks re-read a valid one
+            const int i = min(i0 + (c % G::IB) * G::CE, ncols - G::CE);
+            const int kb = k0 + (c / G::IB) * G::CE;
+#pragma unroll
+            for (int kk = 0; kk < G::CE; ++kk) {
+                const int k = min(kb + kk, kend - 1);
+                const u32x4 *p = reinterpret_cast<const u32x4 *>(src + (int64_t)k * ld + i);
+#pragma unroll
+                for (int q = 0; q < NV; ++q) reg[SLOT][u][kk][q] = p[q];
+            }
+        }
+    }
+    template <int SLOT> __device__ void store(TC *lds, bool live)
     {
         const int t = threadIdx.x;
 #pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
-            const int i = i0 + (c % G::IB) * G::CE;
-            const int kb = k0 + (c / G::IB) * G::CE;
+            const bool icol = i0 + (c % G::IB) * G::CE < ncols;
+            const int kb = kpos[SLOT] + (c / G::IB) * G::CE;
+            Chunk<TC> blk[G::CE];
 #pragma unroll
             for (int kk = 0; kk < G::CE; ++kk) {
-                if (c < G::TOTAL && kb + kk < kend && i < ncols) {
-                    const SRC *p = src + (int64_t)(kb + kk) * ld + i;
-                    if (sizeof(SRC) == sizeof(TC) && !SUMS) {
-                        reg[u][kk] = *reinterpret_cast<const Chunk<TC> *>(p);
-                    } else {
+                const bool keep = icol && kb + kk < kend && c < G::TOTAL;
+                SrcChunk<SRC, G::CE> in;
+                __builtin_memcpy(&in, &reg[SLOT][u][kk][0], sizeof(in));
 #pragma unroll
-                        for (int e = 0; e < G::CE; ++e) {
-                            const float f = to_f32(p[e]);
-                            if (SUMS) sums[e] += f;
-                            reg[u][kk].e[e] = to_tc(f, TC());
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < G::CE; ++e) reg[u][kk].e[e] = to_tc(0.f, TC());
+                for (int e = 0; e < G::CE; ++e) {
+                    const float f = keep ? to_f32(in.e[e]) : 0.f;
+                    if (SUMS) sums[e] += live ? f : 0.f;
+                    blk[kk].e[e] = to_tc(f, TC());
                 }
             }
+            if (c < G::TOTAL) cols_store_block<TC, ROWS, KU>(lds, c, blk);
         }
     }
-    __device__ void store(TC *lds) { ColsStore<TC, ROWS, KU>::store(lds, reg); }
 };
 
-// operand[i][k] = x[k][i] = lam * b_l[k][i] + (1 - lam) * s_prev[k][i]
-template <typename TC, int ROWS, int KU> struct LoadColsX {
+// operand[i][k] = x[k][i] = lam * b_l[k][i] + (1 - lam) * s_prev[k][i]   (MIX == false: lam * b)
+template <typename TC, int ROWS, int KU, bool MIX> struct LoadColsX {
     static constexpr bool kSwizzled = ColsSwizzle<TC, KU>::value;
     using S = Stage<TC, KU>;
     using G = ColsGeom<TC, ROWS, KU>;
+    static constexpr int NV = G::CE * 4 / 16;
     const TC *cache;
     RowMap map;
     int layer;
@@ -379,41 +402,58 @@ template <typename TC, int ROWS, int KU> struct LoadColsX {
     int ncols;
     int kend;
     int i0;
-    Chunk<TC> reg[G::NCH][G::CE];
+    int kpos[2];
+    u32x4 regb[2][G::NCH][G::CE];
+    u32x4 regs[2][MIX ? G::NCH : 1][G::CE][NV];
     __device__ void init(int i0_) { i0 = i0_; }
-    __device__ void fetch(int k0)
+    template <int SLOT> __device__ void fetch(int k0)
+    {
+        kpos[SLOT] = k0;
+        const int t = threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = (t + kThreads * u) % G::TOTAL;
+            const int i = min(i0 + (c % G::IB) * G::CE, ncols - G::CE);
+            const int kb = k0 + (c / G::IB) * G::CE;
+#pragma unroll
+            for (int kk = 0; kk < G::CE; ++kk) {
+                const int k = min(kb + kk, kend - 1);
+                regb[SLOT][u][kk] = *reinterpret_cast<const u32x4 *>(cache + map.rowoff[k] +
+                                                                     (int64_t)layer * map.rowstride[k] + i);
+                if (MIX) {
+                    const u32x4 *p = reinterpret_cast<const u32x4 *>(s_prev + (int64_t)k * ld_s + i);
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) regs[SLOT][u][kk][q] = p[q];
+                }
+            }
+        }
+    }
+    template <int SLOT> __device__ void store(TC *lds, bool live)
     {
         const int t = threadIdx.x;
 #pragma unroll
         for (int u = 0; u < G::NCH; ++u) {
             const int c = t + kThreads * u;
-            const int i = i0 + (c % G::IB) * G::CE;
-            const int kb = k0 + (c / G::IB) * G::CE;
+            const bool icol = i0 + (c % G::IB) * G::CE < ncols;
+            const int kb = kpos[SLOT] + (c / G::IB) * G::CE;
+            Chunk<TC> blk[G::CE];
 #pragma unroll
             for (int kk = 0; kk < G::CE; ++kk) {
-                const int k = kb + kk;
-                if (c < G::TOTAL && k < kend && i < ncols) {
-                    const TC *bp = cache + map.rowoff[k] + (int64_t)layer * map.rowstride[k] + i;
-                    const Chunk<TC> b = *reinterpret_cast<const Chunk<TC> *>(bp);
-                    if (s_prev) {
-                        const float *sp = s_prev + (int64_t)k * ld_s + i;
+                const bool keep = icol && kb + kk < kend && c < G::TOTAL;
+                Chunk<TC> b;
+                __builtin_memcpy(&b, &regb[SLOT][u][kk], 16);
+                SrcChunk<float, G::CE> sv;
+                if (MIX) __builtin_memcpy(&sv, &regs[SLOT][u][kk][0], sizeof(sv));
 #pragma unroll
-                        for (int e = 0; e < G::CE; ++e)
-                            reg[u][kk].e[e] = to_tc(lam * to_f32(b.e[e]) + (1.f - lam) * sp[e], TC());
-                    } else if (lam == 1.f) {
-                        reg[u][kk] = b;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < G::CE; ++e) reg[u][kk].e[e] = to_tc(lam * to_f32(b.e[e]), TC());
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < G::CE; ++e) reg[u][kk].e[e] = to_tc(0.f, TC());
+                for (int e = 0; e < G::CE; ++e) {
+                    float f = lam * to_f32(b.e[e]);
+                    if (MIX) f += (1.f - lam) * sv.e[e];
+                    blk[kk].e[e] = to_tc(keep ? f : 0.f, TC());
                 }
             }
+            if (c < G::TOTAL) cols_store_block<TC, ROWS, KU>(lds, c, blk);
         }
     }
-    __device__ void store(TC *lds) { ColsStore<TC, ROWS, KU>::store(lds, reg); }
 };
 
 // ---------------------------------------------------------------------------
@@ -469,9 +509,10 @@ __device__ __forceinline__ void mma_tile(const float *As, const float *Bs, f32x1
     }
 }
 
-// Shape of a workgroup tile.
-template <int WM_, int WN_, int WTM_, int WTN_, int KU_> struct Tile {
-    static constexpr int WM = WM_, WN = WN_, WTM = WTM_, WTN = WTN_, KU = KU_;
+// Shape of a workgroup tile; PF = K steps kept in flight in registers (1 or 2).
+template <int WM_, int WN_, int WTM_, int WTN_, int KU_, int PF_ = 1> struct Tile {
+    static constexpr int WM = WM_, WN = WN_, WTM = WTM_, WTN = WTN_, KU = KU_, PF = PF_;
+    static_assert(PF == 1 || PF == 2, "one or two K steps in flight");
     static constexpr int BM = 32 * WM * WTM, BN = 32 * WN * WTN;
     static_assert(WM * WN * 64 == kThreads, "four wavefronts per workgroup");
 };
@@ -505,21 +546,51 @@ __device__ __forceinline__ void gemm_tile(void *lds /* tile_lds_bytes<TC, TL>(),
 
     al.init(row0);
     bl.init(col0);
-    if (kbegin < kend) {
-        al.fetch(kbegin);
-        bl.fetch(kbegin);
-    }
-    for (int k0 = kbegin; k0 < kend; k0 += S::BK) {
-        al.store(As);
-        bl.store(Bs);
-        __syncthreads();
-        if (k0 + S::BK < kend) {
-            al.fetch(k0 + S::BK);
-            bl.fetch(k0 + S::BK);
-        }
+    // One or two K steps are in flight.  Every path issues the same loads (steps past the end re-read
+    // the last one and are never used), so the waits before the LDS stores cover only the older step.
+    const int nsteps = (kend - kbegin + S::BK - 1) / S::BK;
+    auto mma = [&]() {
         mma_tile<TL::KU, TL::WTM, TL::WTN, ALoad::kSwizzled, BLoad::kSwizzled>(As, Bs, acc, wm * TL::WTM * 32,
                                                                               wn * TL::WTN * 32, lane);
-        __syncthreads();
+    };
+    if (nsteps > 0 && TL::PF == 1) {
+        const int klast = kbegin + (nsteps - 1) * S::BK;
+        al.template fetch<0>(kbegin);
+        bl.template fetch<0>(kbegin);
+        for (int st = 0; st < nsteps; ++st) {
+            al.template store<0>(As, true);
+            bl.template store<0>(Bs, true);
+            __syncthreads();
+            al.template fetch<0>(min(kbegin + (st + 1) * S::BK, klast));
+            bl.template fetch<0>(min(kbegin + (st + 1) * S::BK, klast));
+            mma();
+            __syncthreads();
+        }
+    }
+    if (nsteps > 0 && TL::PF == 2) {
+        const int klast = kbegin + (nsteps - 1) * S::BK;
+        al.template fetch<0>(kbegin);
+        bl.template fetch<0>(kbegin);
+        al.template fetch<1>(min(kbegin + S::BK, klast));
+        bl.template fetch<1>(min(kbegin + S::BK, klast));
+        for (int st = 0; st < nsteps; st += 2) {
+            const int k0 = kbegin + st * S::BK;
+            al.template store<0>(As, true);
+            bl.template store<0>(Bs, true);
+            __syncthreads();
+            al.template fetch<0>(min(k0 + 2 * S::BK, klast));
+            bl.template fetch<0>(min(k0 + 2 * S::BK, klast));
+            mma();
+            __syncthreads();
+            const bool live = st + 1 < nsteps; // otherwise a repeat of the last step, staged but not used
+            al.template store<1>(As, live);
+            bl.template store<1>(Bs, live);
+            __syncthreads();
+            al.template fetch<1>(min(k0 + 3 * S::BK, klast));
+            bl.template fetch<1>(min(k0 + 3 * S::BK, klast));
+            if (live) mma();
+            __syncthreads();
+        }
     }
     const int i = lane & 31, g = lane >> 5;
 #pragma unroll

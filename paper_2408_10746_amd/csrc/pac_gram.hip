@@ -301,7 +301,7 @@ template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArg
     const int b = blockIdx.x + a.blk_off;
     if (b < a.nb_U) {
         const int l = b / a.row_tiles, mt = b % a.row_tiles;
-        LoadRowsX<bf16_t, TU::BM, KU> al;
+        LoadRowsX<bf16_t, TU::BM, KU, false> al;
         al.cache = a.cache; al.map = a.map; al.layer = l; al.s_prev = nullptr; al.ld_s = 0; al.lam = 1.f;
         LoadRowsTC<bf16_t, TU::BN, KU> bl;
         bl.src = a.WdT + (int64_t)l * a.r * a.d; bl.ld = a.d; bl.nrows = a.r;
@@ -747,7 +747,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         const int l = b / (a.se * a.e_tiles);
         const int kbegin = split * a.rows_per_se;
         const int kend = min(M, kbegin + a.rows_per_se);
-        LoadColsX<bf16_t, TE::BM, 4> al;
+        LoadColsX<bf16_t, TE::BM, 4, false> al;
         al.cache = a.cache; al.map = a.map; al.layer = l; al.s_prev = nullptr; al.ld_s = 0; al.lam = 1.f;
         al.ncols = a.d; al.kend = kend;
         LoadCols<bf16_t, TE::BN, 4, bf16_t, false> bl;
@@ -912,7 +912,7 @@ struct EpiW {
 
 __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
 {
-    constexpr int kVecLds = 256 * 4 + 256 * kMaxClasses * 4;
+    constexpr int kVecLds = 128 * 4 + 128 * kMaxClasses * 4 + kMaxBatch * kMaxClasses * 4;
     constexpr int kLds = 56 * 1024;
     static_assert(kLds >= tile_lds_bytes<bf16_t, T64K>() && kLds >= kVecLds, "LDS budget of the gradient kernel");
     __shared__ __attribute__((aligned(16))) char smem[kLds];
@@ -956,57 +956,100 @@ __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
     }
     const int vb = b - a.nb_F - a.nb_W;
     if (vb < a.nb_vec - 1) {
-        // thread (jj, k): hidden index j = vb * jpb + jj, layer k
+        // thread (jj, k, hf): hidden index j = vb * jpb + jj, layer k, half hf of the r-wide rows
         float *tsh = reinterpret_cast<float *>(smem);          // [jpb][L]      (1-lambda_k) W_down^k[j] . cs_k
-        float *wsh = tsh + 256;                                // [jpb][L][C]   W_up^k[.][j] . Z_k
-        const int jpb = 256 / L;
-        const int jj = t / L, k = t % L;
+        float *wsh = tsh + 128;                                // [jpb][L][C]   W_up^k[.][j] . Z_k + pooled part
+        float *sdz = wsh + 128 * kMaxClasses;                  // [B][C]
+        float *stage = sdz + kMaxBatch * kMaxClasses;          // cs [Lr], Z [Lr][C] when they fit
+        const int jpb = 128 / L;
+        const int hf = t & 1, jk = t >> 1;
+        const int jj = jk / L, k = jk % L;
         const int j = vb * jpb + jj;
         const bool act = jj < jpb && j < d;
+        const int rh = r / 2; // a multiple of 16
         const float *Wc = a.params + (int64_t)L * a.PL;
-        // cs and Z are read by every thread: stage them in LDS when they fit
-        float *stage = wsh + 256 * kMaxClasses;
+        // this thread's two row segments, requested before anything else is waited for
+        constexpr int kMaxChunks = 8; // r / 2 <= 64
+        u32x4 wv[kMaxChunks], uv[kMaxChunks];
+        {
+            const int64_t row = act ? (int64_t)j * Lr + (int64_t)k * r + hf * rh : 0;
+#pragma unroll
+            for (int q = 0; q < kMaxChunks; ++q) {
+                const int qq = q * 8 < rh ? q * 8 : 0;
+                wv[q] = *reinterpret_cast<const u32x4 *>(a.Wds + row + qq);
+                uv[q] = *reinterpret_cast<const u32x4 *>(a.WuTs + row + qq);
+            }
+        }
         const bool staged = (int64_t)Lr * (1 + C) * 4 + kVecLds <= kLds;
+        for (int q = t; q < a.B * C; q += 256) sdz[q] = a.dz[q];
         if (staged) {
             for (int q = t; q < Lr; q += 256) stage[q] = a.cs[q];
             for (int q = t; q < Lr * C; q += 256) stage[Lr + q] = a.Z[q];
-            __syncthreads();
         }
-        float wz[kMaxClasses];
+        float pbv[2]; // pooled last-layer means of the samples s = k + (2q + hf) L this thread covers first
 #pragma unroll
-        for (int c = 0; c < kMaxClasses; ++c) wz[c] = 0.f;
-        if (act) {
-            const bf16_t *wrow = a.Wds + (int64_t)j * Lr + (int64_t)k * r;
-            const bf16_t *urow = a.WuTs + (int64_t)j * Lr + (int64_t)k * r;
-            const float *csk = staged ? stage + (int64_t)k * r : a.cs + (int64_t)k * r;
-            const float *Zk = staged ? stage + Lr + (int64_t)k * r * C : a.Z + (int64_t)k * r * C;
+        for (int q = 0; q < 2; ++q) {
+            const int s2 = k + (2 * q + hf) * L;
+            pbv[q] = (act && s2 < a.B) ? a.pb[(int64_t)s2 * d + j] : 0.f;
+        }
+        const float cl = act ? a.cusum[(int64_t)L * d + j] : 0.f;
+        const float lamk = a.params[(int64_t)k * a.PL + a.PL - 1];
+        __syncthreads();
+        {
+            const float *csk = (staged ? stage : a.cs) + (int64_t)k * r + hf * rh;
+            const float *Zk = (staged ? stage + Lr : a.Z) + ((int64_t)k * r + hf * rh) * C;
             float acc = 0.f;
-            for (int b0 = 0; b0 < r; b0 += 8) {
-                const Chunk<bf16_t> wv = *reinterpret_cast<const Chunk<bf16_t> *>(wrow + b0);
-                const Chunk<bf16_t> uv = *reinterpret_cast<const Chunk<bf16_t> *>(urow + b0);
+            float wz[kMaxClasses];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    acc += csk[b0 + e] * to_f32(wv.e[e]);
-                    const float u = to_f32(uv.e[e]);
-                    for (int c = 0; c < C; ++c) wz[c] += u * Zk[(int64_t)(b0 + e) * C + c];
+            for (int c = 0; c < kMaxClasses; ++c) wz[c] = 0.f;
+            if (act) {
+#pragma unroll
+                for (int q = 0; q < kMaxChunks; ++q)
+                    if (q * 8 < rh) {
+                        Chunk<bf16_t> w8, u8;
+                        __builtin_memcpy(&w8, &wv[q], 16);
+                        __builtin_memcpy(&u8, &uv[q], 16);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            acc += csk[q * 8 + e] * to_f32(w8.e[e]);
+                            const float u = to_f32(u8.e[e]);
+#pragma unroll
+                            for (int c = 0; c < kMaxClasses; ++c)
+                                if (c < C) wz[c] += u * Zk[(int64_t)(q * 8 + e) * C + c];
+                        }
+                    }
+                // pooled part of dW_cls, the samples dealt over (k, hf)
+                for (int s2 = k + hf * L, q = 0; s2 < a.B; s2 += 2 * L, ++q) {
+                    const float pv = (q < 2 ? pbv[q] : a.pb[(int64_t)s2 * d + j]) + cl;
+#pragma unroll
+                    for (int c = 0; c < kMaxClasses; ++c)
+                        if (c < C) wz[c] += pv * sdz[s2 * C + c];
                 }
             }
-            const float lam = a.params[(int64_t)k * a.PL + a.PL - 1];
-            tsh[jj * L + k] = (1.f - lam) * acc;
-            for (int c = 0; c < C; ++c) wsh[(jj * L + k) * C + c] = wz[c];
+            // the two halves sit in neighbouring lanes
+            acc += __shfl_xor(acc, 1, 64);
+#pragma unroll
+            for (int c = 0; c < kMaxClasses; ++c)
+                if (c < C) wz[c] += __shfl_xor(wz[c], 1, 64);
+            if (act && hf == 0) {
+                tsh[jj * L + k] = (1.f - lamk) * acc;
+#pragma unroll
+                for (int c = 0; c < kMaxClasses; ++c)
+                    if (c < C) wsh[(jj * L + k) * C + c] = wz[c];
+            }
         }
         __syncthreads();
         if (!act) return;
-        // dc_up^k[j] = (sum_s dz_s) W_cls^T [j] + sum_{k'>k} t[j][k']
-        float base = 0.f;
-        for (int c = 0; c < C; ++c) base += a.dzsum[c] * Wc[(int64_t)j * C + c];
-        for (int k2 = k + 1; k2 < L; ++k2) base += tsh[jj * L + k2];
-        a.grads[(int64_t)k * a.PL + 2 * dr + r + j] = base;
+        if (hf == 0) {
+            // dc_up^k[j] = (sum_s dz_s) W_cls^T [j] + sum_{k'>k} t[j][k']
+            float base = 0.f;
+            for (int c = 0; c < C; ++c) base += a.dzsum[c] * Wc[(int64_t)j * C + c];
+            for (int k2 = k + 1; k2 < L; ++k2) base += tsh[jj * L + k2];
+            a.grads[(int64_t)k * a.PL + 2 * dr + r + j] = base;
+        }
         // dW_cls[j][c] = sum_s (pb[s][j] + cusum_L[j]) dz[s][c] + sum_k W_up^k[.][j] . Z_k[.][c]
-        for (int c = k; c < C; c += L) {
-            const float cl = a.cusum[(int64_t)L * d + j];
+        for (int c = 2 * k + hf; c < C; c += 2 * L) {
             float acc = 0.f;
-            for (int s2 = 0; s2 < a.B; ++s2) acc += (a.pb[(int64_t)s2 * d + j] + cl) * a.dz[s2 * C + c];
             for (int k2 = 0; k2 < L; ++k2) acc += wsh[(jj * L + k2) * C + c];
             a.grads[(int64_t)L * a.PL + (int64_t)j * C + c] = acc;
         }
@@ -1195,7 +1238,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         }
         PostArgs pa;
         pa.L = L; pa.d = d; pa.r = r; pa.C = C; pa.B = B; pa.se = 1;
-        pa.nb_F = L * cdiv(d, 64) * cdiv(r, 64); pa.nb_W = pa.nb_F; pa.nb_vec = cdiv(d, 256 / L) + 1;
+        pa.nb_F = L * cdiv(d, 64) * cdiv(r, 64); pa.nb_W = pa.nb_F; pa.nb_vec = cdiv(d, 128 / L) + 1;
         pa.params = io.params; pa.PL = D.PL; pa.WuTs = WuTs; pa.Wds = Wds; pa.GGT = GGT; pa.GGsc = GGsc;
         pa.Epart = (const float *)(ws + W.g_E); pa.cusum = cusum; pa.cs = cs; pa.Z = Z; pa.dzsum = dzsum; pa.dz = dz; pa.pb = pb;
         pa.grads = io.grads; pa.dlam_part = dlam_part; pa.counter = counter;

@@ -251,15 +251,21 @@ template <typename TC> struct EpiFwdDown {
     }
 };
 
-template <typename TC> __global__ __launch_bounds__(256) void k_fwd_down(FwdDownArgs<TC> a)
+template <typename TC, bool MIX> __device__ __forceinline__ void fwd_down_tile(const FwdDownArgs<TC> &a, char *smem)
 {
-    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
-    LoadRowsX<TC, 64, 1> al;
+    LoadRowsX<TC, 64, 1, MIX> al;
     al.cache = a.cache; al.map = a.map; al.layer = a.layer; al.s_prev = a.s_prev; al.ld_s = a.d; al.lam = *a.lam;
     LoadRowsTC<TC, 64, 1> bl;
     bl.src = a.WdT; bl.ld = a.d; bl.nrows = a.r;
     EpiFwdDown<TC> epi{a.c_down, a.pre, a.h, a.r};
     gemm_tile<TC, T64>(smem, al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.r);
+}
+
+template <typename TC> __global__ __launch_bounds__(256) void k_fwd_down(FwdDownArgs<TC> a)
+{
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
+    if (a.s_prev) fwd_down_tile<TC, true>(a, smem);
+    else fwd_down_tile<TC, false>(a, smem);
 }
 
 template <typename TC> struct FwdUpArgs {
@@ -524,13 +530,20 @@ template <typename TC> __global__ __launch_bounds__(256) void k_bwd_wgrad(BwdWgr
     } else {
         const int tj = a.r / 64 + (a.r % 64 ? 1 : 0);
         const int ti = blockIdx.x / tj, tjx = blockIdx.x % tj;
-        LoadColsX<TC, 64, 4> al;
-        al.cache = a.cache; al.map = a.map; al.layer = a.layer; al.s_prev = a.s_prev; al.ld_s = a.d;
-        al.lam = *a.lam; al.ncols = a.d; al.kend = kend;
         LoadCols<TC, 64, 4, TC, true> bl;
         bl.src = a.dpre; bl.ld = a.r; bl.ncols = a.r; bl.kend = kend;
         EpiStore epi{part, a.r};
-        gemm_tile<TC, T64K>(smem, al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.d, a.r);
+        if (a.s_prev) {
+            LoadColsX<TC, 64, 4, true> al;
+            al.cache = a.cache; al.map = a.map; al.layer = a.layer; al.s_prev = a.s_prev; al.ld_s = a.d;
+            al.lam = *a.lam; al.ncols = a.d; al.kend = kend;
+            gemm_tile<TC, T64K>(smem, al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.d, a.r);
+        } else {
+            LoadColsX<TC, 64, 4, false> al;
+            al.cache = a.cache; al.map = a.map; al.layer = a.layer; al.s_prev = nullptr; al.ld_s = a.d;
+            al.lam = *a.lam; al.ncols = a.d; al.kend = kend;
+            gemm_tile<TC, T64K>(smem, al, bl, epi, kbegin, kend, ti * 64, tjx * 64, a.d, a.r);
+        }
         if (ti == 0) write_colsums<TC>(bl, reinterpret_cast<float *>(smem), part + dr, a.r, tjx * 64);
     }
 }
