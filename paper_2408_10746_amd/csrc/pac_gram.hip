@@ -33,7 +33,7 @@ namespace pac {
 static inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
 static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
-constexpr int kChainRows = 32;   // token rows per chain workgroup
+constexpr int kChainRows = 16;   // token rows per chain workgroup
 constexpr int kChainPad = 8;     // bf16 elements of padding per LDS row
 constexpr int kMaxD = 4096;
 
@@ -259,12 +259,13 @@ struct EpiStoreF32 {
 };
 
 // Q is stored twice, each time in the order the chain kernels' matrix instructions consume it
-// ("fragment-major"): for the contraction sum_kk A[.][kk] B[n][kk], element B[n][kk] sits at
-//   ((n/32 * r/16 + kk/16) * 64 + (n%32) + 32*((kk%16)/8)) * 8 + kk%8,
-// so that one wavefront load of a 32-column x 16-deep operand fragment reads 1 KB contiguously.
+// ("fragment-major"): for the contraction sum_kk A[.][kk] B[n][kk] in 16-column x 32-deep operand
+// fragments, element B[n][kk] sits at
+//   ((n/16 * r/32 + kk/32) * 64 + (n%16) + 16*((kk%32)/8)) * 8 + kk%8,
+// so that one wavefront load of a fragment reads 1 KB contiguously.
 __device__ __forceinline__ int64_t frag_index(int n, int kk, int r)
 {
-    return ((int64_t)((n >> 5) * (r >> 4) + (kk >> 4)) * 64 + (n & 31) + 32 * ((kk & 15) >> 3)) * 8 + (kk & 7);
+    return ((int64_t)((n >> 4) * (r >> 5) + (kk >> 5)) * 64 + (n & 15) + 16 * ((kk & 31) >> 3)) * 8 + (kk & 7);
 }
 
 struct EpiQ {
@@ -372,8 +373,8 @@ template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArg
 }
 
 // ---------------------------------------------------------------------------
-// launches 3 and 5: the r-wide chains over the layers, one 32-token tile per workgroup.
-// Wavefront w owns columns [32w, 32w+32) of the r-wide state; earlier layers' tiles stay in LDS.
+// launches 3 and 5: the r-wide chains over the layers, one 16-token tile per workgroup.
+// Wavefront w owns columns [16w, 16w+16) of the r-wide state; earlier layers' tiles stay in LDS.
 // ---------------------------------------------------------------------------
 struct ChainArgs {
     int L, r, M;
@@ -392,12 +393,13 @@ struct ChainArgs {
 
 constexpr int kRing = 4; // layers of per-token inputs staged ahead in LDS
 
-// LDS of the chain kernels:
-//   Hs   [L][32][r+pad] bf16   h (forward) or dpre (backward) of every layer: the contraction operand
-//   ring [kRing][32][r]        per-token inputs of the coming layers: U (fp32, forward) or GELU' (bf16, backward)
-//   vecS [L][r] fp32           per-layer vector: (1-lambda) chat + c_down (forward), ghat of the sample (backward)
-//   lamS [L] fp32, Cs [L][r] fp32 column sums
-// Wavefronts 0..NT-1 contract and apply the nonlinearity; one more wavefront only moves the
+// LDS of the chain kernels (T = kChainRows):
+//   Hs   [L][T][r+pad] bf16   h (forward) or dpre (backward) of every layer: the contraction operand
+//   ring [kRing][T][r]        per-token inputs of the coming layers: U (fp32, forward) or GELU' (bf16, backward)
+//   Gst  [2][T][r] bf16       forward only: GELU' of the layer just finished, on its way to global memory
+//   vecS [L][r] fp32          per-layer vector: (1-lambda) chat + c_down (forward), ghat of the sample (backward)
+//   Cs   [L][r] fp32 column sums, lamS [L] fp32
+// Wavefronts 0..r/16-1 contract and apply the nonlinearity; one more wavefront only moves the
 // per-token inputs of later layers from global memory into the ring, so that no contracting
 // wavefront ever waits on those loads.
 static size_t chain_lds(int L, int r, bool fwd)
@@ -423,29 +425,30 @@ __device__ __forceinline__ void gelu_pair(float u, float &h, float &gp)
     gp = Phi + u * 0.3989422804014327f * ex;
 }
 
-template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_gchain(ChainArgs a)
+// The chain runs in L steps; step s produces layer s (forward) or L-1-s (backward) and contracts the
+// tiles of steps 0..s-1, oldest first, so that the tile finished last is also needed last.
+template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void k_gchain(ChainArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char dyn_smem[];
-    constexpr int r = 32 * NT, RP = r + kChainPad, KQ = r / 16;
-    constexpr int GP = 4; // layer pairs per operand group
+    constexpr int r = 32 * NT, RP = r + kChainPad, KS = NT, NW = 2 * NT, T = kChainRows;
     using RingT = typename std::conditional<FWD, float, bf16_t>::type;
-    constexpr int kTileBytes = kChainRows * r * (int)sizeof(RingT);
+    constexpr int kTileBytes = T * r * (int)sizeof(RingT);
     constexpr int kChunksPerLane = kTileBytes / 16 / 64; // 16-byte chunks each helper lane moves per layer
-    constexpr int kGChunks = kChainRows * r * 2 / 16 / 64; // same for a GELU' tile (bf16)
+    constexpr int kGChunks = (T * r * 2 / 16 + 63) / 64; // same for a GELU' tile (bf16), rounded up
     static_assert(kTileBytes % (16 * 64) == 0, "ring tile must split evenly over the helper wavefront");
     const int L = a.L;
-    bf16_t *Hs = reinterpret_cast<bf16_t *>(dyn_smem);                                      // [L][32][RP]
-    RingT *ring = reinterpret_cast<RingT *>(Hs + (size_t)L * kChainRows * RP);              // [kRing][32][r]
-    bf16_t *Gst = reinterpret_cast<bf16_t *>(ring + (size_t)kRing * kChainRows * r);        // [2][32][r] (forward)
-    float *vecS = reinterpret_cast<float *>(Gst + (FWD ? (size_t)2 * kChainRows * r : 0));  // [L][r]
-    float *Cs = vecS + (size_t)L * r;                                                       // [L][r]
-    float *lamS = Cs + (size_t)L * r;                                                       // [L]
+    bf16_t *Hs = reinterpret_cast<bf16_t *>(dyn_smem);                              // [L][T][RP]
+    RingT *ring = reinterpret_cast<RingT *>(Hs + (size_t)L * T * RP);               // [kRing][T][r]
+    bf16_t *Gst = reinterpret_cast<bf16_t *>(ring + (size_t)kRing * T * r);         // [2][T][r] (forward)
+    float *vecS = reinterpret_cast<float *>(Gst + (FWD ? (size_t)2 * T * r : 0));   // [L][r]
+    float *Cs = vecS + (size_t)L * r;                                               // [L][r]
+    float *lamS = Cs + (size_t)L * r;                                               // [L]
     const int tile = blockIdx.x;
     const int m0 = a.tile_row0[tile], nrows = a.tile_rows[tile], samp = a.tile_samp[tile];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t Lr = (int64_t)L * r;
     constexpr int64_t rr = (int64_t)r * r;
-    const int nthreads = 64 * (NT + 1);
+    constexpr int nthreads = 64 * (NW + 1);
     auto layer_at = [&](int step) { return FWD ? step : L - 1 - step; };
 
     // per-layer vectors
@@ -460,13 +463,13 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
     }
     for (int l = threadIdx.x; l < L; l += nthreads) lamS[l] = a.params[(int64_t)l * a.PL + a.PL - 1];
 
-    if (wave == NT) {
+    if (wave == NW) {
         // ---- helper wavefront: all global traffic of the per-token tiles.  It keeps the input ring
         // filled three layers ahead and (forward) writes out the GELU' tile of the layer just finished,
         // so the contracting wavefronts issue no global store and wait on no per-token load.
         const RingT *src = FWD ? reinterpret_cast<const RingT *>(a.U) : reinterpret_cast<const RingT *>(a.Gp);
         constexpr int EPC = 16 / (int)sizeof(RingT); // elements per chunk
-        auto fetch = [&](int step, uint4(&reg)[kChunksPerLane]) {
+        auto fetch = [&](int step, u32x4(&reg)[kChunksPerLane]) {
             if (step >= L) return;
             const RingT *base = src + ((int64_t)layer_at(step) * a.M + m0) * r;
 #pragma unroll
@@ -474,26 +477,26 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
                 // rows past the end of a short tile re-read the tile's last chunk (never used: the
                 // contracting wavefronts mask those rows); no branch, no register is zeroed
                 const int e = min((lane + 64 * q) * EPC, nrows * r - EPC);
-                reg[q] = *reinterpret_cast<const uint4 *>(base + e);
+                reg[q] = *reinterpret_cast<const u32x4 *>(base + e);
             }
         };
-        auto put = [&](int step, const uint4(&reg)[kChunksPerLane]) {
+        auto put = [&](int step, const u32x4(&reg)[kChunksPerLane]) {
             if (step >= L) return;
-            RingT *dst = ring + (size_t)(step % kRing) * kChainRows * r;
+            RingT *dst = ring + (size_t)(step % kRing) * T * r;
 #pragma unroll
-            for (int q = 0; q < kChunksPerLane; ++q) *reinterpret_cast<uint4 *>(dst + (lane + 64 * q) * EPC) = reg[q];
+            for (int q = 0; q < kChunksPerLane; ++q) *reinterpret_cast<u32x4 *>(dst + (lane + 64 * q) * EPC) = reg[q];
         };
         auto drain = [&](int step) { // GELU' tile of a finished step: LDS staging -> global
             if (!FWD || step < 0 || step >= L) return;
-            const bf16_t *st = Gst + (size_t)(step & 1) * kChainRows * r;
+            const bf16_t *st = Gst + (size_t)(step & 1) * T * r;
             bf16_t *dst = a.Gp + ((int64_t)layer_at(step) * a.M + m0) * r;
 #pragma unroll
             for (int q = 0; q < kGChunks; ++q) {
                 const int e = (lane + 64 * q) * 8;
-                if (e < nrows * r) *reinterpret_cast<uint4 *>(dst + e) = *reinterpret_cast<const uint4 *>(st + e);
+                if (e < nrows * r) *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(st + e);
             }
         };
-        uint4 ra[kChunksPerLane], rb[kChunksPerLane], rc[kChunksPerLane];
+        u32x4 ra[kChunksPerLane], rb[kChunksPerLane], rc[kChunksPerLane];
         fetch(0, ra);
         fetch(1, rb);
         fetch(2, rc);
@@ -523,68 +526,58 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
         drain(L - 1);
     } else {
         // ---- contracting wavefronts ----
-        // The (k, l) layer pairs of the whole kernel form one sequence; their r x r operands do not
-        // depend on anything computed here, so they are requested kDepth pairs ahead of their use
-        // (across layer boundaries) into a register FIFO.
-        constexpr int kDepth = NT == 4 ? 4 : 8; // bounded by the register file at 320 threads per workgroup
-        const int i = lane & 31, g = lane >> 5;
-        const int n = 32 * wave + i;
-        auto k_first = [&](int step) { return FWD ? 0 : layer_at(step) + 1; };
-        auto k_last = [&](int step) { return FWD ? layer_at(step) : L; };
+        // The (step, earlier step) pairs of the whole kernel form one sequence; their r x r operands
+        // do not depend on anything computed here, so they are requested kDepth pairs ahead of their
+        // use (across layer boundaries) into a register FIFO.
+        constexpr int kDepth = NT == 1 ? 16 : NT == 2 ? 12 : NT == 3 ? 10 : 6; // bounded by the register file
+        const int i = lane & 15, g = lane >> 4;
+        const int n = 16 * wave + i;
+        const int total_pairs = L * (L - 1) / 2;
         // next pair to request.  A request is issued for every FIFO slot on every path (once the
         // sequence is exhausted the last pair is requested again and never used): the compiler can
         // then count the loads in flight and wait only for the oldest ones.
-        int ls = 0, lk = 0;
-        while (ls < L && k_first(ls) >= k_last(ls)) ++ls;
-        if (ls < L) lk = k_first(ls);
-        const int total_pairs = L * (L - 1) / 2;
-        auto issue = [&](bf16x8(&bq)[KQ]) {
-            const int lsc = ls < L ? ls : L - 1;
-            const int l = layer_at(lsc);
-            int kq = lk;
-            if (total_pairs == 0) kq = 0;
-            const int pi = total_pairs == 0 ? 0 : (FWD ? pair_index(kq, l) : pair_index(l, kq));
-            const bf16_t *Qp = a.Q + pi * rr + (int64_t)wave * KQ * 512;
+        int is = 1, ij = 0;
+        auto issue = [&](bf16x8(&bq)[KS]) {
+            const int s = is < L ? is : L - 1;
+            const int j = is < L ? ij : L - 2;
+            const int ls = layer_at(s), lj = layer_at(j);
+            const int pi = FWD ? pair_index(lj, ls) : pair_index(ls, lj);
+            const bf16_t *Qp = a.Q + pi * rr + (int64_t)wave * KS * 512;
 #pragma unroll
-            for (int q = 0; q < KQ; ++q) bq[q] = *reinterpret_cast<const bf16x8 *>(Qp + (q * 64 + lane) * 8);
-            if (ls < L && ++lk >= k_last(ls)) {
-                ++ls;
-                while (ls < L && k_first(ls) >= k_last(ls)) ++ls;
-                if (ls < L) lk = k_first(ls);
-                else { ls = L; lk = FWD ? L - 2 : L - 1; } // stay on the last pair: (L-2, L-1) / (0, L-1)
+            for (int q = 0; q < KS; ++q) bq[q] = *reinterpret_cast<const bf16x8 *>(Qp + (q * 64 + lane) * 8);
+            if (is < L && ++ij >= is) {
+                ++is;
+                ij = 0;
             }
         };
-        bf16x8 fifo[kDepth][KQ];
+        bf16x8 fifo[kDepth][KS];
+        if (total_pairs > 0) {
 #pragma unroll
-        for (int slot = 0; slot < kDepth; ++slot) issue(fifo[slot]);
-        // two accumulators so that consecutive matrix instructions do not depend on each other
-        f32x16 acc0, acc1;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            acc0[v] = 0.f;
-            acc1[v] = 0.f;
+            for (int slot = 0; slot < kDepth; ++slot) issue(fifo[slot]);
         }
-        auto contract = [&](const bf16x8(&bq)[KQ], int k) {
-            const bf16_t *Hk = Hs + ((int64_t)k * kChainRows + i) * RP;
-            bf16x8 av[KQ];
+        // two accumulators so that consecutive matrix instructions do not depend on each other
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        auto contract = [&](const bf16x8(&bq)[KS], int j) {
+            const bf16_t *Hk = Hs + ((int64_t)layer_at(j) * T + i) * RP;
+            bf16x8 av[KS];
 #pragma unroll
-            for (int q = 0; q < KQ; ++q) av[q] = *reinterpret_cast<const bf16x8 *>(Hk + 16 * q + 8 * g);
+            for (int q = 0; q < KS; ++q) av[q] = *reinterpret_cast<const bf16x8 *>(Hk + 32 * q + 8 * g);
 #pragma unroll
-            for (int q = 0; q < KQ; q += 2) {
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[q], bq[q], acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[q + 1], bq[q + 1], acc1, 0, 0, 0);
+            for (int q = 0; q < KS; ++q) {
+                if (q & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[q], bq[q], acc1, 0, 0, 0);
+                else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[q], bq[q], acc0, 0, 0, 0);
             }
         };
         auto finish_layer = [&](int step) { // nonlinearity, tiles to LDS, barrier
             const int l = layer_at(step);
             const float lam = lamS[l];
             const float cvec = vecS[l * r + n];
-            const RingT *rt = ring + (size_t)(step % kRing) * kChainRows * r;
-            bf16_t *gst = Gst + (size_t)(step & 1) * kChainRows * r;
+            const RingT *rt = ring + (size_t)(step % kRing) * T * r;
+            bf16_t *gst = Gst + (size_t)(step & 1) * T * r;
             float colsum = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = 8 * (v >> 2) + 4 * g + (v & 3);
+            for (int v = 0; v < 4; ++v) {
+                const int row = 4 * g + v;
                 const bool valid = row < nrows;
                 const float uin = to_f32(rt[row * r + n]);
                 const float accv = acc0[v] + acc1[v];
@@ -598,28 +591,27 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
                 } else {
                     if (valid) out = (cvec + accv) * uin;
                 }
-                Hs[((int64_t)l * kChainRows + row) * RP + n] = static_cast<bf16_t>(out);
+                Hs[((int64_t)l * T + row) * RP + n] = static_cast<bf16_t>(out);
                 colsum += out;
                 acc0[v] = 0.f;
                 acc1[v] = 0.f;
             }
+            colsum += __shfl_xor(colsum, 16, 64);
             colsum += __shfl_xor(colsum, 32, 64);
             if (g == 0) Cs[l * r + n] = colsum;
             __syncthreads();
         };
         __syncthreads();
-        int cs = 0, ck = 0; // pair being contracted
-        while (cs < L && k_first(cs) >= k_last(cs)) finish_layer(cs++);
-        if (cs < L) ck = k_first(cs);
+        finish_layer(0); // the first step has nothing to contract
+        int cs = 1, cj = 0; // pair being contracted
         for (int p0 = 0; p0 < total_pairs; p0 += kDepth) {
 #pragma unroll
             for (int slot = 0; slot < kDepth; ++slot) {
                 if (p0 + slot < total_pairs) {
-                    contract(fifo[slot], ck);
-                    if (++ck >= k_last(cs)) {
+                    contract(fifo[slot], cj);
+                    if (++cj >= cs) {
                         finish_layer(cs++);
-                        while (cs < L && k_first(cs) >= k_last(cs)) finish_layer(cs++);
-                        if (cs < L) ck = k_first(cs);
+                        cj = 0;
                     }
                 }
                 issue(fifo[slot]);
@@ -628,14 +620,14 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (NT + 1)) void k_g
     }
     // flush: 16-byte chunks of the valid rows, then the column sums
     __syncthreads();
-    const int chunks_per_row = r / 8;
-    for (int c = threadIdx.x; c < L * kChainRows * chunks_per_row; c += nthreads) {
-        const int l = c / (kChainRows * chunks_per_row);
-        const int rem = c - l * kChainRows * chunks_per_row;
+    constexpr int chunks_per_row = r / 8;
+    for (int c = threadIdx.x; c < L * T * chunks_per_row; c += nthreads) {
+        const int l = c / (T * chunks_per_row);
+        const int rem = c - l * T * chunks_per_row;
         const int row = rem / chunks_per_row, cc = rem % chunks_per_row;
         if (row < nrows)
-            *reinterpret_cast<uint4 *>(a.Hg + (int64_t)(m0 + row) * Lr + (int64_t)l * r + cc * 8) =
-                *reinterpret_cast<const uint4 *>(Hs + ((int64_t)l * kChainRows + row) * RP + cc * 8);
+            *reinterpret_cast<u32x4 *>(a.Hg + (int64_t)(m0 + row) * Lr + (int64_t)l * r + cc * 8) =
+                *reinterpret_cast<const u32x4 *>(Hs + ((int64_t)l * T + row) * RP + cc * 8);
     }
     for (int c = threadIdx.x; c < L * r; c += nthreads) a.part[(int64_t)tile * Lr + c] = Cs[c];
 }
@@ -1189,7 +1181,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     {
         ChainArgs a = ca;
         a.Q = QpT; a.Hg = H; a.part = HSpart;
-        PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * (NT + 1)), lds_fwd, st, a);
+        PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_fwd, st, a);
     }
     {
         HeadArgs a;
@@ -1207,7 +1199,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     {
         ChainArgs a = ca;
         a.Q = QpN; a.Hg = DP; a.part = cspart;
-        PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, (k_gchain<false, NT>), dim3(ntiles), dim3(64 * (NT + 1)), lds_bwd, st, a);
+        PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, (k_gchain<false, NT>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_bwd, st, a);
     }
     {
         TokRedArgs a;
