@@ -23,9 +23,9 @@ struct pac_ctx {
 static const char *const kClassNames[KC_COUNT] = {
     "cache_fill", "setup", "shadows", "fwd_down", "fwd_up", "pool", "head", "head_bwd",
     "bwd_dpre", "bwd_wgrad", "bwd_dx", "reduce", "adamw",
-    "g_prep", "g_proj", "g_chain_fwd", "g_head", "g_chain_bwd", "g_tokred", "g_reduce", "g_post", "g_finish",
+    "g_prep", "g_proj", "g_chain_fwd", "g_head", "g_chain_bwd", "g_tokred", "g_ggsum", "g_post", "g_finish",
     "g_prep.setup", "g_prep.copy", "g_prep.chat", "g_prep.V", "g_proj.U", "g_proj.Q", "g_proj.pb",
-    "g_tokred.E", "g_tokred.G", "g_reduce.GG", "g_reduce.E", "g_reduce.vec", "g_post.F", "g_post.W", "g_post.vec"};
+    "g_tokred.E", "g_tokred.G", "g_tokred.vec", "g_post.F", "g_post.W", "g_post.vec"};
 
 static void drop_events(Profiler &p)
 {

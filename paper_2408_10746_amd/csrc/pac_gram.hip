@@ -37,18 +37,27 @@ constexpr int kChainRows = 16;   // token rows per chain workgroup
 constexpr int kChainPad = 8;     // bf16 elements of padding per LDS row
 constexpr int kMaxD = 4096;
 
-static int64_t chain_lds_bytes(const Dims &D)
+constexpr int kRing = 4; // layers of per-token inputs the chain kernels stage ahead in LDS
+
+// LDS of the chain kernels (T = kChainRows):
+//   Hs   [L][T][r+pad] bf16   h (forward) or dpre (backward) of every layer: the contraction operand
+//   ring [kRing][T][r]        per-token inputs of the coming layers: U (fp32, forward) or GELU' (bf16, backward)
+//   Gst  [2][T][r] bf16       forward only: GELU' of the layer just finished, on its way to global memory
+//   vecS [L][r] fp32          per-layer vector: (1-lambda) chat + c_down (forward), ghat of the sample (backward)
+//   Cs   [L][r] fp32 column sums, lamS [L] fp32, zs / dzs [kMaxClasses] fp32 each
+static size_t chain_lds(int L, int r, bool fwd)
 {
-    // the forward chain's LDS (see chain_lds below): operand tiles of every layer, the input ring, vectors
-    return (int64_t)D.L * kChainRows * (D.r + kChainPad) * 2 + 4 * (int64_t)kChainRows * D.r * 4 +
-           2 * (int64_t)kChainRows * D.r * 2 + (int64_t)D.L * D.r * 8 + (int64_t)(D.L + 4) * 4;
+    const size_t hs = (size_t)L * kChainRows * (r + kChainPad) * 2;
+    const size_t ring = (size_t)kRing * kChainRows * r * (fwd ? 4 : 2);
+    const size_t gstage = fwd ? (size_t)2 * kChainRows * r * 2 : 0;
+    return hs + ring + gstage + (size_t)L * r * 4 * 2 + (size_t)((L + 3) / 4 * 4) * 4 + 2 * kMaxClasses * 4;
 }
 
 bool gram_path_fits(const Dims &D)
 {
     if (D.cache_dtype != 0 || (D.flags & 1)) return false; // PAC_FLAG_PER_LAYER
     if (D.r > 128 || D.d > kMaxD || D.L > 128) return false;
-    return chain_lds_bytes(D) <= 160 * 1024;
+    return chain_lds(D.L, D.r, true) <= 160 * 1024;
 }
 
 void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
@@ -81,21 +90,21 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.g_Gp = take(D.Mmax * Lr * 2);
     W.g_HSpart = take((int64_t)W.max_tiles * Lr * 4);
     W.g_cspart = take((int64_t)W.max_tiles * Lr * 4);
-    W.g_ghat = take((int64_t)D.B_max * Lr * 4);
+    W.g_zpart = take((int64_t)W.max_tiles * D.C * 4);
+    W.g_zpb = take((int64_t)D.B_max * D.C * 4);
     W.g_Z = take(Lr * D.C * 4);
     W.g_dzsum = take(kMaxClasses * 4);
     W.g_cs = take(Lr * 4);
     W.g_Epart = take((int64_t)W.se * D.L * D.d * D.r * 4);
     W.g_GGpart = take((int64_t)W.sg * Lr * Lr * 4);
+    W.g_E = take((int64_t)D.L * D.d * D.r * 4);
     W.g_GGT = take(Lr * Lr * 2);
     W.g_GGsc = take(Lr * Lr * 2);
     W.g_dlam_slots = cdiv(D.d, 64) * cdiv(D.r, 64);
     W.g_dlam_part = take((int64_t)D.L * W.g_dlam_slots * 4);
     W.g_counter = take((int64_t)(D.L + 1) * 4);
     W.g_samp_tile0 = take((kMaxBatch + 1) * 4);
-    W.g_HSm = take((int64_t)D.B_max * Lr * 4);
     W.g_loss_part = take(kMaxBatch * 4);
-    W.g_E = take((int64_t)D.L * D.d * D.r * 4);
 }
 
 __device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }
@@ -289,7 +298,6 @@ struct EpiChat {
 
 using T64 = Tile<2, 2, 1, 1, 1>;
 using T64K = Tile<2, 2, 1, 1, 4>; // 128-token K step for the token contractions
-using TG = Tile<2, 2, 2, 2, 4>;   // 128 x 128 tile of the Gram matrix
 
 template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArgs a)
 {
@@ -388,27 +396,65 @@ struct ChainArgs {
     const bf16_t *Q;     // forward: QpT ; backward: QpN scaled by (1 - lambda) of the later layer
     bf16_t *Hg;          // forward: H [M][L*r] ; backward: DP [M][L*r]
     float *part;         // forward: HSpart ; backward: cspart   [tiles][L][r]
-    const float *ghat;   // backward: [B][L][r]
+    // classifier head: the forward chain leaves each tile's share of the logits, the backward chain
+    // (or k_glogits when no gradients are wanted) turns them into the loss and dz
+    int B, C;
+    const float *V;      // [L*r][C]
+    const float *pb;     // [B][d] token means of the last cached layer
+    const float *cusumL; // [d] sum of all c_up
+    float *zpart;        // [tiles][C]  sum_kk (column sums of h over the tile)[kk] V[kk][c]
+    float *zpb;          // [B][C]      (pb + cusumL) W_cls, written by the first tile of each sample
+    const int32_t *samp_tile0, *samp_len, *labels;
+    float *logits_ws, *logits_out, *dz, *loss_part;
 };
 
-constexpr int kRing = 4; // layers of per-token inputs staged ahead in LDS
+// Logits, loss term and dz of sample s, by a whole workgroup (at least C threads).
+// zs, dzs: C floats of LDS each; dzs holds dz of the sample on return.
+__device__ __forceinline__ void sample_head(const ChainArgs &a, int s, bool write, float *zs, float *dzs)
+{
+    const int t = threadIdx.x, C = a.C;
+    if (t < C) {
+        const int tl0 = a.samp_tile0[s], tl1 = a.samp_tile0[s + 1];
+        float z = 0.f;
+#pragma unroll 8
+        for (int k = tl0; k < tl1; ++k) z += a.zpart[(int64_t)k * C + t];
+        const float *c_cls = a.params + (int64_t)a.L * a.PL + (int64_t)a.d * C;
+        zs[t] = z / (float)a.samp_len[s] + a.zpb[s * C + t] + c_cls[t];
+    }
+    __syncthreads();
+    if (t == 0) {
+        float zmax = -INFINITY;
+        for (int c = 0; c < C; ++c) zmax = fmaxf(zmax, zs[c]);
+        float se = 0.f;
+        for (int c = 0; c < C; ++c) se += expf(zs[c] - zmax);
+        const float lse = zmax + logf(se);
+        const int y = a.labels[s];
+        float lossv = NAN;
+        for (int c = 0; c < C; ++c) {
+            const float gz = (expf(zs[c] - lse) - (c == y ? 1.f : 0.f)) / (float)a.B;
+            dzs[c] = gz;
+            if (c == y) lossv = lse - zs[c];
+            if (write) {
+                a.logits_ws[s * C + c] = zs[c];
+                if (a.logits_out) a.logits_out[s * C + c] = zs[c];
+                a.dz[s * C + c] = gz;
+            }
+        }
+        if (write) a.loss_part[s] = lossv; // summed in sample order by k_gfinish
+    }
+    __syncthreads();
+}
 
-// LDS of the chain kernels (T = kChainRows):
-//   Hs   [L][T][r+pad] bf16   h (forward) or dpre (backward) of every layer: the contraction operand
-//   ring [kRing][T][r]        per-token inputs of the coming layers: U (fp32, forward) or GELU' (bf16, backward)
-//   Gst  [2][T][r] bf16       forward only: GELU' of the layer just finished, on its way to global memory
-//   vecS [L][r] fp32          per-layer vector: (1-lambda) chat + c_down (forward), ghat of the sample (backward)
-//   Cs   [L][r] fp32 column sums, lamS [L] fp32
+// forward-only calls: the head without a backward chain, one workgroup per sample
+__global__ __launch_bounds__(64) void k_glogits(ChainArgs a)
+{
+    __shared__ float zs[kMaxClasses], dzs[kMaxClasses];
+    sample_head(a, blockIdx.x, true, zs, dzs);
+}
+
 // Wavefronts 0..r/16-1 contract and apply the nonlinearity; one more wavefront only moves the
 // per-token inputs of later layers from global memory into the ring, so that no contracting
 // wavefront ever waits on those loads.
-static size_t chain_lds(int L, int r, bool fwd)
-{
-    const size_t hs = (size_t)L * kChainRows * (r + kChainPad) * 2;
-    const size_t ring = (size_t)kRing * kChainRows * r * (fwd ? 4 : 2);
-    const size_t gstage = fwd ? (size_t)2 * kChainRows * r * 2 : 0;
-    return hs + ring + gstage + (size_t)L * r * 4 * 2 + (size_t)((L + 3) / 4 * 4) * 4;
-}
 
 // GELU(u) and GELU'(u) from one exponential: erf by the five-term rational approximation of
 // Abramowitz & Stegun 7.1.26 (absolute error below 1.5e-7), whose exp(-x^2) with x = |u|/sqrt(2)
@@ -443,6 +489,7 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
     float *vecS = reinterpret_cast<float *>(Gst + (FWD ? (size_t)2 * T * r : 0));   // [L][r]
     float *Cs = vecS + (size_t)L * r;                                               // [L][r]
     float *lamS = Cs + (size_t)L * r;                                               // [L]
+    float *zs = lamS + (L + 3) / 4 * 4, *dzs = zs + kMaxClasses;                    // [kMaxClasses] each
     const int tile = blockIdx.x;
     const int m0 = a.tile_row0[tile], nrows = a.tile_rows[tile], samp = a.tile_samp[tile];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -452,13 +499,18 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
     auto layer_at = [&](int step) { return FWD ? step : L - 1 - step; };
 
     // per-layer vectors
+    if (!FWD) sample_head(a, samp, tile == a.samp_tile0[samp], zs, dzs);
+    const float inv_len = 1.f / (float)a.samp_len[samp];
     for (int c = threadIdx.x; c < L * r; c += nthreads) {
         const int l = c / r, nn = c % r;
         if (FWD) {
             const float *pl = a.params + (int64_t)l * a.PL;
             vecS[c] = (1.f - pl[a.PL - 1]) * a.chat[c] + pl[(int64_t)a.d * r + nn];
         } else {
-            vecS[c] = a.ghat[(int64_t)samp * Lr + c];
+            // ghat = dz V^T / len: what the head hands to every token of the sample
+            float v = 0.f;
+            for (int q = 0; q < a.C; ++q) v += dzs[q] * a.V[(int64_t)c * a.C + q];
+            vecS[c] = v * inv_len;
         }
     }
     for (int l = threadIdx.x; l < L; l += nthreads) lamS[l] = a.params[(int64_t)l * a.PL + a.PL - 1];
@@ -630,107 +682,90 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
                 *reinterpret_cast<const u32x4 *>(Hs + ((int64_t)l * T + row) * RP + cc * 8);
     }
     for (int c = threadIdx.x; c < L * r; c += nthreads) a.part[(int64_t)tile * Lr + c] = Cs[c];
-}
-
-// ---------------------------------------------------------------------------
-// launch 4: logits, loss, dz, and the small per-sample quantities of the backward pass
-// ---------------------------------------------------------------------------
-struct HeadArgs {
-    int B, L, d, r, C;
-    const float *params;
-    int64_t PL;
-    const float *pb, *cusum, *V, *HSpart;
-    const int32_t *samp_tile0, *samp_len, *labels;
-    float *logits_ws, *logits_out, *dz, *loss_out, *ghat, *HSm, *loss_part;
-    unsigned *counter; // one counter after the per-layer ones
-};
-
-// One workgroup per sample: logits, loss term, dz, ghat = (dz V^T)/len, and the token mean of h.
-__global__ __launch_bounds__(256) void k_ghead(HeadArgs a)
-{
-    __shared__ float red[4][kMaxClasses];
-    __shared__ float sdz[kMaxClasses];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int s = blockIdx.x;
-    const int B = a.B, L = a.L, d = a.d, r = a.r, C = a.C;
-    const int64_t Lr = (int64_t)L * r;
-    const float *Wc = a.params + (int64_t)L * a.PL;
-    const float *cc = Wc + (int64_t)d * C;
-    const float *cusumL = a.cusum + (int64_t)L * d;
-    const int tl0 = a.samp_tile0[s], tl1 = a.samp_tile0[s + 1];
-    const float inv_len = 1.f / (float)a.samp_len[s];
-    float acc[kMaxClasses];
+    if (FWD) {
+        // this tile's share of the logits; the first tile of a sample adds the part that comes
+        // from the cached last layer and the biases
+        const int C = a.C;
+        const bool first = tile == a.samp_tile0[samp];
+        float za[kMaxClasses], zb[kMaxClasses];
 #pragma unroll
-    for (int c = 0; c < kMaxClasses; ++c) acc[c] = 0.f;
-    for (int64_t kk = t; kk < Lr; kk += 256) {
-        float hs = 0.f;
-        for (int k = tl0; k < tl1; ++k) hs += a.HSpart[(int64_t)k * Lr + kk];
-        hs *= inv_len;
-        a.HSm[(int64_t)s * Lr + kk] = hs;
-        for (int c = 0; c < C; ++c) acc[c] += hs * a.V[kk * C + c];
-    }
-    for (int j = t; j < d; j += 256) {
-        const float p = a.pb[(int64_t)s * d + j] + cusumL[j];
-        for (int c = 0; c < C; ++c) acc[c] += p * Wc[(int64_t)j * C + c];
-    }
-    for (int c = 0; c < C; ++c) {
-        float v = acc[c];
+        for (int c = 0; c < kMaxClasses; ++c) za[c] = zb[c] = 0.f;
+        for (int kk = threadIdx.x; kk < L * r; kk += nthreads) {
+            const float hs = Cs[kk];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
-        if (lane == 0) red[wave][c] = v;
-    }
-    __syncthreads();
-    if (t == 0) {
-        float z[kMaxClasses];
-        float zmax = -INFINITY;
-        for (int c = 0; c < C; ++c) {
-            z[c] = red[0][c] + red[1][c] + red[2][c] + red[3][c] + cc[c];
-            zmax = fmaxf(zmax, z[c]);
+            for (int c = 0; c < kMaxClasses; ++c)
+                if (c < C) za[c] += hs * a.V[(int64_t)kk * C + c];
         }
-        float se = 0.f;
-        for (int c = 0; c < C; ++c) se += expf(z[c] - zmax);
-        const float lse = zmax + logf(se);
-        const int y = a.labels[s];
-        float lossv = NAN;
-        for (int c = 0; c < C; ++c) {
-            a.logits_ws[s * C + c] = z[c];
-            if (a.logits_out) a.logits_out[s * C + c] = z[c];
-            const float gz = (expf(z[c] - lse) - (c == y ? 1.f : 0.f)) / (float)B;
-            a.dz[s * C + c] = gz;
-            sdz[c] = gz;
-            if (c == y) lossv = lse - z[c];
+        if (first) {
+            const float *Wc = a.params + (int64_t)L * a.PL;
+            for (int j = threadIdx.x; j < a.d; j += nthreads) {
+                const float pv = a.pb[(int64_t)samp * a.d + j] + a.cusumL[j];
+#pragma unroll
+                for (int c = 0; c < kMaxClasses; ++c)
+                    if (c < C) zb[c] += pv * Wc[(int64_t)j * C + c];
+            }
         }
-        a.loss_part[s] = lossv; // summed in sample order by k_gfinish
-    }
-    __syncthreads();
-    for (int64_t kk = t; kk < Lr; kk += 256) {
-        float v = 0.f;
-        for (int c = 0; c < C; ++c) v += sdz[c] * a.V[kk * C + c];
-        a.ghat[(int64_t)s * Lr + kk] = v * inv_len;
+        float *red = reinterpret_cast<float *>(ring); // [NW + 1][2][kMaxClasses]; the ring is idle by now
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c)
+            if (c < C) {
+                float va = za[c], vb = zb[c];
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) {
+                    va += __shfl_down(va, o, 64);
+                    vb += __shfl_down(vb, o, 64);
+                }
+                if (lane == 0) {
+                    red[(wave * 2 + 0) * kMaxClasses + c] = va;
+                    red[(wave * 2 + 1) * kMaxClasses + c] = vb;
+                }
+            }
+        __syncthreads();
+        if ((int)threadIdx.x < C) {
+            float s0 = 0.f, s1 = 0.f;
+            for (int w = 0; w <= NW; ++w) {
+                s0 += red[(w * 2 + 0) * kMaxClasses + threadIdx.x];
+                s1 += red[(w * 2 + 1) * kMaxClasses + threadIdx.x];
+            }
+            a.zpart[(int64_t)tile * C + threadIdx.x] = s0;
+            if (first) a.zpb[samp * C + threadIdx.x] = s1;
+        }
     }
 }
 
 // ---------------------------------------------------------------------------
-// launch 6: contractions over the tokens.  E_l = b_l^T dpre_l ; GG = H^T DP (all layer pairs at once)
+// launch 5: contractions over the tokens.  E_l = b_l^T dpre_l ; GG = H^T DP (all layer pairs at
+// once, kept only as the two bf16 copies the last launch contracts) ; ordered sums of the tiles'
+// column sums
 // ---------------------------------------------------------------------------
 struct TokRedArgs {
     int blk_off; // first block of this launch (parts may be launched separately for timing)
     const bf16_t *cache;
     RowMap map;
     int L, d, r;
-    int nb_E, e_tiles, se, sg, rows_per_se, rows_per_sg, tg;
+    int nb_E, nb_G, e_tiles, se, sg, rows_per_se, rows_per_sg, tg;
     const bf16_t *H, *DP; // [M][L*r]
     float *Epart;         // [se][L][d][r]
+    const float *params;
+    int64_t PL;
     float *GGpart;        // [sg][L*r][L*r]
+    int ntiles, B, C;
+    const float *cspart, *HSpart, *dz;
+    const int32_t *tile_samp, *samp_len;
+    float *cs, *Z, *dzsum;
 };
+
+using TG = Tile<2, 2, 2, 2, 4>; // 128 x 128 tile of the Gram matrix
 
 template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
 {
     using TE = Tile<4, 1, 1, NT, 4>;
-    constexpr int kLds = tile_lds_bytes<bf16_t, TE>() > tile_lds_bytes<bf16_t, TG>() ? tile_lds_bytes<bf16_t, TE>()
-                                                                                     : tile_lds_bytes<bf16_t, TG>();
+    constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4;
+    constexpr int kTileLds = tile_lds_bytes<bf16_t, TE>() > tile_lds_bytes<bf16_t, TG>()
+                                 ? tile_lds_bytes<bf16_t, TE>() : tile_lds_bytes<bf16_t, TG>();
+    constexpr int kLds = kTileLds > kVecLds ? kTileLds : kVecLds;
     __shared__ __attribute__((aligned(16))) char smem[kLds];
-    const int b = blockIdx.x + a.blk_off;
+    const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
     const int M = a.map.M;
     const int Lr = a.L * a.r;
     if (b < a.nb_E) {
@@ -748,7 +783,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         gemm_tile<bf16_t, TE>(smem, al, bl, epi, kbegin, kend, it * TE::BM, 0, a.d, a.r);
         return;
     }
-    {
+    if (b < a.nb_E + a.nb_G) {
         int idx = b - a.nb_E;
         const int split = idx % a.sg;
         idx /= a.sg;
@@ -765,92 +800,91 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         bl.src = a.DP; bl.ld = Lr; bl.ncols = Lr; bl.kend = kend;
         EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
         gemm_tile<bf16_t, TG>(smem, al, bl, epi, kbegin, kend, ti * TG::BM, tj * TG::BN, Lr, Lr);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// launch 7: ordered sums of the split partials; bf16 copies of GG for the last contractions
-// ---------------------------------------------------------------------------
-struct ReduceArgs {
-    int blk_off; // first block of this launch (parts may be launched separately for timing)
-    int L, r, sg, ntiles, nb_GG, nb_Esum, B, C, se;
-    int64_t e_elems; // L * d * r
-    const float *Epart;
-    float *E;
-    const float *params;
-    int64_t PL;
-    const float *GGpart, *cspart, *HSm, *dz;
-    bf16_t *GGT, *GGsc;
-    float *cs, *Z, *dzsum;
-};
-
-__global__ __launch_bounds__(256) void k_greduce(ReduceArgs a)
-{
-    __shared__ float tile[32][33];
-    const int Lr = a.L * a.r;
-    const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
-    if (b < a.nb_GG) {
-        const int tg = Lr / 32;
-        const int tr = b / tg, tcx = b % tg;
-        // rows of layer k, columns of layer l: used only for k < l
-        if ((tr * 32) / a.r >= (tcx * 32 + 31) / a.r) return;
-        const int tx = t & 31, ty = t >> 5;
-        for (int y = ty; y < 32; y += 8) {
-            const int row = tr * 32 + y, col = tcx * 32 + tx;
-            float acc = 0.f;
-            for (int s = 0; s < a.sg; ++s) acc += a.GGpart[((int64_t)s * Lr + row) * Lr + col];
-            tile[y][tx] = acc;
-            const float lam = a.params[(int64_t)(col / a.r) * a.PL + a.PL - 1];
-            a.GGsc[(int64_t)row * Lr + col] = static_cast<bf16_t>((1.f - lam) * acc);
-        }
-        __syncthreads();
-        for (int y = ty; y < 32; y += 8)
-            a.GGT[(int64_t)(tcx * 32 + y) * Lr + tr * 32 + tx] = static_cast<bf16_t>(tile[tx][y]);
         return;
     }
-    if (b < a.nb_GG + a.nb_Esum) {
-        const int64_t o = ((int64_t)(b - a.nb_GG) * 256 + t) * 4;
-        if (o < a.e_elems) { // e_elems is a multiple of 4
-            float4 acc = *reinterpret_cast<const float4 *>(a.Epart + o);
-            for (int s2 = 1; s2 < a.se; ++s2) {
-                const float4 v = *reinterpret_cast<const float4 *>(a.Epart + (int64_t)s2 * a.e_elems + o);
-                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-            }
-            *reinterpret_cast<float4 *>(a.E + o) = acc;
-        }
-        return;
-    }
-    // cs = ordered sum of the tiles' column sums; Z[kk][c] = sum_s mean_t(h)[s][kk] dz[s][c].
-    // 64 indices per block, the tiles / samples split over 4 thread groups, combined in group order.
-    float *red = &tile[0][0]; // 4 * 64 * (1 + C) floats needed
-    const int vb = b - a.nb_GG - a.nb_Esum;
-    const int idx = vb * 64 + (t & 63), grp = t >> 6;
+    // cs[kk] = sum over the tiles of their column sums of dpre ;
+    // Z[kk][c] = sum_s mean_t(h)[s][kk] dz[s][c], from the tiles' column sums of h.
+    // 16 indices per block, the tiles dealt over 16 thread groups whose sums are combined in group order.
+    const int C = a.C;
+    float *red = reinterpret_cast<float *>(smem); // [16 groups][16 indices][1 + kMaxClasses]
+    const int vb = b - a.nb_E - a.nb_G;
+    const int ii = t & 15, grp = t >> 4;
+    const int idx = vb * 16 + ii;
     float acc = 0.f;
     float zc[kMaxClasses];
 #pragma unroll
     for (int c = 0; c < kMaxClasses; ++c) zc[c] = 0.f;
     if (idx < Lr) {
-        for (int k = grp; k < a.ntiles; k += 4) acc += a.cspart[(int64_t)k * Lr + idx];
-        for (int s = grp; s < a.B; s += 4) {
-            const float hs = a.HSm[(int64_t)s * Lr + idx];
-            for (int c = 0; c < a.C; ++c) zc[c] += hs * a.dz[s * a.C + c];
+#pragma unroll 4
+        for (int k = grp; k < a.ntiles; k += 16) {
+            acc += a.cspart[(int64_t)k * Lr + idx];
+            const int s = a.tile_samp[k];
+            const float hs = a.HSpart[(int64_t)k * Lr + idx] / (float)a.samp_len[s];
+#pragma unroll
+            for (int c = 0; c < kMaxClasses; ++c)
+                if (c < C) zc[c] += hs * a.dz[s * C + c];
         }
     }
-    __shared__ float zred[4 * 64 * kMaxClasses]; // [4][64][C]
-    red[grp * 64 + (t & 63)] = acc;
-    for (int c = 0; c < a.C; ++c) zred[(grp * 64 + (t & 63)) * kMaxClasses + c] = zc[c];
+    red[(grp * 16 + ii) * (1 + kMaxClasses)] = acc;
+#pragma unroll
+    for (int c = 0; c < kMaxClasses; ++c)
+        if (c < C) red[(grp * 16 + ii) * (1 + kMaxClasses) + 1 + c] = zc[c];
     __syncthreads();
-    if (grp == 0 && idx < Lr) {
-        a.cs[idx] = (red[t] + red[64 + t]) + (red[128 + t] + red[192 + t]);
-        for (int c = 0; c < a.C; ++c)
-            a.Z[(int64_t)idx * a.C + c] = (zred[t * kMaxClasses + c] + zred[(64 + t) * kMaxClasses + c]) +
-                                          (zred[(128 + t) * kMaxClasses + c] + zred[(192 + t) * kMaxClasses + c]);
+    // thread (index ii, value q): q = 0 is cs, q = 1 + c is Z[.][c]
+    for (int q = grp; q < 1 + C; q += 16) {
+        float tot = 0.f;
+        for (int g2 = 0; g2 < 16; ++g2) tot += red[(g2 * 16 + ii) * (1 + kMaxClasses) + q];
+        if (idx < Lr) {
+            if (q == 0) a.cs[idx] = tot;
+            else a.Z[(int64_t)idx * C + q - 1] = tot;
+        }
     }
-    if (vb == 0 && t < a.C) {
+    if (vb == 0 && t < C) {
         float sum = 0.f;
-        for (int s = 0; s < a.B; ++s) sum += a.dz[s * a.C + t];
+        for (int s = 0; s < a.B; ++s) sum += a.dz[s * C + t];
         a.dzsum[t] = sum;
     }
+}
+
+// ---------------------------------------------------------------------------
+// launch 6: ordered sums of the token-split partials: E, and the Gram matrix, kept as the two bf16
+// copies the last launch contracts: GG transposed, and GG with column layer l scaled by (1 - lambda_l)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_ggsum(int L, int r, int sg, const float *GGpart, const float *params,
+                                               int64_t PL, bf16_t *GGT, bf16_t *GGsc, int nb_GG, int se,
+                                               int64_t e_elems, const float *Epart, float *E)
+{
+    __shared__ float tile[32][33];
+    const int Lr = L * r;
+    const int b = blockIdx.x, t = threadIdx.x;
+    if (b >= nb_GG) {
+        // E = ordered sum of its token-split partials, four elements per thread
+        const int64_t o = ((int64_t)(b - nb_GG) * 256 + t) * 4;
+        if (o < e_elems) { // e_elems is a multiple of 4
+            f32x4 acc = *reinterpret_cast<const f32x4 *>(Epart + o);
+            for (int s2 = 1; s2 < se; ++s2) acc += *reinterpret_cast<const f32x4 *>(Epart + (int64_t)s2 * e_elems + o);
+            *reinterpret_cast<f32x4 *>(E + o) = acc;
+        }
+        return;
+    }
+    const int tg = Lr / 32;
+    const int tr = b / tg, tcx = b % tg;
+    // rows of layer k, columns of layer l: used only for k < l
+    if ((tr * 32) / r >= (tcx * 32 + 31) / r) return;
+    const int tx = t & 31, ty = t >> 5;
+#pragma unroll
+    for (int y = ty; y < 32; y += 8) {
+        const int row = tr * 32 + y, col = tcx * 32 + tx;
+        float acc = 0.f;
+        for (int s = 0; s < sg; ++s) acc += GGpart[((int64_t)s * Lr + row) * Lr + col];
+        tile[y][tx] = acc;
+        const float lam = params[(int64_t)(col / r) * PL + PL - 1];
+        GGsc[(int64_t)row * Lr + col] = static_cast<bf16_t>((1.f - lam) * acc);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int y = ty; y < 32; y += 8)
+        GGT[(int64_t)(tcx * 32 + y) * Lr + tr * 32 + tx] = static_cast<bf16_t>(tile[tx][y]);
 }
 
 // ---------------------------------------------------------------------------
@@ -1117,7 +1151,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     int32_t *tile_rows = (int32_t *)(ws + W.g_tile_rows);
     int32_t *tile_samp = (int32_t *)(ws + W.g_tile_samp);
     int32_t *samp_tile0 = (int32_t *)(ws + W.g_samp_tile0);
-    float *HSm = (float *)(ws + W.g_HSm), *loss_part = (float *)(ws + W.g_loss_part);
+    float *loss_part = (float *)(ws + W.g_loss_part);
     bf16_t *WdT = (bf16_t *)(ws + W.WdT), *Wu = (bf16_t *)(ws + W.Wu);
     bf16_t *WuTs = (bf16_t *)(ws + W.g_WuTs), *Wds = (bf16_t *)(ws + W.g_Wds);
     float *cusum = (float *)(ws + W.g_cusum), *chat = (float *)(ws + W.g_chat), *V = (float *)(ws + W.g_V);
@@ -1127,7 +1161,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     float *pb = (float *)(ws + W.pooled);
     float *HSpart = (float *)(ws + W.g_HSpart), *cspart = (float *)(ws + W.g_cspart);
     float *logits = (float *)(ws + W.logits), *dz = (float *)(ws + W.dz);
-    float *ghat = (float *)(ws + W.g_ghat), *Z = (float *)(ws + W.g_Z), *dzsum = (float *)(ws + W.g_dzsum);
+    float *zpart = (float *)(ws + W.g_zpart), *zpb = (float *)(ws + W.g_zpb);
+    float *Z = (float *)(ws + W.g_Z), *dzsum = (float *)(ws + W.g_dzsum);
     float *cs = (float *)(ws + W.g_cs);
     float *Epart = (float *)(ws + W.g_Epart), *GGpart = (float *)(ws + W.g_GGpart);
     bf16_t *GGT = (bf16_t *)(ws + W.g_GGT), *GGsc = (bf16_t *)(ws + W.g_GGsc);
@@ -1177,21 +1212,16 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     ChainArgs ca;
     ca.L = L; ca.r = r; ca.M = M; ca.tile_row0 = tile_row0; ca.tile_rows = tile_rows; ca.tile_samp = tile_samp;
     ca.params = io.params; ca.PL = D.PL; ca.d = d; ca.U = pre; ca.Gp = (bf16_t *)(ws + W.g_Gp); ca.chat = chat;
-    ca.ghat = ghat;
+    ca.B = B; ca.C = C; ca.V = V; ca.pb = pb; ca.cusumL = cusum + (int64_t)L * d; ca.zpart = zpart; ca.zpb = zpb;
+    ca.samp_tile0 = samp_tile0; ca.samp_len = samp_len; ca.labels = io.labels;
+    ca.logits_ws = logits; ca.logits_out = io.logits_out; ca.dz = dz; ca.loss_part = loss_part;
     {
         ChainArgs a = ca;
         a.Q = QpT; a.Hg = H; a.part = HSpart;
         PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_fwd, st, a);
     }
-    {
-        HeadArgs a;
-        a.B = B; a.L = L; a.d = d; a.r = r; a.C = C; a.params = io.params; a.PL = D.PL;
-        a.pb = pb; a.cusum = cusum; a.V = V; a.HSpart = HSpart; a.samp_tile0 = samp_tile0; a.samp_len = samp_len;
-        a.labels = io.labels; a.logits_ws = logits; a.logits_out = io.logits_out; a.dz = dz;
-        a.loss_out = io.loss_out; a.ghat = ghat; a.HSm = HSm; a.loss_part = loss_part; a.counter = counter + L;
-        PAC_LAUNCH(prof, st, KC_G_HEAD, k_ghead, dim3(B), dim3(256), 0, st, a);
-    }
     if (!io.grads) {
+        PAC_LAUNCH(prof, st, KC_G_HEAD, k_glogits, dim3(B), dim3(64), 0, st, ca);
         PAC_LAUNCH(prof, st, KC_G_FINISH, k_gfinish, dim3(1), dim3(64), 0, st, loss_part, B, io.loss_out, nullptr, 0, L,
                    D.PL, nullptr);
         return hipGetLastError();
@@ -1211,22 +1241,21 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.sg = cdiv(M, a.rows_per_sg);
         a.tg = cdiv(Lr, 128);
         a.nb_E = L * a.e_tiles * a.se;
+        a.nb_G = L > 1 ? a.tg * a.tg * a.sg : 0;
         a.H = H; a.DP = DP; a.Epart = Epart; a.GGpart = GGpart;
+        a.ntiles = ntiles; a.B = B; a.C = C; a.cspart = cspart; a.HSpart = HSpart; a.dz = dz;
+        a.tile_samp = tile_samp; a.samp_len = samp_len; a.cs = cs; a.Z = Z; a.dzsum = dzsum;
         {
-            const int counts[2] = {a.nb_E, L > 1 ? a.tg * a.tg * a.sg : 0};
-            const int classes[2] = {KC_G_TOKRED_E, KC_G_TOKRED_G};
-            launch_parts(prof, st, split, k_gtokred<NT>, a, 2, counts, classes, KC_G_TOKRED, 256);
+            const int counts[3] = {a.nb_E, a.nb_G, cdiv(Lr, 16)};
+            const int classes[3] = {KC_G_TOKRED_E, KC_G_TOKRED_G, KC_G_TOKRED_VEC};
+            launch_parts(prof, st, split, k_gtokred<NT>, a, 3, counts, classes, KC_G_TOKRED, 256);
         }
-        ReduceArgs ra;
-        ra.L = L; ra.r = r; ra.sg = a.sg; ra.ntiles = ntiles; ra.nb_GG = L > 1 ? (Lr / 32) * (Lr / 32) : 0;
-        ra.params = io.params; ra.PL = D.PL; ra.GGpart = GGpart; ra.cspart = cspart; ra.GGT = GGT; ra.GGsc = GGsc;
-        ra.e_elems = (int64_t)L * d * r; ra.nb_Esum = cdiv(ra.e_elems / 4, 256); ra.se = a.se; ra.Epart = Epart;
-        ra.E = (float *)(ws + W.g_E);
-        ra.cs = cs; ra.B = B; ra.C = C; ra.HSm = HSm; ra.dz = dz; ra.Z = Z; ra.dzsum = dzsum;
         {
-            const int counts[3] = {ra.nb_GG, ra.nb_Esum, cdiv(Lr, 64)};
-            const int classes[3] = {KC_G_REDUCE_GG, KC_G_REDUCE_E, KC_G_REDUCE_VEC};
-            launch_parts(prof, st, split, k_greduce, ra, 3, counts, classes, KC_G_REDUCE, 256);
+            const int nb_GG = L > 1 ? (Lr / 32) * (Lr / 32) : 0;
+            const int64_t e_elems = (int64_t)L * d * r;
+            float *E = (float *)(ws + W.g_E);
+            PAC_LAUNCH(prof, st, KC_G_GGSUM, k_ggsum, dim3(nb_GG + cdiv(e_elems / 4, 256)), dim3(256), 0, st, L, r, a.sg,
+                       GGpart, io.params, D.PL, GGT, GGsc, nb_GG, a.se, e_elems, Epart, E);
         }
         PostArgs pa;
         pa.L = L; pa.d = d; pa.r = r; pa.C = C; pa.B = B; pa.se = 1;

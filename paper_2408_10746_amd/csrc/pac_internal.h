@@ -43,11 +43,12 @@ struct WsLayout {
     int64_t g_QpN, g_QpT;           // bf16 [pairs][r][r], both orientations
     int64_t g_DP;                   // bf16 [Mmax][L*r]
     int64_t g_HSpart, g_cspart;     // f32 [max_tiles][L][r]
-    int64_t g_ghat, g_Z, g_dzsum, g_cs;
+    int64_t g_zpart, g_zpb;         // f32 [max_tiles][C], [B_max][C]: shares of the logits
+    int64_t g_Z, g_dzsum, g_cs;
     int64_t g_Epart, g_GGpart;      // f32 [se][L][d*r], [sg][L*r][L*r]
     int64_t g_GGT, g_GGsc;          // bf16 [L*r][L*r]
     int64_t g_dlam_part, g_counter; // f32 [L][slots], u32 [L + 1]
-    int64_t g_samp_tile0, g_HSm, g_loss_part, g_E, g_Gp;
+    int64_t g_samp_tile0, g_loss_part, g_Gp, g_E;
     int32_t g_dlam_slots;
 };
 
@@ -65,10 +66,10 @@ struct Dims {
 enum KClass {
     KC_CACHE_FILL = 0, KC_SETUP, KC_SHADOWS, KC_FWD_DOWN, KC_FWD_UP, KC_POOL, KC_HEAD, KC_HEAD_BWD,
     KC_BWD_DPRE, KC_BWD_WGRAD, KC_BWD_DX, KC_REDUCE, KC_ADAMW,
-    KC_G_PREP, KC_G_PROJ, KC_G_CHAIN_FWD, KC_G_HEAD, KC_G_CHAIN_BWD, KC_G_TOKRED, KC_G_REDUCE, KC_G_POST, KC_G_FINISH,
+    KC_G_PREP, KC_G_PROJ, KC_G_CHAIN_FWD, KC_G_HEAD, KC_G_CHAIN_BWD, KC_G_TOKRED, KC_G_GGSUM, KC_G_POST, KC_G_FINISH,
     // parts of the fused launches, seen only with PAC_FLAG_SPLIT_LAUNCH
     KC_G_PREP_SETUP, KC_G_PREP_COPY, KC_G_PREP_CHAT, KC_G_PREP_V, KC_G_PROJ_U, KC_G_PROJ_Q, KC_G_PROJ_PB,
-    KC_G_TOKRED_E, KC_G_TOKRED_G, KC_G_REDUCE_GG, KC_G_REDUCE_E, KC_G_REDUCE_VEC, KC_G_POST_F, KC_G_POST_W, KC_G_POST_VEC,
+    KC_G_TOKRED_E, KC_G_TOKRED_G, KC_G_TOKRED_VEC, KC_G_POST_F, KC_G_POST_W, KC_G_POST_VEC,
     KC_COUNT
 };
 
