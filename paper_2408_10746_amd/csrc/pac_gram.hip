@@ -17,7 +17,7 @@
 //
 // This is the same function as the per-layer kernels compute (the layer-by-layer definition is the
 // oracle's); only the order of the floating-point operations differs.  Every reduction is ordered.
-#include "pac_gemm.h"
+#include "pac_mma.h"
 #include "pac_internal.h"
 #include <type_traits>
 
@@ -36,6 +36,7 @@ static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 constexpr int kChainRows = 16;   // token rows per chain workgroup
 constexpr int kChainPad = 8;     // bf16 elements of padding per LDS row
 constexpr int kMaxD = 4096;
+constexpr int kMaxSplitTiles = 512; // 16-token tiles one workgroup of the E contraction walks over at most
 
 constexpr int kRing = 4; // layers of per-token inputs the chain kernels stage ahead in LDS
 
@@ -72,10 +73,12 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     const int max_by_rows = (int)((D.Mmax + 127) / 128);
     if (se > max_by_rows) se = max_by_rows;
     W.se = se < 1 ? 1 : (se > 16 ? 16 : se);
+    if (cdiv(W.max_tiles, W.se) > kMaxSplitTiles) W.se = cdiv(W.max_tiles, kMaxSplitTiles); // LDS tile table of k_gtokred
     const int tg = cdiv(Lr, 128);
     int sg = cdiv(256, (int64_t)tg * (tg + 1) / 2);
     if (sg > max_by_rows) sg = max_by_rows;
     W.sg = sg < 1 ? 1 : (sg > 16 ? 16 : sg);
+    W.g_zero = take(256);
     W.g_tile_row0 = take(W.max_tiles * 4);
     W.g_tile_rows = take(W.max_tiles * 4);
     W.g_tile_samp = take(W.max_tiles * 4);
@@ -132,6 +135,7 @@ struct PrepArgs {
     bf16_t *WdT, *Wu, *WuTs, *Wds;
     float *cusum, *V;
     unsigned *counter;
+    float *zero; // 64 floats kept at zero for the contractions' empty token slots
 };
 
 __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
@@ -148,6 +152,7 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
                 if (t < meta.B) a.samp_len[t] = meta.len[t];
             }
             if (t <= L) a.counter[t] = 0u;
+            if (t < 64) a.zero[t] = 0.f;
             if (t < meta.B) {
                 // tiles of sample t start after the tiles of the samples before it
                 int nt = 0;
@@ -299,23 +304,33 @@ struct EpiChat {
 using T64 = Tile<2, 2, 1, 1, 1>;
 using T64K = Tile<2, 2, 1, 1, 4>; // 128-token K step for the token contractions
 
-template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArgs a)
+template <int NT, int BK> struct ProjShapes {
+    using TU = NtTile<4, 1, 1, NT, BK, 2>;  // 128 token rows x r
+    using TQ = NtTile<2, 2, 1, 1, BK, 3>;   // 64 x 64
+    using TC = Tile<2, 2, 1, 1, BK / 32>;   // the one-row chat contraction (staged through registers)
+    static constexpr int kA = TU::LDS_BYTES > TQ::LDS_BYTES ? TU::LDS_BYTES : TQ::LDS_BYTES;
+    static constexpr int kB = tile_lds_bytes<bf16_t, TC>() > 8 * 256 * 4 ? tile_lds_bytes<bf16_t, TC>() : 8 * 256 * 4;
+    static constexpr int kLds = kA > kB ? kA : kB;
+};
+
+template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArgs a)
 {
-    using TU = Tile<4, 1, 1, NT, KU>;
-    using TQ = Tile<2, 2, 1, 1, KU>;
-    constexpr int kLds = tile_lds_bytes<bf16_t, TU>() > tile_lds_bytes<bf16_t, TQ>() ? tile_lds_bytes<bf16_t, TU>()
-                                                                                     : tile_lds_bytes<bf16_t, TQ>();
-    static_assert(kLds >= 8 * 256 * 4, "pooling scratch must fit");
-    __shared__ __attribute__((aligned(16))) char smem[kLds];
+    using SH = ProjShapes<NT, BK>;
+    using TU = typename SH::TU;
+    using TQ = typename SH::TQ;
+    constexpr int KU = BK / 32;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int b = blockIdx.x + a.blk_off;
     if (b < a.nb_U) {
         const int l = b / a.row_tiles, mt = b % a.row_tiles;
-        LoadRowsX<bf16_t, TU::BM, KU, false> al;
-        al.cache = a.cache; al.map = a.map; al.layer = l; al.s_prev = nullptr; al.ld_s = 0; al.lam = 1.f;
-        LoadRowsTC<bf16_t, TU::BN, KU> bl;
-        bl.src = a.WdT + (int64_t)l * a.r * a.d; bl.ld = a.d; bl.nrows = a.r;
+        const bf16_t *cache = a.cache;
+        const RowMap map = a.map;
+        const bf16_t *W = a.WdT + (int64_t)l * a.r * a.d;
+        const int d = a.d;
+        auto arow = [&](int m) { return cache + map.rowoff[m] + (int64_t)l * map.rowstride[m]; };
+        auto brow = [&](int c) { return W + (int64_t)c * d; };
         EpiStoreF32 epi{a.U + (int64_t)l * a.map.M * a.r, a.r};
-        gemm_tile<bf16_t, TU>(smem, al, bl, epi, 0, a.d, mt * TU::BM, 0, a.map.M, a.r);
+        gemm_nt<TU>(smem, arow, brow, epi, 0, a.d, mt * TU::BM, 0, a.map.M, a.r);
         return;
     }
     const int tq = (a.r + 63) / 64;
@@ -327,13 +342,13 @@ template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArg
         int l = 1;
         while ((l + 1) * l / 2 <= p) ++l;
         const int k = p - l * (l - 1) / 2;
-        LoadRowsTC<bf16_t, 64, KU> al;
-        al.src = a.Wu + (int64_t)k * a.r * a.d; al.ld = a.d; al.nrows = a.r;
-        LoadRowsTC<bf16_t, 64, KU> bl;
-        bl.src = a.WdT + (int64_t)l * a.r * a.d; bl.ld = a.d; bl.nrows = a.r;
+        const bf16_t *Wu = a.Wu + (int64_t)k * a.r * a.d, *Wd = a.WdT + (int64_t)l * a.r * a.d;
+        const int d = a.d;
+        auto arow = [&](int row) { return Wu + (int64_t)row * d; };
+        auto brow = [&](int c) { return Wd + (int64_t)c * d; };
         EpiQ epi{a.QpN + (int64_t)p * a.r * a.r, a.QpT + (int64_t)p * a.r * a.r, a.r,
                  1.f - a.params[(int64_t)l * a.PL + a.PL - 1]};
-        gemm_tile<bf16_t, TQ>(smem, al, bl, epi, 0, a.d, (idx / tq) * 64, (idx % tq) * 64, a.r, a.r);
+        gemm_nt<TQ>(smem, arow, brow, epi, 0, a.d, (idx / tq) * 64, (idx % tq) * 64, a.r, a.r);
         return;
     }
     if (b < a.nb_U + a.nb_Q + a.nb_C) {
@@ -345,7 +360,7 @@ template <int NT, int KU> __global__ __launch_bounds__(256) void k_gproj(ProjArg
         LoadRowsTC<bf16_t, 64, KU> bl;
         bl.src = a.WdT + (int64_t)l * a.r * a.d; bl.ld = a.d; bl.nrows = a.r;
         EpiChat epi{a.chat + (int64_t)l * a.r};
-        gemm_tile<bf16_t, TQ>(smem, al, bl, epi, 0, a.d, 0, nt * 64, 1, a.r);
+        gemm_tile<bf16_t, typename SH::TC>(smem, al, bl, epi, 0, a.d, 0, nt * 64, 1, a.r);
         return;
     }
     {
@@ -743,7 +758,9 @@ struct TokRedArgs {
     const bf16_t *cache;
     RowMap map;
     int L, d, r;
-    int nb_E, nb_G, e_tiles, se, sg, rows_per_se, rows_per_sg, tg;
+    int nb_E, nb_G, e_tiles, se, sg, tiles_per_se, rows_per_sg, tg;
+    const int32_t *tile_row0, *tile_rows;
+    const void *zeros; // at least 16 zero bytes
     const bf16_t *H, *DP; // [M][L*r]
     float *Epart;         // [se][L][d][r]
     const float *params;
@@ -755,32 +772,54 @@ struct TokRedArgs {
     float *cs, *Z, *dzsum;
 };
 
-using TG = Tile<2, 2, 2, 2, 4>; // 128 x 128 tile of the Gram matrix
+constexpr int kTokStages = 4;
+using TG = TnTile<2, 2, 2, 2, 32, kTokStages>; // 128 x 128 tile of the Gram matrix, 32 tokens per stage
+
+template <int NT> struct TokRedShapes {
+    using TE = TnTile<2, 2, 2, (NT > 2 ? 2 : 1), 32, kTokStages>; // 128 columns of d x (64 or 128 >= r)
+    static constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4;
+    static constexpr int kTileLds = TE::LDS_BYTES > TG::LDS_BYTES ? TE::LDS_BYTES : TG::LDS_BYTES;
+    static constexpr int kLds = kTileLds > kVecLds ? kTileLds : kVecLds;
+};
 
 template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
 {
-    using TE = Tile<4, 1, 1, NT, 4>;
-    constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4;
-    constexpr int kTileLds = tile_lds_bytes<bf16_t, TE>() > tile_lds_bytes<bf16_t, TG>()
-                                 ? tile_lds_bytes<bf16_t, TE>() : tile_lds_bytes<bf16_t, TG>();
-    constexpr int kLds = kTileLds > kVecLds ? kTileLds : kVecLds;
-    __shared__ __attribute__((aligned(16))) char smem[kLds];
+    using TE = typename TokRedShapes<NT>::TE;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    __shared__ int64_t t_aoff[kMaxSplitTiles]; // cache offset of the tile's first row in this layer
+    __shared__ int32_t t_m0[kMaxSplitTiles], t_rows[kMaxSplitTiles];
     const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
     const int M = a.map.M;
     const int Lr = a.L * a.r;
     if (b < a.nb_E) {
+        // E_l[d-tile] over the 16-token tiles [tl0, tl1) of this split
         const int split = b % a.se;
         const int it = (b / a.se) % a.e_tiles;
         const int l = b / (a.se * a.e_tiles);
-        const int kbegin = split * a.rows_per_se;
-        const int kend = min(M, kbegin + a.rows_per_se);
-        LoadColsX<bf16_t, TE::BM, 4, false> al;
-        al.cache = a.cache; al.map = a.map; al.layer = l; al.s_prev = nullptr; al.ld_s = 0; al.lam = 1.f;
-        al.ncols = a.d; al.kend = kend;
-        LoadCols<bf16_t, TE::BN, 4, bf16_t, false> bl;
-        bl.src = a.DP + (int64_t)l * a.r; bl.ld = Lr; bl.ncols = a.r; bl.kend = kend;
+        const int tl0 = split * a.tiles_per_se;
+        const int ntl = min(a.ntiles, tl0 + a.tiles_per_se) - tl0;
+        for (int q = t; q < ntl; q += 256) {
+            const int m0 = a.tile_row0[tl0 + q];
+            t_m0[q] = m0;
+            t_rows[q] = a.tile_rows[tl0 + q];
+            t_aoff[q] = a.map.rowoff[m0] + (int64_t)l * a.map.rowstride[m0];
+        }
+        __syncthreads();
+        const bf16_t *cache = a.cache;
+        const bf16_t *dp = a.DP + (int64_t)l * a.r;
+        const int d = a.d;
+        auto atok = [&](int step, int grp, int r8) -> const bf16_t * {
+            const int tl = step * 2 + (grp >> 1), row = (grp & 1) * 8 + r8;
+            if (tl >= ntl || row >= t_rows[tl]) return nullptr;
+            return cache + t_aoff[tl] + (int64_t)row * d;
+        };
+        auto btok = [&](int step, int grp, int r8) -> const bf16_t * {
+            const int tl = step * 2 + (grp >> 1), row = (grp & 1) * 8 + r8;
+            if (tl >= ntl || row >= t_rows[tl]) return nullptr;
+            return dp + (int64_t)(t_m0[tl] + row) * Lr;
+        };
         EpiStoreF32 epi{a.Epart + ((int64_t)split * a.L + l) * a.d * a.r, a.r};
-        gemm_tile<bf16_t, TE>(smem, al, bl, epi, kbegin, kend, it * TE::BM, 0, a.d, a.r);
+        gemm_tn<TE>(smem, atok, btok, a.zeros, epi, (ntl + 1) / 2, it * TE::BM, 0, a.d, a.r, a.d, a.r);
         return;
     }
     if (b < a.nb_E + a.nb_G) {
@@ -794,12 +833,17 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         if (kmin >= lmax) return;
         const int kbegin = split * a.rows_per_sg;
         const int kend = min(M, kbegin + a.rows_per_sg);
-        LoadCols<bf16_t, TG::BM, 4, bf16_t, false> al;
-        al.src = a.H; al.ld = Lr; al.ncols = Lr; al.kend = kend;
-        LoadCols<bf16_t, TG::BN, 4, bf16_t, false> bl;
-        bl.src = a.DP; bl.ld = Lr; bl.ncols = Lr; bl.kend = kend;
+        const bf16_t *H = a.H, *DP = a.DP;
+        auto atok = [&](int step, int grp, int r8) -> const bf16_t * {
+            const int k = kbegin + step * 32 + grp * 8 + r8;
+            return k < kend ? H + (int64_t)k * Lr : nullptr;
+        };
+        auto btok = [&](int step, int grp, int r8) -> const bf16_t * {
+            const int k = kbegin + step * 32 + grp * 8 + r8;
+            return k < kend ? DP + (int64_t)k * Lr : nullptr;
+        };
         EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
-        gemm_tile<bf16_t, TG>(smem, al, bl, epi, kbegin, kend, ti * TG::BM, tj * TG::BN, Lr, Lr);
+        gemm_tn<TG>(smem, atok, btok, a.zeros, epi, (kend - kbegin + 31) / 32, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
         return;
     }
     // cs[kk] = sum over the tiles of their column sums of dpre ;
@@ -1114,19 +1158,19 @@ __global__ __launch_bounds__(64) void k_gfinish(const float *loss_part, int B, f
 // timing) one launch per part with its own profile class.
 template <class Args, class Kern>
 static void launch_parts(Profiler *prof, hipStream_t st, bool split, Kern kern, Args a, int nparts, const int *counts,
-                         const int *classes, int whole_class, unsigned threads)
+                         const int *classes, int whole_class, unsigned threads, size_t lds = 0)
 {
     int total = 0;
     for (int i = 0; i < nparts; ++i) total += counts[i];
     if (!split) {
         a.blk_off = 0;
-        if (total > 0) PAC_LAUNCH(prof, st, whole_class, kern, dim3(total), dim3(threads), 0, st, a);
+        if (total > 0) PAC_LAUNCH(prof, st, whole_class, kern, dim3(total), dim3(threads), lds, st, a);
         return;
     }
     int off = 0;
     for (int i = 0; i < nparts; ++i) {
         a.blk_off = off;
-        if (counts[i] > 0) PAC_LAUNCH(prof, st, classes[i], kern, dim3(counts[i]), dim3(threads), 0, st, a);
+        if (counts[i] > 0) PAC_LAUNCH(prof, st, classes[i], kern, dim3(counts[i]), dim3(threads), lds, st, a);
         off += counts[i];
     }
 }
@@ -1178,7 +1222,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.rowoff = rowoff; a.rowstride = rowstride; a.rowsamp = rowsamp; a.samp_start = samp_start;
         a.samp_len = samp_len; a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.tile_samp = tile_samp; a.samp_tile0 = samp_tile0;
         a.WdT = WdT; a.Wu = Wu; a.WuTs = WuTs; a.Wds = Wds; a.cusum = cusum; a.V = V;
-        a.counter = counter;
+        a.counter = counter; a.zero = (float *)(ws + W.g_zero);
         const int counts[4] = {a.nb_setup, a.nb_shadow, a.nb_chat, cdiv(Lr, 4)};
         const int classes[4] = {KC_G_PREP_SETUP, KC_G_PREP_COPY, KC_G_PREP_CHAT, KC_G_PREP_V};
         launch_parts(prof, st, split, k_gprep, a, 4, counts, classes, KC_G_PREP, 256);
@@ -1194,9 +1238,25 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.samp_start = samp_start; a.samp_len = samp_len; a.pb = pb;
         const int counts[4] = {a.nb_U, a.nb_Q, a.nb_C, B * cdiv(d, 256)};
         const int classes[4] = {KC_G_PROJ_U, KC_G_PROJ_Q, KC_G_PROJ_Q, KC_G_PROJ_PB};
-        if (d % 128 == 0) launch_parts(prof, st, split, k_gproj<NT, 4>, a, 4, counts, classes, KC_G_PROJ, 256);
-        else if (d % 64 == 0) launch_parts(prof, st, split, k_gproj<NT, 2>, a, 4, counts, classes, KC_G_PROJ, 256);
-        else launch_parts(prof, st, split, k_gproj<NT, 1>, a, 4, counts, classes, KC_G_PROJ, 256);
+        if (d % 64 == 0) {
+            static bool done = false;
+            if (!done) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gproj<NT, 64>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, ProjShapes<NT, 64>::kLds);
+                if (e != hipSuccess) return e;
+                done = true;
+            }
+            launch_parts(prof, st, split, k_gproj<NT, 64>, a, 4, counts, classes, KC_G_PROJ, 256, ProjShapes<NT, 64>::kLds);
+        } else {
+            static bool done = false;
+            if (!done) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gproj<NT, 32>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, ProjShapes<NT, 32>::kLds);
+                if (e != hipSuccess) return e;
+                done = true;
+            }
+            launch_parts(prof, st, split, k_gproj<NT, 32>, a, 4, counts, classes, KC_G_PROJ, 256, ProjShapes<NT, 32>::kLds);
+        }
     }
     const size_t lds_fwd = chain_lds(L, r, true), lds_bwd = chain_lds(L, r, false);
     static bool attr_done = false;
@@ -1206,6 +1266,9 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<false, NT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gtokred<NT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, TokRedShapes<NT>::kLds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
@@ -1235,8 +1298,13 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         TokRedArgs a;
         a.cache = cache; a.map = map; a.L = L; a.d = d; a.r = r;
         a.e_tiles = cdiv(d, 128);
-        a.rows_per_se = cdiv(cdiv(M, W.se), 128) * 128;
-        a.se = cdiv(M, a.rows_per_se);
+        {
+            // W.se is fixed by the configuration (the partial buffers are sized for it)
+            if (cdiv(ntiles, W.se) > kMaxSplitTiles) return hipErrorInvalidValue;
+            a.tiles_per_se = cdiv(cdiv(ntiles, W.se), 2) * 2;
+            a.se = cdiv(ntiles, a.tiles_per_se);
+        }
+        a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.zeros = ws + W.g_zero;
         a.rows_per_sg = cdiv(cdiv(M, W.sg), 128) * 128;
         a.sg = cdiv(M, a.rows_per_sg);
         a.tg = cdiv(Lr, 128);
@@ -1248,7 +1316,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         {
             const int counts[3] = {a.nb_E, a.nb_G, cdiv(Lr, 16)};
             const int classes[3] = {KC_G_TOKRED_E, KC_G_TOKRED_G, KC_G_TOKRED_VEC};
-            launch_parts(prof, st, split, k_gtokred<NT>, a, 3, counts, classes, KC_G_TOKRED, 256);
+            launch_parts(prof, st, split, k_gtokred<NT>, a, 3, counts, classes, KC_G_TOKRED, 256, TokRedShapes<NT>::kLds);
         }
         {
             const int nb_GG = L > 1 ? (Lr / 32) * (Lr / 32) : 0;
