@@ -304,6 +304,8 @@ struct EpiChat {
 using T64 = Tile<2, 2, 1, 1, 1>;
 using T64K = Tile<2, 2, 1, 1, 4>; // 128-token K step for the token contractions
 
+// Stage counts are kept small on purpose: more workgroups per compute unit hide the memory latency
+// better than deeper rings in fewer workgroups (measured both ways).
 template <int NT, int BK> struct ProjShapes {
     using TU = NtTile<4, 1, 1, NT, BK, 2>;  // 128 token rows x r
     using TQ = NtTile<2, 2, 1, 1, BK, 3>;   // 64 x 64
@@ -949,6 +951,7 @@ struct PostArgs {
 };
 
 struct EpiF {
+    static constexpr bool kBatched = true;
     const float *Epart;
     int se;
     int64_t split_stride;
@@ -957,35 +960,79 @@ struct EpiF {
     int r;
     float lam;
     float dlam;
-    __device__ void operator()(int row, int col, float v)
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols)
     {
-        const int64_t o = (int64_t)row * r + col;
-        float E = 0.f;
-        for (int s = 0; s < se; ++s) E += Epart[(int64_t)s * split_stride + o];
-        const float F = v + cusum_l[row] * cs_l[col];
-        gWd[o] = lam * E + (1.f - lam) * F;
-        dlam += (E - F) * Wd_l[o];
+        const int cc = min(col, ncols - 1);
+        const float csv = cs_l[cc];
+        float E[16], W[16], cu[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rr = min(epi_row(row_base, v), nrows - 1);
+            const int64_t o = (int64_t)rr * r + cc;
+            E[v] = Epart[o];
+            W[v] = Wd_l[o];
+            cu[v] = cusum_l[rr];
+        }
+        for (int s = 1; s < se; ++s) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = min(epi_row(row_base, v), nrows - 1);
+                E[v] += Epart[(int64_t)s * split_stride + (int64_t)rr * r + cc];
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = epi_row(row_base, v);
+            if (row < nrows && col < ncols) {
+                const float F = acc[v] + cu[v] * csv;
+                gWd[(int64_t)row * r + col] = lam * E[v] + (1.f - lam) * F;
+                dlam += (E[v] - F) * W[v];
+            }
+        }
     }
 };
 
 struct EpiW {
+    static constexpr bool kBatched = true;
     const float *Z_l, *Wc;
     float *gWu;
     int d, C;
-    __device__ void operator()(int row, int col, float v) const
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
     {
-        float acc = v;
-        for (int c = 0; c < C; ++c) acc += Z_l[(int64_t)row * C + c] * Wc[(int64_t)col * C + c];
-        gWu[(int64_t)row * d + col] = acc;
+        const int cc = min(col, ncols - 1);
+        float out[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) out[v] = acc[v];
+        for (int c = 0; c < C; ++c) {
+            const float w = Wc[(int64_t)cc * C + c];
+            float z[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) z[v] = Z_l[(int64_t)min(epi_row(row_base, v), nrows - 1) * C + c];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) out[v] += z[v] * w;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = epi_row(row_base, v);
+            if (row < nrows && col < ncols) gWu[(int64_t)row * d + col] = out[v];
+        }
     }
 };
 
-__global__ __launch_bounds__(256) void k_gpost(PostArgs a)
+template <int BK> struct PostShapes {
+    using TF = NtTile<2, 2, 1, 1, BK, BK == 64 ? 4 : 8>; // 64 x 64, 64 KB of stages
+    static constexpr int kVecLds = 128 * 4 + 128 * kMaxClasses * 4 + kMaxBatch * kMaxClasses * 4;
+    static constexpr int kLds = TF::LDS_BYTES;
+    static_assert(kLds >= kVecLds, "LDS budget of the gradient kernel");
+};
+
+// BK = 64 when r is a multiple of 64, else 32: every K range below is a multiple of r
+template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
 {
-    constexpr int kVecLds = 128 * 4 + 128 * kMaxClasses * 4 + kMaxBatch * kMaxClasses * 4;
-    constexpr int kLds = 56 * 1024;
-    static_assert(kLds >= tile_lds_bytes<bf16_t, T64K>() && kLds >= kVecLds, "LDS budget of the gradient kernel");
-    __shared__ __attribute__((aligned(16))) char smem[kLds];
+    using TF = typename PostShapes<BK>::TF;
+    constexpr int kVecLds = PostShapes<BK>::kVecLds;
+    constexpr int kLds = PostShapes<BK>::kLds;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
     __shared__ float red[16];
     const int L = a.L, d = a.d, r = a.r, C = a.C;
     const int Lr = L * r;
@@ -998,13 +1045,12 @@ __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
         const int slot = b % (ti_d * ti_r);
         const int it = slot / ti_r, nt = slot % ti_r;
         const float *pl = a.params + (int64_t)l * a.PL;
-        LoadRowsTC<bf16_t, 64, 4> al;
-        al.src = a.WuTs; al.ld = Lr; al.nrows = d; al.klim = l * r;
-        LoadRowsTC<bf16_t, 64, 4> bl;
-        bl.src = a.GGT + (int64_t)l * r * Lr; bl.ld = Lr; bl.nrows = r; bl.klim = l * r;
+        const bf16_t *A = a.WuTs, *B = a.GGT + (int64_t)l * r * Lr;
+        auto arow = [&](int row) { return A + (int64_t)row * Lr; };
+        auto brow = [&](int c) { return B + (int64_t)c * Lr; };
         EpiF epi{a.Epart + (int64_t)l * dr, a.se, (int64_t)L * dr, a.cusum + (int64_t)l * d, a.cs + (int64_t)l * r,
                  pl, a.grads + (int64_t)l * a.PL, r, pl[a.PL - 1], 0.f};
-        gemm_tile<bf16_t, T64K>(smem, al, bl, epi, 0, l * r, it * 64, nt * 64, d, r);
+        gemm_nt<TF>(smem, arow, brow, epi, 0, l * r, it * 64, nt * 64, d, r);
         const float tot = block_sum(epi.dlam, red);
         if (t == 0) a.dlam_part[(int64_t)l * a.slots + slot] = tot; // summed in slot order by k_gfinish
         return;
@@ -1015,13 +1061,12 @@ __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
         const int l = idx / (ti_d * ti_r);
         idx %= ti_d * ti_r;
         const int at = idx / ti_d, jt = idx % ti_d;
-        LoadRowsTC<bf16_t, 64, 4> al;
-        al.src = a.GGsc + (int64_t)l * r * Lr; al.ld = Lr; al.nrows = r; al.kmin = (l + 1) * r; al.klim = Lr;
-        LoadRowsTC<bf16_t, 64, 4> bl;
-        bl.src = a.Wds; bl.ld = Lr; bl.nrows = d; bl.kmin = (l + 1) * r; bl.klim = Lr;
+        const bf16_t *A = a.GGsc + (int64_t)l * r * Lr, *B = a.Wds;
+        auto arow = [&](int row) { return A + (int64_t)row * Lr; };
+        auto brow = [&](int c) { return B + (int64_t)c * Lr; };
         EpiW epi{a.Z + (int64_t)l * r * C, a.params + (int64_t)L * a.PL,
                  a.grads + (int64_t)l * a.PL + dr + r, d, C};
-        gemm_tile<bf16_t, T64K>(smem, al, bl, epi, ((l + 1) * r) / 128 * 128, Lr, at * 64, jt * 64, r, d);
+        gemm_nt<TF>(smem, arow, brow, epi, (l + 1) * r, Lr, at * 64, jt * 64, r, d);
         return;
     }
     const int vb = b - a.nb_F - a.nb_W;
@@ -1335,7 +1380,20 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         {
             const int counts[3] = {pa.nb_F, pa.nb_W, pa.nb_vec};
             const int classes[3] = {KC_G_POST_F, KC_G_POST_W, KC_G_POST_VEC};
-            launch_parts(prof, st, split, k_gpost, pa, 3, counts, classes, KC_G_POST, 256);
+            static bool done = false;
+            if (!done) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<64>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<64>::kLds);
+                if (e != hipSuccess) return e;
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<32>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<32>::kLds);
+                if (e != hipSuccess) return e;
+                done = true;
+            }
+            if (r % 64 == 0)
+                launch_parts(prof, st, split, k_gpost<64>, pa, 3, counts, classes, KC_G_POST, 256, PostShapes<64>::kLds);
+            else
+                launch_parts(prof, st, split, k_gpost<32>, pa, 3, counts, classes, KC_G_POST, 256, PostShapes<32>::kLds);
         }
         PAC_LAUNCH(prof, st, KC_G_FINISH, k_gfinish, dim3(1), dim3(64), 0, st, loss_part, B, io.loss_out, dlam_part,
                    pa.slots, L, D.PL, io.grads);
