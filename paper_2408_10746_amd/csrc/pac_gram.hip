@@ -37,6 +37,7 @@ constexpr int kChainRows = 16;   // token rows per chain workgroup
 constexpr int kChainPad = 8;     // bf16 elements of padding per LDS row
 constexpr int kMaxD = 4096;
 constexpr int kMaxSplitTiles = 512; // 16-token tiles one workgroup of the E contraction walks over at most
+constexpr int kMaxTiles = 8192;     // 16-token tiles of a batch (LDS table of the column-sum reduction)
 
 constexpr int kRing = 4; // layers of per-token inputs the chain kernels stage ahead in LDS
 
@@ -58,6 +59,7 @@ bool gram_path_fits(const Dims &D)
 {
     if (D.cache_dtype != 0 || (D.flags & 1)) return false; // PAC_FLAG_PER_LAYER
     if (D.r > 128 || D.d > kMaxD || D.L > 128) return false;
+    if ((int64_t)D.B_max * cdiv(D.n_max, kChainRows) > kMaxTiles) return false;
     return chain_lds(D.L, D.r, true) <= 160 * 1024;
 }
 
@@ -108,6 +110,24 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.g_counter = take((int64_t)(D.L + 1) * 4);
     W.g_samp_tile0 = take((kMaxBatch + 1) * 4);
     W.g_loss_part = take(kMaxBatch * 4);
+}
+
+// Copies n floats (n % 4 == 0, both sides 16-byte aligned) from global memory to LDS with all of a
+// round's loads issued before its first store: a plain copy loop waits for memory once per iteration.
+template <int NTHREADS> __device__ __forceinline__ void stage_to_lds(float *dst, const float *src, int n)
+{
+    const int nch = n >> 2;
+    for (int base = 0; base < nch; base += NTHREADS * 8) {
+        f32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            v[u] = *reinterpret_cast<const f32x4 *>(src + 4 * min(base + u * NTHREADS + (int)threadIdx.x, nch - 1));
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = base + u * NTHREADS + (int)threadIdx.x;
+            if (c < nch) *reinterpret_cast<f32x4 *>(dst + 4 * c) = v[u];
+        }
+    }
 }
 
 __device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }
@@ -515,6 +535,70 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
     constexpr int nthreads = 64 * (NW + 1);
     auto layer_at = [&](int step) { return FWD ? step : L - 1 - step; };
 
+    // Requests that depend on nothing computed here go out first and are in flight while the
+    // per-layer vectors are set up: the helper wavefront's tiles of the first three steps, and the
+    // contracting wavefronts' operands of the first pairs.
+    const RingT *src = FWD ? reinterpret_cast<const RingT *>(a.U) : reinterpret_cast<const RingT *>(a.Gp);
+    constexpr int EPC = 16 / (int)sizeof(RingT); // elements per chunk
+    auto fetch = [&](int step, u32x4(&reg)[kChunksPerLane]) {
+        if (step >= L) return;
+        const RingT *base = src + ((int64_t)layer_at(step) * a.M + m0) * r;
+#pragma unroll
+        for (int q = 0; q < kChunksPerLane; ++q) {
+            // rows past the end of a short tile re-read the tile's last chunk (never used: the
+            // contracting wavefronts mask those rows); no branch, no register is zeroed
+            const int e = min((lane + 64 * q) * EPC, nrows * r - EPC);
+            reg[q] = *reinterpret_cast<const u32x4 *>(base + e);
+        }
+    };
+    auto put = [&](int step, const u32x4(&reg)[kChunksPerLane]) {
+        if (step >= L) return;
+        RingT *dst = ring + (size_t)(step % kRing) * T * r;
+#pragma unroll
+        for (int q = 0; q < kChunksPerLane; ++q) *reinterpret_cast<u32x4 *>(dst + (lane + 64 * q) * EPC) = reg[q];
+    };
+    auto drain = [&](int step) { // GELU' tile of a finished step: LDS staging -> global
+        if (!FWD || step < 0 || step >= L) return;
+        const bf16_t *st = Gst + (size_t)(step & 1) * T * r;
+        bf16_t *dst = a.Gp + ((int64_t)layer_at(step) * a.M + m0) * r;
+#pragma unroll
+        for (int q = 0; q < kGChunks; ++q) {
+            const int e = (lane + 64 * q) * 8;
+            if (e < nrows * r) *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(st + e);
+        }
+    };
+    constexpr int kDepth = NT == 1 ? 16 : NT == 2 ? 12 : NT == 3 ? 10 : 6; // bounded by the register file
+    const int i = lane & 15, g = lane >> 4;
+    const int n = 16 * wave + i;
+    const int total_pairs = L * (L - 1) / 2;
+    // next pair to request.  A request is issued for every FIFO slot on every path (once the
+    // sequence is exhausted the last pair is requested again and never used): the compiler can
+    // then count the loads in flight and wait only for the oldest ones.
+    int is = 1, ij = 0;
+    auto issue = [&](bf16x8(&bq)[KS]) {
+        const int s = is < L ? is : L - 1;
+        const int j = is < L ? ij : L - 2;
+        const int ls = layer_at(s), lj = layer_at(j);
+        const int pi = FWD ? pair_index(lj, ls) : pair_index(ls, lj);
+        const bf16_t *Qp = a.Q + pi * rr + (int64_t)wave * KS * 512;
+#pragma unroll
+        for (int q = 0; q < KS; ++q) bq[q] = *reinterpret_cast<const bf16x8 *>(Qp + (q * 64 + lane) * 8);
+        if (is < L && ++ij >= is) {
+            ++is;
+            ij = 0;
+        }
+    };
+    bf16x8 fifo[kDepth][KS];
+    u32x4 ra[kChunksPerLane], rb[kChunksPerLane], rc[kChunksPerLane];
+    if (wave == NW) {
+        fetch(0, ra);
+        fetch(1, rb);
+        fetch(2, rc);
+    } else if (total_pairs > 0) {
+#pragma unroll
+        for (int slot = 0; slot < kDepth; ++slot) issue(fifo[slot]);
+    }
+
     // per-layer vectors
     if (!FWD) sample_head(a, samp, tile == a.samp_tile0[samp], zs, dzs);
     const float inv_len = 1.f / (float)a.samp_len[samp];
@@ -536,39 +620,6 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
         // ---- helper wavefront: all global traffic of the per-token tiles.  It keeps the input ring
         // filled three layers ahead and (forward) writes out the GELU' tile of the layer just finished,
         // so the contracting wavefronts issue no global store and wait on no per-token load.
-        const RingT *src = FWD ? reinterpret_cast<const RingT *>(a.U) : reinterpret_cast<const RingT *>(a.Gp);
-        constexpr int EPC = 16 / (int)sizeof(RingT); // elements per chunk
-        auto fetch = [&](int step, u32x4(&reg)[kChunksPerLane]) {
-            if (step >= L) return;
-            const RingT *base = src + ((int64_t)layer_at(step) * a.M + m0) * r;
-#pragma unroll
-            for (int q = 0; q < kChunksPerLane; ++q) {
-                // rows past the end of a short tile re-read the tile's last chunk (never used: the
-                // contracting wavefronts mask those rows); no branch, no register is zeroed
-                const int e = min((lane + 64 * q) * EPC, nrows * r - EPC);
-                reg[q] = *reinterpret_cast<const u32x4 *>(base + e);
-            }
-        };
-        auto put = [&](int step, const u32x4(&reg)[kChunksPerLane]) {
-            if (step >= L) return;
-            RingT *dst = ring + (size_t)(step % kRing) * T * r;
-#pragma unroll
-            for (int q = 0; q < kChunksPerLane; ++q) *reinterpret_cast<u32x4 *>(dst + (lane + 64 * q) * EPC) = reg[q];
-        };
-        auto drain = [&](int step) { // GELU' tile of a finished step: LDS staging -> global
-            if (!FWD || step < 0 || step >= L) return;
-            const bf16_t *st = Gst + (size_t)(step & 1) * T * r;
-            bf16_t *dst = a.Gp + ((int64_t)layer_at(step) * a.M + m0) * r;
-#pragma unroll
-            for (int q = 0; q < kGChunks; ++q) {
-                const int e = (lane + 64 * q) * 8;
-                if (e < nrows * r) *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(st + e);
-            }
-        };
-        u32x4 ra[kChunksPerLane], rb[kChunksPerLane], rc[kChunksPerLane];
-        fetch(0, ra);
-        fetch(1, rb);
-        fetch(2, rc);
         put(0, ra);
         __syncthreads();
         // before the barrier that ends step s the tile of step s+1 must be in the ring
@@ -595,35 +646,6 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
         drain(L - 1);
     } else {
         // ---- contracting wavefronts ----
-        // The (step, earlier step) pairs of the whole kernel form one sequence; their r x r operands
-        // do not depend on anything computed here, so they are requested kDepth pairs ahead of their
-        // use (across layer boundaries) into a register FIFO.
-        constexpr int kDepth = NT == 1 ? 16 : NT == 2 ? 12 : NT == 3 ? 10 : 6; // bounded by the register file
-        const int i = lane & 15, g = lane >> 4;
-        const int n = 16 * wave + i;
-        const int total_pairs = L * (L - 1) / 2;
-        // next pair to request.  A request is issued for every FIFO slot on every path (once the
-        // sequence is exhausted the last pair is requested again and never used): the compiler can
-        // then count the loads in flight and wait only for the oldest ones.
-        int is = 1, ij = 0;
-        auto issue = [&](bf16x8(&bq)[KS]) {
-            const int s = is < L ? is : L - 1;
-            const int j = is < L ? ij : L - 2;
-            const int ls = layer_at(s), lj = layer_at(j);
-            const int pi = FWD ? pair_index(lj, ls) : pair_index(ls, lj);
-            const bf16_t *Qp = a.Q + pi * rr + (int64_t)wave * KS * 512;
-#pragma unroll
-            for (int q = 0; q < KS; ++q) bq[q] = *reinterpret_cast<const bf16x8 *>(Qp + (q * 64 + lane) * 8);
-            if (is < L && ++ij >= is) {
-                ++is;
-                ij = 0;
-            }
-        };
-        bf16x8 fifo[kDepth][KS];
-        if (total_pairs > 0) {
-#pragma unroll
-            for (int slot = 0; slot < kDepth; ++slot) issue(fifo[slot]);
-        }
         // two accumulators so that consecutive matrix instructions do not depend on each other
         f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         auto contract = [&](const bf16x8(&bq)[KS], int j) {
@@ -687,19 +709,9 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
             }
         }
     }
-    // flush: 16-byte chunks of the valid rows, then the column sums
-    __syncthreads();
-    constexpr int chunks_per_row = r / 8;
-    for (int c = threadIdx.x; c < L * T * chunks_per_row; c += nthreads) {
-        const int l = c / (T * chunks_per_row);
-        const int rem = c - l * T * chunks_per_row;
-        const int row = rem / chunks_per_row, cc = rem % chunks_per_row;
-        if (row < nrows)
-            *reinterpret_cast<u32x4 *>(a.Hg + (int64_t)(m0 + row) * Lr + (int64_t)l * r + cc * 8) =
-                *reinterpret_cast<const u32x4 *>(Hs + ((int64_t)l * T + row) * RP + cc * 8);
-    }
-    for (int c = threadIdx.x; c < L * r; c += nthreads) a.part[(int64_t)tile * Lr + c] = Cs[c];
+    __syncthreads(); // every layer's tile and column sums are in LDS
     if (FWD) {
+        // (before the stores below: a load issued after them would also wait for them)
         // this tile's share of the logits; the first tile of a sample adds the part that comes
         // from the cached last layer and the biases
         const int C = a.C;
@@ -748,6 +760,17 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
             if (first) a.zpb[samp * C + threadIdx.x] = s1;
         }
     }
+    // flush: 16-byte chunks of the valid rows, then the column sums
+    constexpr int chunks_per_row = r / 8;
+    for (int c = threadIdx.x; c < L * T * chunks_per_row; c += nthreads) {
+        const int l = c / (T * chunks_per_row);
+        const int rem = c - l * T * chunks_per_row;
+        const int row = rem / chunks_per_row, cc = rem % chunks_per_row;
+        if (row < nrows)
+            *reinterpret_cast<u32x4 *>(a.Hg + (int64_t)(m0 + row) * Lr + (int64_t)l * r + cc * 8) =
+                *reinterpret_cast<const u32x4 *>(Hs + ((int64_t)l * T + row) * RP + cc * 8);
+    }
+    for (int c = threadIdx.x; c < L * r; c += nthreads) a.part[(int64_t)tile * Lr + c] = Cs[c];
 }
 
 // ---------------------------------------------------------------------------
@@ -779,7 +802,7 @@ using TG = TnTile<2, 2, 2, 2, 32, kTokStages>; // 128 x 128 tile of the Gram mat
 
 template <int NT> struct TokRedShapes {
     using TE = TnTile<2, 2, 2, (NT > 2 ? 2 : 1), 32, kTokStages>; // 128 columns of d x (64 or 128 >= r)
-    static constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4;
+    static constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4 + kMaxTiles * 4 + kMaxBatch * kMaxClasses * 4; // + tile and sample tables
     static constexpr int kTileLds = TE::LDS_BYTES > TG::LDS_BYTES ? TE::LDS_BYTES : TG::LDS_BYTES;
     static constexpr int kLds = kTileLds > kVecLds ? kTileLds : kVecLds;
 };
@@ -860,17 +883,36 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
     float zc[kMaxClasses];
 #pragma unroll
     for (int c = 0; c < kMaxClasses; ++c) zc[c] = 0.f;
+    // per-sample weights dz / len and the tiles' sample numbers, staged so that the sums below
+    // read global memory only for the column sums themselves
+    int32_t *tsamp = reinterpret_cast<int32_t *>(smem + 256 * (1 + kMaxClasses) * 4); // [ntiles]
+    float *swt = reinterpret_cast<float *>(tsamp + a.ntiles);                          // [B][C]
+    for (int k = t; k < a.ntiles; k += 256) tsamp[k] = a.tile_samp[k];
+    for (int q = t; q < a.B * C; q += 256) swt[q] = a.dz[q] / (float)a.samp_len[q / C];
+    __syncthreads();
     if (idx < Lr) {
-#pragma unroll 4
-        for (int k = grp; k < a.ntiles; k += 16) {
-            acc += a.cspart[(int64_t)k * Lr + idx];
-            const int s = a.tile_samp[k];
-            const float hs = a.HSpart[(int64_t)k * Lr + idx] / (float)a.samp_len[s];
+        for (int k0 = grp; k0 < a.ntiles; k0 += 16 * 4) {
+            float cp[4], hp[4];
 #pragma unroll
-            for (int c = 0; c < kMaxClasses; ++c)
-                if (c < C) zc[c] += hs * a.dz[s * C + c];
+            for (int u = 0; u < 4; ++u) {
+                const int k = min(k0 + 16 * u, a.ntiles - 1);
+                cp[u] = a.cspart[(int64_t)k * Lr + idx];
+                hp[u] = a.HSpart[(int64_t)k * Lr + idx];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int k = k0 + 16 * u;
+                if (k < a.ntiles) {
+                    acc += cp[u];
+                    const float *w = swt + tsamp[k] * C;
+#pragma unroll
+                    for (int c = 0; c < kMaxClasses; ++c)
+                        if (c < C) zc[c] += hp[u] * w[c];
+                }
+            }
         }
     }
+    __syncthreads();
     red[(grp * 16 + ii) * (1 + kMaxClasses)] = acc;
 #pragma unroll
     for (int c = 0; c < kMaxClasses; ++c)
@@ -907,8 +949,14 @@ __global__ __launch_bounds__(256) void k_ggsum(int L, int r, int sg, const float
         // E = ordered sum of its token-split partials, four elements per thread
         const int64_t o = ((int64_t)(b - nb_GG) * 256 + t) * 4;
         if (o < e_elems) { // e_elems is a multiple of 4
-            f32x4 acc = *reinterpret_cast<const f32x4 *>(Epart + o);
-            for (int s2 = 1; s2 < se; ++s2) acc += *reinterpret_cast<const f32x4 *>(Epart + (int64_t)s2 * e_elems + o);
+            f32x4 p[16]; // se <= 16; all partials requested before the first add
+#pragma unroll
+            for (int s2 = 0; s2 < 16; ++s2)
+                if (s2 < se) p[s2] = *reinterpret_cast<const f32x4 *>(Epart + (int64_t)s2 * e_elems + o);
+            f32x4 acc = p[0];
+#pragma unroll
+            for (int s2 = 1; s2 < 16; ++s2)
+                if (s2 < se) acc += p[s2];
             *reinterpret_cast<f32x4 *>(E + o) = acc;
         }
         return;
@@ -918,14 +966,21 @@ __global__ __launch_bounds__(256) void k_ggsum(int L, int r, int sg, const float
     // rows of layer k, columns of layer l: used only for k < l
     if ((tr * 32) / r >= (tcx * 32 + 31) / r) return;
     const int tx = t & 31, ty = t >> 5;
+    const int col = tcx * 32 + tx;
+    const float lam = params[(int64_t)(col / r) * PL + PL - 1];
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < sg; ++s) { // four independent loads per split
+        float p[4];
 #pragma unroll
-    for (int y = ty; y < 32; y += 8) {
-        const int row = tr * 32 + y, col = tcx * 32 + tx;
-        float acc = 0.f;
-        for (int s = 0; s < sg; ++s) acc += GGpart[((int64_t)s * Lr + row) * Lr + col];
-        tile[y][tx] = acc;
-        const float lam = params[(int64_t)(col / r) * PL + PL - 1];
-        GGsc[(int64_t)row * Lr + col] = static_cast<bf16_t>((1.f - lam) * acc);
+        for (int q = 0; q < 4; ++q) p[q] = GGpart[((int64_t)s * Lr + tr * 32 + ty + 8 * q) * Lr + col];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] += p[q];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int y = ty + 8 * q, row = tr * 32 + y;
+        tile[y][tx] = acc[q];
+        GGsc[(int64_t)row * Lr + col] = static_cast<bf16_t>((1.f - lam) * acc[q]);
     }
     __syncthreads();
 #pragma unroll
@@ -1098,8 +1153,21 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
         const bool staged = (int64_t)Lr * (1 + C) * 4 + kVecLds <= kLds;
         for (int q = t; q < a.B * C; q += 256) sdz[q] = a.dz[q];
         if (staged) {
-            for (int q = t; q < Lr; q += 256) stage[q] = a.cs[q];
-            for (int q = t; q < Lr * C; q += 256) stage[Lr + q] = a.Z[q];
+            stage_to_lds<256>(stage, a.cs, Lr);
+            stage_to_lds<256>(stage + Lr, a.Z, Lr * C);
+        }
+        float base = 0.f; // (sum_s dz_s) W_cls^T [j]
+        {
+            float dzs_r[kMaxClasses], wc_r[kMaxClasses];
+#pragma unroll
+            for (int c = 0; c < kMaxClasses; ++c)
+                if (c < C) {
+                    dzs_r[c] = a.dzsum[c];
+                    wc_r[c] = Wc[(int64_t)(act ? j : 0) * C + c];
+                }
+#pragma unroll
+            for (int c = 0; c < kMaxClasses; ++c)
+                if (c < C) base += dzs_r[c] * wc_r[c];
         }
         float pbv[2]; // pooled last-layer means of the samples s = k + (2q + hf) L this thread covers first
 #pragma unroll
@@ -1157,8 +1225,6 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
         if (!act) return;
         if (hf == 0) {
             // dc_up^k[j] = (sum_s dz_s) W_cls^T [j] + sum_{k'>k} t[j][k']
-            float base = 0.f;
-            for (int c = 0; c < C; ++c) base += a.dzsum[c] * Wc[(int64_t)j * C + c];
             for (int k2 = k + 1; k2 < L; ++k2) base += tsh[jj * L + k2];
             a.grads[(int64_t)k * a.PL + 2 * dr + r + j] = base;
         }
