@@ -56,6 +56,10 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2408_10746_amd.build`")
+        # PyTorch first: it brings its own HIP runtime, and the library must bind to the same one as
+        # the device pointers and streams it is handed (loaded the other way round, the system's
+        # runtime is loaded as well and launches on PyTorch's streams fail).
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         L.pac_create.restype = C.c_int

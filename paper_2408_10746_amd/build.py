@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libpac.so")
 SOURCES = ["pac_api.hip", "pac_kernels.hip", "pac_gram.hip"]
-HEADERS = ["pac_gemm.h", "pac_internal.h", os.path.join("..", "..", "include", "pac.h")]
+HEADERS = ["pac_gemm.h", "pac_mma.h", "pac_internal.h", os.path.join("..", "..", "include", "pac.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -185,6 +185,10 @@ pac_status pac_cache_fill(pac_ctx *ctx, void *cache, int64_t cache_bytes, const 
     if (acts_dtype != PAC_BF16 && acts_dtype != PAC_F32) return PAC_ERR_SHAPE;
     if (!aligned(cache, 256) || !aligned(acts, 16)) return PAC_ERR_ALIGN;
     if (count == 0) return PAC_OK;
+    // The launches below are checked with hipGetLastError, which also reports an error left behind
+    // by an earlier, unrelated HIP call of this thread (another library's probe of a host pointer,
+    // say): drop such a leftover first.
+    (void)hipGetLastError();
     const Dims &D = ctx->D;
     const int64_t eb = elem_bytes(D.cache_dtype);
     // validate everything and lay out new blocks before touching the context
@@ -283,6 +287,7 @@ pac_status pac_adapter_loss_grad(pac_ctx *ctx, const void *cache, const int64_t 
     if (s != PAC_OK) return s;
     StepIO io{cache, labels, params, static_cast<char *>(workspace), loss_out, logits_out, grads_out,
               static_cast<hipStream_t>(hip_stream), ctx->prof.on ? &ctx->prof : nullptr};
+    (void)hipGetLastError(); // drop an error left behind by an unrelated earlier call (see pac_cache_fill)
     return launch_loss_grad(ctx->D, ctx->W, meta, io) == hipSuccess ? PAC_OK : PAC_ERR_DEVICE;
 }
 
@@ -307,6 +312,7 @@ pac_status pac_adapter_step(pac_ctx *ctx, const void *cache, const int64_t *samp
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Profiler *prof = ctx->prof.on ? &ctx->prof : nullptr;
     StepIO io{cache, labels, params, ws, loss_out, nullptr, grads, st, prof};
+    (void)hipGetLastError(); // drop an error left behind by an unrelated earlier call (see pac_cache_fill)
     if (launch_loss_grad(ctx->D, ctx->W, meta, io) != hipSuccess) return PAC_ERR_DEVICE;
     const int64_t t = *step + 1;
     AdamArgs a;
