@@ -312,6 +312,8 @@ pac_status pac_adapter_step(pac_ctx *ctx, const void *cache, const int64_t *samp
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Profiler *prof = ctx->prof.on ? &ctx->prof : nullptr;
     StepIO io{cache, labels, params, ws, loss_out, nullptr, grads, st, prof};
+    Deferred fin;
+    io.defer = &fin;
     (void)hipGetLastError(); // drop an error left behind by an unrelated earlier call (see pac_cache_fill)
     if (launch_loss_grad(ctx->D, ctx->W, meta, io) != hipSuccess) return PAC_ERR_DEVICE;
     const int64_t t = *step + 1;
@@ -319,7 +321,7 @@ pac_status pac_adapter_step(pac_ctx *ctx, const void *cache, const int64_t *samp
     a.lr = hp->lr; a.beta1 = hp->beta1; a.beta2 = hp->beta2; a.eps = hp->eps; a.wd = hp->weight_decay;
     a.bc1 = (float)(1.0 - pow((double)hp->beta1, (double)t));
     a.bc2 = (float)(1.0 - pow((double)hp->beta2, (double)t));
-    if (launch_adamw(ctx->D, params, m, v, grads, a, st, prof) != hipSuccess) return PAC_ERR_DEVICE;
+    if (launch_adamw(ctx->D, params, m, v, grads, a, st, prof, &fin) != hipSuccess) return PAC_ERR_DEVICE;
     *step = t;
     return PAC_OK;
 }

@@ -36,6 +36,7 @@ static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 constexpr int kChainRows = 16;   // token rows per chain workgroup
 constexpr int kChainPad = 8;     // bf16 elements of padding per LDS row
 constexpr int kMaxD = 4096;
+constexpr int kETileCols = 128; // columns of d one workgroup of the E contraction covers
 constexpr int kMaxSplitTiles = 512; // 16-token tiles one workgroup of the E contraction walks over at most
 constexpr int kMaxTiles = 8192;     // 16-token tiles of a batch (LDS table of the column-sum reduction)
 
@@ -70,7 +71,7 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.use_gram = 1;
     W.max_tiles = D.B_max * cdiv(D.n_max, kChainRows);
     W.pairs = D.L * (D.L - 1) / 2;
-    const int e_tiles = D.L * cdiv(D.d, 128);
+    const int e_tiles = D.L * cdiv(D.d, kETileCols);
     int se = cdiv(288, e_tiles);
     const int max_by_rows = (int)((D.Mmax + 127) / 128);
     if (se > max_by_rows) se = max_by_rows;
@@ -238,9 +239,17 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
         if (j >= d) return;
         float acc = 0.f;
         a.cusum[j] = 0.f;
-        for (int l = 1; l <= L; ++l) {
-            acc += a.params[(int64_t)(l - 1) * a.PL + 2 * (int64_t)d * r + r + j];
-            a.cusum[(int64_t)l * d + j] = acc;
+        for (int l0 = 0; l0 < L; l0 += 8) { // eight layers' loads issued together
+            float cu[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                cu[u] = a.params[(int64_t)min(l0 + u, L - 1) * a.PL + 2 * (int64_t)d * r + r + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (l0 + u < L) {
+                    acc += cu[u];
+                    a.cusum[(int64_t)(l0 + u + 1) * d + j] = acc;
+                }
         }
         return;
     }
@@ -252,10 +261,23 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
         const float *wu = a.params + (int64_t)k * a.PL + (int64_t)d * r + r + (int64_t)aa * d;
         const float *Wc = a.params + (int64_t)L * a.PL;
         float acc[kMaxClasses];
+#pragma unroll
         for (int c = 0; c < kMaxClasses; ++c) acc[c] = 0.f;
-        for (int j = lane; j < d; j += 64) {
-            const float w = wu[j];
-            for (int c = 0; c < C; ++c) acc[c] += w * Wc[(int64_t)j * C + c];
+        // eight columns per lane and round, their loads issued together (d is a multiple of 32)
+        for (int j0 = 0; j0 < d; j0 += 64 * 8) {
+            float w[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = j0 + 64 * u + lane;
+                w[u] = j < d ? wu[j] : 0.f;
+            }
+            for (int c = 0; c < C; ++c) {
+                float wc[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) wc[u] = Wc[(int64_t)min(j0 + 64 * u + lane, d - 1) * C + c];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc[c] += w[u] * wc[u];
+            }
         }
         for (int c = 0; c < C; ++c) {
             float v = acc[c];
@@ -801,7 +823,7 @@ constexpr int kTokStages = 4;
 using TG = TnTile<2, 2, 2, 2, 32, kTokStages>; // 128 x 128 tile of the Gram matrix, 32 tokens per stage
 
 template <int NT> struct TokRedShapes {
-    using TE = TnTile<2, 2, 2, (NT > 2 ? 2 : 1), 32, kTokStages>; // 128 columns of d x (64 or 128 >= r)
+    using TE = TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), 32, kTokStages>; // kETileCols columns of d x (64 or 128 >= r)
     static constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4 + kMaxTiles * 4 + kMaxBatch * kMaxClasses * 4; // + tile and sample tables
     static constexpr int kTileLds = TE::LDS_BYTES > TG::LDS_BYTES ? TE::LDS_BYTES : TG::LDS_BYTES;
     static constexpr int kLds = kTileLds > kVecLds ? kTileLds : kVecLds;
@@ -1192,13 +1214,32 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
                         Chunk<bf16_t> w8, u8;
                         __builtin_memcpy(&w8, &wv[q], 16);
                         __builtin_memcpy(&u8, &uv[q], 16);
+                        // 16-byte reads of the column sums (both sides are 16-byte aligned: rh % 16 == 0)
+                        const f32x4 c0 = *reinterpret_cast<const f32x4 *>(csk + q * 8);
+                        const f32x4 c1 = *reinterpret_cast<const f32x4 *>(csk + q * 8 + 4);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            acc += csk[q * 8 + e] * to_f32(w8.e[e]);
-                            const float u = to_f32(u8.e[e]);
+                        for (int e = 0; e < 4; ++e) {
+                            acc += c0[e] * to_f32(w8.e[e]);
+                            acc += c1[e] * to_f32(w8.e[4 + e]);
+                        }
+                        if (C == 3) { // 8 rows x 3 classes = six 16-byte reads
+                            f32x4 z[6];
 #pragma unroll
-                            for (int c = 0; c < kMaxClasses; ++c)
-                                if (c < C) wz[c] += u * Zk[(int64_t)(q * 8 + e) * C + c];
+                            for (int v = 0; v < 6; ++v) z[v] = *reinterpret_cast<const f32x4 *>(Zk + (int64_t)q * 24 + 4 * v);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                const float u = to_f32(u8.e[e]);
+#pragma unroll
+                                for (int c = 0; c < 3; ++c) wz[c] += u * z[(3 * e + c) >> 2][(3 * e + c) & 3];
+                            }
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                const float u = to_f32(u8.e[e]);
+#pragma unroll
+                                for (int c = 0; c < kMaxClasses; ++c)
+                                    if (c < C) wz[c] += u * Zk[(int64_t)(q * 8 + e) * C + c];
+                            }
                         }
                     }
                 // pooled part of dW_cls, the samples dealt over (k, hf)
@@ -1408,7 +1449,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     {
         TokRedArgs a;
         a.cache = cache; a.map = map; a.L = L; a.d = d; a.r = r;
-        a.e_tiles = cdiv(d, 128);
+        a.e_tiles = cdiv(d, kETileCols);
         {
             // W.se is fixed by the configuration (the partial buffers are sized for it)
             if (cdiv(ntiles, W.se) > kMaxSplitTiles) return hipErrorInvalidValue;
@@ -1461,8 +1502,14 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             else
                 launch_parts(prof, st, split, k_gpost<32>, pa, 3, counts, classes, KC_G_POST, 256, PostShapes<32>::kLds);
         }
-        PAC_LAUNCH(prof, st, KC_G_FINISH, k_gfinish, dim3(1), dim3(64), 0, st, loss_part, B, io.loss_out, dlam_part,
-                   pa.slots, L, D.PL, io.grads);
+        if (io.defer) { // the optimizer launch that follows does the last two sums
+            io.defer->used = true;
+            io.defer->loss_part = loss_part; io.defer->B = B; io.defer->loss_out = io.loss_out;
+            io.defer->dlam_part = dlam_part; io.defer->slots = pa.slots; io.defer->grads = io.grads;
+        } else {
+            PAC_LAUNCH(prof, st, KC_G_FINISH, k_gfinish, dim3(1), dim3(64), 0, st, loss_part, B, io.loss_out, dlam_part,
+                       pa.slots, L, D.PL, io.grads);
+        }
     }
     return hipGetLastError();
 }

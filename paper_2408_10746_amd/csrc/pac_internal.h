@@ -100,6 +100,20 @@ struct StepIO {
     float *grads;      // null: forward only
     hipStream_t stream;
     Profiler *prof; // may be null
+    // A training step can leave the last two ordered sums (the loss over the samples, the gate
+    // gradients over the workgroups' partials) to the optimizer launch.  When `defer` is set and the
+    // path that ran supports it, it fills *defer and skips its own last launch.
+    struct Deferred *defer = nullptr;
+};
+
+struct Deferred {
+    bool used = false;
+    const float *loss_part = nullptr; // [B]
+    int B = 0;
+    float *loss_out = nullptr;
+    const float *dlam_part = nullptr; // [L][slots]
+    int slots = 0;
+    float *grads = nullptr; // where the gate gradients go as well
 };
 
 struct AdamArgs {
@@ -116,7 +130,7 @@ hipError_t launch_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &m
 bool gram_path_fits(const Dims &D);
 void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &offset);
 hipError_t launch_gram_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io);
-hipError_t launch_adamw(const Dims &D, float *p, float *m, float *v, const float *g,
-                        const AdamArgs &a, hipStream_t st, Profiler *prof);
+hipError_t launch_adamw(const Dims &D, float *p, float *m, float *v, float *g,
+                        const AdamArgs &a, hipStream_t st, Profiler *prof, const Deferred *fin = nullptr);
 
 } // namespace pac

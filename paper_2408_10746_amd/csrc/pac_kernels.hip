@@ -613,21 +613,38 @@ __global__ __launch_bounds__(256) void k_reduce_layer(const float *__restrict__ 
 // ---------------------------------------------------------------------------
 // AdamW over the flat parameter vector
 // ---------------------------------------------------------------------------
+// When the loss / gate-gradient sums were left to this launch (fin.used), the thread that owns a
+// gate sums that layer's partials in slot order, and the first thread sums the samples' loss terms.
 __global__ __launch_bounds__(256) void k_adamw(float *__restrict__ p, float *__restrict__ m, float *__restrict__ v,
-                                               const float *__restrict__ g, int64_t P, int64_t PL, int L, int d,
-                                               int r, int C, AdamArgs a)
+                                               float *__restrict__ g, int64_t P, int64_t PL, int L, int d,
+                                               int r, int C, AdamArgs a, Deferred fin)
 {
     const int64_t dr = (int64_t)d * r;
     const int64_t head = (int64_t)L * PL;
+    if (fin.used && blockIdx.x == 0 && threadIdx.x == 0) {
+        float tot = 0.f;
+        for (int s = 0; s < fin.B; ++s) tot += fin.loss_part[s];
+        *fin.loss_out = tot / (float)fin.B;
+    }
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < P; i += (int64_t)gridDim.x * 256) {
         bool decayed;
+        float gi;
         if (i < head) {
             const int64_t o = i % PL;
             decayed = (o < dr) || (o >= dr + r && o < 2 * dr + r);
+            if (fin.used && o == PL - 1) {
+                const float *part = fin.dlam_part + (i / PL) * fin.slots;
+                float acc = 0.f;
+                for (int s = 0; s < fin.slots; ++s) acc += part[s];
+                gi = acc;
+                g[i] = acc;
+            } else {
+                gi = g[i];
+            }
         } else {
             decayed = (i - head) < (int64_t)d * C;
+            gi = g[i];
         }
-        const float gi = g[i];
         const float mi = a.beta1 * m[i] + (1.f - a.beta1) * gi;
         const float vi = a.beta2 * v[i] + (1.f - a.beta2) * gi * gi;
         m[i] = mi;
@@ -639,12 +656,13 @@ __global__ __launch_bounds__(256) void k_adamw(float *__restrict__ p, float *__r
     }
 }
 
-hipError_t launch_adamw(const Dims &D, float *p, float *m, float *v, const float *g, const AdamArgs &a,
-                        hipStream_t st, Profiler *prof)
+hipError_t launch_adamw(const Dims &D, float *p, float *m, float *v, float *g, const AdamArgs &a, hipStream_t st,
+                        Profiler *prof, const Deferred *fin)
 {
     int blocks = cdiv(D.P, 256);
     if (blocks > 4096) blocks = 4096;
-    PAC_LAUNCH(prof, st, KC_ADAMW, k_adamw, dim3(blocks), dim3(256), 0, st, p, m, v, g, D.P, D.PL, D.L, D.d, D.r, D.C, a);
+    const Deferred f = fin ? *fin : Deferred();
+    PAC_LAUNCH(prof, st, KC_ADAMW, k_adamw, dim3(blocks), dim3(256), 0, st, p, m, v, g, D.P, D.PL, D.L, D.d, D.r, D.C, a, f);
     return hipGetLastError();
 }
 
