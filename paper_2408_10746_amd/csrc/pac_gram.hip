@@ -364,7 +364,9 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
     using TQ = typename SH::TQ;
     constexpr int KU = BK / 32;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int b = blockIdx.x + a.blk_off;
+    // workgroups are numbered with the big streaming part first but dispatched in reverse: the small
+    // latency-bound parts start at once and run alongside it
+    const int b = (int)(gridDim.x - 1 - blockIdx.x) + a.blk_off;
     if (b < a.nb_U) {
         const int l = b / a.row_tiles, mt = b % a.row_tiles;
         const bf16_t *cache = a.cache;
@@ -835,7 +837,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     __shared__ int64_t t_aoff[kMaxSplitTiles]; // cache offset of the tile's first row in this layer
     __shared__ int32_t t_m0[kMaxSplitTiles], t_rows[kMaxSplitTiles];
-    const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
+    const int b = blockIdx.x + a.blk_off, t = threadIdx.x; // (dispatching the small parts first is slower here)
     const int M = a.map.M;
     const int Lr = a.L * a.r;
     if (b < a.nb_E) {
@@ -1114,7 +1116,7 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
     const int L = a.L, d = a.d, r = a.r, C = a.C;
     const int Lr = L * r;
     const int64_t dr = (int64_t)d * r;
-    const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
+    const int b = (int)(gridDim.x - 1 - blockIdx.x) + a.blk_off, t = threadIdx.x; // reverse dispatch, as in k_gproj
     const int ti_d = (d + 63) / 64, ti_r = (r + 63) / 64;
     if (b < a.nb_F) {
         // F_l = sum_{k<l} W_up^{kT} G_{kl}   ([d] x [l*r] times [l*r] x [r])
