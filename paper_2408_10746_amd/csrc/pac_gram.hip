@@ -822,10 +822,11 @@ struct TokRedArgs {
 };
 
 constexpr int kTokStages = 4;
-using TG = TnTile<2, 2, 2, 2, 32, kTokStages>; // 128 x 128 tile of the Gram matrix, 32 tokens per stage
+constexpr int kTokKT = 32;    // tokens per stage of the token contractions (a multiple of 16)
+using TG = TnTile<2, 2, 2, 2, kTokKT, kTokStages>; // 128 x 128 tile of the Gram matrix
 
 template <int NT> struct TokRedShapes {
-    using TE = TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), 32, kTokStages>; // kETileCols columns of d x (64 or 128 >= r)
+    using TE = TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), kTokKT, kTokStages>; // kETileCols columns of d x (64 or 128 >= r)
     static constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4 + kMaxTiles * 4 + kMaxBatch * kMaxClasses * 4; // + tile and sample tables
     static constexpr int kTileLds = TE::LDS_BYTES > TG::LDS_BYTES ? TE::LDS_BYTES : TG::LDS_BYTES;
     static constexpr int kLds = kTileLds > kVecLds ? kTileLds : kVecLds;
@@ -858,17 +859,17 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         const bf16_t *dp = a.DP + (int64_t)l * a.r;
         const int d = a.d;
         auto atok = [&](int step, int grp, int r8) -> const bf16_t * {
-            const int tl = step * 2 + (grp >> 1), row = (grp & 1) * 8 + r8;
+            const int tl = step * (kTokKT / 16) + (grp >> 1), row = (grp & 1) * 8 + r8;
             if (tl >= ntl || row >= t_rows[tl]) return nullptr;
             return cache + t_aoff[tl] + (int64_t)row * d;
         };
         auto btok = [&](int step, int grp, int r8) -> const bf16_t * {
-            const int tl = step * 2 + (grp >> 1), row = (grp & 1) * 8 + r8;
+            const int tl = step * (kTokKT / 16) + (grp >> 1), row = (grp & 1) * 8 + r8;
             if (tl >= ntl || row >= t_rows[tl]) return nullptr;
             return dp + (int64_t)(t_m0[tl] + row) * Lr;
         };
         EpiStoreF32 epi{a.Epart + ((int64_t)split * a.L + l) * a.d * a.r, a.r};
-        gemm_tn<TE>(smem, atok, btok, a.zeros, epi, (ntl + 1) / 2, it * TE::BM, 0, a.d, a.r, a.d, a.r);
+        gemm_tn<TE>(smem, atok, btok, a.zeros, epi, (ntl * 16 + kTokKT - 1) / kTokKT, it * TE::BM, 0, a.d, a.r, a.d, a.r);
         return;
     }
     if (b < a.nb_E + a.nb_G) {
@@ -884,15 +885,15 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         const int kend = min(M, kbegin + a.rows_per_sg);
         const bf16_t *H = a.H, *DP = a.DP;
         auto atok = [&](int step, int grp, int r8) -> const bf16_t * {
-            const int k = kbegin + step * 32 + grp * 8 + r8;
+            const int k = kbegin + step * kTokKT + grp * 8 + r8;
             return k < kend ? H + (int64_t)k * Lr : nullptr;
         };
         auto btok = [&](int step, int grp, int r8) -> const bf16_t * {
-            const int k = kbegin + step * 32 + grp * 8 + r8;
+            const int k = kbegin + step * kTokKT + grp * 8 + r8;
             return k < kend ? DP + (int64_t)k * Lr : nullptr;
         };
         EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
-        gemm_tn<TG>(smem, atok, btok, a.zeros, epi, (kend - kbegin + 31) / 32, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
+        gemm_tn<TG>(smem, atok, btok, a.zeros, epi, (kend - kbegin + kTokKT - 1) / kTokKT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
         return;
     }
     // cs[kk] = sum over the tiles of their column sums of dpre ;
@@ -1455,7 +1456,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         {
             // W.se is fixed by the configuration (the partial buffers are sized for it)
             if (cdiv(ntiles, W.se) > kMaxSplitTiles) return hipErrorInvalidValue;
-            a.tiles_per_se = cdiv(cdiv(ntiles, W.se), 2) * 2;
+            a.tiles_per_se = cdiv(cdiv(ntiles, W.se), kTokKT / 16) * (kTokKT / 16);
             a.se = cdiv(ntiles, a.tiles_per_se);
         }
         a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.zeros = ws + W.g_zero;
