@@ -22,6 +22,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace pac {
 
@@ -517,6 +518,39 @@ template <int WM_, int WN_, int WTM_, int WTN_, int KU_, int PF_ = 1> struct Til
     static_assert(WM * WN * 64 == kThreads, "four wavefronts per workgroup");
 };
 
+// Hands the accumulators to the epilogue functor.  A lane holds column col and the 16 rows
+// row_base + 8 (v / 4) + v % 4 of each 32 x 32 block.  Plain functors get (row, col, value) for every
+// element inside (nrows, ncols).  A functor that reads global memory should instead declare
+// `static constexpr bool kBatched = true` and provide batch(row_base, col, values, nrows, ncols):
+// it can then issue all its loads (from clamped indices) before the first use, where the
+// element-wise form would wait for memory once per element.
+template <class E, class = void> struct epi_is_batched : std::false_type {};
+template <class E> struct epi_is_batched<E, std::void_t<decltype(E::kBatched)>> : std::true_type {};
+__device__ __forceinline__ int epi_row(int row_base, int v) { return row_base + 8 * (v >> 2) + (v & 3); }
+
+template <class TL, class Epi>
+__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TL::WTM][TL::WTN], Epi &epi, int wm, int wn, int lane,
+                                              int row0, int col0, int nrows, int ncols)
+{
+    const int i = lane & 31, g = lane >> 5;
+#pragma unroll
+    for (int x = 0; x < TL::WTM; ++x)
+#pragma unroll
+        for (int y = 0; y < TL::WTN; ++y) {
+            const int col = col0 + (wn * TL::WTN + y) * 32 + i;
+            const int row_base = row0 + (wm * TL::WTM + x) * 32 + 4 * g;
+            if constexpr (epi_is_batched<Epi>::value) {
+                epi.batch(row_base, col, acc[x][y], nrows, ncols);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = epi_row(row_base, v);
+                    if (row < nrows && col < ncols) epi(row, col, acc[x][y][v]);
+                }
+            }
+        }
+}
+
 // C[row0.., col0..] = sum_{k in [kbegin, kend)} A[row][k] * B[col][k]; the
 // epilogue functor receives (row, col, value) for every element inside
 // (nrows, ncols).  kbegin must be a multiple of the K step.
@@ -592,18 +626,7 @@ __device__ __forceinline__ void gemm_tile(void *lds /* tile_lds_bytes<TC, TL>(),
             __syncthreads();
         }
     }
-    const int i = lane & 31, g = lane >> 5;
-#pragma unroll
-    for (int x = 0; x < TL::WTM; ++x)
-#pragma unroll
-        for (int y = 0; y < TL::WTN; ++y) {
-            const int col = col0 + (wn * TL::WTN + y) * 32 + i;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row0 + (wm * TL::WTM + x) * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (row < nrows && col < ncols) epi(row, col, acc[x][y][v]);
-            }
-        }
+    tile_epilogue<TL>(acc, epi, wm, wn, lane, row0, col0, nrows, ncols);
 }
 
 // Sum of one float per thread over the workgroup; result valid in thread 0.

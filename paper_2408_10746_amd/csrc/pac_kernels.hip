@@ -14,6 +14,7 @@
 namespace pac {
 
 using T64 = Tile<2, 2, 1, 1, 1>;  // 64 x 64 workgroup tile, 64 bytes of K per step
+template <int KU> using T64U = Tile<2, 2, 1, 1, KU>; // same tile, KU * 64 bytes of K per step
 using T64K = Tile<2, 2, 1, 1, 4>; // same tile, 256 bytes of K per step (token reductions)
 
 // launch, optionally bracketed by timing events of its kernel class
@@ -239,33 +240,42 @@ template <typename TC> struct FwdDownArgs {
 };
 
 template <typename TC> struct EpiFwdDown {
+    static constexpr bool kBatched = true;
     const float *c_down;
     float *pre;
     TC *h;
     int r;
-    __device__ void operator()(int row, int col, float v) const
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
     {
-        const float u = v + c_down[col];
-        pre[(int64_t)row * r + col] = u;
-        h[(int64_t)row * r + col] = to_tc(gelu_f(u), TC());
+        const float cd = c_down[min(col, ncols - 1)];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = epi_row(row_base, v);
+            if (row < nrows && col < ncols) {
+                const float u = acc[v] + cd;
+                pre[(int64_t)row * r + col] = u;
+                h[(int64_t)row * r + col] = to_tc(gelu_f(u), TC());
+            }
+        }
     }
 };
 
-template <typename TC, bool MIX> __device__ __forceinline__ void fwd_down_tile(const FwdDownArgs<TC> &a, char *smem)
+template <typename TC, bool MIX, int KU> __device__ __forceinline__ void fwd_down_tile(const FwdDownArgs<TC> &a, char *smem)
 {
-    LoadRowsX<TC, 64, 1, MIX> al;
+    LoadRowsX<TC, 64, KU, MIX> al;
     al.cache = a.cache; al.map = a.map; al.layer = a.layer; al.s_prev = a.s_prev; al.ld_s = a.d; al.lam = *a.lam;
-    LoadRowsTC<TC, 64, 1> bl;
+    LoadRowsTC<TC, 64, KU> bl;
     bl.src = a.WdT; bl.ld = a.d; bl.nrows = a.r;
     EpiFwdDown<TC> epi{a.c_down, a.pre, a.h, a.r};
-    gemm_tile<TC, T64>(smem, al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.r);
+    gemm_tile<TC, T64U<KU>>(smem, al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.r);
 }
 
-template <typename TC> __global__ __launch_bounds__(256) void k_fwd_down(FwdDownArgs<TC> a)
+// KU = 4 needs the contraction length to be a multiple of 4 * 64 bytes of K; else KU = 1
+template <typename TC, int KU> __global__ __launch_bounds__(256) void k_fwd_down(FwdDownArgs<TC> a)
 {
-    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
-    if (a.s_prev) fwd_down_tile<TC, true>(a, smem);
-    else fwd_down_tile<TC, false>(a, smem);
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64U<KU>>()];
+    if (a.s_prev) fwd_down_tile<TC, true, KU>(a, smem);
+    else fwd_down_tile<TC, false, KU>(a, smem);
 }
 
 template <typename TC> struct FwdUpArgs {
@@ -278,26 +288,36 @@ template <typename TC> struct FwdUpArgs {
 };
 
 struct EpiFwdUp {
+    static constexpr bool kBatched = true;
     const float *c_up;
     const float *s_prev;
     float *s_out;
     int d;
-    __device__ void operator()(int row, int col, float v) const
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
     {
-        const int64_t o = (int64_t)row * d + col;
-        s_out[o] = (s_prev ? s_prev[o] : 0.f) + v + c_up[col];
+        const int cc = min(col, ncols - 1);
+        const float cu = c_up[cc];
+        float sp[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            sp[v] = s_prev ? s_prev[(int64_t)min(epi_row(row_base, v), nrows - 1) * d + cc] : 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = epi_row(row_base, v);
+            if (row < nrows && col < ncols) s_out[(int64_t)row * d + col] = sp[v] + acc[v] + cu;
+        }
     }
 };
 
-template <typename TC> __global__ __launch_bounds__(256) void k_fwd_up(FwdUpArgs<TC> a)
+template <typename TC, int KU> __global__ __launch_bounds__(256) void k_fwd_up(FwdUpArgs<TC> a)
 {
-    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
-    LoadRowsTC<TC, 64, 1> al;
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64U<KU>>()];
+    LoadRowsTC<TC, 64, KU> al;
     al.src = a.h; al.ld = a.r; al.nrows = a.M;
-    LoadRowsTC<TC, 64, 1> bl;
+    LoadRowsTC<TC, 64, KU> bl;
     bl.src = a.WuT; bl.ld = a.r; bl.nrows = a.d;
     EpiFwdUp epi{a.c_up, a.s_prev, a.s_out, a.d};
-    gemm_tile<TC, T64>(smem, al, bl, epi, 0, a.r, blockIdx.x * 64, blockIdx.y * 64, a.M, a.d);
+    gemm_tile<TC, T64U<KU>>(smem, al, bl, epi, 0, a.r, blockIdx.x * 64, blockIdx.y * 64, a.M, a.d);
 }
 
 // pooled[s][j] = mean_t ( b_L[t][j] + s_L[t][j] )
@@ -413,25 +433,33 @@ template <typename TC> struct BwdDpreArgs {
 };
 
 template <typename TC> struct EpiDpre {
+    static constexpr bool kBatched = true;
     const float *pre;
     TC *dpre;
     int r;
-    __device__ void operator()(int row, int col, float v) const
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
     {
-        const int64_t o = (int64_t)row * r + col;
-        dpre[o] = to_tc(v * gelu_grad_f(pre[o]), TC());
+        const int cc = min(col, ncols - 1);
+        float pv[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) pv[v] = pre[(int64_t)min(epi_row(row_base, v), nrows - 1) * r + cc];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = epi_row(row_base, v);
+            if (row < nrows && col < ncols) dpre[(int64_t)row * r + col] = to_tc(acc[v] * gelu_grad_f(pv[v]), TC());
+        }
     }
 };
 
-template <typename TC> __global__ __launch_bounds__(256) void k_bwd_dpre(BwdDpreArgs<TC> a)
+template <typename TC, int KU> __global__ __launch_bounds__(256) void k_bwd_dpre(BwdDpreArgs<TC> a)
 {
-    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
-    LoadRowsF32<TC, 64, 1> al;
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64U<KU>>()];
+    LoadRowsF32<TC, 64, KU> al;
     al.src = a.ds; al.ld = a.d; al.nrows = a.M;
-    LoadRowsTC<TC, 64, 1> bl;
+    LoadRowsTC<TC, 64, KU> bl;
     bl.src = a.Wu; bl.ld = a.d; bl.nrows = a.r;
     EpiDpre<TC> epi{a.pre, a.dpre, a.r};
-    gemm_tile<TC, T64>(smem, al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.M, a.r);
+    gemm_tile<TC, T64U<KU>>(smem, al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.M, a.r);
 }
 
 // Top layer: ds_L is the same vector for every token of a sample (dp_s / len_s), so
@@ -562,6 +590,7 @@ template <typename TC> struct BwdDxArgs {
 };
 
 template <typename TC> struct EpiDx {
+    static constexpr bool kBatched = true;
     const TC *cache;
     RowMap map;
     int layer, d;
@@ -569,26 +598,47 @@ template <typename TC> struct EpiDx {
     float lam;
     float *ds;
     float dlam;
-    __device__ void operator()(int row, int col, float v)
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols)
     {
-        const int64_t o = (int64_t)row * d + col;
-        const float b = to_f32(cache[map.rowoff[row] + (int64_t)layer * map.rowstride[row] + col]);
-        const float s = s_prev ? s_prev[o] : 0.f;
-        dlam += (b - s) * v;
-        ds[o] += (1.f - lam) * v;
+        const int cc = min(col, ncols - 1);
+        int64_t ro[16];
+        int rs[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rr = min(epi_row(row_base, v), nrows - 1);
+            ro[v] = map.rowoff[rr];
+            rs[v] = map.rowstride[rr];
+        }
+        float b[16], s[16], dsv[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rr = min(epi_row(row_base, v), nrows - 1);
+            const int64_t o = (int64_t)rr * d + cc;
+            b[v] = to_f32(cache[ro[v] + (int64_t)layer * rs[v] + cc]);
+            s[v] = s_prev ? s_prev[o] : 0.f;
+            dsv[v] = ds[o];
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = epi_row(row_base, v);
+            if (row < nrows && col < ncols) {
+                dlam += (b[v] - s[v]) * acc[v];
+                ds[(int64_t)row * d + col] = dsv[v] + (1.f - lam) * acc[v];
+            }
+        }
     }
 };
 
-template <typename TC> __global__ __launch_bounds__(256) void k_bwd_dx(BwdDxArgs<TC> a)
+template <typename TC, int KU> __global__ __launch_bounds__(256) void k_bwd_dx(BwdDxArgs<TC> a)
 {
-    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64>()];
+    __shared__ __attribute__((aligned(16))) char smem[tile_lds_bytes<TC, T64U<KU>>()];
     __shared__ float red[4];
-    LoadRowsTC<TC, 64, 1> al;
+    LoadRowsTC<TC, 64, KU> al;
     al.src = a.dpre; al.ld = a.r; al.nrows = a.map.M;
-    LoadRowsTC<TC, 64, 1> bl;
+    LoadRowsTC<TC, 64, KU> bl;
     bl.src = a.Wd; bl.ld = a.r; bl.nrows = a.d;
     EpiDx<TC> epi{a.cache, a.map, a.layer, a.d, a.s_prev, *a.lam, a.ds, 0.f};
-    gemm_tile<TC, T64>(smem, al, bl, epi, 0, a.r, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.d);
+    gemm_tile<TC, T64U<KU>>(smem, al, bl, epi, 0, a.r, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.d);
     const float tot = block_sum(epi.dlam, red);
     if (threadIdx.x == 0) a.dlam_part[blockIdx.y * gridDim.x + blockIdx.x] = tot;
 }
@@ -598,15 +648,32 @@ __global__ __launch_bounds__(256) void k_reduce_layer(const float *__restrict__ 
                                                       const float *__restrict__ dlam_part, int nslots,
                                                       float *__restrict__ g_layer)
 {
+    __shared__ float red[256];
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < PL - 1) {
         float acc = 0.f;
         for (int s = 0; s < splits; ++s) acc += part[(int64_t)s * PL + i];
         g_layer[i] = acc;
-    } else if (i == PL - 1) {
+    }
+    if ((int64_t)blockIdx.x == (PL - 1) / 256) {
+        // the gate: the workgroup that owns it sums the dx partials, each thread a strided share in
+        // slot order, the 256 shares combined in a fixed tree
         float acc = 0.f;
-        for (int s = 0; s < nslots; ++s) acc += dlam_part[s];
-        g_layer[i] = acc;
+        for (int s0 = threadIdx.x; s0 < nslots; s0 += 256 * 8) {
+            float p[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) p[u] = dlam_part[min(s0 + 256 * u, nslots - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + 256 * u < nslots) acc += p[u];
+        }
+        red[threadIdx.x] = acc;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) g_layer[PL - 1] = red[0];
     }
 }
 
@@ -704,15 +771,19 @@ static hipError_t run_loss_grad(const Dims &D, const WsLayout &W, const BatchMet
                        WdT, Wu, WuT);
 
     const dim3 g_rows_r(cdiv(M, 64), cdiv(r, 64)), g_rows_d(cdiv(M, 64), cdiv(d, 64));
+    // long K steps where the contraction length allows them
+    const bool wide_d = d % Stage<TC, 4>::BK == 0, wide_r = r % Stage<TC, 4>::BK == 0;
     for (int l = 0; l < L; ++l) {
         const float *pl = params + (int64_t)l * PL;
         const float *s_prev = l == 0 ? nullptr : s_all + (int64_t)(l - 1) * Md;
         FwdDownArgs<TC> fa{cache, map, l, d, r, s_prev, WdT + (int64_t)l * dr, pl + dr, pl + PL - 1,
                            pre_all + (int64_t)l * Mr, h_all + (int64_t)l * Mr};
-        PAC_LAUNCH(prof, st, KC_FWD_DOWN, (k_fwd_down<TC>), g_rows_r, dim3(256), 0, st, fa);
+        if (wide_d) PAC_LAUNCH(prof, st, KC_FWD_DOWN, (k_fwd_down<TC, 4>), g_rows_r, dim3(256), 0, st, fa);
+        else PAC_LAUNCH(prof, st, KC_FWD_DOWN, (k_fwd_down<TC, 1>), g_rows_r, dim3(256), 0, st, fa);
         FwdUpArgs<TC> fu{h_all + (int64_t)l * Mr, WuT + (int64_t)l * dr, pl + 2 * dr + r, s_prev,
                          s_all + (int64_t)l * Md, M, d, r};
-        PAC_LAUNCH(prof, st, KC_FWD_UP, (k_fwd_up<TC>), g_rows_d, dim3(256), 0, st, fu);
+        if (wide_r) PAC_LAUNCH(prof, st, KC_FWD_UP, (k_fwd_up<TC, 4>), g_rows_d, dim3(256), 0, st, fu);
+        else PAC_LAUNCH(prof, st, KC_FWD_UP, (k_fwd_up<TC, 1>), g_rows_d, dim3(256), 0, st, fu);
     }
     PAC_LAUNCH(prof, st, KC_POOL, (k_pool<TC>), dim3(meta.B, cdiv(d, 256)), dim3(256), 0, st, cache, map, L - 1, d,
                        s_all + (int64_t)(L - 1) * Md, samp_start, samp_len, pooled);
@@ -745,13 +816,15 @@ static hipError_t run_loss_grad(const Dims &D, const WsLayout &W, const BatchMet
                        pre_all + (int64_t)l * Mr, rowsamp, M, r, dpre);
         } else {
             BwdDpreArgs<TC> ba{ds, Wu + (int64_t)l * dr, pre_all + (int64_t)l * Mr, dpre, M, d, r};
-            PAC_LAUNCH(prof, st, KC_BWD_DPRE, (k_bwd_dpre<TC>), g_rows_r, dim3(256), 0, st, ba);
+            if (wide_d) PAC_LAUNCH(prof, st, KC_BWD_DPRE, (k_bwd_dpre<TC, 4>), g_rows_r, dim3(256), 0, st, ba);
+            else PAC_LAUNCH(prof, st, KC_BWD_DPRE, (k_bwd_dpre<TC, 1>), g_rows_r, dim3(256), 0, st, ba);
         }
         BwdWgradArgs<TC> wa{cache, map, l, d, r, s_prev, pl + PL - 1, h_all + (int64_t)l * Mr, ds, dpre, part, PL,
                             rows_per_split};
         PAC_LAUNCH(prof, st, KC_BWD_WGRAD, (k_bwd_wgrad<TC>), dim3(wg_tiles, splits, 2), dim3(256), 0, st, wa);
         BwdDxArgs<TC> xa{dpre, Wd + (int64_t)l * dr, cache, map, l, d, r, s_prev, pl + PL - 1, ds, dlam_part};
-        PAC_LAUNCH(prof, st, KC_BWD_DX, (k_bwd_dx<TC>), g_rows_d, dim3(256), 0, st, xa);
+        if (wide_r) PAC_LAUNCH(prof, st, KC_BWD_DX, (k_bwd_dx<TC, 4>), g_rows_d, dim3(256), 0, st, xa);
+        else PAC_LAUNCH(prof, st, KC_BWD_DX, (k_bwd_dx<TC, 1>), g_rows_d, dim3(256), 0, st, xa);
         PAC_LAUNCH(prof, st, KC_REDUCE, k_reduce_layer, dim3(cdiv(PL, 256)), dim3(256), 0, st, part, splits, PL, dlam_part,
                            (int)(g_rows_d.x * g_rows_d.y), grads + (int64_t)l * PL);
     }

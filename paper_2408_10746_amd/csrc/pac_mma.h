@@ -19,7 +19,6 @@
 //            (ds_read_b64_tr_b16).
 #pragma once
 #include "pac_gemm.h"
-#include <type_traits>
 
 namespace pac {
 
@@ -42,39 +41,6 @@ __device__ __forceinline__ void dma16(const void *g, void *lds_wave_base)
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)lds_wave_base);
     // one wait state between the write of M0 and the transfer that reads it
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(l), "v"(g) : "memory", "m0");
-}
-
-// Hands the accumulators to the epilogue functor.  A lane holds column col and the 16 rows
-// row_base + 8 (v / 4) + v % 4 of each 32 x 32 block.  Plain functors get (row, col, value) for every
-// element inside (nrows, ncols).  A functor that reads global memory should instead declare
-// `static constexpr bool kBatched = true` and provide batch(row_base, col, values, nrows, ncols):
-// it can then issue all its loads (from clamped indices) before the first use, where the
-// element-wise form would wait for memory once per element.
-template <class E, class = void> struct epi_is_batched : std::false_type {};
-template <class E> struct epi_is_batched<E, std::void_t<decltype(E::kBatched)>> : std::true_type {};
-__device__ __forceinline__ int epi_row(int row_base, int v) { return row_base + 8 * (v >> 2) + (v & 3); }
-
-template <class TL, class Epi>
-__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TL::WTM][TL::WTN], Epi &epi, int wm, int wn, int lane,
-                                              int row0, int col0, int nrows, int ncols)
-{
-    const int i = lane & 31, g = lane >> 5;
-#pragma unroll
-    for (int x = 0; x < TL::WTM; ++x)
-#pragma unroll
-        for (int y = 0; y < TL::WTN; ++y) {
-            const int col = col0 + (wn * TL::WTN + y) * 32 + i;
-            const int row_base = row0 + (wm * TL::WTM + x) * 32 + 4 * g;
-            if constexpr (epi_is_batched<Epi>::value) {
-                epi.batch(row_base, col, acc[x][y], nrows, ncols);
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = epi_row(row_base, v);
-                    if (row < nrows && col < ncols) epi(row, col, acc[x][y][v]);
-                }
-            }
-        }
 }
 
 // ---------------------------------------------------------------------------
