@@ -197,6 +197,73 @@ def test_bf16_paths(w, flags):
             assert np.all(grads[sl[nm]] == 0.0), nm
 
 
+@pytest.mark.parametrize("flags", [0, 1], ids=["gram", "per_layer"])
+def test_forward_only_call(flags):
+    """loss and logits without gradients (no backward launches; the gradient buffer stays untouched)."""
+    w = GRAM[1]
+    lens = inputs.lengths(w)
+    ids = np.arange(w.B)
+    acts = inputs.batch_acts(w, ids)
+    labels = inputs.labels(w)[ids]
+    params = inputs.random_params(w, up_scale=0.5)
+    dims, ref = oracle_batch(w, acts, lens, labels, params, want_grads=False)
+    sess = make_session(w, lens=lens, flags=flags)
+    sess.cache_fill(ids, acts, lens)
+    sess.set_params(params)
+    sess.grads.fill_(123.0)
+    sess.loss_grad(ids, torch.from_numpy(labels).to(sess.dev), want_grads=False)
+    torch.cuda.synchronize()
+    loss = float(sess.loss.item())
+    logits = sess.logits.cpu().numpy()[: w.B * w.C].reshape(w.B, w.C)
+    assert abs(loss - ref["loss"]) <= TOL["bf16"] * abs(ref["loss"]), (loss, ref["loss"])
+    assert rel_err(logits, ref["logits"]) <= TOL["bf16"]
+    assert torch.all(sess.grads == 123.0)
+
+
+def test_maximum_batch_many_ragged_tiles():
+    """64 samples (the largest batch the kernel argument block describes), lengths from 1 to 100:
+    more than 200 token tiles, most of them ragged, several samples of a single token."""
+    w = Workload("gmax", L=4, d=128, n_max=100, B=64, r=64, C=3, N=64, cache_dtype="bf16", len_lo=1)
+    lens = inputs.lengths(w)
+    lens[:3] = 1
+    lens[3] = 100
+    ids = np.arange(w.B)
+    acts = inputs.batch_acts(w, ids)
+    labels = inputs.labels(w)[ids]
+    sess = make_session(w, lens=lens)
+    sess.cache_fill(ids, acts, lens)
+    check_against_oracle(w, sess, ids, acts, lens, labels, inputs.random_params(w, up_scale=0.5), TOL["bf16"],
+                         what="gmax")
+
+
+@pytest.mark.parametrize("w", [GRAM[1], GRAM[3]], ids=["g2", "g4"])
+def test_training_step_loss_and_gate_gradients(w):
+    """In a training step the optimizer launch does the last two ordered sums (loss, gate gradients):
+    both must equal what the gradient call reports, bit for bit, and match the oracle."""
+    lens = inputs.lengths(w)
+    ids = np.arange(w.B)
+    acts = inputs.batch_acts(w, ids)
+    labels = inputs.labels(w)[ids]
+    params = inputs.random_params(w, up_scale=0.5)
+    sess = make_session(w, lens=lens)
+    sess.cache_fill(ids, acts, lens)
+    ref, loss_lg, grads_lg, _ = check_against_oracle(w, sess, ids, acts, lens, labels, params, TOL["bf16"],
+                                                     what=f"{w.name}/loss_grad")
+    sess.set_params(params)
+    sess.grads.zero_()
+    sess.step(ids, torch.from_numpy(labels).to(sess.dev), keep_grads=True)
+    torch.cuda.synchronize()
+    assert float(sess.loss.item()) == loss_lg
+    assert np.array_equal(sess.grads.cpu().numpy(), grads_lg)
+    # and the parameters moved as AdamW says they should from those gradients
+    dims = orc.Dims(w.L, w.d, w.r, w.C)
+    p, m, v = params.astype(np.float64), np.zeros(dims.P), np.zeros(dims.P)
+    hp = sess.hp
+    orc.adamw(dims, p, m, v, 1, grads_lg.astype(np.float64),
+              orc.AdamW(lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, weight_decay=hp.weight_decay))
+    assert np.max(np.abs(sess.params.cpu().numpy() - p)) <= 1e-6
+
+
 def test_outlier_channels_bf16():
     w = Workload("out", L=3, d=512, n_max=40, B=4, r=64, C=4, N=4, cache_dtype="bf16", outlier_frac=0.01)
     ids = np.arange(w.B)
