@@ -40,7 +40,10 @@ constexpr int kETileCols = 128; // columns of d one workgroup of the E contracti
 constexpr int kMaxSplitTiles = 512; // 16-token tiles one workgroup of the E contraction walks over at most
 constexpr int kMaxTiles = 8192;     // 16-token tiles of a batch (LDS table of the column-sum reduction)
 
-constexpr int kRing = 4; // layers of per-token inputs the chain kernels stage ahead in LDS
+// Slots of the chain kernels' LDS ring of per-token inputs.  Two suffice: the helper wavefront keeps the
+// tiles of the next three steps in registers and writes the tile of step s+1 while the contracting
+// wavefronts read that of step s; a barrier separates that from the write of step s+2 into the same slot.
+constexpr int kRing = 2;
 
 // LDS of the chain kernels (T = kChainRows):
 //   Hs   [L][T][r+pad] bf16   h (forward) or dpre (backward) of every layer: the contraction operand

@@ -174,6 +174,8 @@ GRAM = [
     Workload("g2", L=5, d=128, n_max=70, B=4, r=64, C=3, N=4, cache_dtype="bf16", len_lo=20),
     Workload("g3", L=3, d=224, n_max=33, B=6, r=128, C=5, N=6, cache_dtype="bf16", len_lo=30),
     Workload("g4", L=6, d=192, n_max=64, B=2, r=96, C=16, N=2, cache_dtype="bf16"),
+    # as many layers and as wide an adapter as the Large-shaped configuration: the chain kernels' LDS near its limit
+    Workload("g5", L=24, d=128, n_max=40, B=3, r=128, C=2, N=3, cache_dtype="bf16", len_lo=17),
 ]
 
 
