@@ -25,9 +25,15 @@ namespace pac {
 
 #define PAC_LAUNCH(prof, st, cls, ...)                         \
     do {                                                       \
-        if (prof) (prof)->mark((st), (cls), true);             \
+        if (prof) (void)(prof)->mark((st), (cls), true);           \
         hipLaunchKernelGGL(__VA_ARGS__);                       \
-        if (prof) (prof)->mark((st), (cls), false);            \
+        if (prof) (void)(prof)->mark((st), (cls), false);           \
+    } while (0)
+
+#define PAC_HIP_TRY(expr)                          \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess) return e_;           \
     } while (0)
 
 static inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
@@ -413,7 +419,9 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
         return;
     }
     {
-        // mean over the valid tokens of the last cached layer: 8 token groups x 32 column chunks
+        // mean over the valid tokens of the last cached layer: 8 token groups x 32 column chunks.
+        // The tokens of a sample are consecutive rows of one block, so one table lookup gives them all;
+        // eight rows are requested per round.
         int idx = b - a.nb_U - a.nb_Q - a.nb_C;
         const int jt = (a.d + 255) / 256;
         const int s = idx / jt, j0 = (idx % jt) * 256;
@@ -423,12 +431,20 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = 0.f;
         if (j < a.d) {
-            for (int tkn = tg; tkn < len; tkn += 8) {
-                const int m = m0 + tkn;
-                const Chunk<bf16_t> c = *reinterpret_cast<const Chunk<bf16_t> *>(
-                    a.cache + a.map.rowoff[m] + (int64_t)(a.L - 1) * a.map.rowstride[m] + j);
+            const bf16_t *base = a.cache + a.map.rowoff[m0] + (int64_t)(a.L - 1) * a.map.rowstride[m0] + j;
+            for (int t0 = tg; t0 < len; t0 += 8 * 8) {
+                u32x4 c[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[e] += to_f32(c.e[e]);
+                for (int u = 0; u < 8; ++u)
+                    c[u] = *reinterpret_cast<const u32x4 *>(base + (int64_t)min(t0 + 8 * u, len - 1) * a.d);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (t0 + 8 * u < len) {
+                        Chunk<bf16_t> ch;
+                        __builtin_memcpy(&ch, &c[u], 16);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[e] += to_f32(ch.e[e]);
+                    }
             }
         }
         float *red = reinterpret_cast<float *>(smem); // [8][256]
@@ -1385,6 +1401,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         const int classes[4] = {KC_G_PREP_SETUP, KC_G_PREP_COPY, KC_G_PREP_CHAT, KC_G_PREP_V};
         launch_parts(prof, st, split, k_gprep, a, 4, counts, classes, KC_G_PREP, 256);
     }
+    // a launch that was refused leaves the tables the later kernels index with unwritten: stop here
+    PAC_HIP_TRY(hipGetLastError());
     {
         ProjArgs a;
         a.cache = cache; a.map = map; a.L = L; a.d = d; a.r = r; a.B = B;
@@ -1416,6 +1434,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             launch_parts(prof, st, split, k_gproj<NT, 32>, a, 4, counts, classes, KC_G_PROJ, 256, ProjShapes<NT, 32>::kLds);
         }
     }
+    PAC_HIP_TRY(hipGetLastError());
     const size_t lds_fwd = chain_lds(L, r, true), lds_bwd = chain_lds(L, r, false);
     static bool attr_done = false;
     if (!attr_done) {

@@ -20,9 +20,9 @@ using T64K = Tile<2, 2, 1, 1, 4>; // same tile, 256 bytes of K per step (token r
 // launch, optionally bracketed by timing events of its kernel class
 #define PAC_LAUNCH(prof, st, cls, ...)                         \
     do {                                                       \
-        if (prof) (prof)->mark((st), (cls), true);             \
+        if (prof) (void)(prof)->mark((st), (cls), true);           \
         hipLaunchKernelGGL(__VA_ARGS__);                       \
-        if (prof) (prof)->mark((st), (cls), false);            \
+        if (prof) (void)(prof)->mark((st), (cls), false);           \
     } while (0)
 
 #define PAC_HIP_TRY(expr)                          \

@@ -123,21 +123,27 @@ __device__ __forceinline__ void gemm_nt(char *lds /* TL::LDS_BYTES, 1 KB aligned
             __syncthreads();                       // ... and everybody else's; stage st-1 is free
             issue(slot == 0 ? TL::STAGES - 1 : slot - 1, st + TL::STAGES - 1);
             const char *sb = lds + slot * TL::STAGE_BYTES;
+            // all fragments of the stage are read before the first matrix instruction: with one or two
+            // wavefronts per SIMD a read-wait-multiply sequence per K step would expose the LDS latency
+            // BK / 16 times per stage
+            bf16x8 a[TL::BK / 16][TL::WTM], b[TL::BK / 16][TL::WTN];
 #pragma unroll
             for (int ks = 0; ks < TL::BK / 16; ++ks) {
-                bf16x8 a[TL::WTM], b[TL::WTN];
 #pragma unroll
                 for (int x = 0; x < TL::WTM; ++x)
-                    a[x] = *reinterpret_cast<const bf16x8 *>(sb + arow_b[x] + (((2 * ks + g) ^ asw[x]) << 4));
+                    a[ks][x] = *reinterpret_cast<const bf16x8 *>(sb + arow_b[x] + (((2 * ks + g) ^ asw[x]) << 4));
 #pragma unroll
                 for (int y = 0; y < TL::WTN; ++y)
-                    b[y] = *reinterpret_cast<const bf16x8 *>(sb + brow_b[y] + (((2 * ks + g) ^ bsw[y]) << 4));
+                    b[ks][y] = *reinterpret_cast<const bf16x8 *>(sb + brow_b[y] + (((2 * ks + g) ^ bsw[y]) << 4));
+            }
+            __builtin_amdgcn_sched_barrier(0); // keep the scheduler from sinking the reads to their uses
+#pragma unroll
+            for (int ks = 0; ks < TL::BK / 16; ++ks)
 #pragma unroll
                 for (int x = 0; x < TL::WTM; ++x)
 #pragma unroll
                     for (int y = 0; y < TL::WTN; ++y)
-                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b[y], acc[x][y], 0, 0, 0);
-            }
+                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][x], b[ks][y], acc[x][y], 0, 0, 0);
             slot = slot + 1 == TL::STAGES ? 0 : slot + 1;
         }
         wait_vm<0>(); // the repeated transfers of the last steps must not outlive this use of the LDS
@@ -258,21 +264,25 @@ __device__ __forceinline__ void gemm_tn(char *lds /* TL::LDS_BYTES, 1 KB aligned
 #pragma unroll
             for (int q = 0; q < TL::NI; ++q) nxt[q] = source(q, st + TL::STAGES);
             const char *sb = lds + slot * TL::STAGE_BYTES;
+            // (all fragments of the stage first, as in gemm_nt)
+            bf16x8 a[TL::KT / 16][TL::WTM], b[TL::KT / 16][TL::WTN];
 #pragma unroll
             for (int ks = 0; ks < TL::KT / 16; ++ks) {
-                bf16x8 a[TL::WTM], b[TL::WTN];
 #pragma unroll
                 for (int x = 0; x < TL::WTM; ++x)
-                    a[x] = tr_read2(sb + aoff[x] + ks * 2048, sb + aoff[x] + ks * 2048 + 512);
+                    a[ks][x] = tr_read2(sb + aoff[x] + ks * 2048, sb + aoff[x] + ks * 2048 + 512);
 #pragma unroll
                 for (int y = 0; y < TL::WTN; ++y)
-                    b[y] = tr_read2(sb + boff[y] + ks * 2048, sb + boff[y] + ks * 2048 + 512);
+                    b[ks][y] = tr_read2(sb + boff[y] + ks * 2048, sb + boff[y] + ks * 2048 + 512);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < TL::KT / 16; ++ks)
 #pragma unroll
                 for (int x = 0; x < TL::WTM; ++x)
 #pragma unroll
                     for (int y = 0; y < TL::WTN; ++y)
-                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b[y], acc[x][y], 0, 0, 0);
-            }
+                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][x], b[ks][y], acc[x][y], 0, 0, 0);
             slot = slot + 1 == TL::STAGES ? 0 : slot + 1;
         }
         wait_vm<0>(); // the repeated transfers of the last steps must not outlive this use of the LDS
