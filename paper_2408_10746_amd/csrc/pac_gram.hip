@@ -106,7 +106,7 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.g_HSpart = take((int64_t)W.max_tiles * Lr * 4);
     W.g_cspart = take((int64_t)W.max_tiles * Lr * 4);
     W.g_zpart = take((int64_t)W.max_tiles * D.C * 4);
-    W.g_zpb = take((int64_t)D.B_max * D.C * 4);
+    W.g_zpb = take((int64_t)D.B_max * cdiv(D.d, 256) * D.C * 4);
     W.g_Z = take(Lr * D.C * 4);
     W.g_dzsum = take(kMaxClasses * 4);
     W.g_cs = take(Lr * 4);
@@ -315,6 +315,8 @@ struct ProjArgs {
     bf16_t *QpN, *QpT; // [pairs][r][r]
     const int32_t *samp_start, *samp_len;
     float *pb; // [B][d]
+    int C;
+    float *zpbp; // [B][ceil(d/256)][C]: ((mean b_L + sum of all c_up) W_cls) summed over this block's 256 columns
 };
 
 struct EpiStoreF32 {
@@ -451,12 +453,29 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
 #pragma unroll
         for (int e = 0; e < 8; ++e) red[tg * 256 + (t & 31) * 8 + e] = acc[e];
         __syncthreads();
-        if (j0 + t < a.d) {
+        float pv = 0.f; // mean b_L + sum of all c_up, this thread's column
+        const bool act = j0 + t < a.d;
+        if (act) {
             float tot = 0.f;
 #pragma unroll
             for (int q = 0; q < 8; ++q) tot += red[q * 256 + t];
-            a.pb[(int64_t)s * a.d + j0 + t] = tot / (float)len;
+            tot /= (float)len;
+            a.pb[(int64_t)s * a.d + j0 + t] = tot;
+            pv = tot + a.cusum[(int64_t)a.L * a.d + j0 + t];
         }
+        // this block's share of the sample's logits: wavefront sums, then the four wavefronts in order
+        const float *Wc = a.params + (int64_t)a.L * a.PL;
+        __syncthreads(); // red is reused
+        for (int c = 0; c < a.C; ++c) {
+            float v = act ? pv * Wc[(int64_t)(j0 + t) * a.C + c] : 0.f;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+            if ((t & 63) == 0) red[(t >> 6) * kMaxClasses + c] = v;
+        }
+        __syncthreads();
+        if (t < a.C)
+            a.zpbp[((int64_t)s * jt + (idx % jt)) * a.C + t] =
+                (red[t] + red[kMaxClasses + t]) + (red[2 * kMaxClasses + t] + red[3 * kMaxClasses + t]);
     }
 }
 
@@ -480,10 +499,9 @@ struct ChainArgs {
     // (or k_glogits when no gradients are wanted) turns them into the loss and dz
     int B, C;
     const float *V;      // [L*r][C]
-    const float *pb;     // [B][d] token means of the last cached layer
-    const float *cusumL; // [d] sum of all c_up
     float *zpart;        // [tiles][C]  sum_kk (column sums of h over the tile)[kk] V[kk][c]
-    float *zpb;          // [B][C]      (pb + cusumL) W_cls, written by the first tile of each sample
+    const float *zpbp;   // [B][nzb][C] shares of (mean b_L + sum of all c_up) W_cls, from the projection launch
+    int nzb;
     const int32_t *samp_tile0, *samp_len, *labels;
     float *logits_ws, *logits_out, *dz, *loss_part;
 };
@@ -499,7 +517,9 @@ __device__ __forceinline__ void sample_head(const ChainArgs &a, int s, bool writ
 #pragma unroll 8
         for (int k = tl0; k < tl1; ++k) z += a.zpart[(int64_t)k * C + t];
         const float *c_cls = a.params + (int64_t)a.L * a.PL + (int64_t)a.d * C;
-        zs[t] = z / (float)a.samp_len[s] + a.zpb[s * C + t] + c_cls[t];
+        float zb = 0.f;
+        for (int q = 0; q < a.nzb; ++q) zb += a.zpbp[((int64_t)s * a.nzb + q) * C + t];
+        zs[t] = z / (float)a.samp_len[s] + zb + c_cls[t];
     }
     __syncthreads();
     if (t == 0) {
@@ -642,27 +662,70 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
         for (int slot = 0; slot < kDepth; ++slot) issue(fifo[slot]);
     }
 
-    // per-layer vectors
+    // per-layer vectors.  Forward: the first step's here, the later ones by the helper wavefront, one
+    // step ahead.  Backward: all of them here (leaving them to the helper was measured slower).
     if (!FWD) sample_head(a, samp, tile == a.samp_tile0[samp], zs, dzs);
     const float inv_len = 1.f / (float)a.samp_len[samp];
-    for (int c = threadIdx.x; c < L * r; c += nthreads) {
-        const int l = c / r, nn = c % r;
-        if (FWD) {
-            const float *pl = a.params + (int64_t)l * a.PL;
-            vecS[c] = (1.f - pl[a.PL - 1]) * a.chat[c] + pl[(int64_t)a.d * r + nn];
-        } else {
+    for (int l = threadIdx.x; l < L; l += nthreads) lamS[l] = a.params[(int64_t)l * a.PL + a.PL - 1];
+    if (FWD) {
+        for (int nn = threadIdx.x; nn < r; nn += nthreads) {
+            const float *pl = a.params;
+            vecS[nn] = (1.f - pl[a.PL - 1]) * a.chat[nn] + pl[(int64_t)a.d * r + nn];
+        }
+    } else {
+        for (int c = threadIdx.x; c < L * r; c += nthreads) {
             // ghat = dz V^T / len: what the head hands to every token of the sample
             float v = 0.f;
             for (int q = 0; q < a.C; ++q) v += dzs[q] * a.V[(int64_t)c * a.C + q];
             vecS[c] = v * inv_len;
         }
     }
-    for (int l = threadIdx.x; l < L; l += nthreads) lamS[l] = a.params[(int64_t)l * a.PL + a.PL - 1];
 
     if (wave == NW) {
         // ---- helper wavefront: all global traffic of the per-token tiles.  It keeps the input ring
         // filled three layers ahead and (forward) writes out the GELU' tile of the layer just finished,
         // so the contracting wavefronts issue no global store and wait on no per-token load.
+        // Forward, the helper also prepares, one step ahead, what does not depend on the chain: the next
+        // step's per-layer vector (vecS), and it folds the finished layers' column sums into this tile's
+        // share of the logits.  Every value it uses was requested one step earlier, before that step's
+        // tile request, so waiting for it never waits for a tile.
+        constexpr int NP = (r + 63) / 64; // passes of the 64 lanes over the r columns
+        float vpre[NP][kMaxClasses];      // V rows of the layer finished last
+        float cpre[NP][2];                // chat and c_down of the next step's layer
+        float zacc[kMaxClasses];
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c) zacc[c] = 0.f;
+        const int C = a.C;
+        auto side_load = [&](int s) { // requests for what side_use(s + 1) needs
+            if (!FWD) return;
+            const int lv = min(max(s, 0), L - 1); // V rows of the layer of step s
+            const int lc = min(s + 2, L - 1);     // chat, c_down of the layer of step s+2
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const int nn = min(lane + 64 * p, r - 1);
+#pragma unroll
+                for (int c = 0; c < kMaxClasses; ++c)
+                    if (c < C) vpre[p][c] = a.V[((int64_t)lv * r + nn) * C + c];
+                cpre[p][0] = a.chat[lc * r + nn];
+                cpre[p][1] = a.params[(int64_t)lc * a.PL + (int64_t)a.d * r + nn];
+            }
+        };
+        auto side_use = [&](int s) { // during step s
+            if (!FWD) return;
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const int nn = lane + 64 * p;
+                if (nn >= r) continue;
+                if (s + 1 < L) vecS[(s + 1) * r + nn] = (1.f - lamS[s + 1]) * cpre[p][0] + cpre[p][1];
+                if (s >= 1) { // layer s-1 is finished: its column sums are final
+                    const float hs = Cs[(s - 1) * r + nn];
+#pragma unroll
+                    for (int c = 0; c < kMaxClasses; ++c)
+                        if (c < C) zacc[c] += hs * vpre[p][c];
+                }
+            }
+        };
+        side_load(-1);
         put(0, ra);
         __syncthreads();
         // before the barrier that ends step s the tile of step s+1 must be in the ring
@@ -670,23 +733,40 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
             // the tile consumed here was requested two steps ago; the new request goes out after it
             // so that waiting for the old one never means waiting for the new one
             put(s + 1, rb);
+            side_use(s);
             drain(s - 1);
+            side_load(s);
             fetch(s + 3, ra);
             __syncthreads();
             if (s + 1 < L) {
                 put(s + 2, rc);
+                side_use(s + 1);
                 drain(s);
+                side_load(s + 1);
                 fetch(s + 4, rb);
                 __syncthreads();
             }
             if (s + 2 < L) {
                 put(s + 3, ra);
+                side_use(s + 2);
                 drain(s + 1);
+                side_load(s + 2);
                 fetch(s + 5, rc);
                 __syncthreads();
             }
         }
         drain(L - 1);
+        if (FWD) {
+            side_use(L); // the last layer's column sums
+#pragma unroll
+            for (int c = 0; c < kMaxClasses; ++c)
+                if (c < C) {
+                    float v = zacc[c];
+#pragma unroll
+                    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+                    if (lane == 0) a.zpart[(int64_t)tile * C + c] = v;
+                }
+        }
     } else {
         // ---- contracting wavefronts ----
         // two accumulators so that consecutive matrix instructions do not depend on each other
@@ -753,56 +833,6 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
         }
     }
     __syncthreads(); // every layer's tile and column sums are in LDS
-    if (FWD) {
-        // (before the stores below: a load issued after them would also wait for them)
-        // this tile's share of the logits; the first tile of a sample adds the part that comes
-        // from the cached last layer and the biases
-        const int C = a.C;
-        const bool first = tile == a.samp_tile0[samp];
-        float za[kMaxClasses], zb[kMaxClasses];
-#pragma unroll
-        for (int c = 0; c < kMaxClasses; ++c) za[c] = zb[c] = 0.f;
-        for (int kk = threadIdx.x; kk < L * r; kk += nthreads) {
-            const float hs = Cs[kk];
-#pragma unroll
-            for (int c = 0; c < kMaxClasses; ++c)
-                if (c < C) za[c] += hs * a.V[(int64_t)kk * C + c];
-        }
-        if (first) {
-            const float *Wc = a.params + (int64_t)L * a.PL;
-            for (int j = threadIdx.x; j < a.d; j += nthreads) {
-                const float pv = a.pb[(int64_t)samp * a.d + j] + a.cusumL[j];
-#pragma unroll
-                for (int c = 0; c < kMaxClasses; ++c)
-                    if (c < C) zb[c] += pv * Wc[(int64_t)j * C + c];
-            }
-        }
-        float *red = reinterpret_cast<float *>(ring); // [NW + 1][2][kMaxClasses]; the ring is idle by now
-#pragma unroll
-        for (int c = 0; c < kMaxClasses; ++c)
-            if (c < C) {
-                float va = za[c], vb = zb[c];
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) {
-                    va += __shfl_down(va, o, 64);
-                    vb += __shfl_down(vb, o, 64);
-                }
-                if (lane == 0) {
-                    red[(wave * 2 + 0) * kMaxClasses + c] = va;
-                    red[(wave * 2 + 1) * kMaxClasses + c] = vb;
-                }
-            }
-        __syncthreads();
-        if ((int)threadIdx.x < C) {
-            float s0 = 0.f, s1 = 0.f;
-            for (int w = 0; w <= NW; ++w) {
-                s0 += red[(w * 2 + 0) * kMaxClasses + threadIdx.x];
-                s1 += red[(w * 2 + 1) * kMaxClasses + threadIdx.x];
-            }
-            a.zpart[(int64_t)tile * C + threadIdx.x] = s0;
-            if (first) a.zpb[samp * C + threadIdx.x] = s1;
-        }
-    }
     // flush: 16-byte chunks of the valid rows, then the column sums
     constexpr int chunks_per_row = r / 8;
     for (int c = threadIdx.x; c < L * T * chunks_per_row; c += nthreads) {
@@ -1411,7 +1441,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.nb_C = L * cdiv(r, 64);
         a.cusum = cusum; a.chat = chat; a.params = io.params; a.PL = D.PL;
         a.WdT = WdT; a.Wu = Wu; a.U = pre; a.QpN = QpN; a.QpT = QpT;
-        a.samp_start = samp_start; a.samp_len = samp_len; a.pb = pb;
+        a.samp_start = samp_start; a.samp_len = samp_len; a.pb = pb; a.C = C; a.zpbp = zpb;
         const int counts[4] = {a.nb_U, a.nb_Q, a.nb_C, B * cdiv(d, 256)};
         const int classes[4] = {KC_G_PROJ_U, KC_G_PROJ_Q, KC_G_PROJ_Q, KC_G_PROJ_PB};
         if (d % 64 == 0) {
@@ -1452,7 +1482,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     ChainArgs ca;
     ca.L = L; ca.r = r; ca.M = M; ca.tile_row0 = tile_row0; ca.tile_rows = tile_rows; ca.tile_samp = tile_samp;
     ca.params = io.params; ca.PL = D.PL; ca.d = d; ca.U = pre; ca.Gp = (bf16_t *)(ws + W.g_Gp); ca.chat = chat;
-    ca.B = B; ca.C = C; ca.V = V; ca.pb = pb; ca.cusumL = cusum + (int64_t)L * d; ca.zpart = zpart; ca.zpb = zpb;
+    ca.B = B; ca.C = C; ca.V = V; ca.zpart = zpart; ca.zpbp = zpb; ca.nzb = cdiv(d, 256);
     ca.samp_tile0 = samp_tile0; ca.samp_len = samp_len; ca.labels = io.labels;
     ca.logits_ws = logits; ca.logits_out = io.logits_out; ca.dz = dz; ca.loss_part = loss_part;
     {
