@@ -680,56 +680,86 @@ __global__ __launch_bounds__(256) void k_reduce_layer(const float *__restrict__ 
 // ---------------------------------------------------------------------------
 // AdamW over the flat parameter vector
 // ---------------------------------------------------------------------------
-// When the loss / gate-gradient sums were left to this launch (fin.used), the thread that owns a
-// gate sums that layer's partials in slot order, and the first thread sums the samples' loss terms.
+// One element of the update.  When the loss / gate-gradient sums were left to this launch (fin.used),
+// the thread that owns a gate first sums that layer's partials in slot order.
+__device__ __forceinline__ void adamw_elem(int64_t i, float &pi, float &mi, float &vi, float &gi, int64_t PL,
+                                           int64_t dr, int r, int64_t head, int64_t dC, const AdamArgs &a,
+                                           const Deferred &fin)
+{
+    bool decayed;
+    if (i < head) {
+        const int64_t o = i % PL;
+        decayed = (o < dr) || (o >= dr + r && o < 2 * dr + r);
+        if (fin.used && o == PL - 1) {
+            const float *part = fin.dlam_part + (i / PL) * fin.slots;
+            float acc = 0.f;
+            for (int s = 0; s < fin.slots; ++s) acc += part[s];
+            gi = acc;
+        }
+    } else {
+        decayed = (i - head) < dC;
+    }
+    mi = a.beta1 * mi + (1.f - a.beta1) * gi;
+    vi = a.beta2 * vi + (1.f - a.beta2) * gi * gi;
+    if (decayed) pi -= a.lr * a.wd * pi;
+    pi -= a.lr * (mi / a.bc1) / (sqrtf(vi / a.bc2) + a.eps);
+}
+
+// VEC = 4: 16-byte accesses (all four arrays 16-byte aligned), the tail element by element
+template <int VEC>
 __global__ __launch_bounds__(256) void k_adamw(float *__restrict__ p, float *__restrict__ m, float *__restrict__ v,
                                                float *__restrict__ g, int64_t P, int64_t PL, int L, int d,
                                                int r, int C, AdamArgs a, Deferred fin)
 {
     const int64_t dr = (int64_t)d * r;
-    const int64_t head = (int64_t)L * PL;
+    const int64_t head = (int64_t)L * PL, dC = (int64_t)d * C;
     if (fin.used && blockIdx.x == 0 && threadIdx.x == 0) {
         float tot = 0.f;
         for (int s = 0; s < fin.B; ++s) tot += fin.loss_part[s];
         *fin.loss_out = tot / (float)fin.B;
     }
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < P; i += (int64_t)gridDim.x * 256) {
-        bool decayed;
-        float gi;
-        if (i < head) {
-            const int64_t o = i % PL;
-            decayed = (o < dr) || (o >= dr + r && o < 2 * dr + r);
-            if (fin.used && o == PL - 1) {
-                const float *part = fin.dlam_part + (i / PL) * fin.slots;
-                float acc = 0.f;
-                for (int s = 0; s < fin.slots; ++s) acc += part[s];
-                gi = acc;
-                g[i] = acc;
-            } else {
-                gi = g[i];
+    const int64_t ngroups = (P + VEC - 1) / VEC;
+    for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < ngroups; q += (int64_t)gridDim.x * 256) {
+        const int64_t i0 = q * VEC;
+        if (VEC == 4 && i0 + 3 < P) {
+            f32x4 pv = *reinterpret_cast<const f32x4 *>(p + i0), mv = *reinterpret_cast<const f32x4 *>(m + i0);
+            f32x4 vv = *reinterpret_cast<const f32x4 *>(v + i0), gv = *reinterpret_cast<const f32x4 *>(g + i0);
+            const f32x4 g_in = gv;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float pi = pv[e], mi = mv[e], vi = vv[e], gi = gv[e];
+                adamw_elem(i0 + e, pi, mi, vi, gi, PL, dr, r, head, dC, a, fin);
+                pv[e] = pi; mv[e] = mi; vv[e] = vi; gv[e] = gi;
             }
+            *reinterpret_cast<f32x4 *>(p + i0) = pv;
+            *reinterpret_cast<f32x4 *>(m + i0) = mv;
+            *reinterpret_cast<f32x4 *>(v + i0) = vv;
+            if (fin.used && (gv[0] != g_in[0] || gv[1] != g_in[1] || gv[2] != g_in[2] || gv[3] != g_in[3]))
+                *reinterpret_cast<f32x4 *>(g + i0) = gv; // a gate gradient was summed here: keep it
         } else {
-            decayed = (i - head) < (int64_t)d * C;
-            gi = g[i];
+            for (int64_t i = i0; i < P && i < i0 + VEC; ++i) {
+                float pi = p[i], mi = m[i], vi = v[i], gi = g[i];
+                const float g_in = gi;
+                adamw_elem(i, pi, mi, vi, gi, PL, dr, r, head, dC, a, fin);
+                p[i] = pi; m[i] = mi; v[i] = vi;
+                if (gi != g_in) g[i] = gi;
+            }
         }
-        const float mi = a.beta1 * m[i] + (1.f - a.beta1) * gi;
-        const float vi = a.beta2 * v[i] + (1.f - a.beta2) * gi * gi;
-        m[i] = mi;
-        v[i] = vi;
-        float pi = p[i];
-        if (decayed) pi -= a.lr * a.wd * pi;
-        pi -= a.lr * (mi / a.bc1) / (sqrtf(vi / a.bc2) + a.eps);
-        p[i] = pi;
     }
 }
 
 hipError_t launch_adamw(const Dims &D, float *p, float *m, float *v, float *g, const AdamArgs &a, hipStream_t st,
                         Profiler *prof, const Deferred *fin)
 {
-    int blocks = cdiv(D.P, 256);
-    if (blocks > 4096) blocks = 4096;
     const Deferred f = fin ? *fin : Deferred();
-    PAC_LAUNCH(prof, st, KC_ADAMW, k_adamw, dim3(blocks), dim3(256), 0, st, p, m, v, g, D.P, D.PL, D.L, D.d, D.r, D.C, a, f);
+    const bool vec = ((reinterpret_cast<uintptr_t>(p) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(v) |
+                       reinterpret_cast<uintptr_t>(g)) & 15) == 0;
+    int blocks = cdiv(cdiv(D.P, vec ? 4 : 1), 256);
+    if (blocks > 4096) blocks = 4096;
+    if (vec)
+        PAC_LAUNCH(prof, st, KC_ADAMW, k_adamw<4>, dim3(blocks), dim3(256), 0, st, p, m, v, g, D.P, D.PL, D.L, D.d, D.r, D.C, a, f);
+    else
+        PAC_LAUNCH(prof, st, KC_ADAMW, k_adamw<1>, dim3(blocks), dim3(256), 0, st, p, m, v, g, D.P, D.PL, D.L, D.d, D.r, D.C, a, f);
     return hipGetLastError();
 }
 
