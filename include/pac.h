@@ -91,6 +91,10 @@ typedef struct {
 /* Measurement aid: launch every part of the fused multi-part launches on its own, so that
  * pac_profile_end reports one class per part (slower; results unchanged). */
 #define PAC_FLAG_SPLIT_LAUNCH 2
+/* On the Gram-matrix path, run the two chains over the layers as one contraction launch per layer
+ * (the form used where a 16-token tile's history of all layers does not fit a compute unit's LDS,
+ * e.g. r > 128) even where the single-launch chains apply (same results up to rounding). */
+#define PAC_FLAG_LAYER_CHAIN 4
 
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay;

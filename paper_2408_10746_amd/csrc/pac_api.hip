@@ -61,7 +61,7 @@ pac_status pac_create(const pac_config *cfg, pac_ctx **out)
     if (cfg->L < 1 || cfg->d < 1 || cfg->n_max < 1 || cfg->r < 1 || cfg->C < 1 || cfg->B_max < 1 || cfg->N < 1)
         return PAC_ERR_SHAPE;
     if (cfg->cache_dtype != PAC_BF16 && cfg->cache_dtype != PAC_F32) return PAC_ERR_SHAPE;
-    if (cfg->flags & ~(PAC_FLAG_PER_LAYER | PAC_FLAG_SPLIT_LAUNCH)) return PAC_ERR_SHAPE;
+    if (cfg->flags & ~(PAC_FLAG_PER_LAYER | PAC_FLAG_SPLIT_LAUNCH | PAC_FLAG_LAYER_CHAIN)) return PAC_ERR_SHAPE;
     if (cfg->d % 32 || cfg->r % 32) return PAC_ERR_UNSUPPORTED;
     if (cfg->C > kMaxClasses || cfg->B_max > kMaxBatch) return PAC_ERR_UNSUPPORTED;
     if ((int64_t)cfg->B_max * cfg->n_max > (int64_t)1 << 24) return PAC_ERR_UNSUPPORTED;

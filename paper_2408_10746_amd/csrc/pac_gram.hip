@@ -45,6 +45,7 @@ constexpr int kMaxD = 4096;
 constexpr int kETileCols = 128; // columns of d one workgroup of the E contraction covers
 constexpr int kMaxSplitTiles = 512; // 16-token tiles one workgroup of the E contraction walks over at most
 constexpr int kMaxTiles = 8192;     // 16-token tiles of a batch (LDS table of the column-sum reduction)
+constexpr int kSeqTile = 128;       // side of the workgroup tile of a per-layer chain contraction
 
 // Slots of the chain kernels' LDS ring of per-token inputs.  Two suffice: the helper wavefront keeps the
 // tiles of the next three steps in registers and writes the tile of step s+1 while the contracting
@@ -65,22 +66,28 @@ static size_t chain_lds(int L, int r, bool fwd)
     return hs + ring + gstage + (size_t)L * r * 4 * 2 + (size_t)((L + 3) / 4 * 4) * 4 + 2 * kMaxClasses * 4;
 }
 
-bool gram_path_fits(const Dims &D)
+// Side of the square workgroup tiles of the contractions outside the chains: 64 up to r = 128, 128 above
+static int big_shapes(int r) { return r > 128; }
+
+int gram_path_kind(const Dims &D)
 {
-    if (D.cache_dtype != 0 || (D.flags & 1)) return false; // PAC_FLAG_PER_LAYER
-    if (D.r > 128 || D.d > kMaxD || D.L > 128) return false;
-    if ((int64_t)D.B_max * cdiv(D.n_max, kChainRows) > kMaxTiles) return false;
-    return chain_lds(D.L, D.r, true) <= 160 * 1024;
+    if (D.cache_dtype != 0 || (D.flags & 1)) return 0; // PAC_FLAG_PER_LAYER
+    if (D.r > 256 || D.d > kMaxD || D.L > 128) return 0;
+    if ((int64_t)D.B_max * cdiv(D.n_max, kChainRows) > kMaxTiles) return 0;
+    const bool lds_chain = D.r <= 128 && chain_lds(D.L, D.r, true) <= 160 * 1024;
+    if (lds_chain && !(D.flags & 4)) return 1; // PAC_FLAG_LAYER_CHAIN
+    // one chain launch per layer; the vector part of the gradient launch deals 64 threads over the layers
+    return D.L <= (big_shapes(D.r) ? 64 : 128) ? 2 : 0;
 }
 
 void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
 {
     auto take = [&](int64_t bytes) { int64_t at = o; o = align256(o + bytes); return at; };
     const int64_t Lr = (int64_t)D.L * D.r;
-    W.use_gram = 1;
+    W.use_gram = gram_path_kind(D);
     W.max_tiles = D.B_max * cdiv(D.n_max, kChainRows);
     W.pairs = D.L * (D.L - 1) / 2;
-    const int e_tiles = D.L * cdiv(D.d, kETileCols);
+    const int e_tiles = D.L * cdiv(D.d, kETileCols) * cdiv(D.r, 128);
     int se = cdiv(288, e_tiles);
     const int max_by_rows = (int)((D.Mmax + 127) / 128);
     if (se > max_by_rows) se = max_by_rows;
@@ -99,8 +106,17 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.g_cusum = take((int64_t)(D.L + 1) * D.d * 4);
     W.g_chat = take(Lr * 4);
     W.g_V = take(Lr * D.C * 4);
-    W.g_QpN = take((int64_t)(W.pairs + 1) * D.r * D.r * 2);
-    W.g_QpT = take((int64_t)(W.pairs + 1) * D.r * D.r * 2);
+    const int64_t q_bytes = W.use_gram == 2 ? Lr * Lr * 2 : (int64_t)(W.pairs + 1) * D.r * D.r * 2;
+    W.g_QpN = take(q_bytes);
+    W.g_QpT = take(q_bytes);
+    W.sq = 1;
+    W.g_P = 0;
+    if (W.use_gram == 2) {
+        // about two workgroups per compute unit at the largest batch
+        const int tiles = cdiv(D.Mmax, kSeqTile) * cdiv(D.r, kSeqTile);
+        W.sq = cdiv(512, tiles) > 16 ? 16 : cdiv(512, tiles);
+        W.g_P = take((int64_t)W.sq * D.Mmax * D.r * 4);
+    }
     W.g_DP = take(D.Mmax * Lr * 2);
     W.g_Gp = take(D.Mmax * Lr * 2);
     W.g_HSpart = take((int64_t)W.max_tiles * Lr * 4);
@@ -312,7 +328,8 @@ struct ProjArgs {
     const float *params;
     int64_t PL;
     float *U;          // [L][M][r]
-    bf16_t *QpN, *QpT; // [pairs][r][r]
+    bf16_t *QpN, *QpT; // [pairs][r][r] in fragment-major order, or (q_full) [L*r][L*r] each: see EpiQ
+    int q_full;
     const int32_t *samp_start, *samp_len;
     float *pb; // [B][d]
     int C;
@@ -336,13 +353,46 @@ __device__ __forceinline__ int64_t frag_index(int n, int kk, int r)
 }
 
 struct EpiQ {
+    static constexpr bool kBatched = true;
     bf16_t *qn, *qt;
     int r;
     float one_minus_lam; // of the later layer of the pair: the backward chain uses (1-lambda_l) Q_{kl}
-    __device__ void operator()(int row, int col, float v) const
+    // full = false: qn, qt are this pair's r x r blocks in fragment-major order.
+    // full = true:  qn, qt are [L*r][L*r] matrices whose row (layer, n) holds, K-contiguous over (layer', j),
+    //   what the per-layer chain contractions read as their second operand:
+    //   qt[(l, col)][(k, row)] = Q_{kl}[row][col]  and  qn[(k, row)][(l, col)] = (1-lambda_l) Q_{kl}[row][col].
+    bool full;
+    int k, l;
+    int64_t Lr;
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
     {
-        qn[frag_index(row, col, r)] = static_cast<bf16_t>(one_minus_lam * v); // backward: B[n=row][kk=col]
-        qt[frag_index(col, row, r)] = static_cast<bf16_t>(v);                 // forward:  B[n=col][kk=row]
+        if (col >= ncols) return;
+        if (!full) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = epi_row(row_base, v);
+                if (row < nrows) {
+                    qn[frag_index(row, col, r)] = static_cast<bf16_t>(one_minus_lam * acc[v]); // backward: B[n=row][kk=col]
+                    qt[frag_index(col, row, r)] = static_cast<bf16_t>(acc[v]);                 // forward:  B[n=col][kk=row]
+                }
+            }
+            return;
+        }
+        bf16_t *qt_row = qt + ((int64_t)l * r + col) * Lr + (int64_t)k * r;
+        bf16_t *qn_col = qn + (int64_t)k * r * Lr + (int64_t)l * r + col;
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+            const int row = row_base + 8 * vg; // four consecutive rows; nrows is a multiple of 4
+            if (row < nrows) {
+                bf16x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    pk[e] = static_cast<bf16_t>(acc[4 * vg + e]);
+                    qn_col[(int64_t)(row + e) * Lr] = static_cast<bf16_t>(one_minus_lam * acc[4 * vg + e]);
+                }
+                *reinterpret_cast<bf16x4 *>(qt_row + row) = pk;
+            }
+        }
     }
 };
 
@@ -360,8 +410,10 @@ using T64K = Tile<2, 2, 1, 1, 4>; // 128-token K step for the token contractions
 // Stage counts are kept small on purpose: more workgroups per compute unit hide the memory latency
 // better than deeper rings in fewer workgroups (measured both ways).
 template <int NT, int BK> struct ProjShapes {
-    using TU = NtTile<4, 1, 1, NT, BK, 2>;  // 128 token rows x r
-    using TQ = NtTile<2, 2, 1, 1, BK, 3>;   // 64 x 64
+    static constexpr bool BIG = NT > 4;
+    using T128 = NtTile<2, 2, 2, 2, BK, 2>;
+    using TU = typename std::conditional<BIG, T128, NtTile<4, 1, 1, (BIG ? 1 : NT), BK, 2>>::type; // 128 token rows x r (or 128)
+    using TQ = typename std::conditional<BIG, T128, NtTile<2, 2, 1, 1, BK, 3>>::type;              // 64 x 64 (or 128 x 128)
     using TC = Tile<2, 2, 1, 1, BK / 32>;   // the one-row chat contraction (staged through registers)
     static constexpr int kA = TU::LDS_BYTES > TQ::LDS_BYTES ? TU::LDS_BYTES : TQ::LDS_BYTES;
     static constexpr int kB = tile_lds_bytes<bf16_t, TC>() > 8 * 256 * 4 ? tile_lds_bytes<bf16_t, TC>() : 8 * 256 * 4;
@@ -379,7 +431,9 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
     // latency-bound parts start at once and run alongside it
     const int b = (int)(gridDim.x - 1 - blockIdx.x) + a.blk_off;
     if (b < a.nb_U) {
-        const int l = b / a.row_tiles, mt = b % a.row_tiles;
+        // (layer, row tile, column tile), the column tiles of a row tile next to each other
+        const int uct = (a.r + TU::BN - 1) / TU::BN;
+        const int ct = b % uct, mt = (b / uct) % a.row_tiles, l = b / (uct * a.row_tiles);
         const bf16_t *cache = a.cache;
         const RowMap map = a.map;
         const bf16_t *W = a.WdT + (int64_t)l * a.r * a.d;
@@ -387,10 +441,10 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
         auto arow = [&](int m) { return cache + map.rowoff[m] + (int64_t)l * map.rowstride[m]; };
         auto brow = [&](int c) { return W + (int64_t)c * d; };
         EpiStoreF32 epi{a.U + (int64_t)l * a.map.M * a.r, a.r};
-        gemm_nt<TU>(smem, arow, brow, epi, 0, a.d, mt * TU::BM, 0, a.map.M, a.r);
+        gemm_nt<TU>(smem, arow, brow, epi, 0, a.d, mt * TU::BM, ct * TU::BN, a.map.M, a.r);
         return;
     }
-    const int tq = (a.r + 63) / 64;
+    const int tq = (a.r + TQ::BM - 1) / TQ::BM, tc64 = (a.r + 63) / 64;
     if (b < a.nb_U + a.nb_Q) {
         int idx = b - a.nb_U;
         const int p = idx / (tq * tq);
@@ -403,15 +457,16 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
         const int d = a.d;
         auto arow = [&](int row) { return Wu + (int64_t)row * d; };
         auto brow = [&](int c) { return Wd + (int64_t)c * d; };
-        EpiQ epi{a.QpN + (int64_t)p * a.r * a.r, a.QpT + (int64_t)p * a.r * a.r, a.r,
-                 1.f - a.params[(int64_t)l * a.PL + a.PL - 1]};
-        gemm_nt<TQ>(smem, arow, brow, epi, 0, a.d, (idx / tq) * 64, (idx % tq) * 64, a.r, a.r);
+        const int64_t qoff = a.q_full ? 0 : (int64_t)p * a.r * a.r;
+        EpiQ epi{a.QpN + qoff, a.QpT + qoff, a.r, 1.f - a.params[(int64_t)l * a.PL + a.PL - 1],
+                 a.q_full != 0, k, l, (int64_t)a.L * a.r};
+        gemm_nt<TQ>(smem, arow, brow, epi, 0, a.d, (idx / tq) * TQ::BM, (idx % tq) * TQ::BN, a.r, a.r);
         return;
     }
     if (b < a.nb_U + a.nb_Q + a.nb_C) {
         // chat_l = cusum_l W_down^l: a one-row contraction on the same tile code
         const int idx = b - a.nb_U - a.nb_Q;
-        const int l = idx / tq, nt = idx % tq;
+        const int l = idx / tc64, nt = idx % tc64;
         LoadRowsF32<bf16_t, 64, KU> al;
         al.src = a.cusum + (int64_t)l * a.d; al.ld = a.d; al.nrows = 1;
         LoadRowsTC<bf16_t, 64, KU> bl;
@@ -847,6 +902,132 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
 }
 
 // ---------------------------------------------------------------------------
+// The chains as one contraction per layer (adapter widths whose 16-token history of all layers does
+// not fit the LDS).  Layer l of the forward chain needs sum_{k<l} h_k Q_{kl}: with H [M][L*r] and the
+// matrix QT [(l,n)][(k,j)] = Q_{kl}[j][n] that is the product of the first l*r columns of H with rows
+// (l, .) of QT, both K-contiguous; the backward chain takes columns (l+1)*r.. of DP and rows (l, .) of
+// QN [(l,n)][(k,j)] = (1-lambda_k) Q_{lk}[n][j].  The contraction range is split over several
+// workgroups per tile (the early and late layers' ranges are short, the batch has few row tiles);
+// a second small launch sums the partials in split order and applies the layer's nonlinearity.
+// ---------------------------------------------------------------------------
+struct SeqMmArgs {
+    const bf16_t *A;  // H or DP [M][L*r]
+    const bf16_t *Bq; // QT or QN [L*r][L*r]
+    float *P;         // [splits][M][r]
+    int l, L, r, M;
+    int kbegin, kend, ksplit; // columns of A contracted; ksplit (a multiple of BK) per split
+    int ctiles;
+};
+
+template <int BK> struct SeqShapes {
+    using TL = NtTile<2, 2, 2, 2, BK, 2>; // kSeqTile x kSeqTile
+    static_assert(TL::BM == kSeqTile && TL::BN == kSeqTile, "tile side of the per-layer chain contraction");
+};
+
+template <int BK> __global__ __launch_bounds__(256) void k_gseq_mm(SeqMmArgs a)
+{
+    using TL = typename SeqShapes<BK>::TL;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int ct = blockIdx.x % a.ctiles, rt = blockIdx.x / a.ctiles, sp = blockIdx.y;
+    const int kb = a.kbegin + sp * a.ksplit, ke = min(a.kend, kb + a.ksplit);
+    const int64_t Lr = (int64_t)a.L * a.r;
+    const bf16_t *A = a.A, *Bq = a.Bq + (int64_t)a.l * a.r * Lr;
+    auto arow = [&](int m) { return A + (int64_t)m * Lr; };
+    auto brow = [&](int n) { return Bq + (int64_t)n * Lr; };
+    EpiStoreF32 epi{a.P + (int64_t)sp * a.M * a.r, a.r};
+    gemm_nt<TL>(smem, arow, brow, epi, kb, max(kb, ke), rt * kSeqTile, ct * kSeqTile, a.M, a.r);
+}
+
+struct SeqFinArgs {
+    int l, L, r, M, S, C, d;
+    const float *P;      // [S][M][r]
+    const float *U;      // forward: [L][M][r]
+    bf16_t *Gp;          // [L][M][r]: written forward, read backward
+    const float *chat;   // [L][r]
+    const float *params;
+    int64_t PL;
+    bf16_t *Hg;          // forward: H, backward: DP   [M][L*r]
+    float *part;         // forward: HSpart, backward: cspart   [tiles][L*r]
+    const int32_t *tile_row0, *tile_rows, *tile_samp, *samp_len;
+    const float *dz, *V; // backward: [B][C], [L*r][C]
+};
+
+// one 16-token tile per workgroup, one column per thread
+template <bool FWD> __global__ __launch_bounds__(256) void k_gseq_fin(SeqFinArgs a)
+{
+    const int tile = blockIdx.x, n = threadIdx.x;
+    if (n >= a.r) return;
+    const int m0 = a.tile_row0[tile], nrows = a.tile_rows[tile];
+    const int l = a.l, r = a.r;
+    const int64_t Lr = (int64_t)a.L * r, Mr = (int64_t)a.M * r;
+    const float lam = a.params[(int64_t)l * a.PL + a.PL - 1];
+    float cvec;
+    if (FWD) {
+        cvec = (1.f - lam) * a.chat[l * r + n] + a.params[(int64_t)l * a.PL + (int64_t)a.d * r + n];
+    } else {
+        // ghat = dz V^T / len: what the head hands to every token of the sample
+        const int samp = a.tile_samp[tile];
+        float v = 0.f;
+        for (int c = 0; c < a.C; ++c) v += a.dz[samp * a.C + c] * a.V[((int64_t)l * r + n) * a.C + c];
+        cvec = v / (float)a.samp_len[samp];
+    }
+    constexpr int T = kChainRows;
+    float x[T], acc[T];
+#pragma unroll
+    for (int row = 0; row < T; ++row) {
+        const int64_t o = ((int64_t)l * a.M + m0 + min(row, nrows - 1)) * r + n;
+        x[row] = FWD ? a.U[o] : to_f32(a.Gp[o]);
+        acc[row] = 0.f;
+    }
+    for (int sp = 0; sp < a.S; ++sp) {
+        float p[T];
+#pragma unroll
+        for (int row = 0; row < T; ++row) p[row] = a.P[(int64_t)sp * Mr + (int64_t)(m0 + min(row, nrows - 1)) * r + n];
+#pragma unroll
+        for (int row = 0; row < T; ++row) acc[row] += p[row];
+    }
+    float colsum = 0.f;
+#pragma unroll
+    for (int row = 0; row < T; ++row) {
+        if (row < nrows) {
+            float out;
+            if (FWD) {
+                const float pre = lam * x[row] + (1.f - lam) * acc[row] + cvec;
+                float h, gp;
+                gelu_pair(pre, h, gp);
+                out = h;
+                a.Gp[((int64_t)l * a.M + m0 + row) * r + n] = static_cast<bf16_t>(gp);
+            } else {
+                out = (cvec + acc[row]) * x[row];
+            }
+            a.Hg[(int64_t)(m0 + row) * Lr + (int64_t)l * r + n] = static_cast<bf16_t>(out);
+            colsum += out;
+        }
+    }
+    a.part[(int64_t)tile * Lr + (int64_t)l * r + n] = colsum;
+}
+
+// zpart[tile][c] = sum_kk (column sums of h over the tile)[kk] V[kk][c]
+__global__ __launch_bounds__(256) void k_gseq_zpart(const float *HSpart, const float *V, int Lr, int C, float *zpart)
+{
+    __shared__ float red[16];
+    const int tile = blockIdx.x, t = threadIdx.x;
+    float acc[kMaxClasses];
+#pragma unroll
+    for (int c = 0; c < kMaxClasses; ++c) acc[c] = 0.f;
+    for (int kk = t; kk < Lr; kk += 256) {
+        const float hs = HSpart[(int64_t)tile * Lr + kk];
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c)
+            if (c < C) acc[c] += hs * V[(int64_t)kk * C + c];
+    }
+    for (int c = 0; c < C; ++c) {
+        const float tot = block_sum(acc[c], red);
+        if (t == 0) zpart[(int64_t)tile * C + c] = tot;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // launch 5: contractions over the tokens.  E_l = b_l^T dpre_l ; GG = H^T DP (all layer pairs at
 // once, kept only as the two bf16 copies the last launch contracts) ; ordered sums of the tiles'
 // column sums
@@ -875,7 +1056,7 @@ constexpr int kTokKT = 32;    // tokens per stage of the token contractions (a m
 using TG = TnTile<2, 2, 2, 2, kTokKT, kTokStages>; // 128 x 128 tile of the Gram matrix
 
 template <int NT> struct TokRedShapes {
-    using TE = TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), kTokKT, kTokStages>; // kETileCols columns of d x (64 or 128 >= r)
+    using TE = TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), kTokKT, kTokStages>; // kETileCols columns of d x 64 or 128 of r
     static constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4 + kMaxTiles * 4 + kMaxBatch * kMaxClasses * 4; // + tile and sample tables
     static constexpr int kTileLds = TE::LDS_BYTES > TG::LDS_BYTES ? TE::LDS_BYTES : TG::LDS_BYTES;
     static constexpr int kLds = kTileLds > kVecLds ? kTileLds : kVecLds;
@@ -892,9 +1073,11 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
     const int Lr = a.L * a.r;
     if (b < a.nb_E) {
         // E_l[d-tile] over the 16-token tiles [tl0, tl1) of this split
+        const int ect = (a.r + TE::BN - 1) / TE::BN; // column tiles of r (one up to r = 128)
         const int split = b % a.se;
-        const int it = (b / a.se) % a.e_tiles;
-        const int l = b / (a.se * a.e_tiles);
+        const int ct = (b / a.se) % ect;
+        const int it = (b / (a.se * ect)) % a.e_tiles;
+        const int l = b / (a.se * ect * a.e_tiles);
         const int tl0 = split * a.tiles_per_se;
         const int ntl = min(a.ntiles, tl0 + a.tiles_per_se) - tl0;
         for (int q = t; q < ntl; q += 256) {
@@ -918,7 +1101,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
             return dp + (int64_t)(t_m0[tl] + row) * Lr;
         };
         EpiStoreF32 epi{a.Epart + ((int64_t)split * a.L + l) * a.d * a.r, a.r};
-        gemm_tn<TE>(smem, atok, btok, a.zeros, epi, (ntl * 16 + kTokKT - 1) / kTokKT, it * TE::BM, 0, a.d, a.r, a.d, a.r);
+        gemm_tn<TE>(smem, atok, btok, a.zeros, epi, (ntl * 16 + kTokKT - 1) / kTokKT, it * TE::BM, ct * TE::BN, a.d, a.r, a.d, a.r);
         return;
     }
     if (b < a.nb_E + a.nb_G) {
@@ -1148,26 +1331,31 @@ struct EpiW {
     }
 };
 
-template <int BK> struct PostShapes {
-    using TF = NtTile<2, 2, 1, 1, BK, BK == 64 ? 4 : 8>; // 64 x 64, 64 KB of stages
+template <int BK, bool BIG> struct PostShapes {
+    // 64 x 64 with 64 KB of stages, or (r > 128) 128 x 128 with two stages
+    using TF = typename std::conditional<BIG, NtTile<2, 2, 2, 2, BK, 2>, NtTile<2, 2, 1, 1, BK, BK == 64 ? 4 : 8>>::type;
+    static constexpr int TS = TF::BM; // tile side
+    static constexpr int NH = BIG ? 4 : 2; // threads sharing one r-wide row in the vector part
+    static_assert(TF::BM == TF::BN, "square tiles");
     static constexpr int kVecLds = 128 * 4 + 128 * kMaxClasses * 4 + kMaxBatch * kMaxClasses * 4;
     static constexpr int kLds = TF::LDS_BYTES;
     static_assert(kLds >= kVecLds, "LDS budget of the gradient kernel");
 };
 
 // BK = 64 when r is a multiple of 64, else 32: every K range below is a multiple of r
-template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
+template <int BK, bool BIG> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
 {
-    using TF = typename PostShapes<BK>::TF;
-    constexpr int kVecLds = PostShapes<BK>::kVecLds;
-    constexpr int kLds = PostShapes<BK>::kLds;
+    using TF = typename PostShapes<BK, BIG>::TF;
+    constexpr int kVecLds = PostShapes<BK, BIG>::kVecLds;
+    constexpr int kLds = PostShapes<BK, BIG>::kLds;
+    constexpr int TS = PostShapes<BK, BIG>::TS, NH = PostShapes<BK, BIG>::NH;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     __shared__ float red[16];
     const int L = a.L, d = a.d, r = a.r, C = a.C;
     const int Lr = L * r;
     const int64_t dr = (int64_t)d * r;
     const int b = (int)(gridDim.x - 1 - blockIdx.x) + a.blk_off, t = threadIdx.x; // reverse dispatch, as in k_gproj
-    const int ti_d = (d + 63) / 64, ti_r = (r + 63) / 64;
+    const int ti_d = (d + TS - 1) / TS, ti_r = (r + TS - 1) / TS;
     if (b < a.nb_F) {
         // F_l = sum_{k<l} W_up^{kT} G_{kl}   ([d] x [l*r] times [l*r] x [r])
         const int l = b / (ti_d * ti_r);
@@ -1179,7 +1367,7 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
         auto brow = [&](int c) { return B + (int64_t)c * Lr; };
         EpiF epi{a.Epart + (int64_t)l * dr, a.se, (int64_t)L * dr, a.cusum + (int64_t)l * d, a.cs + (int64_t)l * r,
                  pl, a.grads + (int64_t)l * a.PL, r, pl[a.PL - 1], 0.f};
-        gemm_nt<TF>(smem, arow, brow, epi, 0, l * r, it * 64, nt * 64, d, r);
+        gemm_nt<TF>(smem, arow, brow, epi, 0, l * r, it * TS, nt * TS, d, r);
         const float tot = block_sum(epi.dlam, red);
         if (t == 0) a.dlam_part[(int64_t)l * a.slots + slot] = tot; // summed in slot order by k_gfinish
         return;
@@ -1195,25 +1383,25 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
         auto brow = [&](int c) { return B + (int64_t)c * Lr; };
         EpiW epi{a.Z + (int64_t)l * r * C, a.params + (int64_t)L * a.PL,
                  a.grads + (int64_t)l * a.PL + dr + r, d, C};
-        gemm_nt<TF>(smem, arow, brow, epi, (l + 1) * r, Lr, at * 64, jt * 64, r, d);
+        gemm_nt<TF>(smem, arow, brow, epi, (l + 1) * r, Lr, at * TS, jt * TS, r, d);
         return;
     }
     const int vb = b - a.nb_F - a.nb_W;
     if (vb < a.nb_vec - 1) {
-        // thread (jj, k, hf): hidden index j = vb * jpb + jj, layer k, half hf of the r-wide rows
+        // thread (jj, k, hf): hidden index j = vb * jpb + jj, layer k, part hf (of NH) of the r-wide rows
         float *tsh = reinterpret_cast<float *>(smem);          // [jpb][L]      (1-lambda_k) W_down^k[j] . cs_k
         float *wsh = tsh + 128;                                // [jpb][L][C]   W_up^k[.][j] . Z_k + pooled part
         float *sdz = wsh + 128 * kMaxClasses;                  // [B][C]
         float *stage = sdz + kMaxBatch * kMaxClasses;          // cs [Lr], Z [Lr][C] when they fit
-        const int jpb = 128 / L;
-        const int hf = t & 1, jk = t >> 1;
+        const int jpb = (256 / NH) / L;
+        const int hf = t % NH, jk = t / NH;
         const int jj = jk / L, k = jk % L;
         const int j = vb * jpb + jj;
         const bool act = jj < jpb && j < d;
-        const int rh = r / 2; // a multiple of 16
+        const int rh = r / NH; // a multiple of 8
         const float *Wc = a.params + (int64_t)L * a.PL;
         // this thread's two row segments, requested before anything else is waited for
-        constexpr int kMaxChunks = 8; // r / 2 <= 64
+        constexpr int kMaxChunks = 8; // r / NH <= 64
         u32x4 wv[kMaxChunks], uv[kMaxChunks];
         {
             const int64_t row = act ? (int64_t)j * Lr + (int64_t)k * r + hf * rh : 0;
@@ -1243,10 +1431,10 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
             for (int c = 0; c < kMaxClasses; ++c)
                 if (c < C) base += dzs_r[c] * wc_r[c];
         }
-        float pbv[2]; // pooled last-layer means of the samples s = k + (2q + hf) L this thread covers first
+        float pbv[2]; // pooled last-layer means of the samples s = k + (NH q + hf) L this thread covers first
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-            const int s2 = k + (2 * q + hf) * L;
+            const int s2 = k + (NH * q + hf) * L;
             pbv[q] = (act && s2 < a.B) ? a.pb[(int64_t)s2 * d + j] : 0.f;
         }
         const float cl = act ? a.cusum[(int64_t)L * d + j] : 0.f;
@@ -1266,7 +1454,7 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
                         Chunk<bf16_t> w8, u8;
                         __builtin_memcpy(&w8, &wv[q], 16);
                         __builtin_memcpy(&u8, &uv[q], 16);
-                        // 16-byte reads of the column sums (both sides are 16-byte aligned: rh % 16 == 0)
+                        // 16-byte reads of the column sums (both sides are 16-byte aligned: rh % 8 == 0)
                         const f32x4 c0 = *reinterpret_cast<const f32x4 *>(csk + q * 8);
                         const f32x4 c1 = *reinterpret_cast<const f32x4 *>(csk + q * 8 + 4);
 #pragma unroll
@@ -1295,18 +1483,21 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
                         }
                     }
                 // pooled part of dW_cls, the samples dealt over (k, hf)
-                for (int s2 = k + hf * L, q = 0; s2 < a.B; s2 += 2 * L, ++q) {
+                for (int s2 = k + hf * L, q = 0; s2 < a.B; s2 += NH * L, ++q) {
                     const float pv = (q < 2 ? pbv[q] : a.pb[(int64_t)s2 * d + j]) + cl;
 #pragma unroll
                     for (int c = 0; c < kMaxClasses; ++c)
                         if (c < C) wz[c] += pv * sdz[s2 * C + c];
                 }
             }
-            // the two halves sit in neighbouring lanes
-            acc += __shfl_xor(acc, 1, 64);
+            // the parts sit in neighbouring lanes
 #pragma unroll
-            for (int c = 0; c < kMaxClasses; ++c)
-                if (c < C) wz[c] += __shfl_xor(wz[c], 1, 64);
+            for (int o = 1; o < NH; o <<= 1) {
+                acc += __shfl_xor(acc, o, 64);
+#pragma unroll
+                for (int c = 0; c < kMaxClasses; ++c)
+                    if (c < C) wz[c] += __shfl_xor(wz[c], o, 64);
+            }
             if (act && hf == 0) {
                 tsh[jj * L + k] = (1.f - lamk) * acc;
 #pragma unroll
@@ -1322,7 +1513,7 @@ template <int BK> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
             a.grads[(int64_t)k * a.PL + 2 * dr + r + j] = base;
         }
         // dW_cls[j][c] = sum_s (pb[s][j] + cusum_L[j]) dz[s][c] + sum_k W_up^k[.][j] . Z_k[.][c]
-        for (int c = 2 * k + hf; c < C; c += 2 * L) {
+        for (int c = NH * k + hf; c < C; c += NH * L) {
             float acc = 0.f;
             for (int k2 = 0; k2 < L; ++k2) acc += wsh[(jj * L + k2) * C + c];
             a.grads[(int64_t)L * a.PL + (int64_t)j * C + c] = acc;
@@ -1436,8 +1627,10 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     {
         ProjArgs a;
         a.cache = cache; a.map = map; a.L = L; a.d = d; a.r = r; a.B = B;
-        a.row_tiles = cdiv(M, 128); a.nb_U = a.row_tiles * L;
-        a.nb_Q = W.pairs * cdiv(r, 64) * cdiv(r, 64);
+        constexpr int kQSide = NT > 4 ? 128 : 64; // ProjShapes<NT, .>::TQ
+        a.row_tiles = cdiv(M, 128); a.nb_U = a.row_tiles * L * (NT > 4 ? cdiv(r, 128) : 1);
+        a.nb_Q = W.pairs * cdiv(r, kQSide) * cdiv(r, kQSide);
+        a.q_full = W.use_gram == 2;
         a.nb_C = L * cdiv(r, 64);
         a.cusum = cusum; a.chat = chat; a.params = io.params; a.PL = D.PL;
         a.WdT = WdT; a.Wu = Wu; a.U = pre; a.QpN = QpN; a.QpT = QpT;
@@ -1465,17 +1658,10 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         }
     }
     PAC_HIP_TRY(hipGetLastError());
-    const size_t lds_fwd = chain_lds(L, r, true), lds_bwd = chain_lds(L, r, false);
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<true, NT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<false, NT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gtokred<NT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, TokRedShapes<NT>::kLds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gtokred<NT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, TokRedShapes<NT>::kLds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
@@ -1485,21 +1671,87 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     ca.B = B; ca.C = C; ca.V = V; ca.zpart = zpart; ca.zpbp = zpb; ca.nzb = cdiv(d, 256);
     ca.samp_tile0 = samp_tile0; ca.samp_len = samp_len; ca.labels = io.labels;
     ca.logits_ws = logits; ca.logits_out = io.logits_out; ca.dz = dz; ca.loss_part = loss_part;
-    {
-        ChainArgs a = ca;
-        a.Q = QpT; a.Hg = H; a.part = HSpart;
-        PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_fwd, st, a);
-    }
-    if (!io.grads) {
+    if (W.use_gram == 1) {
+        if constexpr (NT <= 4) {
+            const size_t lds_fwd = chain_lds(L, r, true), lds_bwd = chain_lds(L, r, false);
+            static bool chain_attr_done = false;
+            if (!chain_attr_done) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<true, NT>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                if (e != hipSuccess) return e;
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<false, NT>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                if (e != hipSuccess) return e;
+                chain_attr_done = true;
+            }
+            {
+                ChainArgs a = ca;
+                a.Q = QpT; a.Hg = H; a.part = HSpart;
+                PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_fwd, st, a);
+            }
+            if (!io.grads) {
+                PAC_LAUNCH(prof, st, KC_G_HEAD, k_glogits, dim3(B), dim3(64), 0, st, ca);
+                PAC_LAUNCH(prof, st, KC_G_FINISH, k_gfinish, dim3(1), dim3(64), 0, st, loss_part, B, io.loss_out, nullptr, 0, L,
+                           D.PL, nullptr);
+                return hipGetLastError();
+            }
+            {
+                ChainArgs a = ca;
+                a.Q = QpN; a.Hg = DP; a.part = cspart;
+                PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, (k_gchain<false, NT>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_bwd, st, a);
+            }
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else {
+        // one contraction launch and one small nonlinearity launch per layer and direction
+        const bool k64 = r % 64 == 0;
+        const int seq_lds = k64 ? SeqShapes<64>::TL::LDS_BYTES : SeqShapes<32>::TL::LDS_BYTES;
+        static bool seq_attr_done = false;
+        if (!seq_attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gseq_mm<64>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, SeqShapes<64>::TL::LDS_BYTES);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gseq_mm<32>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, SeqShapes<32>::TL::LDS_BYTES);
+            if (e != hipSuccess) return e;
+            seq_attr_done = true;
+        }
+        const int bk = k64 ? 64 : 32;
+        float *P = (float *)(ws + W.g_P);
+        const int rtiles = cdiv(M, kSeqTile), ctiles = cdiv(r, kSeqTile);
+        auto chain_layer = [&](bool fwd, int l) {
+            SeqMmArgs ma;
+            ma.A = fwd ? H : DP; ma.Bq = fwd ? QpT : QpN; ma.P = P; ma.l = l; ma.L = L; ma.r = r; ma.M = M;
+            ma.kbegin = fwd ? 0 : (l + 1) * r; ma.kend = fwd ? l * r : Lr; ma.ctiles = ctiles;
+            const int ksteps = (ma.kend - ma.kbegin) / bk;
+            int S = 0;
+            if (ksteps > 0) {
+                // at least eight K steps per split, at most the planned number of splits
+                S = ksteps / 8 < 1 ? 1 : (ksteps / 8 > W.sq ? W.sq : ksteps / 8);
+                ma.ksplit = cdiv(ksteps, S) * bk;
+                S = cdiv(ma.kend - ma.kbegin, ma.ksplit);
+                const int cls = fwd ? KC_G_CHAIN_FWD : KC_G_CHAIN_BWD;
+                if (k64) PAC_LAUNCH(prof, st, cls, k_gseq_mm<64>, dim3(rtiles * ctiles, S), dim3(256), seq_lds, st, ma);
+                else PAC_LAUNCH(prof, st, cls, k_gseq_mm<32>, dim3(rtiles * ctiles, S), dim3(256), seq_lds, st, ma);
+            }
+            SeqFinArgs fa;
+            fa.l = l; fa.L = L; fa.r = r; fa.M = M; fa.S = S; fa.C = C; fa.d = d; fa.P = P; fa.U = pre; fa.Gp = ca.Gp;
+            fa.chat = chat; fa.params = io.params; fa.PL = D.PL; fa.Hg = fwd ? H : DP; fa.part = fwd ? HSpart : cspart;
+            fa.tile_row0 = tile_row0; fa.tile_rows = tile_rows; fa.tile_samp = tile_samp; fa.samp_len = samp_len;
+            fa.dz = dz; fa.V = V;
+            if (fwd) PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, k_gseq_fin<true>, dim3(ntiles), dim3(256), 0, st, fa);
+            else PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, k_gseq_fin<false>, dim3(ntiles), dim3(256), 0, st, fa);
+        };
+        for (int l = 0; l < L; ++l) chain_layer(true, l);
+        PAC_LAUNCH(prof, st, KC_G_HEAD, k_gseq_zpart, dim3(ntiles), dim3(256), 0, st, HSpart, V, Lr, C, zpart);
         PAC_LAUNCH(prof, st, KC_G_HEAD, k_glogits, dim3(B), dim3(64), 0, st, ca);
-        PAC_LAUNCH(prof, st, KC_G_FINISH, k_gfinish, dim3(1), dim3(64), 0, st, loss_part, B, io.loss_out, nullptr, 0, L,
-                   D.PL, nullptr);
-        return hipGetLastError();
-    }
-    {
-        ChainArgs a = ca;
-        a.Q = QpN; a.Hg = DP; a.part = cspart;
-        PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, (k_gchain<false, NT>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_bwd, st, a);
+        if (!io.grads) {
+            PAC_LAUNCH(prof, st, KC_G_FINISH, k_gfinish, dim3(1), dim3(64), 0, st, loss_part, B, io.loss_out, nullptr, 0, L,
+                       D.PL, nullptr);
+            return hipGetLastError();
+        }
+        for (int l = L - 1; l >= 0; --l) chain_layer(false, l);
     }
     {
         TokRedArgs a;
@@ -1515,7 +1767,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.rows_per_sg = cdiv(cdiv(M, W.sg), 128) * 128;
         a.sg = cdiv(M, a.rows_per_sg);
         a.tg = cdiv(Lr, 128);
-        a.nb_E = L * a.e_tiles * a.se;
+        a.nb_E = L * a.e_tiles * cdiv(r, 128) * a.se;
         a.nb_G = L > 1 ? a.tg * a.tg * a.sg : 0;
         a.H = H; a.DP = DP; a.Epart = Epart; a.GGpart = GGpart;
         a.ntiles = ntiles; a.B = B; a.C = C; a.cspart = cspart; a.HSpart = HSpart; a.dz = dz;
@@ -1534,28 +1786,30 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         }
         PostArgs pa;
         pa.L = L; pa.d = d; pa.r = r; pa.C = C; pa.B = B; pa.se = 1;
-        pa.nb_F = L * cdiv(d, 64) * cdiv(r, 64); pa.nb_W = pa.nb_F; pa.nb_vec = cdiv(d, 128 / L) + 1;
+        constexpr bool BIG = NT > 4;
+        constexpr int TS = BIG ? 128 : 64, NH = BIG ? 4 : 2; // PostShapes<., BIG>
+        pa.nb_F = L * cdiv(d, TS) * cdiv(r, TS); pa.nb_W = pa.nb_F; pa.nb_vec = cdiv(d, (256 / NH) / L) + 1;
         pa.params = io.params; pa.PL = D.PL; pa.WuTs = WuTs; pa.Wds = Wds; pa.GGT = GGT; pa.GGsc = GGsc;
         pa.Epart = (const float *)(ws + W.g_E); pa.cusum = cusum; pa.cs = cs; pa.Z = Z; pa.dzsum = dzsum; pa.dz = dz; pa.pb = pb;
         pa.grads = io.grads; pa.dlam_part = dlam_part; pa.counter = counter;
-        pa.slots = cdiv(d, 64) * cdiv(r, 64);
+        pa.slots = cdiv(d, TS) * cdiv(r, TS);
         {
             const int counts[3] = {pa.nb_F, pa.nb_W, pa.nb_vec};
             const int classes[3] = {KC_G_POST_F, KC_G_POST_W, KC_G_POST_VEC};
             static bool done = false;
             if (!done) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<64>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<64>::kLds);
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<64, BIG>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<64, BIG>::kLds);
                 if (e != hipSuccess) return e;
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<32>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<32>::kLds);
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<32, BIG>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<32, BIG>::kLds);
                 if (e != hipSuccess) return e;
                 done = true;
             }
             if (r % 64 == 0)
-                launch_parts(prof, st, split, k_gpost<64>, pa, 3, counts, classes, KC_G_POST, 256, PostShapes<64>::kLds);
+                launch_parts(prof, st, split, k_gpost<64, BIG>, pa, 3, counts, classes, KC_G_POST, 256, PostShapes<64, BIG>::kLds);
             else
-                launch_parts(prof, st, split, k_gpost<32>, pa, 3, counts, classes, KC_G_POST, 256, PostShapes<32>::kLds);
+                launch_parts(prof, st, split, k_gpost<32, BIG>, pa, 3, counts, classes, KC_G_POST, 256, PostShapes<32, BIG>::kLds);
         }
         if (io.defer) { // the optimizer launch that follows does the last two sums
             io.defer->used = true;
@@ -1576,6 +1830,10 @@ hipError_t launch_gram_loss_grad(const Dims &D, const WsLayout &W, const BatchMe
     case 2: return run_gram<2>(D, W, meta, io);
     case 3: return run_gram<3>(D, W, meta, io);
     case 4: return run_gram<4>(D, W, meta, io);
+    case 5: return run_gram<5>(D, W, meta, io);
+    case 6: return run_gram<6>(D, W, meta, io);
+    case 7: return run_gram<7>(D, W, meta, io);
+    case 8: return run_gram<8>(D, W, meta, io);
     }
     return hipErrorInvalidValue;
 }

@@ -33,14 +33,16 @@ struct WsLayout {
     int32_t dlam_slots; // workgroups of the dx kernel at the largest batch
 
     // ---- regions of the Gram-matrix path (bf16, small adapter widths) ----
-    int32_t use_gram;   // 1: the step runs on the Gram-matrix path
+    int32_t use_gram;   // 0: per-layer kernels; 1: Gram-matrix path, chains in LDS; 2: Gram-matrix path, one chain launch per layer
     int32_t max_tiles;  // 32-row token tiles at the largest batch
     int32_t pairs;      // L (L - 1) / 2 layer pairs k < l
     int32_t se, sg;     // token splits of the E and Gram contractions
+    int32_t sq;         // largest K split of a per-layer chain contraction
+    int64_t g_P;        // f32 [sq][Mmax][r] partial sums of a per-layer chain contraction
     int64_t g_tile_row0, g_tile_rows, g_tile_samp;
     int64_t g_WuTs, g_Wds;          // bf16 [d][L*r] stacked projection copies
     int64_t g_cusum, g_chat, g_V;   // f32 [L+1][d], [L][r], [L*r][C]
-    int64_t g_QpN, g_QpT;           // bf16 [pairs][r][r], both orientations
+    int64_t g_QpN, g_QpT;           // bf16 [pairs][r][r], both orientations (use_gram 2: [L*r][L*r] each)
     int64_t g_DP;                   // bf16 [Mmax][L*r]
     int64_t g_HSpart, g_cspart;     // f32 [max_tiles][L][r]
     int64_t g_zpart, g_zpb;         // f32 [max_tiles][C], [B_max][C]: shares of the logits
@@ -127,7 +129,7 @@ void plan_workspace(const Dims &D, WsLayout &W);
 hipError_t launch_cache_fill(const Dims &D, void *cache, const void *acts, int acts_dtype,
                              const BatchMeta &meta, hipStream_t st, Profiler *prof);
 hipError_t launch_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io);
-bool gram_path_fits(const Dims &D);
+int gram_path_kind(const Dims &D); // a value of WsLayout::use_gram
 void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &offset);
 hipError_t launch_gram_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io);
 hipError_t launch_adamw(const Dims &D, float *p, float *m, float *v, float *g,

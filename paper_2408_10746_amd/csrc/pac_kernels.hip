@@ -76,7 +76,7 @@ void plan_workspace(const Dims &D, WsLayout &W)
     W.dlam_part = take((int64_t)W.dlam_slots * 4);
     W.grads = take(D.P * 4);
     W.use_gram = 0;
-    if (gram_path_fits(D)) plan_gram_workspace(D, W, o);
+    if (gram_path_kind(D)) plan_gram_workspace(D, W, o);
     W.total = o;
 }
 

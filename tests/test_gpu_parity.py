@@ -179,8 +179,17 @@ GRAM = [
 ]
 
 
-@pytest.mark.parametrize("w", GRAM, ids=[w.name for w in GRAM])
-@pytest.mark.parametrize("flags", [0, 1], ids=["gram", "per_layer"])
+# Adapter widths above 128: the Gram-matrix formulation with one chain launch per layer and 128 x 128
+# workgroup tiles (widths that are and are not multiples of 64, several column tiles, ragged rows).
+WIDE = [
+    Workload("w1", L=3, d=160, n_max=37, B=5, r=160, C=3, N=5, cache_dtype="bf16", len_lo=9),
+    Workload("w2", L=5, d=256, n_max=70, B=4, r=256, C=4, N=4, cache_dtype="bf16", len_lo=20),
+    Workload("w3", L=9, d=192, n_max=150, B=3, r=192, C=2, N=3, cache_dtype="bf16", len_lo=100),
+]
+
+
+@pytest.mark.parametrize("w", GRAM + WIDE, ids=[w.name for w in GRAM + WIDE])
+@pytest.mark.parametrize("flags", [0, 1, 4], ids=["gram", "per_layer", "layer_chain"])
 def test_bf16_paths(w, flags):
     lens = inputs.lengths(w)
     ids = np.arange(w.B)
@@ -199,7 +208,7 @@ def test_bf16_paths(w, flags):
             assert np.all(grads[sl[nm]] == 0.0), nm
 
 
-@pytest.mark.parametrize("flags", [0, 1], ids=["gram", "per_layer"])
+@pytest.mark.parametrize("flags", [0, 1, 4], ids=["gram", "per_layer", "layer_chain"])
 def test_forward_only_call(flags):
     """loss and logits without gradients (no backward launches; the gradient buffer stays untouched)."""
     w = GRAM[1]
