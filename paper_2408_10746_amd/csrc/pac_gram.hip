@@ -109,13 +109,14 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     const int64_t q_bytes = W.use_gram == 2 ? Lr * Lr * 2 : (int64_t)(W.pairs + 1) * D.r * D.r * 2;
     W.g_QpN = take(q_bytes);
     W.g_QpT = take(q_bytes);
-    W.sq = 1;
-    W.g_P = 0;
+    W.chain_group = 1;
+    W.g_P = W.g_ghat = 0;
     if (W.use_gram == 2) {
-        // about two workgroups per compute unit at the largest batch
-        const int tiles = cdiv(D.Mmax, kSeqTile) * cdiv(D.r, kSeqTile);
-        W.sq = cdiv(512, tiles) > 16 ? 16 : cdiv(512, tiles);
-        W.g_P = take((int64_t)W.sq * D.Mmax * D.r * 4);
+        // layers per group of the layer-by-layer chains: about 1024 columns per wide contraction
+        const int g = 1024 / D.r;
+        W.chain_group = g < 1 ? 1 : (g > 8 ? 8 : g);
+        W.g_P = take(D.Mmax * (int64_t)W.chain_group * D.r * 4);
+        W.g_ghat = take((int64_t)D.B_max * Lr * 4);
     }
     W.g_DP = take(D.Mmax * Lr * 2);
     W.g_Gp = take(D.Mmax * Lr * 2);
@@ -164,6 +165,27 @@ __device__ __forceinline__ float gelu_grad_f(float u)
     return Phi + u * phi;
 }
 __device__ __forceinline__ int pair_index(int k, int l) { return l * (l - 1) / 2 + k; } // k < l
+
+// Workgroups are handed to the eight accelerator dies (each with its own L2) round-robin by block
+// index.  Given a part's block number u in [0, n) (any numbering that differs from the hardware block
+// index by a constant, or runs against it), this returns a tile number such that each die works
+// through one contiguous range of tile numbers in order: tiles that share an operand and are numbered
+// next to each other then meet in the same L2 instead of each die fetching the operand for itself.
+__device__ __forceinline__ int die_chunk_order(int u, int n)
+{
+    const int q = n >> 3, rem = n & 7, x = u & 7, s = u >> 3;
+    return x * q + min(x, rem) + s;
+}
+// The same in windows of 8 * gs blocks: within a window each die gets gs consecutive tile numbers, and
+// the windows keep the launch's overall order (for parts whose tiles differ in cost and are numbered
+// with that in mind).  The blocks past the last whole window keep their numbers.
+__device__ __forceinline__ int die_group_order(int u, int n, int gs)
+{
+    const int w = 8 * gs;
+    if (u >= (n / w) * w) return u;
+    const int in = u % w;
+    return u - in + (in & 7) * gs + (in >> 3);
+}
 
 // ---------------------------------------------------------------------------
 // launch 1: batch gather, token tiles, projection copies, cusum/chat, V
@@ -433,7 +455,8 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
     if (b < a.nb_U) {
         // (layer, row tile, column tile), the column tiles of a row tile next to each other
         const int uct = (a.r + TU::BN - 1) / TU::BN;
-        const int ct = b % uct, mt = (b / uct) % a.row_tiles, l = b / (uct * a.row_tiles);
+        const int v = uct > 1 ? die_group_order(b, a.nb_U, 4 * uct) : b;
+        const int ct = v % uct, mt = (v / uct) % a.row_tiles, l = v / (uct * a.row_tiles);
         const bf16_t *cache = a.cache;
         const RowMap map = a.map;
         const bf16_t *W = a.WdT + (int64_t)l * a.r * a.d;
@@ -446,7 +469,7 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
     }
     const int tq = (a.r + TQ::BM - 1) / TQ::BM, tc64 = (a.r + 63) / 64;
     if (b < a.nb_U + a.nb_Q) {
-        int idx = b - a.nb_U;
+        int idx = SH::BIG ? die_group_order(b - a.nb_U, a.nb_Q, 2 * tq * tq) : b - a.nb_U;
         const int p = idx / (tq * tq);
         idx -= p * tq * tq;
         // pair p = (k, l), k < l
@@ -902,109 +925,157 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
 }
 
 // ---------------------------------------------------------------------------
-// The chains as one contraction per layer (adapter widths whose 16-token history of all layers does
-// not fit the LDS).  Layer l of the forward chain needs sum_{k<l} h_k Q_{kl}: with H [M][L*r] and the
-// matrix QT [(l,n)][(k,j)] = Q_{kl}[j][n] that is the product of the first l*r columns of H with rows
-// (l, .) of QT, both K-contiguous; the backward chain takes columns (l+1)*r.. of DP and rows (l, .) of
-// QN [(l,n)][(k,j)] = (1-lambda_k) Q_{lk}[n][j].  The contraction range is split over several
-// workgroups per tile (the early and late layers' ranges are short, the batch has few row tiles);
-// a second small launch sums the partials in split order and applies the layer's nonlinearity.
+// The chains as contractions launched layer by layer (adapter widths whose 16-token history of all
+// layers does not fit the LDS).  Layer l of the forward chain needs sum_{k<l} h_k Q_{kl}: with H [M][L*r]
+// and the matrix QT [(l,n)][(k,j)] = Q_{kl}[j][n] that is the product of the first l*r columns of H with
+// rows (l, .) of QT, both K-contiguous; the backward chain takes columns (l+1)*r.. of DP and rows (l, .)
+// of QN [(l,n)][(k,j)] = (1-lambda_k) Q_{lk}[n][j].
+//
+// The layers are taken in groups of g.  What the layers before a group contribute to all g layers of
+// the group is one wide contraction (K = all earlier layers, N = g*r: enough 128 x 128 tiles to fill
+// the chip without splitting K).  Inside the group each layer is a short contraction over the group's
+// earlier layers whose epilogue adds the wide contraction's result and applies the nonlinearity, so
+// that no partial sums travel through memory more than once.  The per-tile column sums the later
+// launches need are taken from the finished bf16 arrays in one pass per direction.
 // ---------------------------------------------------------------------------
-struct SeqMmArgs {
+struct SeqBigArgs {
     const bf16_t *A;  // H or DP [M][L*r]
     const bf16_t *Bq; // QT or QN [L*r][L*r]
-    float *P;         // [splits][M][r]
-    int l, L, r, M;
-    int kbegin, kend, ksplit; // columns of A contracted; ksplit (a multiple of BK) per split
+    float *P;         // [M][ldp]
+    int L, r, M, ldp;
+    int brow0, ncols;  // rows (group's first layer) * r .. + ncols of Bq
+    int kbegin, kend;  // columns of A contracted
     int ctiles;
 };
 
 template <int BK> struct SeqShapes {
-    using TL = NtTile<2, 2, 2, 2, BK, 2>; // kSeqTile x kSeqTile
-    static_assert(TL::BM == kSeqTile && TL::BN == kSeqTile, "tile side of the per-layer chain contraction");
+    using TB = NtTile<2, 2, 2, 2, BK, 2>; // kSeqTile x kSeqTile
+    using TS = NtTile<2, 2, 1, 1, BK, 3>; // 64 x 64 for the short contractions inside a group
+    static_assert(TB::BM == kSeqTile && TB::BN == kSeqTile, "tile side of the wide chain contraction");
 };
 
-template <int BK> __global__ __launch_bounds__(256) void k_gseq_mm(SeqMmArgs a)
+template <int BK> __global__ __launch_bounds__(256) void k_gseq_big(SeqBigArgs a)
 {
-    using TL = typename SeqShapes<BK>::TL;
+    using TL = typename SeqShapes<BK>::TB;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int ct = blockIdx.x % a.ctiles, rt = blockIdx.x / a.ctiles, sp = blockIdx.y;
-    const int kb = a.kbegin + sp * a.ksplit, ke = min(a.kend, kb + a.ksplit);
+    // a die's range of tiles: whole rows of column tiles, so that a row tile of A is fetched by one die only
+    const int v = die_chunk_order(blockIdx.x, gridDim.x);
+    const int ct = v % a.ctiles, rt = v / a.ctiles;
     const int64_t Lr = (int64_t)a.L * a.r;
-    const bf16_t *A = a.A, *Bq = a.Bq + (int64_t)a.l * a.r * Lr;
+    const bf16_t *A = a.A, *Bq = a.Bq + (int64_t)a.brow0 * Lr;
     auto arow = [&](int m) { return A + (int64_t)m * Lr; };
     auto brow = [&](int n) { return Bq + (int64_t)n * Lr; };
-    EpiStoreF32 epi{a.P + (int64_t)sp * a.M * a.r, a.r};
-    gemm_nt<TL>(smem, arow, brow, epi, kb, max(kb, ke), rt * kSeqTile, ct * kSeqTile, a.M, a.r);
+    EpiStoreF32 epi{a.P, a.ldp};
+    gemm_nt<TL>(smem, arow, brow, epi, a.kbegin, a.kend, rt * kSeqTile, ct * kSeqTile, a.M, a.ncols);
 }
 
-struct SeqFinArgs {
-    int l, L, r, M, S, C, d;
-    const float *P;      // [S][M][r]
-    const float *U;      // forward: [L][M][r]
-    bf16_t *Gp;          // [L][M][r]: written forward, read backward
-    const float *chat;   // [L][r]
+struct SeqLayerArgs {
+    const bf16_t *A;  // H or DP [M][L*r]
+    const bf16_t *Bq; // QT or QN [L*r][L*r]
+    const float *P;   // [M][ldp]: the wide contraction's result for this group, or null
+    int ldp, pcol0;
+    int l, L, r, M, d;
+    int kbegin, kend; // columns of A contracted (inside the group)
+    int ctiles;
+    const float *U;     // forward: [L][M][r]
+    bf16_t *Gp;         // [L][M][r]: written forward, read backward
+    const float *chat;  // [L][r]
     const float *params;
     int64_t PL;
-    bf16_t *Hg;          // forward: H, backward: DP   [M][L*r]
-    float *part;         // forward: HSpart, backward: cspart   [tiles][L*r]
-    const int32_t *tile_row0, *tile_rows, *tile_samp, *samp_len;
-    const float *dz, *V; // backward: [B][C], [L*r][C]
+    bf16_t *Hg;         // forward: H, backward: DP   [M][L*r]
+    const float *ghat;  // backward: [B][L*r]
+    const int32_t *rowsamp;
 };
 
-// one 16-token tile per workgroup, one column per thread
-template <bool FWD> __global__ __launch_bounds__(256) void k_gseq_fin(SeqFinArgs a)
-{
-    const int tile = blockIdx.x, n = threadIdx.x;
-    if (n >= a.r) return;
-    const int m0 = a.tile_row0[tile], nrows = a.tile_rows[tile];
-    const int l = a.l, r = a.r;
-    const int64_t Lr = (int64_t)a.L * r, Mr = (int64_t)a.M * r;
-    const float lam = a.params[(int64_t)l * a.PL + a.PL - 1];
-    float cvec;
-    if (FWD) {
-        cvec = (1.f - lam) * a.chat[l * r + n] + a.params[(int64_t)l * a.PL + (int64_t)a.d * r + n];
-    } else {
-        // ghat = dz V^T / len: what the head hands to every token of the sample
-        const int samp = a.tile_samp[tile];
-        float v = 0.f;
-        for (int c = 0; c < a.C; ++c) v += a.dz[samp * a.C + c] * a.V[((int64_t)l * r + n) * a.C + c];
-        cvec = v / (float)a.samp_len[samp];
-    }
-    constexpr int T = kChainRows;
-    float x[T], acc[T];
+// epilogue of a layer's contraction: the rest of the layer
+template <bool FWD> struct EpiSeqLayer {
+    static constexpr bool kBatched = true;
+    const float *P;
+    int ldp, pcol0;
+    const float *U_l;
+    bf16_t *Gp_l;
+    bf16_t *Hg_l; // column l*r of row 0
+    int64_t Lr;
+    int r;
+    float lam;
+    const float *chat_l, *cd_l; // forward
+    const float *ghat_l;        // backward: column l*r of sample 0
+    const int32_t *rowsamp;
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
+    {
+        const int cc = min(col, ncols - 1);
+        float x[16], pb[16], gh[16];
 #pragma unroll
-    for (int row = 0; row < T; ++row) {
-        const int64_t o = ((int64_t)l * a.M + m0 + min(row, nrows - 1)) * r + n;
-        x[row] = FWD ? a.U[o] : to_f32(a.Gp[o]);
-        acc[row] = 0.f;
-    }
-    for (int sp = 0; sp < a.S; ++sp) {
-        float p[T];
+        for (int v = 0; v < 16; ++v) {
+            const int m = min(epi_row(row_base, v), nrows - 1);
+            x[v] = FWD ? U_l[(int64_t)m * r + cc] : to_f32(Gp_l[(int64_t)m * r + cc]);
+            pb[v] = P ? P[(int64_t)m * ldp + pcol0 + cc] : 0.f;
+            gh[v] = FWD ? 0.f : ghat_l[(int64_t)rowsamp[m] * Lr + cc];
+        }
+        const float cvec = FWD ? (1.f - lam) * chat_l[cc] + cd_l[cc] : 0.f;
 #pragma unroll
-        for (int row = 0; row < T; ++row) p[row] = a.P[(int64_t)sp * Mr + (int64_t)(m0 + min(row, nrows - 1)) * r + n];
-#pragma unroll
-        for (int row = 0; row < T; ++row) acc[row] += p[row];
-    }
-    float colsum = 0.f;
-#pragma unroll
-    for (int row = 0; row < T; ++row) {
-        if (row < nrows) {
-            float out;
-            if (FWD) {
-                const float pre = lam * x[row] + (1.f - lam) * acc[row] + cvec;
-                float h, gp;
-                gelu_pair(pre, h, gp);
-                out = h;
-                a.Gp[((int64_t)l * a.M + m0 + row) * r + n] = static_cast<bf16_t>(gp);
-            } else {
-                out = (cvec + acc[row]) * x[row];
+        for (int v = 0; v < 16; ++v) {
+            const int m = epi_row(row_base, v);
+            if (m < nrows && col < ncols) {
+                float out;
+                if (FWD) {
+                    const float pre = lam * x[v] + (1.f - lam) * (acc[v] + pb[v]) + cvec;
+                    float h, gp;
+                    gelu_pair(pre, h, gp);
+                    out = h;
+                    Gp_l[(int64_t)m * r + col] = static_cast<bf16_t>(gp);
+                } else {
+                    out = (gh[v] + acc[v] + pb[v]) * x[v];
+                }
+                Hg_l[(int64_t)m * Lr + col] = static_cast<bf16_t>(out);
             }
-            a.Hg[(int64_t)(m0 + row) * Lr + (int64_t)l * r + n] = static_cast<bf16_t>(out);
-            colsum += out;
         }
     }
-    a.part[(int64_t)tile * Lr + (int64_t)l * r + n] = colsum;
+};
+
+template <bool FWD, int BK> __global__ __launch_bounds__(256) void k_gseq_layer(SeqLayerArgs a)
+{
+    using TL = typename SeqShapes<BK>::TS;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int ct = blockIdx.x % a.ctiles, rt = blockIdx.x / a.ctiles;
+    const int l = a.l, r = a.r;
+    const int64_t Lr = (int64_t)a.L * r, Mr = (int64_t)a.M * r;
+    const bf16_t *A = a.A, *Bq = a.Bq + (int64_t)l * r * Lr;
+    auto arow = [&](int m) { return A + (int64_t)m * Lr; };
+    auto brow = [&](int n) { return Bq + (int64_t)n * Lr; };
+    const float *pl = a.params + (int64_t)l * a.PL;
+    EpiSeqLayer<FWD> epi{a.P, a.ldp, a.pcol0, FWD ? a.U + (int64_t)l * Mr : nullptr, a.Gp + (int64_t)l * Mr,
+                         a.Hg + (int64_t)l * r, Lr, r, pl[a.PL - 1], a.chat + (int64_t)l * r, pl + (int64_t)a.d * r,
+                         FWD ? nullptr : a.ghat + (int64_t)l * r, a.rowsamp};
+    gemm_nt<TL>(smem, arow, brow, epi, a.kbegin, a.kend, rt * TL::BM, ct * TL::BN, a.M, r);
+}
+
+// part[tile][kk] = sum over the tile's valid rows of X[row][kk]   (X = H or DP, bf16 [M][L*r])
+__global__ __launch_bounds__(256) void k_gseq_colsum(const bf16_t *X, int Lr, const int32_t *tile_row0,
+                                                     const int32_t *tile_rows, float *part)
+{
+    const int tile = blockIdx.x, kk = blockIdx.y * 256 + threadIdx.x;
+    if (kk >= Lr) return;
+    const int m0 = tile_row0[tile], nrows = tile_rows[tile];
+    float x[kChainRows];
+#pragma unroll
+    for (int row = 0; row < kChainRows; ++row) x[row] = to_f32(X[(int64_t)(m0 + min(row, nrows - 1)) * Lr + kk]);
+    float acc = 0.f;
+#pragma unroll
+    for (int row = 0; row < kChainRows; ++row)
+        if (row < nrows) acc += x[row];
+    part[(int64_t)tile * Lr + kk] = acc;
+}
+
+// ghat[s][kk] = (dz_s V[kk]^T) / len_s: what the head hands to every token of sample s
+__global__ __launch_bounds__(256) void k_gseq_ghat(const float *dz, const float *V, const int32_t *samp_len, int Lr, int C,
+                                                   float *ghat)
+{
+    const int s = blockIdx.y, kk = blockIdx.x * 256 + threadIdx.x;
+    if (kk >= Lr) return;
+    float v = 0.f;
+    for (int c = 0; c < C; ++c) v += dz[s * C + c] * V[(int64_t)kk * C + c];
+    ghat[(int64_t)s * Lr + kk] = v / (float)samp_len[s];
 }
 
 // zpart[tile][c] = sum_kk (column sums of h over the tile)[kk] V[kk][c]
@@ -1074,10 +1145,11 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
     if (b < a.nb_E) {
         // E_l[d-tile] over the 16-token tiles [tl0, tl1) of this split
         const int ect = (a.r + TE::BN - 1) / TE::BN; // column tiles of r (one up to r = 128)
-        const int split = b % a.se;
-        const int ct = (b / a.se) % ect;
-        const int it = (b / (a.se * ect)) % a.e_tiles;
-        const int l = b / (a.se * ect * a.e_tiles);
+        const int v = ect > 1 ? die_group_order(b, a.nb_E, 4 * ect * a.se) : b; // the column tiles of a cache tile share a die's L2
+        const int split = v % a.se;
+        const int ct = (v / a.se) % ect;
+        const int it = (v / (a.se * ect)) % a.e_tiles;
+        const int l = v / (a.se * ect * a.e_tiles);
         const int tl0 = split * a.tiles_per_se;
         const int ntl = min(a.ntiles, tl0 + a.tiles_per_se) - tl0;
         for (int q = t; q < ntl; q += 256) {
@@ -1106,6 +1178,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
     }
     if (b < a.nb_E + a.nb_G) {
         int idx = b - a.nb_E;
+        // (numbered row-major, a die sees every eighth column panel of DP only: already local to its L2)
         const int split = idx % a.sg;
         idx /= a.sg;
         const int ti = idx / a.tg, tj = idx % a.tg;
@@ -1331,6 +1404,20 @@ struct EpiW {
     }
 };
 
+// wz[c] += sum_e u[e] Z[e][c] over 8 rows of CC classes each (Z 16-byte aligned)
+template <int CC> __device__ __forceinline__ void zrows(const float *Z, const Chunk<bf16_t> &u8, float (&wz)[kMaxClasses])
+{
+    f32x4 z[2 * CC];
+#pragma unroll
+    for (int v = 0; v < 2 * CC; ++v) z[v] = *reinterpret_cast<const f32x4 *>(Z + 4 * v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float u = to_f32(u8.e[e]);
+#pragma unroll
+        for (int c = 0; c < CC; ++c) wz[c] += u * z[(CC * e + c) >> 2][(CC * e + c) & 3];
+    }
+}
+
 template <int BK, bool BIG> struct PostShapes {
     // 64 x 64 with 64 KB of stages, or (r > 128) 128 x 128 with two stages
     using TF = typename std::conditional<BIG, NtTile<2, 2, 2, 2, BK, 2>, NtTile<2, 2, 1, 1, BK, BK == 64 ? 4 : 8>>::type;
@@ -1358,8 +1445,9 @@ template <int BK, bool BIG> __global__ __launch_bounds__(256) void k_gpost(PostA
     const int ti_d = (d + TS - 1) / TS, ti_r = (r + TS - 1) / TS;
     if (b < a.nb_F) {
         // F_l = sum_{k<l} W_up^{kT} G_{kl}   ([d] x [l*r] times [l*r] x [r])
-        const int l = b / (ti_d * ti_r);
-        const int slot = b % (ti_d * ti_r);
+        const int v = BIG ? die_group_order(b, a.nb_F, 8) : b;
+        const int l = v / (ti_d * ti_r);
+        const int slot = v % (ti_d * ti_r);
         const int it = slot / ti_r, nt = slot % ti_r;
         const float *pl = a.params + (int64_t)l * a.PL;
         const bf16_t *A = a.WuTs, *B = a.GGT + (int64_t)l * r * Lr;
@@ -1374,10 +1462,11 @@ template <int BK, bool BIG> __global__ __launch_bounds__(256) void k_gpost(PostA
     }
     if (b < a.nb_F + a.nb_W) {
         // dW_up^l = Z_l W_cls^T + sum_{k>l} (1-lambda_k) G_{lk} W_down^{kT}
-        int idx = b - a.nb_F;
+        int idx = BIG ? die_group_order(b - a.nb_F, a.nb_W, 8) : b - a.nb_F;
         const int l = idx / (ti_d * ti_r);
         idx %= ti_d * ti_r;
-        const int at = idx / ti_d, jt = idx % ti_d;
+        // (wide shapes: the row tiles of a column tile next to each other)
+        const int at = BIG ? idx % ti_r : idx / ti_d, jt = BIG ? idx / ti_r : idx % ti_d;
         const bf16_t *A = a.GGsc + (int64_t)l * r * Lr, *B = a.Wds;
         auto arow = [&](int row) { return A + (int64_t)row * Lr; };
         auto brow = [&](int c) { return B + (int64_t)c * Lr; };
@@ -1462,17 +1551,11 @@ template <int BK, bool BIG> __global__ __launch_bounds__(256) void k_gpost(PostA
                             acc += c0[e] * to_f32(w8.e[e]);
                             acc += c1[e] * to_f32(w8.e[4 + e]);
                         }
-                        if (C == 3) { // 8 rows x 3 classes = six 16-byte reads
-                            f32x4 z[6];
-#pragma unroll
-                            for (int v = 0; v < 6; ++v) z[v] = *reinterpret_cast<const f32x4 *>(Zk + (int64_t)q * 24 + 4 * v);
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) {
-                                const float u = to_f32(u8.e[e]);
-#pragma unroll
-                                for (int c = 0; c < 3; ++c) wz[c] += u * z[(3 * e + c) >> 2][(3 * e + c) & 3];
-                            }
-                        } else {
+                        // Z of these 8 rows: 8 C consecutive floats, read as 2 C 16-byte pieces
+                        if (C == 3) zrows<3>(Zk + (int64_t)q * 8 * 3, u8, wz);
+                        else if (C == 4) zrows<4>(Zk + (int64_t)q * 8 * 4, u8, wz);
+                        else if (C == 2) zrows<2>(Zk + (int64_t)q * 8 * 2, u8, wz);
+                        else {
 #pragma unroll
                             for (int e = 0; e < 8; ++e) {
                                 const float u = to_f32(u8.e[e]);
@@ -1704,46 +1787,58 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             return hipErrorInvalidValue;
         }
     } else {
-        // one contraction launch and one small nonlinearity launch per layer and direction
+        // groups of W.chain_group layers: one wide contraction per group, one short one per layer
         const bool k64 = r % 64 == 0;
-        const int seq_lds = k64 ? SeqShapes<64>::TL::LDS_BYTES : SeqShapes<32>::TL::LDS_BYTES;
+        const int big_lds = k64 ? SeqShapes<64>::TB::LDS_BYTES : SeqShapes<32>::TB::LDS_BYTES;
+        const int small_lds = k64 ? SeqShapes<64>::TS::LDS_BYTES : SeqShapes<32>::TS::LDS_BYTES;
         static bool seq_attr_done = false;
         if (!seq_attr_done) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gseq_mm<64>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, SeqShapes<64>::TL::LDS_BYTES);
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gseq_big<64>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, SeqShapes<64>::TB::LDS_BYTES);
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gseq_mm<32>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, SeqShapes<32>::TL::LDS_BYTES);
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gseq_big<32>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, SeqShapes<32>::TB::LDS_BYTES);
             if (e != hipSuccess) return e;
             seq_attr_done = true;
         }
-        const int bk = k64 ? 64 : 32;
-        float *P = (float *)(ws + W.g_P);
-        const int rtiles = cdiv(M, kSeqTile), ctiles = cdiv(r, kSeqTile);
-        auto chain_layer = [&](bool fwd, int l) {
-            SeqMmArgs ma;
-            ma.A = fwd ? H : DP; ma.Bq = fwd ? QpT : QpN; ma.P = P; ma.l = l; ma.L = L; ma.r = r; ma.M = M;
-            ma.kbegin = fwd ? 0 : (l + 1) * r; ma.kend = fwd ? l * r : Lr; ma.ctiles = ctiles;
-            const int ksteps = (ma.kend - ma.kbegin) / bk;
-            int S = 0;
-            if (ksteps > 0) {
-                // at least eight K steps per split, at most the planned number of splits
-                S = ksteps / 8 < 1 ? 1 : (ksteps / 8 > W.sq ? W.sq : ksteps / 8);
-                ma.ksplit = cdiv(ksteps, S) * bk;
-                S = cdiv(ma.kend - ma.kbegin, ma.ksplit);
-                const int cls = fwd ? KC_G_CHAIN_FWD : KC_G_CHAIN_BWD;
-                if (k64) PAC_LAUNCH(prof, st, cls, k_gseq_mm<64>, dim3(rtiles * ctiles, S), dim3(256), seq_lds, st, ma);
-                else PAC_LAUNCH(prof, st, cls, k_gseq_mm<32>, dim3(rtiles * ctiles, S), dim3(256), seq_lds, st, ma);
+        float *P = (float *)(ws + W.g_P), *ghat = (float *)(ws + W.g_ghat);
+        const int g = W.chain_group, ldp = g * r;
+        const int rt128 = cdiv(M, kSeqTile), rt64 = cdiv(M, 64), ct64 = cdiv(r, 64);
+        auto chain_group = [&](bool fwd, int l0) {
+            const int l1 = l0 + g < L ? l0 + g : L;
+            const int cls = fwd ? KC_G_CHAIN_FWD : KC_G_CHAIN_BWD;
+            SeqBigArgs ba;
+            ba.A = fwd ? H : DP; ba.Bq = fwd ? QpT : QpN; ba.P = P; ba.L = L; ba.r = r; ba.M = M; ba.ldp = ldp;
+            ba.brow0 = l0 * r; ba.ncols = (l1 - l0) * r;
+            ba.kbegin = fwd ? 0 : l1 * r; ba.kend = fwd ? l0 * r : Lr;
+            ba.ctiles = cdiv(ba.ncols, kSeqTile);
+            const bool have_big = ba.kend > ba.kbegin;
+            if (have_big) {
+                if (k64) PAC_LAUNCH(prof, st, cls, k_gseq_big<64>, dim3(rt128 * ba.ctiles), dim3(256), big_lds, st, ba);
+                else PAC_LAUNCH(prof, st, cls, k_gseq_big<32>, dim3(rt128 * ba.ctiles), dim3(256), big_lds, st, ba);
             }
-            SeqFinArgs fa;
-            fa.l = l; fa.L = L; fa.r = r; fa.M = M; fa.S = S; fa.C = C; fa.d = d; fa.P = P; fa.U = pre; fa.Gp = ca.Gp;
-            fa.chat = chat; fa.params = io.params; fa.PL = D.PL; fa.Hg = fwd ? H : DP; fa.part = fwd ? HSpart : cspart;
-            fa.tile_row0 = tile_row0; fa.tile_rows = tile_rows; fa.tile_samp = tile_samp; fa.samp_len = samp_len;
-            fa.dz = dz; fa.V = V;
-            if (fwd) PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, k_gseq_fin<true>, dim3(ntiles), dim3(256), 0, st, fa);
-            else PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, k_gseq_fin<false>, dim3(ntiles), dim3(256), 0, st, fa);
+            for (int q = 0; q < l1 - l0; ++q) {
+                const int l = fwd ? l0 + q : l1 - 1 - q;
+                SeqLayerArgs la;
+                la.A = ba.A; la.Bq = ba.Bq; la.P = have_big ? P : nullptr; la.ldp = ldp; la.pcol0 = (l - l0) * r;
+                la.l = l; la.L = L; la.r = r; la.M = M; la.d = d;
+                la.kbegin = fwd ? l0 * r : (l + 1) * r; la.kend = fwd ? l * r : l1 * r; la.ctiles = ct64;
+                la.U = pre; la.Gp = ca.Gp; la.chat = chat; la.params = io.params; la.PL = D.PL;
+                la.Hg = fwd ? H : DP; la.ghat = ghat; la.rowsamp = rowsamp;
+                const dim3 grid(rt64 * ct64);
+                if (fwd) {
+                    if (k64) PAC_LAUNCH(prof, st, cls, (k_gseq_layer<true, 64>), grid, dim3(256), small_lds, st, la);
+                    else PAC_LAUNCH(prof, st, cls, (k_gseq_layer<true, 32>), grid, dim3(256), small_lds, st, la);
+                } else {
+                    if (k64) PAC_LAUNCH(prof, st, cls, (k_gseq_layer<false, 64>), grid, dim3(256), small_lds, st, la);
+                    else PAC_LAUNCH(prof, st, cls, (k_gseq_layer<false, 32>), grid, dim3(256), small_lds, st, la);
+                }
+            }
         };
-        for (int l = 0; l < L; ++l) chain_layer(true, l);
+        const int ngroups = cdiv(L, g);
+        for (int q = 0; q < ngroups; ++q) chain_group(true, q * g);
+        PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, k_gseq_colsum, dim3(ntiles, cdiv(Lr, 256)), dim3(256), 0, st, H, Lr, tile_row0,
+                   tile_rows, HSpart);
         PAC_LAUNCH(prof, st, KC_G_HEAD, k_gseq_zpart, dim3(ntiles), dim3(256), 0, st, HSpart, V, Lr, C, zpart);
         PAC_LAUNCH(prof, st, KC_G_HEAD, k_glogits, dim3(B), dim3(64), 0, st, ca);
         if (!io.grads) {
@@ -1751,7 +1846,10 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
                        D.PL, nullptr);
             return hipGetLastError();
         }
-        for (int l = L - 1; l >= 0; --l) chain_layer(false, l);
+        PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, k_gseq_ghat, dim3(cdiv(Lr, 256), B), dim3(256), 0, st, dz, V, samp_len, Lr, C, ghat);
+        for (int q = ngroups - 1; q >= 0; --q) chain_group(false, q * g);
+        PAC_LAUNCH(prof, st, KC_G_CHAIN_BWD, k_gseq_colsum, dim3(ntiles, cdiv(Lr, 256)), dim3(256), 0, st, DP, Lr, tile_row0,
+                   tile_rows, cspart);
     }
     {
         TokRedArgs a;

@@ -37,8 +37,9 @@ struct WsLayout {
     int32_t max_tiles;  // 32-row token tiles at the largest batch
     int32_t pairs;      // L (L - 1) / 2 layer pairs k < l
     int32_t se, sg;     // token splits of the E and Gram contractions
-    int32_t sq;         // largest K split of a per-layer chain contraction
-    int64_t g_P;        // f32 [sq][Mmax][r] partial sums of a per-layer chain contraction
+    int32_t chain_group; // layers per group of the layer-by-layer chains
+    int64_t g_P;        // f32 [Mmax][chain_group * r]: what the layers outside a group contribute to the group's layers
+    int64_t g_ghat;     // f32 [B_max][L*r]
     int64_t g_tile_row0, g_tile_rows, g_tile_samp;
     int64_t g_WuTs, g_Wds;          // bf16 [d][L*r] stacked projection copies
     int64_t g_cusum, g_chat, g_V;   // f32 [L+1][d], [L][r], [L*r][C]
