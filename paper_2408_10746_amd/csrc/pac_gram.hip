@@ -190,6 +190,8 @@ __device__ __forceinline__ int die_group_order(int u, int n, int gs)
 // ---------------------------------------------------------------------------
 // launch 1: batch gather, token tiles, projection copies, cusum/chat, V
 // ---------------------------------------------------------------------------
+constexpr int kPrepTiles = 4; // 32 x 32 tiles of the projection matrices one workgroup of the set-up launch copies
+
 struct PrepArgs {
     int blk_off; // first block of this launch (parts may be launched separately for timing)
     BatchMeta meta;
@@ -208,7 +210,7 @@ struct PrepArgs {
 
 __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
 {
-    __shared__ float sh[32 * 33];
+    __shared__ float sh[kPrepTiles * 32 * 33];
     const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
     const int L = a.L, d = a.d, r = a.r, C = a.C;
     const int64_t Lr = (int64_t)L * r;
@@ -249,35 +251,54 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
         return;
     }
     if (b < a.nb_setup + a.nb_shadow) {
-        // one 32 x 32 tile of W_down^k (which = 0, [d][r]) or W_up^k (which = 1, [r][d])
-        int idx = b - a.nb_setup;
+        // four 32 x 32 tiles of W_down^k (which = 0, [d][r]) or W_up^k (which = 1, [r][d]); all loads first
         const int per_mat = (d / 32) * (r / 32);
-        const int which = idx / (per_mat * L);
-        idx -= which * per_mat * L;
-        const int k = idx / per_mat;
-        idx -= k * per_mat;
-        const int rows = which == 0 ? d : r, cols = which == 0 ? r : d;
-        const int tiles_c = cols / 32;
-        const int tr = idx / tiles_c, tcx = idx % tiles_c;
-        const float *src = a.params + (int64_t)k * a.PL + (which == 0 ? 0 : (int64_t)d * r + r);
-        float(*tile)[33] = reinterpret_cast<float(*)[33]>(sh);
+        const int total = 2 * L * per_mat;
+        const int t0 = (b - a.nb_setup) * kPrepTiles;
         const int tx = t & 31, ty = t >> 5;
-        for (int y = ty; y < 32; y += 8) {
-            const int row = tr * 32 + y, col = tcx * 32 + tx;
-            const float f = src[(int64_t)row * cols + col];
-            tile[y][tx] = f;
-            if (which == 0) a.Wds[(int64_t)row * Lr + (int64_t)k * r + col] = static_cast<bf16_t>(f);
-            else a.Wu[((int64_t)k * r + row) * d + col] = static_cast<bf16_t>(f);
+        float v[kPrepTiles][4];
+        int which[kPrepTiles], kk[kPrepTiles], trr[kPrepTiles], tcc[kPrepTiles];
+#pragma unroll
+        for (int q = 0; q < kPrepTiles; ++q) {
+            int idx = min(t0 + q, total - 1);
+            which[q] = idx / (per_mat * L);
+            idx -= which[q] * per_mat * L;
+            kk[q] = idx / per_mat;
+            idx -= kk[q] * per_mat;
+            const int cols = which[q] == 0 ? r : d;
+            const int tiles_c = cols / 32;
+            trr[q] = idx / tiles_c;
+            tcc[q] = idx % tiles_c;
+            const float *src = a.params + (int64_t)kk[q] * a.PL + (which[q] == 0 ? 0 : (int64_t)d * r + r);
+#pragma unroll
+            for (int yi = 0; yi < 4; ++yi)
+                v[q][yi] = src[(int64_t)(trr[q] * 32 + ty + 8 * yi) * cols + tcc[q] * 32 + tx];
+        }
+        float(*tile)[32][33] = reinterpret_cast<float(*)[32][33]>(sh);
+#pragma unroll
+        for (int q = 0; q < kPrepTiles; ++q) {
+            if (t0 + q >= total) continue;
+#pragma unroll
+            for (int yi = 0; yi < 4; ++yi) {
+                const int y = ty + 8 * yi, row = trr[q] * 32 + y, col = tcc[q] * 32 + tx;
+                tile[q][y][tx] = v[q][yi];
+                if (which[q] == 0) a.Wds[(int64_t)row * Lr + (int64_t)kk[q] * r + col] = static_cast<bf16_t>(v[q][yi]);
+                else a.Wu[((int64_t)kk[q] * r + row) * d + col] = static_cast<bf16_t>(v[q][yi]);
+            }
         }
         __syncthreads();
-        for (int y = ty; y < 32; y += 8) {
-            // element (row = tr*32 + tx, col = tcx*32 + y) written at the transposed position
-            const int row = tr * 32 + tx, col = tcx * 32 + y;
-            const bf16_t v = static_cast<bf16_t>(tile[tx][y]);
-            if (which == 0) a.WdT[((int64_t)k * r + col) * d + row] = v;
-            else a.WuTs[(int64_t)col * Lr + (int64_t)k * r + row] = v;
+#pragma unroll
+        for (int q = 0; q < kPrepTiles; ++q) {
+            if (t0 + q >= total) continue;
+#pragma unroll
+            for (int yi = 0; yi < 4; ++yi) {
+                // element (row = tr*32 + tx, col = tc*32 + y) written at the transposed position
+                const int y = ty + 8 * yi, row = trr[q] * 32 + tx, col = tcc[q] * 32 + y;
+                const bf16_t w = static_cast<bf16_t>(tile[q][tx][y]);
+                if (which[q] == 0) a.WdT[((int64_t)kk[q] * r + col) * d + row] = w;
+                else a.WuTs[(int64_t)col * Lr + (int64_t)kk[q] * r + row] = w;
+            }
         }
-        (void)rows;
         return;
     }
     if (b < a.nb_setup + a.nb_shadow + a.nb_chat) {
@@ -1696,7 +1717,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     {
         PrepArgs a;
         a.meta = meta; a.params = io.params; a.PL = D.PL; a.L = L; a.d = d; a.r = r; a.C = C;
-        a.nb_setup = cdiv(M, 256); a.nb_shadow = (d / 32) * (r / 32) * L * 2; a.nb_chat = cdiv(d, 256);
+        a.nb_setup = cdiv(M, 256); a.nb_shadow = cdiv((int64_t)(d / 32) * (r / 32) * L * 2, kPrepTiles); a.nb_chat = cdiv(d, 256);
         a.rowoff = rowoff; a.rowstride = rowstride; a.rowsamp = rowsamp; a.samp_start = samp_start;
         a.samp_len = samp_len; a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.tile_samp = tile_samp; a.samp_tile0 = samp_tile0;
         a.WdT = WdT; a.Wu = Wu; a.WuTs = WuTs; a.Wds = Wds; a.cusum = cusum; a.V = V;
