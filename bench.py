@@ -21,7 +21,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 def kernel_models(w, M):
-    """Algorithmic work of one launch of each kernel class: (HBM bytes, flops).
+    """Algorithmic work of one step's launches of each kernel class: (HBM bytes, flops).
+    (The per-layer classes launch once per layer; the layer-by-layer chains of the wide-adapter
+    path launch several kernels per layer; every other class is one launch per step.)
 
     Bytes are what the method must move for that piece of the step (cache slab of the layer,
     saved pre-activations, parameters/gradients), not what a particular kernel happens to
@@ -32,13 +34,13 @@ def kernel_models(w, M):
     PL = 2 * d * r + r + d + 1
     pairs = L * (L - 1) // 2
     return {
-        "fwd_down": (slab + pre, 2.0 * M * d * r),
-        "fwd_up": (0, 2.0 * M * d * r),
-        "bwd_dpre": (pre, 2.0 * M * d * r),
-        "bwd_wgrad": (slab + PL * 4, 4.0 * M * d * r),
-        "bwd_dx": (slab, 2.0 * M * d * r),
+        "fwd_down": (L * (slab + pre), 2.0 * M * d * r * L),
+        "fwd_up": (0, 2.0 * M * d * r * L),
+        "bwd_dpre": (L * pre, 2.0 * M * d * r * L),
+        "bwd_wgrad": (L * (slab + PL * 4), 4.0 * M * d * r * L),
+        "bwd_dx": (L * slab, 2.0 * M * d * r * L),
         "adamw": (w.P * 28, 12.0 * w.P),
-        "reduce": (PL * 4, 0.0),
+        "reduce": (L * PL * 4, 0.0),
         "shadows": (w.P * 4, 0.0),
         "pool": (slab, 0.0),
         "head": (B * d * 4, 2.0 * B * d * C),
@@ -151,12 +153,13 @@ def main():
     dom = max((c for c in prof if c in models), key=lambda c: prof[c][0])
     dom_ms, dom_n = prof[dom]
     avg_s = dom_ms * 1e-3 / dom_n
+    step_s = dom_ms * 1e-3 / prof_steps   # all of the class's launches of one step
     abytes, aflops = models[dom]
     if aflops and (abytes == 0 or aflops / abytes > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)):
-        roof = {"bound": "mfma", "achieved": aflops / avg_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+        roof = {"bound": "mfma", "achieved": aflops / step_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s"}
     else:
-        roof = {"bound": "hbm", "achieved": abytes / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+        roof = {"bound": "hbm", "achieved": abytes / step_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["kernel"] = dom
     roof["avg_launch_us"] = avg_s * 1e6

@@ -199,6 +199,7 @@ struct PrepArgs {
     int64_t PL;
     int L, d, r, C;
     int nb_setup, nb_shadow, nb_chat;
+    int v_rpw; // rows of V per wavefront
     int64_t *rowoff;
     int32_t *rowstride, *rowsamp, *samp_start, *samp_len;
     int32_t *tile_row0, *tile_rows, *tile_samp, *samp_tile0;
@@ -322,36 +323,56 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
         return;
     }
     {
-        // V[(k,a)][c] = sum_j W_up^k[a][j] W_cls[j][c]; one wavefront per row
-        const int row = (b - a.nb_setup - a.nb_shadow - a.nb_chat) * 4 + (t >> 6);
-        if (row >= Lr) return;
-        const int k = row / r, aa = row % r, lane = t & 63;
-        const float *wu = a.params + (int64_t)k * a.PL + (int64_t)d * r + r + (int64_t)aa * d;
+        // V[(k,a)][c] = sum_j W_up^k[a][j] W_cls[j][c]; a wavefront takes v_rpw (1 or 4) consecutive rows and
+        // reads each piece of W_cls once for all of them
+        constexpr int kRpw = 4;
+        const int rpw = a.v_rpw;
+        const int row0 = ((b - a.nb_setup - a.nb_shadow - a.nb_chat) * 4 + (t >> 6)) * rpw;
+        if (row0 >= Lr) return;
+        const int lane = t & 63;
         const float *Wc = a.params + (int64_t)L * a.PL;
-        float acc[kMaxClasses];
+        const float *wu[kRpw];
+        float acc[kRpw][kMaxClasses];
 #pragma unroll
-        for (int c = 0; c < kMaxClasses; ++c) acc[c] = 0.f;
+        for (int q = 0; q < kRpw; ++q) {
+            const int row = min(row0 + q, (int)Lr - 1);
+            wu[q] = a.params + (int64_t)(row / r) * a.PL + (int64_t)d * r + r + (int64_t)(row % r) * d;
+#pragma unroll
+            for (int c = 0; c < kMaxClasses; ++c) acc[q][c] = 0.f;
+        }
         // eight columns per lane and round, their loads issued together (d is a multiple of 32)
         for (int j0 = 0; j0 < d; j0 += 64 * 8) {
-            float w[8];
+            float w[kRpw][8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int j = j0 + 64 * u + lane;
-                w[u] = j < d ? wu[j] : 0.f;
-            }
+            for (int q = 0; q < kRpw; ++q)
+                if (q < rpw) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int j = j0 + 64 * u + lane;
+                        w[q][u] = j < d ? wu[q][j] : 0.f;
+                    }
+                }
             for (int c = 0; c < C; ++c) {
                 float wc[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) wc[u] = Wc[(int64_t)min(j0 + 64 * u + lane, d - 1) * C + c];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc[c] += w[u] * wc[u];
+                for (int q = 0; q < kRpw; ++q)
+                    if (q < rpw) {
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) acc[q][c] += w[q][u] * wc[u];
+                    }
             }
         }
-        for (int c = 0; c < C; ++c) {
-            float v = acc[c];
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
-            if (lane == 0) a.V[(int64_t)row * C + c] = v;
+        for (int q = 0; q < kRpw; ++q) {
+            if (q >= rpw || row0 + q >= Lr) continue;
+            for (int c = 0; c < C; ++c) {
+                float v = acc[q][c];
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+                if (lane == 0) a.V[(int64_t)(row0 + q) * C + c] = v;
+            }
         }
     }
 }
@@ -970,12 +991,12 @@ struct SeqBigArgs {
 };
 
 template <int BK> struct SeqShapes {
-    using TB = NtTile<2, 2, 2, 2, BK, 2>; // kSeqTile x kSeqTile
+    using TB = NtTile<4, 2, 1, 2, BK, 2>; // kSeqTile x kSeqTile, eight wavefronts: there is one such workgroup per compute unit
     using TS = NtTile<2, 2, 1, 1, BK, 3>; // 64 x 64 for the short contractions inside a group
     static_assert(TB::BM == kSeqTile && TB::BN == kSeqTile, "tile side of the wide chain contraction");
 };
 
-template <int BK> __global__ __launch_bounds__(256) void k_gseq_big(SeqBigArgs a)
+template <int BK> __global__ __launch_bounds__(512) void k_gseq_big(SeqBigArgs a)
 {
     using TL = typename SeqShapes<BK>::TB;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -1722,7 +1743,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.samp_len = samp_len; a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.tile_samp = tile_samp; a.samp_tile0 = samp_tile0;
         a.WdT = WdT; a.Wu = Wu; a.WuTs = WuTs; a.Wds = Wds; a.cusum = cusum; a.V = V;
         a.counter = counter; a.zero = (float *)(ws + W.g_zero);
-        const int counts[4] = {a.nb_setup, a.nb_shadow, a.nb_chat, cdiv(Lr, 4)};
+        a.v_rpw = Lr >= 4096 ? 4 : 1;
+        const int counts[4] = {a.nb_setup, a.nb_shadow, a.nb_chat, cdiv(Lr, 4 * a.v_rpw)};
         const int classes[4] = {KC_G_PREP_SETUP, KC_G_PREP_COPY, KC_G_PREP_CHAT, KC_G_PREP_V};
         launch_parts(prof, st, split, k_gprep, a, 4, counts, classes, KC_G_PREP, 256);
     }
@@ -1835,8 +1857,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             ba.ctiles = cdiv(ba.ncols, kSeqTile);
             const bool have_big = ba.kend > ba.kbegin;
             if (have_big) {
-                if (k64) PAC_LAUNCH(prof, st, cls, k_gseq_big<64>, dim3(rt128 * ba.ctiles), dim3(256), big_lds, st, ba);
-                else PAC_LAUNCH(prof, st, cls, k_gseq_big<32>, dim3(rt128 * ba.ctiles), dim3(256), big_lds, st, ba);
+                if (k64) PAC_LAUNCH(prof, st, cls, k_gseq_big<64>, dim3(rt128 * ba.ctiles), dim3(512), big_lds, st, ba);
+                else PAC_LAUNCH(prof, st, cls, k_gseq_big<32>, dim3(rt128 * ba.ctiles), dim3(512), big_lds, st, ba);
             }
             for (int q = 0; q < l1 - l0; ++q) {
                 const int l = fwd ? l0 + q : l1 - 1 - q;
