@@ -199,7 +199,6 @@ struct PrepArgs {
     int64_t PL;
     int L, d, r, C;
     int nb_setup, nb_shadow, nb_chat;
-    int v_rpw; // rows of V per wavefront
     int64_t *rowoff;
     int32_t *rowstride, *rowsamp, *samp_start, *samp_len;
     int32_t *tile_row0, *tile_rows, *tile_samp, *samp_tile0;
@@ -209,9 +208,10 @@ struct PrepArgs {
     float *zero; // 64 floats kept at zero for the contractions' empty token slots
 };
 
-__global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
+// TPB weight tiles per workgroup of the copy part, RPW rows of V per wavefront: 1, 1 for small shapes
+template <int TPB, int RPW> __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
 {
-    __shared__ float sh[kPrepTiles * 32 * 33];
+    __shared__ float sh[TPB * 32 * 33];
     const int b = blockIdx.x + a.blk_off, t = threadIdx.x;
     const int L = a.L, d = a.d, r = a.r, C = a.C;
     const int64_t Lr = (int64_t)L * r;
@@ -252,15 +252,15 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
         return;
     }
     if (b < a.nb_setup + a.nb_shadow) {
-        // four 32 x 32 tiles of W_down^k (which = 0, [d][r]) or W_up^k (which = 1, [r][d]); all loads first
+        // TPB 32 x 32 tiles of W_down^k (which = 0, [d][r]) or W_up^k (which = 1, [r][d]); all loads first
         const int per_mat = (d / 32) * (r / 32);
         const int total = 2 * L * per_mat;
-        const int t0 = (b - a.nb_setup) * kPrepTiles;
+        const int t0 = (b - a.nb_setup) * TPB;
         const int tx = t & 31, ty = t >> 5;
-        float v[kPrepTiles][4];
-        int which[kPrepTiles], kk[kPrepTiles], trr[kPrepTiles], tcc[kPrepTiles];
+        float v[TPB][4];
+        int which[TPB], kk[TPB], trr[TPB], tcc[TPB];
 #pragma unroll
-        for (int q = 0; q < kPrepTiles; ++q) {
+        for (int q = 0; q < TPB; ++q) {
             int idx = min(t0 + q, total - 1);
             which[q] = idx / (per_mat * L);
             idx -= which[q] * per_mat * L;
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
         }
         float(*tile)[32][33] = reinterpret_cast<float(*)[32][33]>(sh);
 #pragma unroll
-        for (int q = 0; q < kPrepTiles; ++q) {
+        for (int q = 0; q < TPB; ++q) {
             if (t0 + q >= total) continue;
 #pragma unroll
             for (int yi = 0; yi < 4; ++yi) {
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
         }
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < kPrepTiles; ++q) {
+        for (int q = 0; q < TPB; ++q) {
             if (t0 + q >= total) continue;
 #pragma unroll
             for (int yi = 0; yi < 4; ++yi) {
@@ -323,11 +323,10 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
         return;
     }
     {
-        // V[(k,a)][c] = sum_j W_up^k[a][j] W_cls[j][c]; a wavefront takes v_rpw (1 or 4) consecutive rows and
+        // V[(k,a)][c] = sum_j W_up^k[a][j] W_cls[j][c]; a wavefront takes RPW consecutive rows and
         // reads each piece of W_cls once for all of them
-        constexpr int kRpw = 4;
-        const int rpw = a.v_rpw;
-        const int row0 = ((b - a.nb_setup - a.nb_shadow - a.nb_chat) * 4 + (t >> 6)) * rpw;
+        constexpr int kRpw = RPW;
+        const int row0 = ((b - a.nb_setup - a.nb_shadow - a.nb_chat) * 4 + (t >> 6)) * kRpw;
         if (row0 >= Lr) return;
         const int lane = t & 63;
         const float *Wc = a.params + (int64_t)L * a.PL;
@@ -345,29 +344,29 @@ __global__ __launch_bounds__(256) void k_gprep(PrepArgs a)
             float w[kRpw][8];
 #pragma unroll
             for (int q = 0; q < kRpw; ++q)
-                if (q < rpw) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int j = j0 + 64 * u + lane;
-                        w[q][u] = j < d ? wu[q][j] : 0.f;
-                    }
+                for (int u = 0; u < 8; ++u) {
+                    const int j = j0 + 64 * u + lane;
+                    w[q][u] = j < d ? wu[q][j] : 0.f;
                 }
-            for (int c = 0; c < C; ++c) {
+#pragma unroll
+            for (int c = 0; c < kMaxClasses; ++c) { // (unrolled: the accumulators stay in registers)
+                if (c >= C) continue;
                 float wc[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) wc[u] = Wc[(int64_t)min(j0 + 64 * u + lane, d - 1) * C + c];
 #pragma unroll
                 for (int q = 0; q < kRpw; ++q)
-                    if (q < rpw) {
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) acc[q][c] += w[q][u] * wc[u];
-                    }
+                    for (int u = 0; u < 8; ++u) acc[q][c] += w[q][u] * wc[u];
             }
         }
 #pragma unroll
         for (int q = 0; q < kRpw; ++q) {
-            if (q >= rpw || row0 + q >= Lr) continue;
-            for (int c = 0; c < C; ++c) {
+            if (row0 + q >= Lr) continue;
+#pragma unroll
+            for (int c = 0; c < kMaxClasses; ++c) {
+                if (c >= C) continue;
                 float v = acc[q][c];
 #pragma unroll
                 for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
@@ -392,8 +391,7 @@ struct ProjArgs {
     const float *params;
     int64_t PL;
     float *U;          // [L][M][r]
-    bf16_t *QpN, *QpT; // [pairs][r][r] in fragment-major order, or (q_full) [L*r][L*r] each: see EpiQ
-    int q_full;
+    bf16_t *QpN, *QpT; // [pairs][r][r] in fragment-major order (EpiQ), or (q_full) [L*r][L*r] each (EpiQFull)
     const int32_t *samp_start, *samp_len;
     float *pb; // [B][d]
     int C;
@@ -417,31 +415,29 @@ __device__ __forceinline__ int64_t frag_index(int n, int kk, int r)
 }
 
 struct EpiQ {
-    static constexpr bool kBatched = true;
     bf16_t *qn, *qt;
     int r;
     float one_minus_lam; // of the later layer of the pair: the backward chain uses (1-lambda_l) Q_{kl}
-    // full = false: qn, qt are this pair's r x r blocks in fragment-major order.
-    // full = true:  qn, qt are [L*r][L*r] matrices whose row (layer, n) holds, K-contiguous over (layer', j),
-    //   what the per-layer chain contractions read as their second operand:
-    //   qt[(l, col)][(k, row)] = Q_{kl}[row][col]  and  qn[(k, row)][(l, col)] = (1-lambda_l) Q_{kl}[row][col].
-    bool full;
+    __device__ void operator()(int row, int col, float v) const
+    {
+        qn[frag_index(row, col, r)] = static_cast<bf16_t>(one_minus_lam * v); // backward: B[n=row][kk=col]
+        qt[frag_index(col, row, r)] = static_cast<bf16_t>(v);                 // forward:  B[n=col][kk=row]
+    }
+};
+
+// The layer-by-layer chains read Q from two [L*r][L*r] matrices whose row (layer, n) holds, K-contiguous
+// over (layer', j), the second operand of their contractions:
+//   qt[(l, col)][(k, row)] = Q_{kl}[row][col]  and  qn[(k, row)][(l, col)] = (1-lambda_l) Q_{kl}[row][col].
+struct EpiQFull {
+    static constexpr bool kBatched = true;
+    bf16_t *qn, *qt;
+    int r;
+    float one_minus_lam;
     int k, l;
     int64_t Lr;
     __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
     {
         if (col >= ncols) return;
-        if (!full) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = epi_row(row_base, v);
-                if (row < nrows) {
-                    qn[frag_index(row, col, r)] = static_cast<bf16_t>(one_minus_lam * acc[v]); // backward: B[n=row][kk=col]
-                    qt[frag_index(col, row, r)] = static_cast<bf16_t>(acc[v]);                 // forward:  B[n=col][kk=row]
-                }
-            }
-            return;
-        }
         bf16_t *qt_row = qt + ((int64_t)l * r + col) * Lr + (int64_t)k * r;
         bf16_t *qn_col = qn + (int64_t)k * r * Lr + (int64_t)l * r + col;
 #pragma unroll
@@ -484,7 +480,7 @@ template <int NT, int BK> struct ProjShapes {
     static constexpr int kLds = kA > kB ? kA : kB;
 };
 
-template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArgs a)
+template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(256) void k_gproj(ProjArgs a)
 {
     using SH = ProjShapes<NT, BK>;
     using TU = typename SH::TU;
@@ -522,10 +518,14 @@ template <int NT, int BK> __global__ __launch_bounds__(256) void k_gproj(ProjArg
         const int d = a.d;
         auto arow = [&](int row) { return Wu + (int64_t)row * d; };
         auto brow = [&](int c) { return Wd + (int64_t)c * d; };
-        const int64_t qoff = a.q_full ? 0 : (int64_t)p * a.r * a.r;
-        EpiQ epi{a.QpN + qoff, a.QpT + qoff, a.r, 1.f - a.params[(int64_t)l * a.PL + a.PL - 1],
-                 a.q_full != 0, k, l, (int64_t)a.L * a.r};
-        gemm_nt<TQ>(smem, arow, brow, epi, 0, a.d, (idx / tq) * TQ::BM, (idx % tq) * TQ::BN, a.r, a.r);
+        const float oml = 1.f - a.params[(int64_t)l * a.PL + a.PL - 1];
+        if constexpr (QFULL) {
+            EpiQFull epi{a.QpN, a.QpT, a.r, oml, k, l, (int64_t)a.L * a.r};
+            gemm_nt<TQ>(smem, arow, brow, epi, 0, a.d, (idx / tq) * TQ::BM, (idx % tq) * TQ::BN, a.r, a.r);
+        } else {
+            EpiQ epi{a.QpN + (int64_t)p * a.r * a.r, a.QpT + (int64_t)p * a.r * a.r, a.r, oml};
+            gemm_nt<TQ>(smem, arow, brow, epi, 0, a.d, (idx / tq) * TQ::BM, (idx % tq) * TQ::BN, a.r, a.r);
+        }
         return;
     }
     if (b < a.nb_U + a.nb_Q + a.nb_C) {
@@ -1695,6 +1695,16 @@ static void launch_parts(Profiler *prof, hipStream_t st, bool split, Kern kern, 
     }
 }
 
+// raises a kernel's dynamic LDS limit the first time it is about to be launched
+template <auto Kern> static hipError_t allow_lds_once(int lds)
+{
+    static bool done = false;
+    if (done) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) done = true;
+    return e;
+}
+
 template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io)
 {
     hipStream_t st = io.stream;
@@ -1738,15 +1748,18 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     {
         PrepArgs a;
         a.meta = meta; a.params = io.params; a.PL = D.PL; a.L = L; a.d = d; a.r = r; a.C = C;
-        a.nb_setup = cdiv(M, 256); a.nb_shadow = cdiv((int64_t)(d / 32) * (r / 32) * L * 2, kPrepTiles); a.nb_chat = cdiv(d, 256);
+        a.nb_setup = cdiv(M, 256); // several weight tiles per workgroup only where that still leaves thousands of workgroups
+        const int tpb = (int64_t)(d / 32) * (r / 32) * L * 2 >= 8192 * kPrepTiles ? kPrepTiles : 1;
+        a.nb_shadow = cdiv((int64_t)(d / 32) * (r / 32) * L * 2, tpb); a.nb_chat = cdiv(d, 256);
         a.rowoff = rowoff; a.rowstride = rowstride; a.rowsamp = rowsamp; a.samp_start = samp_start;
         a.samp_len = samp_len; a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.tile_samp = tile_samp; a.samp_tile0 = samp_tile0;
         a.WdT = WdT; a.Wu = Wu; a.WuTs = WuTs; a.Wds = Wds; a.cusum = cusum; a.V = V;
         a.counter = counter; a.zero = (float *)(ws + W.g_zero);
-        a.v_rpw = Lr >= 4096 ? 4 : 1;
-        const int counts[4] = {a.nb_setup, a.nb_shadow, a.nb_chat, cdiv(Lr, 4 * a.v_rpw)};
+        const int v_rpw = tpb == 1 ? 1 : 4;
+        const int counts[4] = {a.nb_setup, a.nb_shadow, a.nb_chat, cdiv(Lr, 4 * v_rpw)};
         const int classes[4] = {KC_G_PREP_SETUP, KC_G_PREP_COPY, KC_G_PREP_CHAT, KC_G_PREP_V};
-        launch_parts(prof, st, split, k_gprep, a, 4, counts, classes, KC_G_PREP, 256);
+        if (tpb == 1) launch_parts(prof, st, split, k_gprep<1, 1>, a, 4, counts, classes, KC_G_PREP, 256);
+        else launch_parts(prof, st, split, k_gprep<kPrepTiles, 4>, a, 4, counts, classes, KC_G_PREP, 256);
     }
     // a launch that was refused leaves the tables the later kernels index with unwritten: stop here
     PAC_HIP_TRY(hipGetLastError());
@@ -1756,31 +1769,24 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         constexpr int kQSide = NT > 4 ? 128 : 64; // ProjShapes<NT, .>::TQ
         a.row_tiles = cdiv(M, 128); a.nb_U = a.row_tiles * L * (NT > 4 ? cdiv(r, 128) : 1);
         a.nb_Q = W.pairs * cdiv(r, kQSide) * cdiv(r, kQSide);
-        a.q_full = W.use_gram == 2;
         a.nb_C = L * cdiv(r, 64);
         a.cusum = cusum; a.chat = chat; a.params = io.params; a.PL = D.PL;
         a.WdT = WdT; a.Wu = Wu; a.U = pre; a.QpN = QpN; a.QpT = QpT;
         a.samp_start = samp_start; a.samp_len = samp_len; a.pb = pb; a.C = C; a.zpbp = zpb;
         const int counts[4] = {a.nb_U, a.nb_Q, a.nb_C, B * cdiv(d, 256)};
         const int classes[4] = {KC_G_PROJ_U, KC_G_PROJ_Q, KC_G_PROJ_Q, KC_G_PROJ_PB};
+        auto launch_proj = [&](auto kern, int lds) {
+            launch_parts(prof, st, split, kern, a, 4, counts, classes, KC_G_PROJ, 256, lds);
+        };
+        const bool q_full = W.use_gram == 2;
         if (d % 64 == 0) {
-            static bool done = false;
-            if (!done) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gproj<NT, 64>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, ProjShapes<NT, 64>::kLds);
-                if (e != hipSuccess) return e;
-                done = true;
-            }
-            launch_parts(prof, st, split, k_gproj<NT, 64>, a, 4, counts, classes, KC_G_PROJ, 256, ProjShapes<NT, 64>::kLds);
+            constexpr int lds = ProjShapes<NT, 64>::kLds;
+            if (q_full) { PAC_HIP_TRY((allow_lds_once<&k_gproj<NT, 64, true>>(lds))); launch_proj(&k_gproj<NT, 64, true>, lds); }
+            else { PAC_HIP_TRY((allow_lds_once<&k_gproj<NT, 64, false>>(lds))); launch_proj(&k_gproj<NT, 64, false>, lds); }
         } else {
-            static bool done = false;
-            if (!done) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gproj<NT, 32>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, ProjShapes<NT, 32>::kLds);
-                if (e != hipSuccess) return e;
-                done = true;
-            }
-            launch_parts(prof, st, split, k_gproj<NT, 32>, a, 4, counts, classes, KC_G_PROJ, 256, ProjShapes<NT, 32>::kLds);
+            constexpr int lds = ProjShapes<NT, 32>::kLds;
+            if (q_full) { PAC_HIP_TRY((allow_lds_once<&k_gproj<NT, 32, true>>(lds))); launch_proj(&k_gproj<NT, 32, true>, lds); }
+            else { PAC_HIP_TRY((allow_lds_once<&k_gproj<NT, 32, false>>(lds))); launch_proj(&k_gproj<NT, 32, false>, lds); }
         }
     }
     PAC_HIP_TRY(hipGetLastError());
