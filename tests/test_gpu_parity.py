@@ -208,10 +208,11 @@ def test_bf16_paths(w, flags):
             assert np.all(grads[sl[nm]] == 0.0), nm
 
 
+@pytest.mark.parametrize("wname", ["g2", "w2"])
 @pytest.mark.parametrize("flags", [0, 1, 4], ids=["gram", "per_layer", "layer_chain"])
-def test_forward_only_call(flags):
+def test_forward_only_call(flags, wname):
     """loss and logits without gradients (no backward launches; the gradient buffer stays untouched)."""
-    w = GRAM[1]
+    w = {x.name: x for x in GRAM + WIDE}[wname]
     lens = inputs.lengths(w)
     ids = np.arange(w.B)
     acts = inputs.batch_acts(w, ids)
@@ -247,7 +248,7 @@ def test_maximum_batch_many_ragged_tiles():
                          what="gmax")
 
 
-@pytest.mark.parametrize("w", [GRAM[1], GRAM[3]], ids=["g2", "g4"])
+@pytest.mark.parametrize("w", [GRAM[1], GRAM[3], WIDE[1], WIDE[2]], ids=["g2", "g4", "w2", "w3"])
 def test_training_step_loss_and_gate_gradients(w):
     """In a training step the optimizer launch does the last two ordered sums (loss, gate gradients):
     both must equal what the gradient call reports, bit for bit, and match the oracle."""
@@ -273,6 +274,22 @@ def test_training_step_loss_and_gate_gradients(w):
     orc.adamw(dims, p, m, v, 1, grads_lg.astype(np.float64),
               orc.AdamW(lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, weight_decay=hp.weight_decay))
     assert np.max(np.abs(sess.params.cpu().numpy() - p)) <= 1e-6
+
+
+def test_wide_adapter_many_ragged_tiles_and_groups():
+    """r = 256 with more layers than two chain groups of four, 40 samples of 1..90 tokens (row tiles of the
+    128-row contractions end inside samples, the last one is short), a single-token sample first and last."""
+    w = Workload("wmax", L=10, d=128, n_max=90, B=40, r=256, C=3, N=40, cache_dtype="bf16", len_lo=1)
+    lens = inputs.lengths(w)
+    lens[0] = lens[-1] = 1
+    lens[1] = 90
+    ids = np.arange(w.B)
+    acts = inputs.batch_acts(w, ids)
+    labels = inputs.labels(w)[ids]
+    sess = make_session(w, lens=lens)
+    sess.cache_fill(ids, acts, lens)
+    check_against_oracle(w, sess, ids, acts, lens, labels, inputs.random_params(w, up_scale=0.5), TOL["bf16"],
+                         what="wmax")
 
 
 def test_outlier_channels_bf16():
@@ -302,8 +319,8 @@ def test_subset_and_order_of_cached_samples():
     check_against_oracle(w, sess, ids, acts[ids], lens[ids], labels, inputs.random_params(w), TOL["f32"], "gather2")
 
 
-def test_bitwise_reproducible():
-    w = SMALL[2]
+@pytest.mark.parametrize("w", [SMALL[2], WIDE[2]], ids=["s3", "w3"])
+def test_bitwise_reproducible(w):
     lens = inputs.lengths(w)
     ids = np.arange(w.B)
     sess = make_session(w, lens=lens)
