@@ -61,8 +61,12 @@ template <int WM_, int WN_, int WTM_, int WTN_, int BK_, int STAGES_> struct NtT
     static_assert(STAGES >= 2 && NI * (STAGES - 1) < 64, "transfers in flight must fit the counter");
 };
 
-// chunk swizzle of an LDS row: 64-byte rows share a 128-byte line in pairs
-template <int BK> __device__ __forceinline__ int nt_swz(int lds_row) { return BK == 64 ? (lds_row & 7) : ((lds_row >> 1) & 3); }
+// Chunk swizzle of an LDS row.  The LDS has 64 banks of 4 bytes, and a 16-byte-per-lane read is served 16 lanes
+// at a time: the 16 consecutive rows those lanes read must land on 16 different 16-byte positions of the
+// 256-byte bank line.  Two 128-byte rows (four 64-byte rows) share a bank line, so the swizzle must differ
+// between rows 2 (4) apart, for 8 (4) such rows.  (With row & 7 rows 8 apart collided: the counters showed
+// every second cycle of the fragment reads as a bank conflict.)
+template <int BK> __device__ __forceinline__ int nt_swz(int lds_row) { return BK == 64 ? ((lds_row >> 1) & 7) : ((lds_row >> 2) & 3); }
 
 // C[row0.., col0..] = sum_{k in [kbegin, kend)} A[row][k] * B[col][k]; (kend - kbegin) % BK == 0.
 // arow(row) / brow(col) return the address of element k = 0 of that row; rows >= nrows and
