@@ -680,24 +680,24 @@ __global__ __launch_bounds__(256) void k_reduce_layer(const float *__restrict__ 
 // ---------------------------------------------------------------------------
 // AdamW over the flat parameter vector
 // ---------------------------------------------------------------------------
-// One element of the update.  When the loss / gate-gradient sums were left to this launch (fin.used),
-// the thread that owns a gate first sums that layer's partials in slot order.
-__device__ __forceinline__ void adamw_elem(int64_t i, float &pi, float &mi, float &vi, float &gi, int64_t PL,
-                                           int64_t dr, int r, int64_t head, int64_t dC, const AdamArgs &a,
+// One element of the update: element o of layer `layer`'s block (layer < L), or element o of the head
+// (layer == L).  When the loss / gate-gradient sums were left to this launch (fin.used), the thread that
+// owns a gate first sums that layer's partials in slot order.
+__device__ __forceinline__ void adamw_elem(int layer, int64_t o, int L, float &pi, float &mi, float &vi, float &gi,
+                                           int64_t PL, int64_t dr, int r, int64_t dC, const AdamArgs &a,
                                            const Deferred &fin)
 {
     bool decayed;
-    if (i < head) {
-        const int64_t o = i % PL;
+    if (layer < L) {
         decayed = (o < dr) || (o >= dr + r && o < 2 * dr + r);
         if (fin.used && o == PL - 1) {
-            const float *part = fin.dlam_part + (i / PL) * fin.slots;
+            const float *part = fin.dlam_part + (int64_t)layer * fin.slots;
             float acc = 0.f;
             for (int s = 0; s < fin.slots; ++s) acc += part[s];
             gi = acc;
         }
     } else {
-        decayed = (i - head) < dC;
+        decayed = o < dC;
     }
     mi = a.beta1 * mi + (1.f - a.beta1) * gi;
     vi = a.beta2 * vi + (1.f - a.beta2) * gi * gi;
@@ -705,7 +705,9 @@ __device__ __forceinline__ void adamw_elem(int64_t i, float &pi, float &mi, floa
     pi -= a.lr * (mi / a.bc1) / (sqrtf(vi / a.bc2) + a.eps);
 }
 
-// VEC = 4: 16-byte accesses (all four arrays 16-byte aligned), the tail element by element
+// VEC = 4: 16-byte accesses (all four arrays 16-byte aligned), the tail element by element.
+// The position of a group's first element inside its layer block takes one division (32-bit where the
+// parameter count allows); the following elements step from it.
 template <int VEC>
 __global__ __launch_bounds__(256) void k_adamw(float *__restrict__ p, float *__restrict__ m, float *__restrict__ v,
                                                float *__restrict__ g, int64_t P, int64_t PL, int L, int d,
@@ -718,9 +720,29 @@ __global__ __launch_bounds__(256) void k_adamw(float *__restrict__ p, float *__r
         for (int s = 0; s < fin.B; ++s) tot += fin.loss_part[s];
         *fin.loss_out = tot / (float)fin.B;
     }
+    const bool small = P < (int64_t(1) << 31);
     const int64_t ngroups = (P + VEC - 1) / VEC;
     for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < ngroups; q += (int64_t)gridDim.x * 256) {
         const int64_t i0 = q * VEC;
+        int layer;
+        int64_t o;
+        if (i0 >= head) {
+            layer = L;
+            o = i0 - head;
+        } else if (small) {
+            layer = (int)((uint32_t)i0 / (uint32_t)PL);
+            o = i0 - (int64_t)layer * PL;
+        } else {
+            layer = (int)(i0 / PL);
+            o = i0 - (int64_t)layer * PL;
+        }
+        auto step = [&]() { // to the next element
+            ++o;
+            if (layer < L && o == PL) {
+                o = 0;
+                ++layer;
+            }
+        };
         if (VEC == 4 && i0 + 3 < P) {
             f32x4 pv = *reinterpret_cast<const f32x4 *>(p + i0), mv = *reinterpret_cast<const f32x4 *>(m + i0);
             f32x4 vv = *reinterpret_cast<const f32x4 *>(v + i0), gv = *reinterpret_cast<const f32x4 *>(g + i0);
@@ -728,8 +750,9 @@ __global__ __launch_bounds__(256) void k_adamw(float *__restrict__ p, float *__r
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float pi = pv[e], mi = mv[e], vi = vv[e], gi = gv[e];
-                adamw_elem(i0 + e, pi, mi, vi, gi, PL, dr, r, head, dC, a, fin);
+                adamw_elem(layer, o, L, pi, mi, vi, gi, PL, dr, r, dC, a, fin);
                 pv[e] = pi; mv[e] = mi; vv[e] = vi; gv[e] = gi;
+                step();
             }
             *reinterpret_cast<f32x4 *>(p + i0) = pv;
             *reinterpret_cast<f32x4 *>(m + i0) = mv;
@@ -740,9 +763,10 @@ __global__ __launch_bounds__(256) void k_adamw(float *__restrict__ p, float *__r
             for (int64_t i = i0; i < P && i < i0 + VEC; ++i) {
                 float pi = p[i], mi = m[i], vi = v[i], gi = g[i];
                 const float g_in = gi;
-                adamw_elem(i, pi, mi, vi, gi, PL, dr, r, head, dC, a, fin);
+                adamw_elem(layer, o, L, pi, mi, vi, gi, PL, dr, r, dC, a, fin);
                 p[i] = pi; m[i] = mi; v[i] = vi;
                 if (gi != g_in) g[i] = gi;
+                step();
             }
         }
     }
