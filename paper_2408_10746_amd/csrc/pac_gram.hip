@@ -88,7 +88,10 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.max_tiles = D.B_max * cdiv(D.n_max, kChainRows);
     W.pairs = D.L * (D.L - 1) / 2;
     const int e_tiles = D.L * cdiv(D.d, kETileCols) * cdiv(D.r, 128);
-    int se = cdiv(288, e_tiles);
+    // Token splits of E (measured): with few tiles (T5-Base-shaped: 72) E's workgroups and the Gram tiles that
+    // run beside them should all be resident at once, two per compute unit; with more tiles than that anyway
+    // (Large-shaped: 192) shorter E workgroups balance better.
+    int se = cdiv(e_tiles >= 128 ? 432 : 288, e_tiles);
     const int max_by_rows = (int)((D.Mmax + 127) / 128);
     if (se > max_by_rows) se = max_by_rows;
     W.se = se < 1 ? 1 : (se > 16 ? 16 : se);
@@ -1187,11 +1190,15 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
     if (b < a.nb_E) {
         // E_l[d-tile] over the 16-token tiles [tl0, tl1) of this split
         const int ect = (a.r + TE::BN - 1) / TE::BN; // column tiles of r (one up to r = 128)
-        const int v = ect > 1 ? die_group_order(b, a.nb_E, 4 * ect * a.se) : b; // the column tiles of a cache tile share a die's L2
-        const int split = v % a.se;
-        const int ct = (v / a.se) % ect;
-        const int it = (v / (a.se * ect)) % a.e_tiles;
-        const int l = v / (a.se * ect * a.e_tiles);
+        // All tiles that contract the same token rows of dpre_l (one layer, one token split: e_tiles x ect tiles)
+        // go to one die, so that those rows cross the fabric once and are then found in that die's L2; numbered
+        // round-robin, every die fetched every layer's dpre for itself (as many bytes again as the cache pass).
+        const int per_group = a.e_tiles * ect;
+        const int v = die_group_order(b, a.nb_E, per_group);
+        const int ct = v % ect;
+        const int it = (v / ect) % a.e_tiles;
+        const int split = (v / per_group) % a.se;
+        const int l = v / (per_group * a.se);
         const int tl0 = split * a.tiles_per_se;
         const int ntl = min(a.ntiles, tl0 + a.tiles_per_se) - tl0;
         for (int q = t; q < ntl; q += 256) {
