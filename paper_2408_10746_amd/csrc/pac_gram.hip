@@ -1153,7 +1153,7 @@ struct TokRedArgs {
     const bf16_t *cache;
     RowMap map;
     int L, d, r;
-    int nb_E, nb_G, e_tiles, se, sg, tiles_per_se, rows_per_sg, tg;
+    int nb_E, nb_G, e_tiles, se, sg, tiles_per_se, rows_per_sg, tg, reverse;
     const int32_t *tile_row0, *tile_rows;
     const void *zeros; // at least 16 zero bytes
     const bf16_t *H, *DP; // [M][L*r]
@@ -1184,7 +1184,9 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     __shared__ int64_t t_aoff[kMaxSplitTiles]; // cache offset of the tile's first row in this layer
     __shared__ int32_t t_m0[kMaxSplitTiles], t_rows[kMaxSplitTiles];
-    const int b = blockIdx.x + a.blk_off, t = threadIdx.x; // (dispatching the small parts first is slower here)
+    // dispatch order (measured): E first where its workgroups and the Gram tiles all fit the chip at once
+    // (T5-Base-shaped), the Gram tiles and the column sums first where they do not (Large-shaped)
+    const int b = (a.reverse ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x) + a.blk_off, t = threadIdx.x;
     const int M = a.map.M;
     const int Lr = a.L * a.r;
     if (b < a.nb_E) {
@@ -1922,6 +1924,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.sg = cdiv(M, a.rows_per_sg);
         a.tg = cdiv(Lr, 128);
         a.nb_E = L * a.e_tiles * cdiv(r, 128) * a.se;
+        a.reverse = NT <= 4 && L * a.e_tiles >= 128;
         a.nb_G = L > 1 ? a.tg * a.tg * a.sg : 0;
         a.H = H; a.DP = DP; a.Epart = Epart; a.GGpart = GGpart;
         a.ntiles = ntiles; a.B = B; a.C = C; a.cspart = cspart; a.HSpart = HSpart; a.dz = dz;
