@@ -98,6 +98,11 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     if (cdiv(W.max_tiles, W.se) > kMaxSplitTiles) W.se = cdiv(W.max_tiles, kMaxSplitTiles); // LDS tile table of k_gtokred
     const int tg = cdiv(Lr, 128);
     int sg = cdiv(256, (int64_t)tg * (tg + 1) / 2);
+    // A power of two: the Gram tiles are numbered with the split fastest and dealt round-robin over the eight
+    // dies, so a die then only ever reads the token rows of its own split(s) of H and DP (with six splits
+    // every die fetched most of both matrices: 63 MB over the fabric for 19 MB of operands).
+    for (int p2 = 1; p2 <= 16; p2 *= 2)
+        if (sg <= p2) { sg = p2; break; }
     if (sg > max_by_rows) sg = max_by_rows;
     W.sg = sg < 1 ? 1 : (sg > 16 ? 16 : sg);
     W.g_zero = take(256);
