@@ -999,12 +999,12 @@ struct SeqBigArgs {
 };
 
 template <int BK> struct SeqShapes {
-    using TB = NtTile<4, 2, 1, 2, BK, 2>; // kSeqTile x kSeqTile, eight wavefronts: there is one such workgroup per compute unit
+    using TB = NtTile<2, 2, 2, 2, BK, 3>; // kSeqTile x kSeqTile, three stages, interleaved sub-steps: there is one such workgroup per compute unit
     using TS = NtTile<2, 2, 1, 1, BK, 3>; // 64 x 64 for the short contractions inside a group
     static_assert(TB::BM == kSeqTile && TB::BN == kSeqTile, "tile side of the wide chain contraction");
 };
 
-template <int BK> __global__ __launch_bounds__(512) void k_gseq_big(SeqBigArgs a)
+template <int BK> __global__ __launch_bounds__(256) void k_gseq_big(SeqBigArgs a)
 {
     using TL = typename SeqShapes<BK>::TB;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -1016,7 +1016,7 @@ template <int BK> __global__ __launch_bounds__(512) void k_gseq_big(SeqBigArgs a
     auto arow = [&](int m) { return A + (int64_t)m * Lr; };
     auto brow = [&](int n) { return Bq + (int64_t)n * Lr; };
     EpiStoreF32 epi{a.P, a.ldp};
-    gemm_nt<TL>(smem, arow, brow, epi, a.kbegin, a.kend, rt * kSeqTile, ct * kSeqTile, a.M, a.ncols);
+    gemm_nt<TL, true>(smem, arow, brow, epi, a.kbegin, a.kend, rt * kSeqTile, ct * kSeqTile, a.M, a.ncols);
 }
 
 struct SeqLayerArgs {
@@ -1877,8 +1877,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             ba.ctiles = cdiv(ba.ncols, kSeqTile);
             const bool have_big = ba.kend > ba.kbegin;
             if (have_big) {
-                if (k64) PAC_LAUNCH(prof, st, cls, k_gseq_big<64>, dim3(rt128 * ba.ctiles), dim3(512), big_lds, st, ba);
-                else PAC_LAUNCH(prof, st, cls, k_gseq_big<32>, dim3(rt128 * ba.ctiles), dim3(512), big_lds, st, ba);
+                if (k64) PAC_LAUNCH(prof, st, cls, k_gseq_big<64>, dim3(rt128 * ba.ctiles), dim3(256), big_lds, st, ba);
+                else PAC_LAUNCH(prof, st, cls, k_gseq_big<32>, dim3(rt128 * ba.ctiles), dim3(256), big_lds, st, ba);
             }
             for (int q = 0; q < l1 - l0; ++q) {
                 const int l = fwd ? l0 + q : l1 - 1 - q;
