@@ -479,16 +479,18 @@ using T64K = Tile<2, 2, 1, 1, 4>; // 128-token K step for the token contractions
 // better than deeper rings in fewer workgroups (measured both ways).
 template <int NT, int BK> struct ProjShapes {
     static constexpr bool BIG = NT > 4;
-    using T128 = NtTile<2, 2, 2, 2, BK, 2>;
-    using TU = typename std::conditional<BIG, T128, NtTile<4, 1, 1, (BIG ? 1 : NT), BK, 2>>::type; // 128 token rows x r (or 128)
-    using TQ = typename std::conditional<BIG, T128, NtTile<2, 2, 1, 1, BK, 3>>::type;              // 64 x 64 (or 128 x 128)
+    // r > 128: 128 x 256 tiles (all of r), eight wavefronts, three stages, interleaved sub-steps; one workgroup per CU
+    using TBig = NtTile<2, 4, 2, 2, BK, 3>;
+    using TU = typename std::conditional<BIG, TBig, NtTile<4, 1, 1, (BIG ? 1 : NT), BK, 2>>::type; // 128 token rows x r
+    using TQ = typename std::conditional<BIG, TBig, NtTile<2, 2, 1, 1, BK, 3>>::type;              // 64 x 64 (or 128 x 256)
+    static constexpr int kThreadsPerBlock = BIG ? 512 : 256;
     using TC = Tile<2, 2, 1, 1, BK / 32>;   // the one-row chat contraction (staged through registers)
     static constexpr int kA = TU::LDS_BYTES > TQ::LDS_BYTES ? TU::LDS_BYTES : TQ::LDS_BYTES;
     static constexpr int kB = tile_lds_bytes<bf16_t, TC>() > 8 * 256 * 4 ? tile_lds_bytes<bf16_t, TC>() : 8 * 256 * 4;
     static constexpr int kLds = kA > kB ? kA : kB;
 };
 
-template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(256) void k_gproj(ProjArgs a)
+template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(NT > 4 ? 512 : 256) void k_gproj(ProjArgs a)
 {
     using SH = ProjShapes<NT, BK>;
     using TU = typename SH::TU;
@@ -510,14 +512,14 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(256) void k_g
         auto arow = [&](int m) { return cache + map.rowoff[m] + (int64_t)l * map.rowstride[m]; };
         auto brow = [&](int c) { return W + (int64_t)c * d; };
         EpiStoreF32 epi{a.U + (int64_t)l * a.map.M * a.r, a.r};
-        gemm_nt<TU>(smem, arow, brow, epi, 0, a.d, mt * TU::BM, ct * TU::BN, a.map.M, a.r);
+        gemm_nt<TU, SH::BIG>(smem, arow, brow, epi, 0, a.d, mt * TU::BM, ct * TU::BN, a.map.M, a.r);
         return;
     }
-    const int tq = (a.r + TQ::BM - 1) / TQ::BM, tc64 = (a.r + 63) / 64;
+    const int tqm = (a.r + TQ::BM - 1) / TQ::BM, tqn = (a.r + TQ::BN - 1) / TQ::BN, tq2 = tqm * tqn, tc64 = (a.r + 63) / 64;
     if (b < a.nb_U + a.nb_Q) {
-        int idx = SH::BIG ? die_group_order(b - a.nb_U, a.nb_Q, 2 * tq * tq) : b - a.nb_U;
-        const int p = idx / (tq * tq);
-        idx -= p * tq * tq;
+        int idx = SH::BIG ? die_group_order(b - a.nb_U, a.nb_Q, 2 * tq2) : b - a.nb_U;
+        const int p = idx / tq2;
+        idx -= p * tq2;
         // pair p = (k, l), k < l
         int l = 1;
         while ((l + 1) * l / 2 <= p) ++l;
@@ -529,15 +531,16 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(256) void k_g
         const float oml = 1.f - a.params[(int64_t)l * a.PL + a.PL - 1];
         if constexpr (QFULL) {
             EpiQFull epi{a.QpN, a.QpT, a.r, oml, k, l, (int64_t)a.L * a.r};
-            gemm_nt<TQ>(smem, arow, brow, epi, 0, a.d, (idx / tq) * TQ::BM, (idx % tq) * TQ::BN, a.r, a.r);
+            gemm_nt<TQ, SH::BIG>(smem, arow, brow, epi, 0, a.d, (idx / tqn) * TQ::BM, (idx % tqn) * TQ::BN, a.r, a.r);
         } else {
             EpiQ epi{a.QpN + (int64_t)p * a.r * a.r, a.QpT + (int64_t)p * a.r * a.r, a.r, oml};
-            gemm_nt<TQ>(smem, arow, brow, epi, 0, a.d, (idx / tq) * TQ::BM, (idx % tq) * TQ::BN, a.r, a.r);
+            gemm_nt<TQ, SH::BIG>(smem, arow, brow, epi, 0, a.d, (idx / tqn) * TQ::BM, (idx % tqn) * TQ::BN, a.r, a.r);
         }
         return;
     }
     if (b < a.nb_U + a.nb_Q + a.nb_C) {
-        // chat_l = cusum_l W_down^l: a one-row contraction on the same tile code
+        // chat_l = cusum_l W_down^l: a one-row contraction on the same tile code (four wavefronts)
+        if (SH::BIG && threadIdx.x >= 256) return;
         const int idx = b - a.nb_U - a.nb_Q;
         const int l = idx / tc64, nt = idx % tc64;
         LoadRowsF32<bf16_t, 64, KU> al;
@@ -552,6 +555,7 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(256) void k_g
         // mean over the valid tokens of the last cached layer: 8 token groups x 32 column chunks.
         // The tokens of a sample are consecutive rows of one block, so one table lookup gives them all;
         // eight rows are requested per round.
+        if (SH::BIG && threadIdx.x >= 256) return;
         int idx = b - a.nb_U - a.nb_Q - a.nb_C;
         const int jt = (a.d + 255) / 256;
         const int s = idx / jt, j0 = (idx % jt) * 256;
@@ -1475,31 +1479,34 @@ template <int CC> __device__ __forceinline__ void zrows(const float *Z, const Ch
 }
 
 template <int BK, bool BIG> struct PostShapes {
-    // 64 x 64 with 64 KB of stages, or (r > 128) 128 x 128 with two stages
-    using TF = typename std::conditional<BIG, NtTile<2, 2, 2, 2, BK, 2>, NtTile<2, 2, 1, 1, BK, BK == 64 ? 4 : 8>>::type;
-    static constexpr int TS = TF::BM; // tile side
+    // 64 x 64 with 64 KB of stages; or (r > 128) eight wavefronts, three stages, interleaved sub-steps:
+    // 128 rows of d x 256 columns of r for F, 256 rows of r x 128 columns of d for W
+    using TSmall = NtTile<2, 2, 1, 1, BK, BK == 64 ? 4 : 8>;
+    using TFF = typename std::conditional<BIG, NtTile<2, 4, 2, 2, BK, 3>, TSmall>::type;
+    using TFW = typename std::conditional<BIG, NtTile<4, 2, 2, 2, BK, 3>, TSmall>::type;
     static constexpr int NH = BIG ? 4 : 2; // threads sharing one r-wide row in the vector part
-    static_assert(TF::BM == TF::BN, "square tiles");
+    static constexpr int kThreadsPerBlock = BIG ? 512 : 256;
     static constexpr int kVecLds = 128 * 4 + 128 * kMaxClasses * 4 + kMaxBatch * kMaxClasses * 4;
-    static constexpr int kLds = TF::LDS_BYTES;
+    static constexpr int kLds = TFF::LDS_BYTES > TFW::LDS_BYTES ? TFF::LDS_BYTES : TFW::LDS_BYTES;
     static_assert(kLds >= kVecLds, "LDS budget of the gradient kernel");
 };
 
 // BK = 64 when r is a multiple of 64, else 32: every K range below is a multiple of r
-template <int BK, bool BIG> __global__ __launch_bounds__(256) void k_gpost(PostArgs a)
+template <int BK, bool BIG> __global__ __launch_bounds__(BIG ? 512 : 256) void k_gpost(PostArgs a)
 {
-    using TF = typename PostShapes<BK, BIG>::TF;
+    using TFF = typename PostShapes<BK, BIG>::TFF;
+    using TFW = typename PostShapes<BK, BIG>::TFW;
     constexpr int kVecLds = PostShapes<BK, BIG>::kVecLds;
     constexpr int kLds = PostShapes<BK, BIG>::kLds;
-    constexpr int TS = PostShapes<BK, BIG>::TS, NH = PostShapes<BK, BIG>::NH;
+    constexpr int NH = PostShapes<BK, BIG>::NH;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     __shared__ float red[16];
     const int L = a.L, d = a.d, r = a.r, C = a.C;
     const int Lr = L * r;
     const int64_t dr = (int64_t)d * r;
     const int b = (int)(gridDim.x - 1 - blockIdx.x) + a.blk_off, t = threadIdx.x; // reverse dispatch, as in k_gproj
-    const int ti_d = (d + TS - 1) / TS, ti_r = (r + TS - 1) / TS;
     if (b < a.nb_F) {
+        const int ti_d = (d + TFF::BM - 1) / TFF::BM, ti_r = (r + TFF::BN - 1) / TFF::BN;
         // F_l = sum_{k<l} W_up^{kT} G_{kl}   ([d] x [l*r] times [l*r] x [r])
         const int v = BIG ? die_group_order(b, a.nb_F, 8) : b;
         const int l = v / (ti_d * ti_r);
@@ -1511,13 +1518,14 @@ template <int BK, bool BIG> __global__ __launch_bounds__(256) void k_gpost(PostA
         auto brow = [&](int c) { return B + (int64_t)c * Lr; };
         EpiF epi{a.Epart + (int64_t)l * dr, a.se, (int64_t)L * dr, a.cusum + (int64_t)l * d, a.cs + (int64_t)l * r,
                  pl, a.grads + (int64_t)l * a.PL, r, pl[a.PL - 1], 0.f};
-        gemm_nt<TF>(smem, arow, brow, epi, 0, l * r, it * TS, nt * TS, d, r);
+        gemm_nt<TFF, BIG>(smem, arow, brow, epi, 0, l * r, it * TFF::BM, nt * TFF::BN, d, r);
         const float tot = block_sum(epi.dlam, red);
         if (t == 0) a.dlam_part[(int64_t)l * a.slots + slot] = tot; // summed in slot order by k_gfinish
         return;
     }
     if (b < a.nb_F + a.nb_W) {
         // dW_up^l = Z_l W_cls^T + sum_{k>l} (1-lambda_k) G_{lk} W_down^{kT}
+        const int ti_r = (r + TFW::BM - 1) / TFW::BM, ti_d = (d + TFW::BN - 1) / TFW::BN;
         int idx = BIG ? die_group_order(b - a.nb_F, a.nb_W, 8) : b - a.nb_F;
         const int l = idx / (ti_d * ti_r);
         idx %= ti_d * ti_r;
@@ -1528,9 +1536,10 @@ template <int BK, bool BIG> __global__ __launch_bounds__(256) void k_gpost(PostA
         auto brow = [&](int c) { return B + (int64_t)c * Lr; };
         EpiW epi{a.Z + (int64_t)l * r * C, a.params + (int64_t)L * a.PL,
                  a.grads + (int64_t)l * a.PL + dr + r, d, C};
-        gemm_nt<TF>(smem, arow, brow, epi, (l + 1) * r, Lr, at * TS, jt * TS, r, d);
+        gemm_nt<TFW, BIG>(smem, arow, brow, epi, (l + 1) * r, Lr, at * TFW::BM, jt * TFW::BN, r, d);
         return;
     }
+    if (BIG && t >= 256) return; // the remaining parts are written for four wavefronts
     const int vb = b - a.nb_F - a.nb_W;
     if (vb < a.nb_vec - 1) {
         // thread (jj, k, hf): hidden index j = vb * jpb + jj, layer k, part hf (of NH) of the r-wide rows
@@ -1780,9 +1789,10 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     {
         ProjArgs a;
         a.cache = cache; a.map = map; a.L = L; a.d = d; a.r = r; a.B = B;
-        constexpr int kQSide = NT > 4 ? 128 : 64; // ProjShapes<NT, .>::TQ
-        a.row_tiles = cdiv(M, 128); a.nb_U = a.row_tiles * L * (NT > 4 ? cdiv(r, 128) : 1);
-        a.nb_Q = W.pairs * cdiv(r, kQSide) * cdiv(r, kQSide);
+        constexpr int kQRows = NT > 4 ? 128 : 64, kQCols = NT > 4 ? 256 : 64; // ProjShapes<NT, .>::TQ
+        constexpr int kProjThreads = NT > 4 ? 512 : 256;
+        a.row_tiles = cdiv(M, 128); a.nb_U = a.row_tiles * L * (NT > 4 ? cdiv(r, 256) : 1);
+        a.nb_Q = W.pairs * cdiv(r, kQRows) * cdiv(r, kQCols);
         a.nb_C = L * cdiv(r, 64);
         a.cusum = cusum; a.chat = chat; a.params = io.params; a.PL = D.PL;
         a.WdT = WdT; a.Wu = Wu; a.U = pre; a.QpN = QpN; a.QpT = QpT;
@@ -1790,7 +1800,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         const int counts[4] = {a.nb_U, a.nb_Q, a.nb_C, B * cdiv(d, 256)};
         const int classes[4] = {KC_G_PROJ_U, KC_G_PROJ_Q, KC_G_PROJ_Q, KC_G_PROJ_PB};
         auto launch_proj = [&](auto kern, int lds) {
-            launch_parts(prof, st, split, kern, a, 4, counts, classes, KC_G_PROJ, 256, lds);
+            launch_parts(prof, st, split, kern, a, 4, counts, classes, KC_G_PROJ, kProjThreads, lds);
         };
         const bool q_full = W.use_gram == 2;
         if (d % 64 == 0) {
@@ -1949,12 +1959,15 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         PostArgs pa;
         pa.L = L; pa.d = d; pa.r = r; pa.C = C; pa.B = B; pa.se = 1;
         constexpr bool BIG = NT > 4;
-        constexpr int TS = BIG ? 128 : 64, NH = BIG ? 4 : 2; // PostShapes<., BIG>
-        pa.nb_F = L * cdiv(d, TS) * cdiv(r, TS); pa.nb_W = pa.nb_F; pa.nb_vec = cdiv(d, (256 / NH) / L) + 1;
+        constexpr int NH = BIG ? 4 : 2; // PostShapes<., BIG>
+        constexpr int kFRows = BIG ? 128 : 64, kFCols = BIG ? 256 : 64, kWRows = BIG ? 256 : 64, kWCols = BIG ? 128 : 64;
+        constexpr int kPostThreads = BIG ? 512 : 256;
+        pa.nb_F = L * cdiv(d, kFRows) * cdiv(r, kFCols); pa.nb_W = L * cdiv(r, kWRows) * cdiv(d, kWCols);
+        pa.nb_vec = cdiv(d, (256 / NH) / L) + 1;
         pa.params = io.params; pa.PL = D.PL; pa.WuTs = WuTs; pa.Wds = Wds; pa.GGT = GGT; pa.GGsc = GGsc;
         pa.Epart = (const float *)(ws + W.g_E); pa.cusum = cusum; pa.cs = cs; pa.Z = Z; pa.dzsum = dzsum; pa.dz = dz; pa.pb = pb;
         pa.grads = io.grads; pa.dlam_part = dlam_part; pa.counter = counter;
-        pa.slots = cdiv(d, TS) * cdiv(r, TS);
+        pa.slots = cdiv(d, kFRows) * cdiv(r, kFCols);
         {
             const int counts[3] = {pa.nb_F, pa.nb_W, pa.nb_vec};
             const int classes[3] = {KC_G_POST_F, KC_G_POST_W, KC_G_POST_VEC};
@@ -1969,9 +1982,9 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
                 done = true;
             }
             if (r % 64 == 0)
-                launch_parts(prof, st, split, k_gpost<64, BIG>, pa, 3, counts, classes, KC_G_POST, 256, PostShapes<64, BIG>::kLds);
+                launch_parts(prof, st, split, k_gpost<64, BIG>, pa, 3, counts, classes, KC_G_POST, kPostThreads, PostShapes<64, BIG>::kLds);
             else
-                launch_parts(prof, st, split, k_gpost<32, BIG>, pa, 3, counts, classes, KC_G_POST, 256, PostShapes<32, BIG>::kLds);
+                launch_parts(prof, st, split, k_gpost<32, BIG>, pa, 3, counts, classes, KC_G_POST, kPostThreads, PostShapes<32, BIG>::kLds);
         }
         if (io.defer) { // the optimizer launch that follows does the last two sums
             io.defer->used = true;
