@@ -531,10 +531,10 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(NT > 4 ? 512 
         const float oml = 1.f - a.params[(int64_t)l * a.PL + a.PL - 1];
         if constexpr (QFULL) {
             EpiQFull epi{a.QpN, a.QpT, a.r, oml, k, l, (int64_t)a.L * a.r};
-            gemm_nt<TQ, SH::BIG>(smem, arow, brow, epi, 0, a.d, (idx / tqn) * TQ::BM, (idx % tqn) * TQ::BN, a.r, a.r);
+            gemm_nt<TQ, true>(smem, arow, brow, epi, 0, a.d, (idx / tqn) * TQ::BM, (idx % tqn) * TQ::BN, a.r, a.r);
         } else {
             EpiQ epi{a.QpN + (int64_t)p * a.r * a.r, a.QpT + (int64_t)p * a.r * a.r, a.r, oml};
-            gemm_nt<TQ, SH::BIG>(smem, arow, brow, epi, 0, a.d, (idx / tqn) * TQ::BM, (idx % tqn) * TQ::BN, a.r, a.r);
+            gemm_nt<TQ, true>(smem, arow, brow, epi, 0, a.d, (idx / tqn) * TQ::BM, (idx % tqn) * TQ::BN, a.r, a.r);
         }
         return;
     }
@@ -1518,7 +1518,7 @@ template <int BK, bool BIG> __global__ __launch_bounds__(BIG ? 512 : 256) void k
         auto brow = [&](int c) { return B + (int64_t)c * Lr; };
         EpiF epi{a.Epart + (int64_t)l * dr, a.se, (int64_t)L * dr, a.cusum + (int64_t)l * d, a.cs + (int64_t)l * r,
                  pl, a.grads + (int64_t)l * a.PL, r, pl[a.PL - 1], 0.f};
-        gemm_nt<TFF, BIG>(smem, arow, brow, epi, 0, l * r, it * TFF::BM, nt * TFF::BN, d, r);
+        gemm_nt<TFF, true>(smem, arow, brow, epi, 0, l * r, it * TFF::BM, nt * TFF::BN, d, r);
         const float tot = block_sum(epi.dlam, red);
         if (t == 0) a.dlam_part[(int64_t)l * a.slots + slot] = tot; // summed in slot order by k_gfinish
         return;
@@ -1536,7 +1536,7 @@ template <int BK, bool BIG> __global__ __launch_bounds__(BIG ? 512 : 256) void k
         auto brow = [&](int c) { return B + (int64_t)c * Lr; };
         EpiW epi{a.Z + (int64_t)l * r * C, a.params + (int64_t)L * a.PL,
                  a.grads + (int64_t)l * a.PL + dr + r, d, C};
-        gemm_nt<TFW, BIG>(smem, arow, brow, epi, (l + 1) * r, Lr, at * TFW::BM, jt * TFW::BN, r, d);
+        gemm_nt<TFW, true>(smem, arow, brow, epi, (l + 1) * r, Lr, at * TFW::BM, jt * TFW::BN, r, d);
         return;
     }
     if (BIG && t >= 256) return; // the remaining parts are written for four wavefronts
