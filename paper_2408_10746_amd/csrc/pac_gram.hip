@@ -1233,7 +1233,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
             return dp + (int64_t)(t_m0[tl] + row) * Lr;
         };
         EpiStoreF32 epi{a.Epart + ((int64_t)split * a.L + l) * a.d * a.r, a.r};
-        gemm_tn<TE>(smem, atok, btok, a.zeros, epi, (ntl * 16 + kTokKT - 1) / kTokKT, it * TE::BM, ct * TE::BN, a.d, a.r, a.d, a.r);
+        gemm_tn<TE, true>(smem, atok, btok, a.zeros, epi, (ntl * 16 + kTokKT - 1) / kTokKT, it * TE::BM, ct * TE::BN, a.d, a.r, a.d, a.r);
         return;
     }
     if (b < a.nb_E + a.nb_G) {
@@ -1258,7 +1258,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
             return k < kend ? DP + (int64_t)k * Lr : nullptr;
         };
         EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
-        gemm_tn<TG>(smem, atok, btok, a.zeros, epi, (kend - kbegin + kTokKT - 1) / kTokKT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
+        gemm_tn<TG, true>(smem, atok, btok, a.zeros, epi, (kend - kbegin + kTokKT - 1) / kTokKT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
         return;
     }
     // cs[kk] = sum over the tiles of their column sums of dpre ;

@@ -227,7 +227,8 @@ __device__ __forceinline__ bf16x8 tr_read2(const char *p0, const char *p1)
     return __builtin_bit_cast(bf16x8, v);
 }
 
-template <class TL, class ATok, class BTok, class Epi>
+// PIPE: as in gemm_nt, the 16-token sub-steps of a stage interleave transfer issue, fragment reads and matrix instructions
+template <class TL, bool PIPE = false, class ATok, class BTok, class Epi>
 __device__ __forceinline__ void gemm_tn(char *lds /* TL::LDS_BYTES, 1 KB aligned */, const ATok &atok, const BTok &btok,
                                         const void *zeros, Epi &epi, int nsteps, int row0, int col0, int a_ncols,
                                         int b_ncols, int nrows, int ncols)
@@ -296,6 +297,35 @@ __device__ __forceinline__ void gemm_tn(char *lds /* TL::LDS_BYTES, 1 KB aligned
         for (int st = 0; st < nsteps; ++st) {
             wait_vm<TL::NI * (TL::STAGES - 2)>(); // this wavefront's share of stage st has landed
             __syncthreads();                       // ... and everybody else's; stage st-1 is free
+            if constexpr (PIPE) {
+                const int nslot = slot == 0 ? TL::STAGES - 1 : slot - 1;
+                const char *sb = lds + slot * TL::STAGE_BYTES;
+                constexpr int KS = TL::KT / 16;
+                bf16x8 a[2][TL::WTM], b[2][TL::WTN];
+                auto rd = [&](int ks) {
+#pragma unroll
+                    for (int x = 0; x < TL::WTM; ++x)
+                        a[ks & 1][x] = tr_read2(sb + aoff[x] + ks * 2048, sb + aoff[x] + ks * 2048 + 512);
+#pragma unroll
+                    for (int y = 0; y < TL::WTN; ++y)
+                        b[ks & 1][y] = tr_read2(sb + boff[y] + ks * 2048, sb + boff[y] + ks * 2048 + 512);
+                };
+                rd(0);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    if (ks + 1 < KS) rd(ks + 1);
+#pragma unroll
+                    for (int q = ks * TL::NI / KS; q < (ks + 1) * TL::NI / KS; ++q)
+                        dma16(nxt[q], lds + nslot * TL::STAGE_BYTES + pan[q] * TL::PANEL_BYTES + grp[q] * 1024);
+#pragma unroll
+                    for (int x = 0; x < TL::WTM; ++x)
+#pragma unroll
+                        for (int y = 0; y < TL::WTN; ++y)
+                            acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][x], b[ks & 1][y], acc[x][y], 0, 0, 0);
+                }
+#pragma unroll
+                for (int q = 0; q < TL::NI; ++q) nxt[q] = source(q, st + TL::STAGES);
+            } else {
             issue(slot == 0 ? TL::STAGES - 1 : slot - 1);
 #pragma unroll
             for (int q = 0; q < TL::NI; ++q) nxt[q] = source(q, st + TL::STAGES);
@@ -319,6 +349,7 @@ __device__ __forceinline__ void gemm_tn(char *lds /* TL::LDS_BYTES, 1 KB aligned
 #pragma unroll
                     for (int y = 0; y < TL::WTN; ++y)
                         acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][x], b[ks][y], acc[x][y], 0, 0, 0);
+            }
             slot = slot + 1 == TL::STAGES ? 0 : slot + 1;
         }
         wait_vm<0>(); // the repeated transfers of the last steps must not outlive this use of the LDS
