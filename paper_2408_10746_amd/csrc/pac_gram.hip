@@ -1162,7 +1162,7 @@ struct TokRedArgs {
     const bf16_t *cache;
     RowMap map;
     int L, d, r;
-    int nb_E, nb_G, e_tiles, se, sg, tiles_per_se, rows_per_sg, tg, reverse;
+    int nb_E, nb_G, e_tiles, se, sg, tiles_per_se, rows_per_sg, tg, tgn, reverse; // tg x tgn tiles of the Gram matrix
     const int32_t *tile_row0, *tile_rows;
     const void *zeros; // at least 16 zero bytes
     const bf16_t *H, *DP; // [M][L*r]
@@ -1178,18 +1178,22 @@ struct TokRedArgs {
 
 constexpr int kTokStages = 4;
 constexpr int kTokKT = 32;    // tokens per stage of the token contractions (a multiple of 16)
-using TG = TnTile<2, 2, 2, 2, kTokKT, kTokStages>; // 128 x 128 tile of the Gram matrix
-
 template <int NT> struct TokRedShapes {
-    using TE = TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), kTokKT, kTokStages>; // kETileCols columns of d x 64 or 128 of r
+    static constexpr bool BIG = NT > 4;
+    // r > 128: 128 x 256 tiles, eight wavefronts, three stages (E then covers all of r: the cache is read once)
+    using TBig = TnTile<2, 4, 2, 2, kTokKT, 3>;
+    using TE = typename std::conditional<BIG, TBig, TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), kTokKT, kTokStages>>::type; // kETileCols columns of d x 64 or 128 (or 256) of r
+    using TG = typename std::conditional<BIG, TBig, TnTile<2, 2, 2, 2, kTokKT, kTokStages>>::type; // tile of the Gram matrix
+    static constexpr int kThreadsPerBlock = BIG ? 512 : 256;
     static constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4 + kMaxTiles * 4 + kMaxBatch * kMaxClasses * 4; // + tile and sample tables
     static constexpr int kTileLds = TE::LDS_BYTES > TG::LDS_BYTES ? TE::LDS_BYTES : TG::LDS_BYTES;
     static constexpr int kLds = kTileLds > kVecLds ? kTileLds : kVecLds;
 };
 
-template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
+template <int NT> __global__ __launch_bounds__(NT > 4 ? 512 : 256) void k_gtokred(TokRedArgs a)
 {
     using TE = typename TokRedShapes<NT>::TE;
+    using TG = typename TokRedShapes<NT>::TG;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     __shared__ int64_t t_aoff[kMaxSplitTiles]; // cache offset of the tile's first row in this layer
     __shared__ int32_t t_m0[kMaxSplitTiles], t_rows[kMaxSplitTiles];
@@ -1212,7 +1216,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         const int l = v / (per_group * a.se);
         const int tl0 = split * a.tiles_per_se;
         const int ntl = min(a.ntiles, tl0 + a.tiles_per_se) - tl0;
-        for (int q = t; q < ntl; q += 256) {
+        for (int q = t; q < ntl; q += (int)blockDim.x) {
             const int m0 = a.tile_row0[tl0 + q];
             t_m0[q] = m0;
             t_rows[q] = a.tile_rows[tl0 + q];
@@ -1241,7 +1245,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
         // (numbered row-major, a die sees every eighth column panel of DP only: already local to its L2)
         const int split = idx % a.sg;
         idx /= a.sg;
-        const int ti = idx / a.tg, tj = idx % a.tg;
+        const int ti = idx / a.tgn, tj = idx % a.tgn;
         // needed only where some row layer is below some column layer
         const int kmin = (ti * TG::BM) / a.r;
         const int lmax = min(Lr - 1, tj * TG::BN + TG::BN - 1) / a.r;
@@ -1264,6 +1268,7 @@ template <int NT> __global__ __launch_bounds__(256) void k_gtokred(TokRedArgs a)
     // cs[kk] = sum over the tiles of their column sums of dpre ;
     // Z[kk][c] = sum_s mean_t(h)[s][kk] dz[s][c], from the tiles' column sums of h.
     // 16 indices per block, the tiles dealt over 16 thread groups whose sums are combined in group order.
+    if (TokRedShapes<NT>::BIG && t >= 256) return; // this part is written for four wavefronts
     const int C = a.C;
     float *red = reinterpret_cast<float *>(smem); // [16 groups][16 indices][1 + kMaxClasses]
     const int vb = b - a.nb_E - a.nb_G;
@@ -1938,16 +1943,17 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.rows_per_sg = cdiv(cdiv(M, W.sg), 128) * 128;
         a.sg = cdiv(M, a.rows_per_sg);
         a.tg = cdiv(Lr, 128);
-        a.nb_E = L * a.e_tiles * cdiv(r, 128) * a.se;
+        a.tgn = cdiv(Lr, NT > 4 ? 256 : 128);
+        a.nb_E = L * a.e_tiles * cdiv(r, NT > 4 ? 256 : 128) * a.se;
         a.reverse = NT <= 4 && L * a.e_tiles >= 128;
-        a.nb_G = L > 1 ? a.tg * a.tg * a.sg : 0;
+        a.nb_G = L > 1 ? a.tg * a.tgn * a.sg : 0;
         a.H = H; a.DP = DP; a.Epart = Epart; a.GGpart = GGpart;
         a.ntiles = ntiles; a.B = B; a.C = C; a.cspart = cspart; a.HSpart = HSpart; a.dz = dz;
         a.tile_samp = tile_samp; a.samp_len = samp_len; a.cs = cs; a.Z = Z; a.dzsum = dzsum;
         {
             const int counts[3] = {a.nb_E, a.nb_G, cdiv(Lr, 16)};
             const int classes[3] = {KC_G_TOKRED_E, KC_G_TOKRED_G, KC_G_TOKRED_VEC};
-            launch_parts(prof, st, split, k_gtokred<NT>, a, 3, counts, classes, KC_G_TOKRED, 256, TokRedShapes<NT>::kLds);
+            launch_parts(prof, st, split, k_gtokred<NT>, a, 3, counts, classes, KC_G_TOKRED, TokRedShapes<NT>::kThreadsPerBlock, TokRedShapes<NT>::kLds);
         }
         {
             const int nb_GG = L > 1 ? (Lr / 32) * (Lr / 32) : 0;
