@@ -1182,15 +1182,18 @@ template <int NT> struct TokRedShapes {
     static constexpr bool BIG = NT > 4;
     // r > 128: 128 x 256 tiles, eight wavefronts, three stages (E then covers all of r: the cache is read once)
     using TBig = TnTile<2, 4, 2, 2, kTokKT, 3>;
-    using TE = typename std::conditional<BIG, TBig, TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), kTokKT, kTokStages>>::type; // kETileCols columns of d x 64 or 128 (or 256) of r
-    using TG = typename std::conditional<BIG, TBig, TnTile<2, 2, 2, 2, kTokKT, kTokStages>>::type; // tile of the Gram matrix
-    static constexpr int kThreadsPerBlock = BIG ? 512 : 256;
+    // r = 96, 128: the same 128 x 128 tile as 4 x 2 wavefronts of 32 x 64 (eight wavefronts issue the transfers of a
+    // stage in half the time each; measured 42 -> 39 us on the T5-Base-shaped step)
+    static constexpr bool W8 = NT == 3 || NT == 4;
+    using TE = typename std::conditional<BIG, TBig, typename std::conditional<W8, TnTile<4, 2, 1, 2, kTokKT, kTokStages>, TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), kTokKT, kTokStages>>::type>::type;
+    using TG = typename std::conditional<BIG, TBig, typename std::conditional<W8, TnTile<4, 2, 1, 2, kTokKT, kTokStages>, TnTile<2, 2, 2, 2, kTokKT, kTokStages>>::type>::type; // tile of the Gram matrix
+    static constexpr int kThreadsPerBlock = (BIG || W8) ? 512 : 256;
     static constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4 + kMaxTiles * 4 + kMaxBatch * kMaxClasses * 4; // + tile and sample tables
     static constexpr int kTileLds = TE::LDS_BYTES > TG::LDS_BYTES ? TE::LDS_BYTES : TG::LDS_BYTES;
     static constexpr int kLds = kTileLds > kVecLds ? kTileLds : kVecLds;
 };
 
-template <int NT> __global__ __launch_bounds__(NT > 4 ? 512 : 256) void k_gtokred(TokRedArgs a)
+template <int NT> __global__ __launch_bounds__(TokRedShapes<NT>::kThreadsPerBlock) void k_gtokred(TokRedArgs a)
 {
     using TE = typename TokRedShapes<NT>::TE;
     using TG = typename TokRedShapes<NT>::TG;
@@ -1268,7 +1271,7 @@ template <int NT> __global__ __launch_bounds__(NT > 4 ? 512 : 256) void k_gtokre
     // cs[kk] = sum over the tiles of their column sums of dpre ;
     // Z[kk][c] = sum_s mean_t(h)[s][kk] dz[s][c], from the tiles' column sums of h.
     // 16 indices per block, the tiles dealt over 16 thread groups whose sums are combined in group order.
-    if (TokRedShapes<NT>::BIG && t >= 256) return; // this part is written for four wavefronts
+    if (t >= 256) return; // this part is written for four wavefronts
     const int C = a.C;
     float *red = reinterpret_cast<float *>(smem); // [16 groups][16 indices][1 + kMaxClasses]
     const int vb = b - a.nb_E - a.nb_G;
