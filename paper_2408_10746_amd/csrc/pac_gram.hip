@@ -1176,7 +1176,7 @@ struct TokRedArgs {
     float *cs, *Z, *dzsum;
 };
 
-constexpr int kTokStages = 4;
+constexpr int kTokStages = 3;
 constexpr int kTokKT = 32;    // tokens per stage of the token contractions (a multiple of 16)
 template <int NT> struct TokRedShapes {
     static constexpr bool BIG = NT > 4;
