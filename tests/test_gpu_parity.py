@@ -185,6 +185,7 @@ WIDE = [
     Workload("w1", L=3, d=160, n_max=37, B=5, r=160, C=3, N=5, cache_dtype="bf16", len_lo=9),
     Workload("w2", L=5, d=256, n_max=70, B=4, r=256, C=4, N=4, cache_dtype="bf16", len_lo=20),
     Workload("w3", L=9, d=192, n_max=150, B=3, r=192, C=2, N=3, cache_dtype="bf16", len_lo=100),
+    Workload("w4", L=6, d=96, n_max=50, B=3, r=224, C=16, N=3, cache_dtype="bf16", len_lo=3),
 ]
 
 
