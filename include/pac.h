@@ -73,7 +73,7 @@ typedef enum { PAC_BF16 = 0, PAC_F32 = 1 } pac_dtype;
 
 /*
  * L      cached layers (>= 1)                d      hidden size (multiple of 32)
- * n_max  longest sequence (>= 1)             r      adapter width (multiple of 32, <= d... any)
+ * n_max  longest sequence (>= 1)             r      adapter width (multiple of 32)
  * C      classes (1..16)                     B_max  largest batch of one step (1..64)
  * N      samples the cache can index (>= 1)  cache_dtype  PAC_BF16 or PAC_F32
  * flags  see PAC_FLAG_* below
@@ -91,9 +91,10 @@ typedef struct {
 /* Measurement aid: launch every part of the fused multi-part launches on its own, so that
  * pac_profile_end reports one class per part (slower; results unchanged). */
 #define PAC_FLAG_SPLIT_LAUNCH 2
-/* On the Gram-matrix path, run the two chains over the layers as one contraction launch per layer
- * (the form used where a 16-token tile's history of all layers does not fit a compute unit's LDS,
- * e.g. r > 128) even where the single-launch chains apply (same results up to rounding). */
+/* On the Gram-matrix path, run the two chains over the layers layer by layer (groups of layers: one
+ * wide contraction per group, one short one per layer; the form used where a 16-token tile's history
+ * of all layers does not fit a compute unit's LDS, e.g. r > 128) even where the single-launch chains
+ * apply (same results up to rounding). */
 #define PAC_FLAG_LAYER_CHAIN 4
 
 typedef struct {

@@ -1,4 +1,5 @@
-// Gram-matrix formulation of the cached Parallel-Adapter step (bf16 cache, adapter width <= 128).
+// Gram-matrix formulation of the cached Parallel-Adapter step (bf16 cache, adapter width <= 256: up to 128
+// with the chains over the layers as one launch per direction, above that launched layer by layer).
 //
 // The side state is a sum of rank-r terms, s_{l-1} = sum_{k<l} (h_k W_up^k + c_up^k), and so is its
 // gradient, ds_l = ds_L + sum_{k>l} (1-lambda_k) dpre_k W_down^{kT}.  Substituting both into the
@@ -612,7 +613,7 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(NT > 4 ? 512 
 }
 
 // ---------------------------------------------------------------------------
-// launches 3 and 5: the r-wide chains over the layers, one 16-token tile per workgroup.
+// launches 3 and 4: the r-wide chains over the layers, one 16-token tile per workgroup.
 // Wavefront w owns columns [16w, 16w+16) of the r-wide state; earlier layers' tiles stay in LDS.
 // ---------------------------------------------------------------------------
 struct ChainArgs {
@@ -1387,7 +1388,7 @@ __global__ __launch_bounds__(256) void k_ggsum(int L, int r, int sg, const float
 }
 
 // ---------------------------------------------------------------------------
-// launch 8: the gradients
+// launch 7: the gradients
 // ---------------------------------------------------------------------------
 struct PostArgs {
     int blk_off; // first block of this launch (parts may be launched separately for timing)
