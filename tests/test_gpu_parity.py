@@ -450,3 +450,29 @@ def test_llama7b_shape_reduced_batch():
     w, sess, ids, lens_all, labels, params = _full_size("llama7b", 16, B_check=2, steps_before=2)
     acts = inputs.batch_acts(w, ids)
     check_against_oracle(w, sess, ids, acts, None, labels[ids], params, TOL["bf16"], "llama7b")
+
+    # The launch configuration bench.py times is the full batch (16 samples, 4096 token rows: 256 chain tiles,
+    # 32 row tiles of the wide contractions), which the oracle would take minutes for.  A property that holds at
+    # any size instead: loss and gradients are batch means, so the full batch must equal the mean of its two
+    # halves, whose launch shapes differ from the full one's (and from the oracle-checked two-sample one's).
+    def run(sel):
+        sess.set_params(params)
+        sess.grads.zero_()
+        sess.loss_grad(np.asarray(sel), torch.from_numpy(labels[sel]).to(sess.dev))
+        torch.cuda.synchronize()
+        return float(sess.loss.item()), sess.grads.cpu().numpy().astype(np.float64)
+
+    full = np.arange(16)
+    l_full, g_full = run(full)
+    l_a, g_a = run(full[:8])
+    l_b, g_b = run(full[8:])
+    assert abs(l_full - 0.5 * (l_a + l_b)) <= 1e-4 * abs(l_full)
+    dims = orc.Dims(w.L, w.d, w.r, w.C)
+    sl = orc.param_slices(dims)
+    g_half = 0.5 * (g_a + g_b)
+    for l in (0, 15, 31):
+        for nm in (f"W_down{l}", f"c_down{l}", f"W_up{l}", f"c_up{l}"):
+            e = rel_err(g_full[sl[nm]], g_half[sl[nm]])
+            note(f"llama7b full vs halves {nm}: {e:.2e}")
+            assert e <= 5e-3, (nm, e)
+    assert rel_err(g_full[sl["W_cls"]], g_half[sl["W_cls"]]) <= 5e-3
