@@ -215,6 +215,8 @@ def main():
         "config": {"workload": f"{w.name}: L={w.L} d={w.d} seq={w.n_max} B={w.B} r={w.r} C={w.C} "
                                f"N={N} resident ({sess.cache_bytes / 1e9:.2f} GB {w.cache_dtype} cache)",
                    "tokens_per_step": M, "cache_fill_s": t_fill,
+                   "formulation": ["per-layer kernels", "gram, single-launch chains",
+                                   "gram, layer-by-layer chains"][pb.pac_step_path(sess.ctx)],
                    "gpu_event_ms_per_step": ev0.elapsed_time(ev1) / args.steps,
                    "final_loss": final_loss},
         "roofline": roof,

@@ -123,6 +123,12 @@ int64_t pac_cache_bytes(const pac_ctx *ctx, const int32_t *lens /*HOST*/, int64_
  * a batch of up to B_max samples of up to n_max tokens.  -1 if ctx is NULL. */
 int64_t pac_workspace_bytes(const pac_ctx *ctx);
 
+/* Which formulation of the step (paper Sec. 4.1, 5.2: the same function of the same inputs in each)
+ * this configuration runs on: 0 the per-layer kernels; 1 the Gram-matrix formulation with the chains
+ * over the layers as one launch per direction; 2 the Gram-matrix formulation with the chains launched
+ * layer by layer.  Decided by pac_create from the shape, cache dtype and flags.  -1 if ctx is NULL. */
+int32_t pac_step_path(const pac_ctx *ctx);
+
 /*
  * Store one backbone forward's per-layer activations (paper Sec. 4.2: during
  * the first epoch everything the adapters consume is cached).

@@ -21,10 +21,11 @@ PAC_ERR_UNSUPPORTED, PAC_ERR_WORKSPACE, PAC_ERR_DEVICE, PAC_ERR_STATE = 5, 6, 7,
 PAC_BF16, PAC_F32 = 0, 1
 PAC_FLAG_PER_LAYER = 1
 PAC_FLAG_SPLIT_LAUNCH = 2
+PAC_FLAG_LAYER_CHAIN = 4
 
 EXPORTS = [
     "pac_create", "pac_destroy", "pac_status_str", "pac_param_count", "pac_param_offsets",
-    "pac_cache_bytes", "pac_workspace_bytes", "pac_cache_fill", "pac_cache_lookup",
+    "pac_cache_bytes", "pac_workspace_bytes", "pac_step_path", "pac_cache_fill", "pac_cache_lookup",
     "pac_adapter_loss_grad", "pac_adapter_step",
     "pac_profile_begin", "pac_profile_end", "pac_profile_class_name",
 ]
@@ -76,6 +77,8 @@ def lib():
         L.pac_cache_bytes.argtypes = [vp, vp, i64]
         L.pac_workspace_bytes.restype = i64
         L.pac_workspace_bytes.argtypes = [vp]
+        L.pac_step_path.restype = C.c_int32
+        L.pac_step_path.argtypes = [vp]
         L.pac_cache_fill.restype = C.c_int
         L.pac_cache_fill.argtypes = [vp, vp, i64, vp, i32, vp, i32, vp, vp]
         L.pac_cache_lookup.restype = C.c_int
@@ -145,6 +148,10 @@ def pac_cache_bytes(ctx, lens, count: int) -> int:
 
 def pac_workspace_bytes(ctx) -> int:
     return int(lib().pac_workspace_bytes(ctx))
+
+
+def pac_step_path(ctx) -> int:
+    return int(lib().pac_step_path(ctx))
 
 
 def pac_cache_fill(ctx, cache_ptr, cache_bytes, sample_ids, acts_ptr, acts_dtype, lens=None, stream=0) -> None:

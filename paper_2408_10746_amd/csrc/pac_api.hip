@@ -167,6 +167,8 @@ int64_t pac_cache_bytes(const pac_ctx *ctx, const int32_t *lens, int64_t count)
 
 int64_t pac_workspace_bytes(const pac_ctx *ctx) { return ctx ? ctx->W.total : -1; }
 
+int32_t pac_step_path(const pac_ctx *ctx) { return ctx ? ctx->W.use_gram : -1; }
+
 pac_status pac_cache_lookup(const pac_ctx *ctx, int64_t sample_id, int64_t *offset_elems, int32_t *len)
 {
     if (!ctx || !offset_elems || !len) return PAC_ERR_NULL;

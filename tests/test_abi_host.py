@@ -64,6 +64,29 @@ def test_create_validation_and_sizes():
     pb.pac_destroy(None)
 
 
+def test_formulation_chosen_per_configuration():
+    """Host logic: which formulation a configuration runs on (0 per-layer, 1 Gram with single-launch chains,
+    2 Gram with layer-by-layer chains)."""
+    def path(L, d, n, r, C, B, dtype=pb.PAC_BF16, flags=0):
+        ctx = pb.pac_create(L, d, n, r, C, B, 64, dtype, flags)
+        try:
+            return pb.pac_step_path(ctx)
+        finally:
+            pb.pac_destroy(ctx)
+
+    assert path(12, 768, 128, 96, 3, 32) == 1            # T5-Base-shaped
+    assert path(24, 1024, 128, 128, 2, 32) == 1          # Large-shaped: the chain kernels' LDS just fits
+    assert path(32, 4096, 256, 256, 4, 16) == 2          # LLaMA-7B-shaped: r > 128
+    assert path(12, 768, 128, 160, 3, 32) == 2
+    assert path(40, 1024, 128, 128, 2, 32) == 2          # too many layers for the LDS-resident chains
+    assert path(12, 768, 128, 96, 3, 32, pb.PAC_F32) == 0
+    assert path(12, 768, 128, 96, 3, 32, flags=pb.PAC_FLAG_PER_LAYER) == 0
+    assert path(12, 768, 128, 96, 3, 32, flags=pb.PAC_FLAG_LAYER_CHAIN) == 2
+    assert path(12, 768, 128, 288, 3, 32) == 0           # wider than the Gram path's tiles
+    assert path(80, 4096, 64, 256, 3, 8) == 0            # more layers than the wide path's vector part deals with
+    assert pb.lib().pac_step_path(None) == -1
+
+
 def test_argument_errors_are_caught_before_any_launch():
     """Fake (never dereferenced) device addresses: every call below must fail on the host."""
     ctx = pb.pac_create(2, 64, 16, 32, 3, 4, 8, pb.PAC_BF16)
