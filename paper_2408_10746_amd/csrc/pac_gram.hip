@@ -503,8 +503,10 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(NT > 4 ? 512 
     const int b = (int)(gridDim.x - 1 - blockIdx.x) + a.blk_off;
     if (b < a.nb_U) {
         // (layer, row tile, column tile), the column tiles of a row tile next to each other
+        // Wide shapes: the tiles of a layer go to one die, which then fetches that layer's projection once (numbered
+        // round-robin every die fetched every layer's: half as many bytes again as the cache itself).
         const int uct = (a.r + TU::BN - 1) / TU::BN;
-        const int v = uct > 1 ? die_group_order(b, a.nb_U, 4 * uct) : b;
+        const int v = SH::BIG ? die_group_order(b, a.nb_U, uct * a.row_tiles) : b;
         const int ct = v % uct, mt = (v / uct) % a.row_tiles, l = v / (uct * a.row_tiles);
         const bf16_t *cache = a.cache;
         const RowMap map = a.map;
@@ -518,13 +520,33 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(NT > 4 ? 512 
     }
     const int tqm = (a.r + TQ::BM - 1) / TQ::BM, tqn = (a.r + TQ::BN - 1) / TQ::BN, tq2 = tqm * tqn, tc64 = (a.r + 63) / 64;
     if (b < a.nb_U + a.nb_Q) {
-        int idx = SH::BIG ? die_group_order(b - a.nb_U, a.nb_Q, 2 * tq2) : b - a.nb_U;
-        const int p = idx / tq2;
-        idx -= p * tq2;
-        // pair p = (k, l), k < l
-        int l = 1;
-        while ((l + 1) * l / 2 <= p) ++l;
-        const int k = p - l * (l - 1) / 2;
+        int idx, k, l, p;
+        if constexpr (SH::BIG) {
+            // Blocks of 4 x 4 layer pairs (k in 4 kb.., l in 4 lb.., kb <= lb), one block per die at a time: its tiles
+            // read 4 + 4 projection matrices between them instead of two each (numbered pair by pair and round-robin,
+            // the 134 MB of projections crossed the fabric ten times).  Slots with k >= l or past L are empty.
+            const int per_block = 16 * tq2;
+            int v = die_group_order(b - a.nb_U, a.nb_Q, per_block);
+            const int blk = v / per_block;
+            v -= blk * per_block;
+            int lb = 0;
+            while ((lb + 1) * (lb + 2) / 2 <= blk) ++lb;
+            const int kb = blk - lb * (lb + 1) / 2;
+            const int pr = v / tq2;
+            idx = v - pr * tq2;
+            k = 4 * kb + (pr & 3);
+            l = 4 * lb + (pr >> 2);
+            if (k >= l || l >= a.L) return;
+            p = pair_index(k, l);
+        } else {
+            idx = b - a.nb_U;
+            p = idx / tq2;
+            idx -= p * tq2;
+            // pair p = (k, l), k < l
+            l = 1;
+            while ((l + 1) * l / 2 <= p) ++l;
+            k = p - l * (l - 1) / 2;
+        }
         const bf16_t *Wu = a.Wu + (int64_t)k * a.r * a.d, *Wd = a.WdT + (int64_t)l * a.r * a.d;
         const int d = a.d;
         auto arow = [&](int row) { return Wu + (int64_t)row * d; };
@@ -1517,10 +1539,26 @@ template <int BK, bool BIG> __global__ __launch_bounds__(BIG ? 512 : 256) void k
     if (b < a.nb_F) {
         const int ti_d = (d + TFF::BM - 1) / TFF::BM, ti_r = (r + TFF::BN - 1) / TFF::BN;
         // F_l = sum_{k<l} W_up^{kT} G_{kl}   ([d] x [l*r] times [l*r] x [r])
-        const int v = BIG ? die_group_order(b, a.nb_F, 8) : b;
-        const int l = v / (ti_d * ti_r);
-        const int slot = v % (ti_d * ti_r);
-        const int it = slot / ti_r, nt = slot % ti_r;
+        int l, slot, it, nt;
+        if (BIG && ti_d % 8 == 0) {
+            // A die takes ti_d / 8 tiles along d for every layer: the rows of the stacked W_up copy those tiles read are
+            // shared by all layers (each layer contracts a prefix of them), so they cross the fabric once per die
+            // instead of once per layer.  Within a die the layers run from the last (longest contraction) down.
+            const int per_die = ti_d / 8 * ti_r * L;
+            const int v = die_chunk_order(b, a.nb_F);
+            const int die = v / per_die, w = v % per_die;
+            l = w / (ti_d / 8 * ti_r);
+            const int q = w % (ti_d / 8 * ti_r);
+            it = die * (ti_d / 8) + q / ti_r;
+            nt = q % ti_r;
+            slot = it * ti_r + nt;
+        } else {
+            const int v = BIG ? die_group_order(b, a.nb_F, 8) : b;
+            l = v / (ti_d * ti_r);
+            slot = v % (ti_d * ti_r);
+            it = slot / ti_r;
+            nt = slot % ti_r;
+        }
         const float *pl = a.params + (int64_t)l * a.PL;
         const bf16_t *A = a.WuTs, *B = a.GGT + (int64_t)l * r * Lr;
         auto arow = [&](int row) { return A + (int64_t)row * Lr; };
@@ -1535,11 +1573,24 @@ template <int BK, bool BIG> __global__ __launch_bounds__(BIG ? 512 : 256) void k
     if (b < a.nb_F + a.nb_W) {
         // dW_up^l = Z_l W_cls^T + sum_{k>l} (1-lambda_k) G_{lk} W_down^{kT}
         const int ti_r = (r + TFW::BM - 1) / TFW::BM, ti_d = (d + TFW::BN - 1) / TFW::BN;
-        int idx = BIG ? die_group_order(b - a.nb_F, a.nb_W, 8) : b - a.nb_F;
-        const int l = idx / (ti_d * ti_r);
-        idx %= ti_d * ti_r;
-        // (wide shapes: the row tiles of a column tile next to each other)
-        const int at = BIG ? idx % ti_r : idx / ti_d, jt = BIG ? idx / ti_r : idx % ti_d;
+        int l, at, jt;
+        if (BIG && ti_d % 8 == 0) {
+            // as for F: a die takes ti_d / 8 tiles along d (rows of the stacked W_down copy) for every layer
+            const int per_die = ti_d / 8 * ti_r * L;
+            const int v = die_chunk_order(b - a.nb_F, a.nb_W);
+            const int die = v / per_die, w = v % per_die;
+            l = L - 1 - w / (ti_d / 8 * ti_r); // the first layers have the longest contractions here
+            const int q = w % (ti_d / 8 * ti_r);
+            jt = die * (ti_d / 8) + q / ti_r;
+            at = q % ti_r;
+        } else {
+            int idx = BIG ? die_group_order(b - a.nb_F, a.nb_W, 8) : b - a.nb_F;
+            l = idx / (ti_d * ti_r);
+            idx %= ti_d * ti_r;
+            // (wide shapes: the row tiles of a column tile next to each other)
+            at = BIG ? idx % ti_r : idx / ti_d;
+            jt = BIG ? idx / ti_r : idx % ti_d;
+        }
         const bf16_t *A = a.GGsc + (int64_t)l * r * Lr, *B = a.Wds;
         auto arow = [&](int row) { return A + (int64_t)row * Lr; };
         auto brow = [&](int c) { return B + (int64_t)c * Lr; };
@@ -1802,6 +1853,10 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         constexpr int kProjThreads = NT > 4 ? 512 : 256;
         a.row_tiles = cdiv(M, 128); a.nb_U = a.row_tiles * L * (NT > 4 ? cdiv(r, 256) : 1);
         a.nb_Q = W.pairs * cdiv(r, kQRows) * cdiv(r, kQCols);
+        if (NT > 4) { // blocks of 4 x 4 layer pairs, see k_gproj
+            const int nlb = cdiv(L, 4);
+            a.nb_Q = L > 1 ? nlb * (nlb + 1) / 2 * 16 * cdiv(r, kQRows) * cdiv(r, kQCols) : 0;
+        }
         a.nb_C = L * cdiv(r, 64);
         a.cusum = cusum; a.chat = chat; a.params = io.params; a.PL = D.PL;
         a.WdT = WdT; a.Wu = Wu; a.U = pre; a.QpN = QpN; a.QpT = QpT;
