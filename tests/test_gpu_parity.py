@@ -209,6 +209,27 @@ def test_bf16_paths(w, flags):
             assert np.all(grads[sl[nm]] == 0.0), nm
 
 
+# Adapter widths above 256 (the long-sequence configuration's r = 512): per-layer kernels in every mode.
+XWIDE = [
+    Workload("x1", L=3, d=160, n_max=70, B=4, r=512, C=2, N=4, cache_dtype="bf16", len_lo=20),
+    Workload("x2", L=4, d=96, n_max=37, B=3, r=288, C=3, N=3, cache_dtype="bf16", len_lo=9),
+]
+
+
+@pytest.mark.parametrize("w", XWIDE, ids=[w.name for w in XWIDE])
+def test_bf16_widths_above_256(w):
+    from paper_2408_10746_amd import binding as pb
+    lens = inputs.lengths(w)
+    ids = np.arange(w.B)
+    acts = inputs.batch_acts(w, ids)
+    labels = inputs.labels(w)[ids]
+    sess = make_session(w, lens=lens)
+    assert pb.pac_step_path(sess.ctx) == 0
+    sess.cache_fill(ids, acts, lens)
+    check_against_oracle(w, sess, ids, acts, lens, labels, inputs.random_params(w, up_scale=0.5), TOL["bf16"],
+                         what=w.name)
+
+
 @pytest.mark.parametrize("wname", ["g2", "w2"])
 @pytest.mark.parametrize("flags", [0, 1, 4], ids=["gram", "per_layer", "layer_chain"])
 def test_forward_only_call(flags, wname):
@@ -476,3 +497,48 @@ def test_llama7b_shape_reduced_batch():
             note(f"llama7b full vs halves {nm}: {e:.2e}")
             assert e <= 5e-3, (nm, e)
     assert rel_err(g_full[sl["W_cls"]], g_half[sl["W_cls"]]) <= 5e-3
+
+
+@pytest.mark.timeout(900)
+def test_longseq_shape_ragged_reduced_batch():
+    """d=4096, r=512, L=32, samples of 256..1024 tokens packed without padding: wider than the Gram formulation
+    takes, so this is the per-layer path at its largest shape.  The oracle runs on the shortest and the longest of
+    the eight cached samples; the full ragged batch is checked through the batch-mean property."""
+    from paper_2408_10746_amd import binding as pb
+    w, sess, ids8, lens_all, labels, trained = _full_size("longseq", 8, steps_before=2)
+    assert pb.pac_step_path(sess.ctx) == 0
+    # Two updates of a 4096-wide classifier on eight samples already separate them (loss about 1e-9: softmax minus
+    # one-hot is then below fp32 resolution and a relative comparison of gradients says nothing), so the trained
+    # state only shows that the update ran at this size; the comparison uses random parameters of ordinary scale.
+    assert np.all(np.isfinite(trained)) and np.any(trained != inputs.init_params(w))
+    params = inputs.random_params(w, up_scale=0.5)
+    lens8 = lens_all[:8]
+    assert lens8.min() < lens8.max() and lens8.max() <= w.n_max
+    ids = np.asarray([int(np.argmin(lens8)), int(np.argmax(lens8))])   # 286 and 899 tokens
+    acts = inputs.batch_acts(w, ids)
+    check_against_oracle(w, sess, ids, acts, lens_all[ids], labels[ids], params, TOL["bf16"], "longseq")
+    del acts
+
+    def run(sel):
+        sess.set_params(params)
+        sess.grads.zero_()
+        sess.loss_grad(np.asarray(sel), torch.from_numpy(labels[sel]).to(sess.dev))
+        torch.cuda.synchronize()
+        return float(sess.loss.item()), sess.grads.cpu().numpy()
+
+    dims = orc.Dims(w.L, w.d, w.r, w.C)
+    sl = orc.param_slices(dims)
+    names = [f"{nm}{l}" for l in (0, 16, 31) for nm in ("W_down", "c_down", "W_up", "c_up")] + ["W_cls"]
+    l_full, g = run(ids8)
+    g_full = {nm: g[sl[nm]].astype(np.float64) for nm in names}
+    l_a, g = run(ids8[:4])
+    g_half = {nm: 0.5 * g[sl[nm]].astype(np.float64) for nm in names}
+    l_b, g = run(ids8[4:])
+    for nm in names:
+        g_half[nm] += 0.5 * g[sl[nm]]
+    del g
+    assert abs(l_full - 0.5 * (l_a + l_b)) <= 1e-4 * abs(l_full)
+    for nm in names:
+        e = rel_err(g_full[nm], g_half[nm])
+        note(f"longseq full vs halves {nm}: {e:.2e}")
+        assert e <= 5e-3, (nm, e)
