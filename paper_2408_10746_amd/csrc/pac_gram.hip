@@ -1,5 +1,6 @@
-// Gram-matrix formulation of the cached Parallel-Adapter step (bf16 cache, adapter width <= 256: up to 128
-// with the chains over the layers as one launch per direction, above that launched layer by layer).
+// Gram-matrix formulation of the cached Parallel-Adapter step (bf16 cache, adapter width <= 512: up to 128
+// with the chains over the layers as one launch per direction, above that launched layer by layer; widths
+// above 256 in multiples of 64 and with at most 32 layers).
 //
 // The side state is a sum of rank-r terms, s_{l-1} = sum_{k<l} (h_k W_up^k + c_up^k), and so is its
 // gradient, ds_l = ds_L + sum_{k>l} (1-lambda_k) dpre_k W_down^{kT}.  Substituting both into the
@@ -73,7 +74,10 @@ static int big_shapes(int r) { return r > 128; }
 int gram_path_kind(const Dims &D)
 {
     if (D.cache_dtype != 0 || (D.flags & 1)) return 0; // PAC_FLAG_PER_LAYER
-    if (D.r > 256 || D.d > kMaxD || D.L > 128) return 0;
+    if (D.r > 512 || D.d > kMaxD || D.L > 128) return 0;
+    // above 256: the vector part of the gradient launch deals eight threads over an r-wide row (16-byte pieces)
+    // and 32 such rows over the layers
+    if (D.r > 256 && (D.r % 64 != 0 || D.L > 32)) return 0;
     if ((int64_t)D.B_max * cdiv(D.n_max, kChainRows) > kMaxTiles) return 0;
     const bool lds_chain = D.r <= 128 && chain_lds(D.L, D.r, true) <= 160 * 1024;
     if (lds_chain && !(D.flags & 4)) return 1; // PAC_FLAG_LAYER_CHAIN
@@ -1509,13 +1513,13 @@ template <int CC> __device__ __forceinline__ void zrows(const float *Z, const Ch
     }
 }
 
-template <int BK, bool BIG> struct PostShapes {
+template <int BK, bool BIG, bool XW = false> struct PostShapes {
     // 64 x 64 with 64 KB of stages; or (r > 128) eight wavefronts, three stages, interleaved sub-steps:
     // 128 rows of d x 256 columns of r for F, 256 rows of r x 128 columns of d for W
     using TSmall = NtTile<2, 2, 1, 1, BK, BK == 64 ? 4 : 8>;
     using TFF = typename std::conditional<BIG, NtTile<2, 4, 2, 2, BK, 3>, TSmall>::type;
     using TFW = typename std::conditional<BIG, NtTile<4, 2, 2, 2, BK, 3>, TSmall>::type;
-    static constexpr int NH = BIG ? 4 : 2; // threads sharing one r-wide row in the vector part
+    static constexpr int NH = XW ? 8 : BIG ? 4 : 2; // threads sharing one r-wide row in the vector part (XW: r > 256)
     static constexpr int kThreadsPerBlock = BIG ? 512 : 256;
     static constexpr int kVecLds = 128 * 4 + 128 * kMaxClasses * 4 + kMaxBatch * kMaxClasses * 4;
     static constexpr int kLds = TFF::LDS_BYTES > TFW::LDS_BYTES ? TFF::LDS_BYTES : TFW::LDS_BYTES;
@@ -1523,13 +1527,13 @@ template <int BK, bool BIG> struct PostShapes {
 };
 
 // BK = 64 when r is a multiple of 64, else 32: every K range below is a multiple of r
-template <int BK, bool BIG> __global__ __launch_bounds__(BIG ? 512 : 256) void k_gpost(PostArgs a)
+template <int BK, bool BIG, bool XW> __global__ __launch_bounds__(BIG ? 512 : 256) void k_gpost(PostArgs a)
 {
-    using TFF = typename PostShapes<BK, BIG>::TFF;
-    using TFW = typename PostShapes<BK, BIG>::TFW;
-    constexpr int kVecLds = PostShapes<BK, BIG>::kVecLds;
-    constexpr int kLds = PostShapes<BK, BIG>::kLds;
-    constexpr int NH = PostShapes<BK, BIG>::NH;
+    using TFF = typename PostShapes<BK, BIG, XW>::TFF;
+    using TFW = typename PostShapes<BK, BIG, XW>::TFW;
+    constexpr int kVecLds = PostShapes<BK, BIG, XW>::kVecLds;
+    constexpr int kLds = PostShapes<BK, BIG, XW>::kLds;
+    constexpr int NH = PostShapes<BK, BIG, XW>::NH;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     __shared__ float red[16];
     const int L = a.L, d = a.d, r = a.r, C = a.C;
@@ -2023,8 +2027,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         }
         PostArgs pa;
         pa.L = L; pa.d = d; pa.r = r; pa.C = C; pa.B = B; pa.se = 1;
-        constexpr bool BIG = NT > 4;
-        constexpr int NH = BIG ? 4 : 2; // PostShapes<., BIG>
+        constexpr bool BIG = NT > 4, XW = NT > 8;
+        constexpr int NH = PostShapes<64, BIG, XW>::NH;
         constexpr int kFRows = BIG ? 128 : 64, kFCols = BIG ? 256 : 64, kWRows = BIG ? 256 : 64, kWCols = BIG ? 128 : 64;
         constexpr int kPostThreads = BIG ? 512 : 256;
         pa.nb_F = L * cdiv(d, kFRows) * cdiv(r, kFCols); pa.nb_W = L * cdiv(r, kWRows) * cdiv(d, kWCols);
@@ -2038,18 +2042,18 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             const int classes[3] = {KC_G_POST_F, KC_G_POST_W, KC_G_POST_VEC};
             static bool done = false;
             if (!done) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<64, BIG>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<64, BIG>::kLds);
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<64, BIG, XW>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<64, BIG, XW>::kLds);
                 if (e != hipSuccess) return e;
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<32, BIG>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<32, BIG>::kLds);
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<32, BIG, XW>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<32, BIG, XW>::kLds);
                 if (e != hipSuccess) return e;
                 done = true;
             }
             if (r % 64 == 0)
-                launch_parts(prof, st, split, k_gpost<64, BIG>, pa, 3, counts, classes, KC_G_POST, kPostThreads, PostShapes<64, BIG>::kLds);
+                launch_parts(prof, st, split, k_gpost<64, BIG, XW>, pa, 3, counts, classes, KC_G_POST, kPostThreads, PostShapes<64, BIG, XW>::kLds);
             else
-                launch_parts(prof, st, split, k_gpost<32, BIG>, pa, 3, counts, classes, KC_G_POST, kPostThreads, PostShapes<32, BIG>::kLds);
+                launch_parts(prof, st, split, k_gpost<32, BIG, XW>, pa, 3, counts, classes, KC_G_POST, kPostThreads, PostShapes<32, BIG, XW>::kLds);
         }
         if (io.defer) { // the optimizer launch that follows does the last two sums
             io.defer->used = true;
@@ -2070,10 +2074,9 @@ hipError_t launch_gram_loss_grad(const Dims &D, const WsLayout &W, const BatchMe
     case 2: return run_gram<2>(D, W, meta, io);
     case 3: return run_gram<3>(D, W, meta, io);
     case 4: return run_gram<4>(D, W, meta, io);
-    case 5: return run_gram<5>(D, W, meta, io);
-    case 6: return run_gram<6>(D, W, meta, io);
-    case 7: return run_gram<7>(D, W, meta, io);
-    case 8: return run_gram<8>(D, W, meta, io);
+    // above 128 the kernels take r as an argument: one instantiation up to 256, one above (gradient vector part)
+    case 5: case 6: case 7: case 8: return run_gram<8>(D, W, meta, io);
+    case 10: case 12: case 14: case 16: return run_gram<16>(D, W, meta, io);
     }
     return hipErrorInvalidValue;
 }

@@ -82,7 +82,11 @@ def test_formulation_chosen_per_configuration():
     assert path(12, 768, 128, 96, 3, 32, pb.PAC_F32) == 0
     assert path(12, 768, 128, 96, 3, 32, flags=pb.PAC_FLAG_PER_LAYER) == 0
     assert path(12, 768, 128, 96, 3, 32, flags=pb.PAC_FLAG_LAYER_CHAIN) == 2
-    assert path(12, 768, 128, 288, 3, 32) == 0           # wider than the Gram path's tiles
+    assert path(32, 4096, 1024, 512, 2, 8) == 2          # long-sequence configuration
+    assert path(12, 768, 128, 320, 3, 32) == 2
+    assert path(12, 768, 128, 288, 3, 32) == 0           # above 256 only in multiples of 64
+    assert path(12, 768, 128, 544, 3, 32) == 0           # wider than the Gram path takes
+    assert path(40, 1024, 128, 384, 2, 32) == 0          # above 256 only up to 32 layers
     assert path(80, 4096, 64, 256, 3, 8) == 0            # more layers than the wide path's vector part deals with
     assert pb.lib().pac_step_path(None) == -1
 
