@@ -779,8 +779,23 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
 #pragma unroll
         for (int q = 0; q < kChunksPerLane; ++q) *reinterpret_cast<u32x4 *>(dst + (lane + 64 * q) * EPC) = reg[q];
     };
-    auto drain = [&](int step) { // GELU' tile of a finished step: LDS staging -> global
-        if (!FWD || step < 0 || step >= L) return;
+    // Tiles of a finished step, LDS -> global.  Backward: the dpre tile (the helper has nothing else to do there;
+    // forward, where it also prepares vectors and logits, the same made its step longer than the contracting
+    // wavefronts' and the h tiles go out together at the end instead).  Forward: the GELU' tile.
+    auto drain = [&](int step) {
+        if (step < 0 || step >= L) return;
+        if (!FWD) {
+            const int l = layer_at(step);
+            constexpr int cpr = r / 8, nch = T * cpr; // 16-byte chunks per row, per tile
+#pragma unroll
+            for (int q = 0; q < (nch + 63) / 64; ++q) {
+                const int c = lane + 64 * q, row = c / cpr, cc = c % cpr;
+                if (c < nch && row < nrows)
+                    *reinterpret_cast<u32x4 *>(a.Hg + (int64_t)(m0 + row) * Lr + (int64_t)l * r + cc * 8) =
+                        *reinterpret_cast<const u32x4 *>(Hs + ((int64_t)l * T + row) * RP + cc * 8);
+            }
+        }
+        if (!FWD) return;
         const bf16_t *st = Gst + (size_t)(step & 1) * T * r;
         bf16_t *dst = a.Gp + ((int64_t)layer_at(step) * a.M + m0) * r;
 #pragma unroll
@@ -992,15 +1007,17 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
         }
     }
     __syncthreads(); // every layer's tile and column sums are in LDS
-    // flush: 16-byte chunks of the valid rows, then the column sums
-    constexpr int chunks_per_row = r / 8;
-    for (int c = threadIdx.x; c < L * T * chunks_per_row; c += nthreads) {
-        const int l = c / (T * chunks_per_row);
-        const int rem = c - l * T * chunks_per_row;
-        const int row = rem / chunks_per_row, cc = rem % chunks_per_row;
-        if (row < nrows)
-            *reinterpret_cast<u32x4 *>(a.Hg + (int64_t)(m0 + row) * Lr + (int64_t)l * r + cc * 8) =
-                *reinterpret_cast<const u32x4 *>(Hs + ((int64_t)l * T + row) * RP + cc * 8);
+    if (FWD) {
+        // flush: 16-byte chunks of the valid rows (backward the tiles went out layer by layer)
+        constexpr int chunks_per_row = r / 8;
+        for (int c = threadIdx.x; c < L * T * chunks_per_row; c += nthreads) {
+            const int l = c / (T * chunks_per_row);
+            const int rem = c - l * T * chunks_per_row;
+            const int row = rem / chunks_per_row, cc = rem % chunks_per_row;
+            if (row < nrows)
+                *reinterpret_cast<u32x4 *>(a.Hg + (int64_t)(m0 + row) * Lr + (int64_t)l * r + cc * 8) =
+                    *reinterpret_cast<const u32x4 *>(Hs + ((int64_t)l * T + row) * RP + cc * 8);
+        }
     }
     for (int c = threadIdx.x; c < L * r; c += nthreads) a.part[(int64_t)tile * Lr + c] = Cs[c];
 }
