@@ -50,7 +50,7 @@ constexpr int kMaxTiles = 8192;     // 16-token tiles of a batch (LDS table of t
 constexpr int kSeqTile = 128;       // side of the workgroup tile of a per-layer chain contraction
 
 // Slots of the chain kernels' LDS ring of per-token inputs.  Two suffice: the helper wavefront keeps the
-// tiles of the next three steps in registers and writes the tile of step s+1 while the contracting
+// tiles of the next two steps in registers and writes the tile of step s+1 while the contracting
 // wavefronts read that of step s; a barrier separates that from the write of step s+2 into the same slot.
 constexpr int kRing = 2;
 
@@ -732,7 +732,9 @@ __device__ __forceinline__ void gelu_pair(float u, float &h, float &gp)
 
 // The chain runs in L steps; step s produces layer s (forward) or L-1-s (backward) and contracts the
 // tiles of steps 0..s-1, oldest first, so that the tile finished last is also needed last.
-template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void k_gchain(ChainArgs a)
+// CMAX: classes the helper wavefront keeps accumulators and prefetched rows of V for (a.C <= CMAX); 4 where that
+// holds, because with 16 the widest forward instantiation no longer fitted its registers (194 spilled)
+template <bool FWD, int NT, int CMAX = kMaxClasses> __global__ __launch_bounds__(64 * (2 * NT + 1)) void k_gchain(ChainArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char dyn_smem[];
     constexpr int r = 32 * NT, RP = r + kChainPad, KS = NT, NW = 2 * NT, T = kChainRows;
@@ -825,50 +827,55 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
             ij = 0;
         }
     };
-    bf16x8 fifo[kDepth][KS];
-    u32x4 ra[kChunksPerLane], rb[kChunksPerLane], rc[kChunksPerLane];
-    if (wave == NW) {
-        fetch(0, ra);
-        fetch(1, rb);
-        fetch(2, rc);
-    } else if (total_pairs > 0) {
-#pragma unroll
-        for (int slot = 0; slot < kDepth; ++slot) issue(fifo[slot]);
-    }
-
     // per-layer vectors.  Forward: the first step's here, the later ones by the helper wavefront, one
     // step ahead.  Backward: all of them here (leaving them to the helper was measured slower).
-    if (!FWD) sample_head(a, samp, tile == a.samp_tile0[samp], zs, dzs);
-    const float inv_len = 1.f / (float)a.samp_len[samp];
-    for (int l = threadIdx.x; l < L; l += nthreads) lamS[l] = a.params[(int64_t)l * a.PL + a.PL - 1];
-    if (FWD) {
-        for (int nn = threadIdx.x; nn < r; nn += nthreads) {
-            const float *pl = a.params;
-            vecS[nn] = (1.f - pl[a.PL - 1]) * a.chat[nn] + pl[(int64_t)a.d * r + nn];
+    // Called by both kinds of wavefront from inside their own branch, after their first requests have gone out:
+    // written once before the branch, the helper's tile registers and the contracting wavefronts' operand FIFO
+    // were both live across it, and the widest forward instantiation spilled 194 registers.
+    auto per_layer_vectors = [&]() {
+        if (!FWD) sample_head(a, samp, tile == a.samp_tile0[samp], zs, dzs);
+        const float inv_len = 1.f / (float)a.samp_len[samp];
+        for (int l = threadIdx.x; l < L; l += nthreads) lamS[l] = a.params[(int64_t)l * a.PL + a.PL - 1];
+        if (FWD) {
+            for (int nn = threadIdx.x; nn < r; nn += nthreads) {
+                const float *pl = a.params;
+                vecS[nn] = (1.f - pl[a.PL - 1]) * a.chat[nn] + pl[(int64_t)a.d * r + nn];
+            }
+        } else {
+            for (int c = threadIdx.x; c < L * r; c += nthreads) {
+                // ghat = dz V^T / len: what the head hands to every token of the sample
+                float v = 0.f;
+                for (int q = 0; q < a.C; ++q) v += dzs[q] * a.V[(int64_t)c * a.C + q];
+                vecS[c] = v * inv_len;
+            }
         }
-    } else {
-        for (int c = threadIdx.x; c < L * r; c += nthreads) {
-            // ghat = dz V^T / len: what the head hands to every token of the sample
-            float v = 0.f;
-            for (int q = 0; q < a.C; ++q) v += dzs[q] * a.V[(int64_t)c * a.C + q];
-            vecS[c] = v * inv_len;
-        }
-    }
+    };
 
     if (wave == NW) {
-        // ---- helper wavefront: all global traffic of the per-token tiles.  It keeps the input ring
-        // filled three layers ahead and (forward) writes out the GELU' tile of the layer just finished,
+        // The helper's few requests per step share the compute unit's memory pipeline with the contracting
+        // wavefronts' operand stream; at equal priority it got one issue slot in nine and its tiles arrived late.
+        __builtin_amdgcn_s_setprio(3);
+        // Two tiles in registers (even steps in ra, odd in rb): the tile of step s+3 is requested into the registers
+        // the tile of step s+1 has just left, and is needed one whole step later.  (A third set of registers bought
+        // no more time than that and made the widest forward instantiation spill a tile in every step: the spill's
+        // store waited for the request it had just issued, 4.8 us per step of the Large-shaped chain.)
+        u32x4 ra[kChunksPerLane], rb[kChunksPerLane];
+        fetch(0, ra);
+        fetch(1, rb);
+        per_layer_vectors();
+        // ---- helper wavefront: all global traffic of the per-token tiles.  It requests the input tiles
+        // three layers ahead and (forward) writes out the GELU' tile of the layer just finished,
         // so the contracting wavefronts issue no global store and wait on no per-token load.
         // Forward, the helper also prepares, one step ahead, what does not depend on the chain: the next
         // step's per-layer vector (vecS), and it folds the finished layers' column sums into this tile's
         // share of the logits.  Every value it uses was requested one step earlier, before that step's
         // tile request, so waiting for it never waits for a tile.
         constexpr int NP = (r + 63) / 64; // passes of the 64 lanes over the r columns
-        float vpre[NP][kMaxClasses];      // V rows of the layer finished last
+        float vpre[NP][CMAX];      // V rows of the layer finished last
         float cpre[NP][2];                // chat and c_down of the next step's layer
-        float zacc[kMaxClasses];
+        float zacc[CMAX];
 #pragma unroll
-        for (int c = 0; c < kMaxClasses; ++c) zacc[c] = 0.f;
+        for (int c = 0; c < CMAX; ++c) zacc[c] = 0.f;
         const int C = a.C;
         auto side_load = [&](int s) { // requests for what side_use(s + 1) needs
             if (!FWD) return;
@@ -878,7 +885,7 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
             for (int p = 0; p < NP; ++p) {
                 const int nn = min(lane + 64 * p, r - 1);
 #pragma unroll
-                for (int c = 0; c < kMaxClasses; ++c)
+                for (int c = 0; c < CMAX; ++c)
                     if (c < C) vpre[p][c] = a.V[((int64_t)lv * r + nn) * C + c];
                 cpre[p][0] = a.chat[lc * r + nn];
                 cpre[p][1] = a.params[(int64_t)lc * a.PL + (int64_t)a.d * r + nn];
@@ -894,38 +901,31 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
                 if (s >= 1) { // layer s-1 is finished: its column sums are final
                     const float hs = Cs[(s - 1) * r + nn];
 #pragma unroll
-                    for (int c = 0; c < kMaxClasses; ++c)
+                    for (int c = 0; c < CMAX; ++c)
                         if (c < C) zacc[c] += hs * vpre[p][c];
                 }
             }
         };
         side_load(-1);
         put(0, ra);
+        fetch(2, ra);
         __syncthreads();
         // before the barrier that ends step s the tile of step s+1 must be in the ring
-        for (int s = 0; s < L; s += 3) {
-            // the tile consumed here was requested two steps ago; the new request goes out after it
-            // so that waiting for the old one never means waiting for the new one
+        for (int s = 0; s < L; s += 2) {
+            // the tile consumed here was requested a step ago; the new request goes out last, so that waiting
+            // for anything older never means waiting for it
             put(s + 1, rb);
             side_use(s);
             drain(s - 1);
             side_load(s);
-            fetch(s + 3, ra);
+            fetch(s + 3, rb);
             __syncthreads();
             if (s + 1 < L) {
-                put(s + 2, rc);
+                put(s + 2, ra);
                 side_use(s + 1);
                 drain(s);
                 side_load(s + 1);
-                fetch(s + 4, rb);
-                __syncthreads();
-            }
-            if (s + 2 < L) {
-                put(s + 3, ra);
-                side_use(s + 2);
-                drain(s + 1);
-                side_load(s + 2);
-                fetch(s + 5, rc);
+                fetch(s + 4, ra);
                 __syncthreads();
             }
         }
@@ -933,7 +933,7 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
         if (FWD) {
             side_use(L); // the last layer's column sums
 #pragma unroll
-            for (int c = 0; c < kMaxClasses; ++c)
+            for (int c = 0; c < CMAX; ++c)
                 if (c < C) {
                     float v = zacc[c];
 #pragma unroll
@@ -943,6 +943,12 @@ template <bool FWD, int NT> __global__ __launch_bounds__(64 * (2 * NT + 1)) void
         }
     } else {
         // ---- contracting wavefronts ----
+        bf16x8 fifo[kDepth][KS];
+        if (total_pairs > 0) {
+#pragma unroll
+            for (int slot = 0; slot < kDepth; ++slot) issue(fifo[slot]);
+        }
+        per_layer_vectors();
         // two accumulators so that consecutive matrix instructions do not depend on each other
         f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         auto contract = [&](const bf16x8(&bq)[KS], int j) {
@@ -1920,6 +1926,9 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<true, NT>),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
                 if (e != hipSuccess) return e;
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<true, NT, 4>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                if (e != hipSuccess) return e;
                 e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<false, NT>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
                 if (e != hipSuccess) return e;
@@ -1928,7 +1937,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             {
                 ChainArgs a = ca;
                 a.Q = QpT; a.Hg = H; a.part = HSpart;
-                PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_fwd, st, a);
+                if (C <= 4) PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT, 4>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_fwd, st, a);
+                else PAC_LAUNCH(prof, st, KC_G_CHAIN_FWD, (k_gchain<true, NT>), dim3(ntiles), dim3(64 * (2 * NT + 1)), lds_fwd, st, a);
             }
             if (!io.grads) {
                 PAC_LAUNCH(prof, st, KC_G_HEAD, k_glogits, dim3(B), dim3(64), 0, st, ca);
