@@ -16,11 +16,24 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "pac_oracle.c")
-_LIB = os.path.join(_HERE, "liborc.so")
+# PAC_ORACLE_LIB: a differently built copy of the same source (the sanitizer leg of the CPU tests)
+_LIB = os.environ.get("PAC_ORACLE_LIB") or os.path.join(_HERE, "liborc.so")
+
+
+def build_sanitized(path: str) -> str:
+    """The same source built with AddressSanitizer and UndefinedBehaviorSanitizer (host only), for the
+    CPU tests' sanitizer leg.  Returns the library path."""
+    subprocess.check_call(
+        ["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+         "-fno-sanitize-recover=undefined", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+         "-o", path, _SRC, "-lm"])
+    return path
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if os.environ.get("PAC_ORACLE_LIB"):
+        return _LIB
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         tmp = _LIB + ".tmp%d" % os.getpid()
@@ -58,7 +71,7 @@ def lib():
         L.orc_bf16_to_f32_array.restype = None
         L.orc_bf16_to_f32_array.argtypes = [vp, i64, vp]
         L.orc_loss_grad.restype = C.c_int
-        L.orc_loss_grad.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.orc_loss_grad.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.orc_adamw.restype = None
         L.orc_adamw.argtypes = [i32, i32, i32, i32, vp, vp, vp, i64, vp, dbl, dbl, dbl, dbl, dbl]
         _lib = L
@@ -137,7 +150,10 @@ def widen(cache: np.ndarray) -> np.ndarray:
 
 def loss_grad(dims: Dims, cache_f32: np.ndarray, off, lens, labels, params,
               want_grads: bool = True):
-    """Returns dict(loss, logits[B,C], pooled[B,d], grads[P] or None); all float64."""
+    """Returns dict(loss, logits[B,C], pooled[B,d], grads[P] or None, glam_abs[L] or None); all float64.
+
+    glam_abs[l] is the sum of the absolute values of the terms whose signed sum is the gradient
+    of gate l (its cancellation scale)."""
     cache_f32 = np.ascontiguousarray(cache_f32, dtype=np.float32)
     off = np.ascontiguousarray(off, dtype=np.int64)
     lens = np.ascontiguousarray(lens, dtype=np.int32)
@@ -152,12 +168,13 @@ def loss_grad(dims: Dims, cache_f32: np.ndarray, off, lens, labels, params,
     logits = np.empty((B, dims.C), dtype=np.float64)
     pooled = np.empty((B, dims.d), dtype=np.float64)
     grads = np.empty(dims.P, dtype=np.float64) if want_grads else None
+    glam_abs = np.empty(dims.L, dtype=np.float64) if want_grads else None
     rc = lib().orc_loss_grad(dims.L, dims.d, dims.r, dims.C, B, _ptr(cache_f32), _ptr(off),
                              _ptr(lens), _ptr(labels), _ptr(params), C.addressof(loss),
-                             _ptr(logits), _ptr(pooled), _ptr(grads))
+                             _ptr(logits), _ptr(pooled), _ptr(grads), _ptr(glam_abs))
     if rc != 0:
         raise ValueError("oracle rejected the inputs (label/length out of range or no memory)")
-    return {"loss": float(loss.value), "logits": logits, "pooled": pooled, "grads": grads}
+    return {"loss": float(loss.value), "logits": logits, "pooled": pooled, "grads": grads, "glam_abs": glam_abs}
 
 
 @dataclass

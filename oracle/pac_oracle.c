@@ -164,13 +164,19 @@ static double gelu_deriv(double u)
  *   labels[B]
  *   params[P]  (double)
  * out: *loss, logits[B*C] (may be NULL), pooled[B*d] (may be NULL),
- *      grads[P] (may be NULL; overwritten).
+ *      grads[P] (may be NULL; overwritten),
+ *      glam_abs[L] (may be NULL; overwritten; needs grads): the cancellation scale of each gate
+ *      gradient, sum over tokens and channels of |(b_l - s_{l-1}) * dx|, i.e. the same terms as
+ *      dlambda_l with their signs dropped.  It bounds |dlambda_l| from above, with equality when
+ *      all terms share one sign, and is the size against which a rounding error of that sum is
+ *      to be judged (the gate of Sec. 4.1 mixes two d-wide streams, so its gradient is a sum of
+ *      tokens x d signed terms that may cancel).
  * Returns 0, or -1 on allocation failure / bad label / bad length.
  */
 int orc_loss_grad(int32_t L, int32_t d, int32_t r, int32_t C, int32_t B,
                   const float *cache, const int64_t *off, const int32_t *lens,
                   const int32_t *labels, const double *params,
-                  double *loss, double *logits, double *pooled, double *grads)
+                  double *loss, double *logits, double *pooled, double *grads, double *glam_abs)
 {
     const int64_t PL = orc_layer_block(d, r);
     const int64_t P = orc_param_count(L, d, r, C);
@@ -181,6 +187,7 @@ int orc_loss_grad(int32_t L, int32_t d, int32_t r, int32_t C, int32_t B,
         memset(grads, 0, (size_t)P * sizeof(double));
         gWcls = grads + (int64_t)L * PL;
         gccls = gWcls + (int64_t)d * C;
+        if (glam_abs) memset(glam_abs, 0, (size_t)L * sizeof(double));
     }
     double total = 0.0;
 
@@ -319,11 +326,15 @@ int orc_loss_grad(int32_t L, int32_t d, int32_t r, int32_t C, int32_t B,
                     gcu[j] += accu;
                 }
                 {
-                    double acc = 0.0;
+                    double acc = 0.0, acc_abs = 0.0;
                     for (int32_t t = 0; t < len; ++t)
-                        for (int32_t j = 0; j < d; ++j)
-                            acc += ((double)b[(size_t)t * d + j] - Sp[(size_t)t * d + j]) * DX[(size_t)t * d + j];
+                        for (int32_t j = 0; j < d; ++j) {
+                            double term = ((double)b[(size_t)t * d + j] - Sp[(size_t)t * d + j]) * DX[(size_t)t * d + j];
+                            acc += term;
+                            acc_abs += fabs(term);
+                        }
                     *glam += acc;
+                    if (glam_abs) glam_abs[l] += acc_abs;
                 }
                 /* ds_{l-1} = ds_l + (1 - lambda) dx */
 #pragma omp parallel for schedule(static)
