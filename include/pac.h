@@ -32,6 +32,10 @@
  *  - Every entry point returns a pac_status.  Argument errors are detected on
  *    the host before anything is launched and leave device memory untouched.
  *    Nothing throws, aborts or prints.
+ *  - Threads: a pac_ctx may be used by one host thread at a time (pac_cache_fill records sample
+ *    positions in it, the profiling calls keep their events in it).  Different contexts may be used
+ *    from different host threads at once; the library's only process-wide state is the one-time
+ *    kernel attribute set-up, which is done under std::call_once.
  *  - Arithmetic follows the cache dtype: a bf16 cache runs the contractions on
  *    bf16 MFMA with fp32 accumulation (side state, gradients, optimizer and
  *    master weights stay fp32); an fp32 cache runs everything in fp32.
@@ -101,17 +105,25 @@ typedef struct {
     float lr, beta1, beta2, eps, weight_decay;
 } pac_adamw;
 
-/* Validates cfg and builds the host context.  No device work.
- * PAC_ERR_NULL / PAC_ERR_SHAPE / PAC_ERR_UNSUPPORTED on bad input; *out untouched then. */
+/* Fixes the shape of the side network and of its cache (paper Sec. 4.1: one adapter per backbone layer,
+ * width d / reduction factor; Table "model" and Sec. 6.1 for the shapes the paper trains) and builds the
+ * host context: validation, the parameter layout, the workspace plan, the per-sample position table.
+ * No device work.  PAC_ERR_NULL / PAC_ERR_SHAPE / PAC_ERR_UNSUPPORTED on bad input; *out untouched then. */
 pac_status pac_create(const pac_config *cfg /*HOST*/, pac_ctx **out /*HOST*/);
-void pac_destroy(pac_ctx *ctx); /* NULL is allowed */
+/* Frees the host context (the cache and every other device buffer belong to the caller: Sec. 4.2's cache
+ * outlives any one training run).  NULL is allowed. */
+void pac_destroy(pac_ctx *ctx);
+/* Text of a status code (static storage); every entry point of Sec. 4.2 / 5.2's two phases reports through it. */
 const char *pac_status_str(pac_status s);
 
-/* P, the length of the flat parameter vector (see layout above); -1 if ctx is NULL. */
+/* P, the number of trainable values: the adapters of Sec. 4.1 (down- and up-projection with biases and the gate
+ * lambda per layer) plus the classification head; the backbone contributes none (it is frozen, Sec. 4.1).
+ * Layout above.  -1 if ctx is NULL. */
 int64_t pac_param_count(const pac_ctx *ctx);
 
-/* Offsets (in elements) into the flat vector.  layer in [0, L): out[0..4] =
- * W_down, c_down, W_up, c_up, lambda.  layer = -1: out[0..1] = W_cls, c_cls (out[2..4] = -1). */
+/* Where each tensor of Sec. 4.1's adapter l sits in the flat vector (offsets in elements).  layer in [0, L):
+ * out[0..4] = W_down, c_down, W_up, c_up, lambda.  layer = -1: out[0..1] = W_cls, c_cls (out[2..4] = -1).
+ * PAC_ERR_NULL, PAC_ERR_RANGE. */
 pac_status pac_param_offsets(const pac_ctx *ctx, int32_t layer, int64_t out[5] /*HOST*/);
 
 /* Bytes of cache needed for `count` samples with the given valid lengths
@@ -119,8 +131,10 @@ pac_status pac_param_offsets(const pac_ctx *ctx, int32_t layer, int64_t out[5] /
  * NULL = every sample has n_max tokens.  -1 on bad arguments. */
 int64_t pac_cache_bytes(const pac_ctx *ctx, const int32_t *lens /*HOST*/, int64_t count);
 
-/* Bytes of device workspace pac_adapter_step / pac_adapter_loss_grad need for
- * a batch of up to B_max samples of up to n_max tokens.  -1 if ctx is NULL. */
+/* Bytes of device workspace pac_adapter_step / pac_adapter_loss_grad need for a batch of up to B_max samples
+ * of up to n_max tokens: what the cached phase of Sec. 5.2 keeps per step besides the cache (r-wide
+ * activations of the side network, compute-dtype copies of the projections, partial sums of the token
+ * reductions; no d-wide per-token state on the Gram-matrix path).  -1 if ctx is NULL. */
 int64_t pac_workspace_bytes(const pac_ctx *ctx);
 
 /* Which formulation of the step (paper Sec. 4.1, 5.2: the same function of the same inputs in each)
@@ -148,14 +162,16 @@ pac_status pac_cache_fill(pac_ctx *ctx, void *cache /*DEVICE*/, int64_t cache_by
                           const void *acts /*DEVICE*/, int32_t acts_dtype,
                           const int32_t *lens /*HOST*/, void *hip_stream);
 
-/* Where a filled sample lives: element offset of its block and its length.
- * PAC_ERR_STATE if it was never filled. */
+/* Where a filled sample lives: element offset of its block ([layer][token][d], Sec. 5.2's tokens x hidden x
+ * layers elements) and its length.  PAC_ERR_NULL, PAC_ERR_RANGE; PAC_ERR_STATE if it was never filled. */
 pac_status pac_cache_lookup(const pac_ctx *ctx, int64_t sample_id,
                             int64_t *offset_elems /*HOST*/, int32_t *len /*HOST*/);
 
 /*
- * Loss and gradients of one batch read from the cache, without an update
- * (same forward/backward as pac_adapter_step; used for evaluation and parity).
+ * Loss and gradients of one batch read from the cache, without an update: the forward pass through the side
+ * network of Sec. 4.1 on cached activations (Sec. 4.2), the loss, and the exact gradients with respect to
+ * the adapters and the head only (Sec. 4.1: no gradient enters the backbone).  Same forward/backward as
+ * pac_adapter_step; used for evaluation and parity.
  *   cache       DEVICE (const: the backbone is frozen, nothing is written to it)
  *   sample_ids  HOST, B entries, each filled before; 1 <= B <= B_max
  *   labels      DEVICE, int32[B], each in [0, C) (out-of-range labels give a NaN loss)
@@ -190,6 +206,25 @@ pac_status pac_adapter_step(pac_ctx *ctx, const void *cache /*DEVICE*/,
                             void *workspace /*DEVICE*/, int64_t workspace_bytes,
                             float *loss_out /*DEVICE*/, float *grads_out /*DEVICE*/,
                             void *hip_stream);
+
+/*
+ * Measurement aids for the two rooflines the step is set against (Sec. 5.2 calls the cached phase
+ * lightweight: it is bound by how fast the cache streams from memory and, for wide adapters, by the matrix
+ * units).  Neither is part of the training path.
+ *   pac_probe_hbm_read   reads `bytes` (a multiple of 16) of `buf` once with every compute unit busy and
+ *                        nothing else to do (16-byte loads, several in flight per lane, xor-folded into
+ *                        sink[0..255] so that the loads cannot be dropped): bytes / duration is the read rate
+ *                        this chip sustains on that buffer, e.g. the resident cache slice of one step.
+ *   pac_probe_mfma_bf16  runs `iters` rounds of four independent 32x32x16 bf16 matrix instructions per
+ *                        wavefront on register operands, four wavefronts per SIMD on every compute unit:
+ *                        pac_probe_mfma_flops(iters) / duration is the matrix rate this chip sustains.
+ * sink: DEVICE, 256 floats, scratch.  The caller times the call with events on the same stream.
+ * Errors: NULL, RANGE (bytes or iters not positive, bytes not a multiple of 16), ALIGN (buf not 16-byte
+ * aligned), DEVICE.
+ */
+pac_status pac_probe_hbm_read(const void *buf /*DEVICE*/, int64_t bytes, float *sink /*DEVICE*/, void *hip_stream);
+pac_status pac_probe_mfma_bf16(int64_t iters, float *sink /*DEVICE*/, void *hip_stream);
+double pac_probe_mfma_flops(int64_t iters); /* flops one pac_probe_mfma_bf16(iters) call executes */
 
 /*
  * Measurement aid (not part of the training path): per-kernel timing with HIP

@@ -27,6 +27,7 @@ EXPORTS = [
     "pac_create", "pac_destroy", "pac_status_str", "pac_param_count", "pac_param_offsets",
     "pac_cache_bytes", "pac_workspace_bytes", "pac_step_path", "pac_cache_fill", "pac_cache_lookup",
     "pac_adapter_loss_grad", "pac_adapter_step",
+    "pac_probe_hbm_read", "pac_probe_mfma_bf16", "pac_probe_mfma_flops",
     "pac_profile_begin", "pac_profile_end", "pac_profile_class_name",
 ]
 
@@ -88,6 +89,12 @@ def lib():
         L.pac_adapter_step.restype = C.c_int
         L.pac_adapter_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, C.POINTER(i64),
                                        C.POINTER(pac_adamw), vp, i64, vp, vp, vp]
+        L.pac_probe_hbm_read.restype = C.c_int
+        L.pac_probe_hbm_read.argtypes = [vp, i64, vp, vp]
+        L.pac_probe_mfma_bf16.restype = C.c_int
+        L.pac_probe_mfma_bf16.argtypes = [i64, vp, vp]
+        L.pac_probe_mfma_flops.restype = C.c_double
+        L.pac_probe_mfma_flops.argtypes = [i64]
         L.pac_profile_begin.restype = C.c_int
         L.pac_profile_begin.argtypes = [vp]
         L.pac_profile_end.restype = C.c_int
@@ -184,6 +191,18 @@ def pac_adapter_step(ctx, cache_ptr, sample_ids, labels_ptr, params_ptr, m_ptr, 
                                   C.byref(st), C.byref(hp), ws_ptr, ws_bytes, loss_ptr, grads_ptr, stream),
            "pac_adapter_step")
     return st.value
+
+
+def pac_probe_hbm_read(buf_ptr, nbytes: int, sink_ptr, stream=0) -> None:
+    _check(lib().pac_probe_hbm_read(buf_ptr, nbytes, sink_ptr, stream), "pac_probe_hbm_read")
+
+
+def pac_probe_mfma_bf16(iters: int, sink_ptr, stream=0) -> None:
+    _check(lib().pac_probe_mfma_bf16(iters, sink_ptr, stream), "pac_probe_mfma_bf16")
+
+
+def pac_probe_mfma_flops(iters: int) -> float:
+    return float(lib().pac_probe_mfma_flops(iters))
 
 
 def pac_profile_begin(ctx) -> None:

@@ -5,6 +5,7 @@
 #include "pac_internal.h"
 
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <vector>
 #include <algorithm>
@@ -293,10 +294,11 @@ pac_status pac_adapter_loss_grad(pac_ctx *ctx, const void *cache, const int64_t 
     return launch_loss_grad(ctx->D, ctx->W, meta, io) == hipSuccess ? PAC_OK : PAC_ERR_DEVICE;
 }
 
-pac_status pac_adapter_step(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
-                            const int32_t *labels, float *params, float *m, float *v, int64_t *step,
-                            const pac_adamw *hp, void *workspace, int64_t workspace_bytes, float *loss_out,
-                            float *grads_out, void *hip_stream)
+// The step behind pac_adapter_step: forward, loss, backward, AdamW on `workspace`.
+static pac_status step_on_workspace(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
+                                    const int32_t *labels, float *params, float *m, float *v, int64_t *step,
+                                    const pac_adamw *hp, void *workspace, int64_t workspace_bytes, float *loss_out,
+                                    float *grads_out, void *hip_stream, bool may_profile)
 {
     pac_status s = check_common(ctx, cache, sample_ids, labels, params, workspace, workspace_bytes, loss_out);
     if (s != PAC_OK) return s;
@@ -312,7 +314,7 @@ pac_status pac_adapter_step(pac_ctx *ctx, const void *cache, const int64_t *samp
     char *ws = static_cast<char *>(workspace);
     float *grads = grads_out ? grads_out : reinterpret_cast<float *>(ws + ctx->W.grads);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    Profiler *prof = ctx->prof.on ? &ctx->prof : nullptr;
+    Profiler *prof = (may_profile && ctx->prof.on) ? &ctx->prof : nullptr;
     StepIO io{cache, labels, params, ws, loss_out, nullptr, grads, st, prof};
     Deferred fin;
     io.defer = &fin;
@@ -326,6 +328,15 @@ pac_status pac_adapter_step(pac_ctx *ctx, const void *cache, const int64_t *samp
     if (launch_adamw(ctx->D, params, m, v, grads, a, st, prof, &fin) != hipSuccess) return PAC_ERR_DEVICE;
     *step = t;
     return PAC_OK;
+}
+
+pac_status pac_adapter_step(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
+                            const int32_t *labels, float *params, float *m, float *v, int64_t *step,
+                            const pac_adamw *hp, void *workspace, int64_t workspace_bytes, float *loss_out,
+                            float *grads_out, void *hip_stream)
+{
+    return step_on_workspace(ctx, cache, sample_ids, B, labels, params, m, v, step, hp, workspace, workspace_bytes,
+                             loss_out, grads_out, hip_stream, true);
 }
 
 } // extern "C"

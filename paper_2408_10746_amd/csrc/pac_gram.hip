@@ -21,6 +21,7 @@
 // oracle's); only the order of the floating-point operations differs.  Every reduction is ordered.
 #include "pac_mma.h"
 #include "pac_internal.h"
+#include <mutex>
 #include <type_traits>
 
 namespace pac {
@@ -147,7 +148,6 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.g_GGsc = take(Lr * Lr * 2);
     W.g_dlam_slots = cdiv(D.d, 64) * cdiv(D.r, 64);
     W.g_dlam_part = take((int64_t)D.L * W.g_dlam_slots * 4);
-    W.g_counter = take((int64_t)(D.L + 1) * 4);
     W.g_samp_tile0 = take((kMaxBatch + 1) * 4);
     W.g_loss_part = take(kMaxBatch * 4);
 }
@@ -217,7 +217,6 @@ struct PrepArgs {
     int32_t *tile_row0, *tile_rows, *tile_samp, *samp_tile0;
     bf16_t *WdT, *Wu, *WuTs, *Wds;
     float *cusum, *V;
-    unsigned *counter;
     float *zero; // 64 floats kept at zero for the contractions' empty token slots
 };
 
@@ -235,7 +234,6 @@ template <int TPB, int RPW> __global__ __launch_bounds__(256) void k_gprep(PrepA
                 a.samp_start[t] = meta.tok_start[t];
                 if (t < meta.B) a.samp_len[t] = meta.len[t];
             }
-            if (t <= L) a.counter[t] = 0u;
             if (t < 64) a.zero[t] = 0.f;
             if (t < meta.B) {
                 // tiles of sample t start after the tiles of the samples before it
@@ -1449,7 +1447,6 @@ struct PostArgs {
     const float *Epart, *cusum, *cs, *Z, *dzsum, *dz, *pb;
     float *grads;
     float *dlam_part;
-    unsigned *counter;
     int slots;
 };
 
@@ -1805,14 +1802,17 @@ static void launch_parts(Profiler *prof, hipStream_t st, bool split, Kern kern, 
     }
 }
 
-// raises a kernel's dynamic LDS limit the first time it is about to be launched
+// Raises a kernel's dynamic LDS limit before its first launch: once per process and kernel, whichever host
+// thread comes first (contexts may be stepped from several threads; the others wait for the call to finish
+// and all see its result).
 template <auto Kern> static hipError_t allow_lds_once(int lds)
 {
-    static bool done = false;
-    if (done) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e == hipSuccess) done = true;
-    return e;
+    static std::once_flag once;
+    static hipError_t result = hipSuccess;
+    std::call_once(once, [&] {
+        result = hipFuncSetAttribute(reinterpret_cast<const void *>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    return result;
 }
 
 template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io)
@@ -1851,7 +1851,6 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     float *Epart = (float *)(ws + W.g_Epart), *GGpart = (float *)(ws + W.g_GGpart);
     bf16_t *GGT = (bf16_t *)(ws + W.g_GGT), *GGsc = (bf16_t *)(ws + W.g_GGsc);
     float *dlam_part = (float *)(ws + W.g_dlam_part);
-    unsigned *counter = (unsigned *)(ws + W.g_counter);
     const RowMap map{rowoff, rowstride, M};
     const bf16_t *cache = (const bf16_t *)io.cache;
 
@@ -1864,7 +1863,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.rowoff = rowoff; a.rowstride = rowstride; a.rowsamp = rowsamp; a.samp_start = samp_start;
         a.samp_len = samp_len; a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.tile_samp = tile_samp; a.samp_tile0 = samp_tile0;
         a.WdT = WdT; a.Wu = Wu; a.WuTs = WuTs; a.Wds = Wds; a.cusum = cusum; a.V = V;
-        a.counter = counter; a.zero = (float *)(ws + W.g_zero);
+        a.zero = (float *)(ws + W.g_zero);
         const int v_rpw = tpb == 1 ? 1 : 4;
         const int counts[4] = {a.nb_setup, a.nb_shadow, a.nb_chat, cdiv(Lr, 4 * v_rpw)};
         const int classes[4] = {KC_G_PREP_SETUP, KC_G_PREP_COPY, KC_G_PREP_CHAT, KC_G_PREP_V};
@@ -1905,13 +1904,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         }
     }
     PAC_HIP_TRY(hipGetLastError());
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gtokred<NT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, TokRedShapes<NT>::kLds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    PAC_HIP_TRY((allow_lds_once<&k_gtokred<NT>>(TokRedShapes<NT>::kLds)));
     ChainArgs ca;
     ca.L = L; ca.r = r; ca.M = M; ca.tile_row0 = tile_row0; ca.tile_rows = tile_rows; ca.tile_samp = tile_samp;
     ca.params = io.params; ca.PL = D.PL; ca.d = d; ca.U = pre; ca.Gp = (bf16_t *)(ws + W.g_Gp); ca.chat = chat;
@@ -1921,19 +1914,9 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
     if (W.use_gram == 1) {
         if constexpr (NT <= 4) {
             const size_t lds_fwd = chain_lds(L, r, true), lds_bwd = chain_lds(L, r, false);
-            static bool chain_attr_done = false;
-            if (!chain_attr_done) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<true, NT>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-                if (e != hipSuccess) return e;
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<true, NT, 4>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-                if (e != hipSuccess) return e;
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gchain<false, NT>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-                if (e != hipSuccess) return e;
-                chain_attr_done = true;
-            }
+            PAC_HIP_TRY((allow_lds_once<&k_gchain<true, NT>>(160 * 1024)));
+            PAC_HIP_TRY((allow_lds_once<&k_gchain<true, NT, 4>>(160 * 1024)));
+            PAC_HIP_TRY((allow_lds_once<&k_gchain<false, NT>>(160 * 1024)));
             {
                 ChainArgs a = ca;
                 a.Q = QpT; a.Hg = H; a.part = HSpart;
@@ -1959,16 +1942,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         const bool k64 = r % 64 == 0;
         const int big_lds = k64 ? SeqShapes<64>::TB::LDS_BYTES : SeqShapes<32>::TB::LDS_BYTES;
         const int small_lds = k64 ? SeqShapes<64>::TS::LDS_BYTES : SeqShapes<32>::TS::LDS_BYTES;
-        static bool seq_attr_done = false;
-        if (!seq_attr_done) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gseq_big<64>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, SeqShapes<64>::TB::LDS_BYTES);
-            if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gseq_big<32>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, SeqShapes<32>::TB::LDS_BYTES);
-            if (e != hipSuccess) return e;
-            seq_attr_done = true;
-        }
+        PAC_HIP_TRY((allow_lds_once<&k_gseq_big<64>>(SeqShapes<64>::TB::LDS_BYTES)));
+        PAC_HIP_TRY((allow_lds_once<&k_gseq_big<32>>(SeqShapes<32>::TB::LDS_BYTES)));
         float *P = (float *)(ws + W.g_P), *ghat = (float *)(ws + W.g_ghat);
         const int g = W.chain_group, ldp = g * r;
         const int rt128 = cdiv(M, kSeqTile), rt64 = cdiv(M, 64), ct64 = cdiv(r, 64);
@@ -2062,21 +2037,13 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         pa.nb_vec = cdiv(d, (256 / NH) / L) + 1;
         pa.params = io.params; pa.PL = D.PL; pa.WuTs = WuTs; pa.Wds = Wds; pa.GGT = GGT; pa.GGsc = GGsc;
         pa.Epart = (const float *)(ws + W.g_E); pa.cusum = cusum; pa.cs = cs; pa.Z = Z; pa.dzsum = dzsum; pa.dz = dz; pa.pb = pb;
-        pa.grads = io.grads; pa.dlam_part = dlam_part; pa.counter = counter;
+        pa.grads = io.grads; pa.dlam_part = dlam_part;
         pa.slots = cdiv(d, kFRows) * cdiv(r, kFCols);
         {
             const int counts[3] = {pa.nb_F, pa.nb_W, pa.nb_vec};
             const int classes[3] = {KC_G_POST_F, KC_G_POST_W, KC_G_POST_VEC};
-            static bool done = false;
-            if (!done) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<64, BIG, XW>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<64, BIG, XW>::kLds);
-                if (e != hipSuccess) return e;
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gpost<32, BIG, XW>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, PostShapes<32, BIG, XW>::kLds);
-                if (e != hipSuccess) return e;
-                done = true;
-            }
+            PAC_HIP_TRY((allow_lds_once<&k_gpost<64, BIG, XW>>(PostShapes<64, BIG, XW>::kLds)));
+            PAC_HIP_TRY((allow_lds_once<&k_gpost<32, BIG, XW>>(PostShapes<32, BIG, XW>::kLds)));
             if (r % 64 == 0)
                 launch_parts(prof, st, split, k_gpost<64, BIG, XW>, pa, 3, counts, classes, KC_G_POST, kPostThreads, PostShapes<64, BIG, XW>::kLds);
             else

@@ -50,7 +50,7 @@ struct WsLayout {
     int64_t g_Z, g_dzsum, g_cs;
     int64_t g_Epart, g_GGpart;      // f32 [se][L][d*r], [sg][L*r][L*r]
     int64_t g_GGT, g_GGsc;          // bf16 [L*r][L*r]
-    int64_t g_dlam_part, g_counter; // f32 [L][slots], u32 [L + 1]
+    int64_t g_dlam_part;            // f32 [L][slots]
     int64_t g_samp_tile0, g_loss_part, g_Gp, g_E, g_zero;
     int32_t g_dlam_slots;
 };

@@ -57,26 +57,29 @@ void plan_workspace(const Dims &D, WsLayout &W)
     W.samp_start = take((kMaxBatch + 1) * 4);
     W.samp_len = take(kMaxBatch * 4);
     const int64_t wbytes = (int64_t)D.L * D.d * D.r * tc;
-    W.Wd = take(wbytes);
+    // The Gram-matrix formulation keeps no d-wide per-token state and needs two of the four projection copies:
+    // the per-layer regions it never touches (gigabytes at the wide shapes) are not reserved for it.
+    const bool gram = gram_path_kind(D) != 0;
+    W.Wd = gram ? 0 : take(wbytes);
     W.WdT = take(wbytes);
     W.Wu = take(wbytes);
-    W.WuT = take(wbytes);
-    W.s_all = take((int64_t)D.L * D.Mmax * D.d * 4);
+    W.WuT = gram ? 0 : take(wbytes);
+    W.s_all = gram ? 0 : take((int64_t)D.L * D.Mmax * D.d * 4);
     W.pre_all = take((int64_t)D.L * D.Mmax * D.r * 4);
     W.h_all = take((int64_t)D.L * D.Mmax * D.r * tc);
-    W.ds = take(D.Mmax * D.d * 4);
-    W.dpre = take(D.Mmax * D.r * tc);
+    W.ds = gram ? 0 : take(D.Mmax * D.d * 4);
+    W.dpre = gram ? 0 : take(D.Mmax * D.r * tc);
     W.pooled = take((int64_t)D.B_max * D.d * 4);
     W.logits = take((int64_t)D.B_max * D.C * 4);
     W.dz = take((int64_t)D.B_max * D.C * 4);
     W.splits = choose_splits(D);
-    W.part = take((int64_t)W.splits * D.PL * 4);
+    W.part = gram ? 0 : take((int64_t)W.splits * D.PL * 4);
     W.dlam_slots = cdiv(D.Mmax, 64) * cdiv(D.d, 64);
     if (W.dlam_slots < D.B_max * D.r) W.dlam_slots = D.B_max * D.r; // also holds the top layer's dh [B][r]
-    W.dlam_part = take((int64_t)W.dlam_slots * 4);
+    W.dlam_part = gram ? 0 : take((int64_t)W.dlam_slots * 4);
     W.grads = take(D.P * 4);
     W.use_gram = 0;
-    if (gram_path_kind(D)) plan_gram_workspace(D, W, o);
+    if (gram) plan_gram_workspace(D, W, o);
     W.total = o;
 }
 

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def header_functions():
     src = open(os.path.join(ROOT, "include", "pac.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(pac_[a-z_]+)\s*\(", src)))
+    return sorted(set(re.findall(r"\b(pac_[a-z0-9_]+)\s*\(", src)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -137,6 +137,14 @@ def test_argument_errors_are_caught_before_any_launch():
         assert stepcall(C.byref(pb.pac_adamw(1e-3, 1.0, 0.999, 1e-8, 0.0)), C.byref(st)) == pb.PAC_ERR_RANGE
         assert stepcall(C.byref(hp), C.byref(C.c_int64(-1))) == pb.PAC_ERR_RANGE
         assert stepcall(C.byref(hp), C.byref(st)) == pb.PAC_ERR_STATE and st.value == 0
+        # measurement probes: argument errors before any launch
+        assert lib.pac_probe_hbm_read(None, 1024, dev, None) == pb.PAC_ERR_NULL
+        assert lib.pac_probe_hbm_read(dev, 0, dev, None) == pb.PAC_ERR_RANGE
+        assert lib.pac_probe_hbm_read(dev, 1000, dev, None) == pb.PAC_ERR_RANGE
+        assert lib.pac_probe_hbm_read(dev + 8, 1024, dev, None) == pb.PAC_ERR_ALIGN
+        assert lib.pac_probe_mfma_bf16(0, dev, None) == pb.PAC_ERR_RANGE
+        assert lib.pac_probe_mfma_bf16(10, None, None) == pb.PAC_ERR_NULL
+        assert pb.pac_probe_mfma_flops(1) == 4 * 2 * 32 * 32 * 16 * 4 * 1024
         assert lib.pac_profile_end(ctx, 32, None, None, None) == pb.PAC_ERR_NULL
         for s in range(9):
             assert isinstance(pb.status_str(s), str) and pb.status_str(s)
