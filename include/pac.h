@@ -35,7 +35,8 @@
  *  - Threads: a pac_ctx may be used by one host thread at a time (pac_cache_fill records sample
  *    positions in it, the profiling calls keep their events in it).  Different contexts may be used
  *    from different host threads at once; the library's only process-wide state is the one-time
- *    kernel attribute set-up, which is done under std::call_once.
+ *    kernel attribute set-up, which is done under std::call_once.  pac_adapter_step_static calls
+ *    additionally share one per-device scratch array (see there).
  *  - Arithmetic follows the cache dtype: a bf16 cache runs the contractions on
  *    bf16 MFMA with fp32 accumulation (side state, gradients, optimizer and
  *    master weights stay fp32); an fp32 cache runs everything in fp32.
@@ -206,6 +207,27 @@ pac_status pac_adapter_step(pac_ctx *ctx, const void *cache /*DEVICE*/,
                             void *workspace /*DEVICE*/, int64_t workspace_bytes,
                             float *loss_out /*DEVICE*/, float *grads_out /*DEVICE*/,
                             void *hip_stream);
+
+/*
+ * The same step for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation): the workspace is a file-scope device
+ * array inside the library, PAC_STATIC_WORKSPACE_BYTES long, which every GPU the library runs on holds
+ * from the first such call until the process ends.  Nothing is allocated or freed, by the library or
+ * through any other library, and nothing is recorded for the profiling calls.
+ * Limits: pac_workspace_bytes(ctx) must not exceed PAC_STATIC_WORKSPACE_BYTES (PAC_ERR_WORKSPACE otherwise,
+ * before anything is launched).  Every call on one GPU uses that GPU's one array, whose contents are scratch
+ * between calls: calls that overlap on one GPU (two streams, two host threads, two contexts) race; calls
+ * ordered on one stream are safe.  Other arguments, results and errors as in pac_adapter_step, which shares
+ * its kernels.
+ */
+#define PAC_STATIC_WORKSPACE_BYTES (64ll << 20)
+pac_status pac_adapter_step_static(pac_ctx *ctx, const void *cache /*DEVICE*/,
+                                   const int64_t *sample_ids /*HOST*/, int32_t B,
+                                   const int32_t *labels /*DEVICE*/,
+                                   float *params /*DEVICE*/, float *m /*DEVICE*/, float *v /*DEVICE*/,
+                                   int64_t *step /*HOST*/, const pac_adamw *hp /*HOST*/,
+                                   float *loss_out /*DEVICE*/, float *grads_out /*DEVICE*/,
+                                   void *hip_stream);
 
 /*
  * Measurement aids for the two rooflines the step is set against (Sec. 5.2 calls the cached phase

@@ -26,10 +26,11 @@ PAC_FLAG_LAYER_CHAIN = 4
 EXPORTS = [
     "pac_create", "pac_destroy", "pac_status_str", "pac_param_count", "pac_param_offsets",
     "pac_cache_bytes", "pac_workspace_bytes", "pac_step_path", "pac_cache_fill", "pac_cache_lookup",
-    "pac_adapter_loss_grad", "pac_adapter_step",
+    "pac_adapter_loss_grad", "pac_adapter_step", "pac_adapter_step_static",
     "pac_probe_hbm_read", "pac_probe_mfma_bf16", "pac_probe_mfma_flops",
     "pac_profile_begin", "pac_profile_end", "pac_profile_class_name",
 ]
+PAC_STATIC_WORKSPACE_BYTES = 64 << 20
 
 
 class pac_config(C.Structure):
@@ -89,6 +90,9 @@ def lib():
         L.pac_adapter_step.restype = C.c_int
         L.pac_adapter_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, C.POINTER(i64),
                                        C.POINTER(pac_adamw), vp, i64, vp, vp, vp]
+        L.pac_adapter_step_static.restype = C.c_int
+        L.pac_adapter_step_static.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, C.POINTER(i64),
+                                              C.POINTER(pac_adamw), vp, vp, vp]
         L.pac_probe_hbm_read.restype = C.c_int
         L.pac_probe_hbm_read.argtypes = [vp, i64, vp, vp]
         L.pac_probe_mfma_bf16.restype = C.c_int
@@ -190,6 +194,17 @@ def pac_adapter_step(ctx, cache_ptr, sample_ids, labels_ptr, params_ptr, m_ptr, 
     _check(lib().pac_adapter_step(ctx, cache_ptr, _hp(ids), ids.shape[0], labels_ptr, params_ptr, m_ptr, v_ptr,
                                   C.byref(st), C.byref(hp), ws_ptr, ws_bytes, loss_ptr, grads_ptr, stream),
            "pac_adapter_step")
+    return st.value
+
+
+def pac_adapter_step_static(ctx, cache_ptr, sample_ids, labels_ptr, params_ptr, m_ptr, v_ptr, step: int,
+                            hp: pac_adamw, loss_ptr, grads_ptr=None, stream=0) -> int:
+    """pac_adapter_step on the library's own static workspace.  Returns the incremented step count."""
+    ids = _host_i64(sample_ids)
+    st = C.c_int64(step)
+    _check(lib().pac_adapter_step_static(ctx, cache_ptr, _hp(ids), ids.shape[0], labels_ptr, params_ptr, m_ptr,
+                                         v_ptr, C.byref(st), C.byref(hp), loss_ptr, grads_ptr, stream),
+           "pac_adapter_step_static")
     return st.value
 
 

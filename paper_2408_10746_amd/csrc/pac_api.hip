@@ -35,6 +35,34 @@ static void drop_events(Profiler &p)
     p.cls.clear();
 }
 
+// Workspace of pac_adapter_step_static: device memory that belongs to the library's code object, so that no
+// call of that entry point allocates.  In host code `scratch` is only a handle for the symbol; the address of
+// each GPU's own copy comes from hipGetSymbolAddress, once per device, and only that address is ever handed to a
+// kernel.  Nothing in it needs to start at zero: the step's first launch writes every table, counter and zero
+// block the later launches read.
+static __device__ __align__(256) unsigned char scratch[PAC_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices]; // per device, null until asked for
+
+static hipError_t static_scratch_address(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
 static inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 static inline int64_t elem_bytes(int32_t dt) { return dt == PAC_BF16 ? 2 : 4; }
 
@@ -294,7 +322,7 @@ pac_status pac_adapter_loss_grad(pac_ctx *ctx, const void *cache, const int64_t 
     return launch_loss_grad(ctx->D, ctx->W, meta, io) == hipSuccess ? PAC_OK : PAC_ERR_DEVICE;
 }
 
-// The step behind pac_adapter_step: forward, loss, backward, AdamW on `workspace`.
+// The step behind pac_adapter_step and pac_adapter_step_static: forward, loss, backward, AdamW on `workspace`.
 static pac_status step_on_workspace(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
                                     const int32_t *labels, float *params, float *m, float *v, int64_t *step,
                                     const pac_adamw *hp, void *workspace, int64_t workspace_bytes, float *loss_out,
@@ -337,6 +365,18 @@ pac_status pac_adapter_step(pac_ctx *ctx, const void *cache, const int64_t *samp
 {
     return step_on_workspace(ctx, cache, sample_ids, B, labels, params, m, v, step, hp, workspace, workspace_bytes,
                              loss_out, grads_out, hip_stream, true);
+}
+
+pac_status pac_adapter_step_static(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
+                                   const int32_t *labels, float *params, float *m, float *v, int64_t *step,
+                                   const pac_adamw *hp, float *loss_out, float *grads_out, void *hip_stream)
+{
+    if (!ctx) return PAC_ERR_NULL;
+    if (ctx->W.total > PAC_STATIC_WORKSPACE_BYTES) return PAC_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (static_scratch_address(&ws) != hipSuccess || !ws) return PAC_ERR_DEVICE;
+    return step_on_workspace(ctx, cache, sample_ids, B, labels, params, m, v, step, hp, ws, PAC_STATIC_WORKSPACE_BYTES,
+                             loss_out, grads_out, hip_stream, false);
 }
 
 } // extern "C"
