@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-CACHE_PASS_CLASSES = ("g_proj", "g_tokred", "fwd_down", "bwd_wgrad", "g_fwd", "g_bwd")
+CACHE_PASS_CLASSES = ("g_proj", "g_tokred", "fwd_down", "bwd_wgrad")
 
 
 def kernel_models(w, M):
