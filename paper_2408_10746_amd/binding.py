@@ -29,6 +29,7 @@ EXPORTS = [
     "pac_adapter_loss_grad", "pac_adapter_step", "pac_adapter_step_static",
     "pac_probe_hbm_read", "pac_probe_mfma_bf16", "pac_probe_mfma_flops",
     "pac_profile_begin", "pac_profile_end", "pac_profile_class_name",
+    "pac_plan_hybrid", "pac_plan_stage_time",
 ]
 PAC_STATIC_WORKSPACE_BYTES = 64 << 20
 
@@ -42,6 +43,21 @@ class pac_config(C.Structure):
 class pac_adamw(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float)]
+
+
+class pac_plan_problem(C.Structure):
+    _dp = C.POINTER(C.c_double)
+    _fields_ = [("L", C.c_int32), ("n_dev", C.c_int32), ("B", C.c_int32), ("M", C.c_int32),
+                ("t_f", _dp), ("t_b", _dp), ("mem_fixed", _dp), ("mem_act", _dp), ("mem_budget", _dp),
+                ("act_bytes", _dp), ("grad_bytes", _dp), ("train_bytes", _dp), ("bandwidth", C.c_double)]
+
+
+class pac_plan_result(C.Structure):
+    _ip, _dp = C.POINTER(C.c_int32), C.POINTER(C.c_double)
+    _fields_ = [("sigma", C.c_int32), ("stage_first_layer", _ip), ("stage_last_layer", _ip),
+                ("stage_first_dev", _ip), ("stage_n_dev", _ip), ("samples", _ip), ("slowest_stage", C.c_double),
+                ("L_b", C.c_double), ("L_e", C.c_double), ("L_n", C.c_double),
+                ("latency_by_stage_count", _dp), ("slowest_by_stage_count", _dp)]
 
 
 class PacError(RuntimeError):
@@ -99,6 +115,10 @@ def lib():
         L.pac_probe_mfma_bf16.argtypes = [i64, vp, vp]
         L.pac_probe_mfma_flops.restype = C.c_double
         L.pac_probe_mfma_flops.argtypes = [i64]
+        L.pac_plan_hybrid.restype = C.c_int
+        L.pac_plan_hybrid.argtypes = [C.POINTER(pac_plan_problem), C.POINTER(pac_plan_result)]
+        L.pac_plan_stage_time.restype = C.c_double
+        L.pac_plan_stage_time.argtypes = [C.POINTER(pac_plan_problem), i32, i32, i32, i32, vp]
         L.pac_profile_begin.restype = C.c_int
         L.pac_profile_begin.argtypes = [vp]
         L.pac_profile_end.restype = C.c_int
@@ -218,6 +238,44 @@ def pac_probe_mfma_bf16(iters: int, sink_ptr, stream=0) -> None:
 
 def pac_probe_mfma_flops(iters: int) -> float:
     return float(lib().pac_probe_mfma_flops(iters))
+
+
+def _plan_problem(t_f, t_b, mem_fixed, mem_act, mem_budget, act_bytes, grad_bytes, train_bytes, bandwidth, M):
+    """Marshals numpy arrays into a pac_plan_problem; returns (struct, arrays kept alive)."""
+    arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in
+            (t_f, t_b, mem_fixed, mem_act, mem_budget, act_bytes, grad_bytes, train_bytes)]
+    n_dev, L, B1 = arrs[0].shape
+    dp = C.POINTER(C.c_double)
+    prob = pac_plan_problem(L, n_dev, B1 - 1, int(M), *[a.ctypes.data_as(dp) for a in arrs], float(bandwidth))
+    return prob, arrs
+
+
+def pac_plan_hybrid(t_f, t_b, mem_fixed, mem_act, mem_budget, act_bytes, grad_bytes, train_bytes, bandwidth, M) -> dict:
+    """Algorithm 1 of Sec. 5.1 on host arrays (t_f, t_b: [n_dev][L][B+1]).  Returns the chosen configuration."""
+    prob, keep = _plan_problem(t_f, t_b, mem_fixed, mem_act, mem_budget, act_bytes, grad_bytes, train_bytes, bandwidth, M)
+    S = min(prob.L, prob.n_dev)
+    ia = [np.zeros(S, dtype=np.int32) for _ in range(4)]
+    samples = np.zeros(prob.n_dev, dtype=np.int32)
+    lat, slow = np.zeros(S + 1), np.zeros(S + 1)
+    ip, dp = C.POINTER(C.c_int32), C.POINTER(C.c_double)
+    res = pac_plan_result(0, *[a.ctypes.data_as(ip) for a in ia], samples.ctypes.data_as(ip), 0.0, 0.0, 0.0, 0.0,
+                          lat.ctypes.data_as(dp), slow.ctypes.data_as(dp))
+    _check(lib().pac_plan_hybrid(C.byref(prob), C.byref(res)), "pac_plan_hybrid")
+    s = res.sigma
+    return {"sigma": s, "stage_first_layer": ia[0][:s].tolist(), "stage_last_layer": ia[1][:s].tolist(),
+            "stage_first_dev": ia[2][:s].tolist(), "stage_n_dev": ia[3][:s].tolist(), "samples": samples.tolist(),
+            "slowest_stage": res.slowest_stage, "L_b": res.L_b, "L_e": res.L_e, "L_n": res.L_n,
+            "latency_by_stage_count": lat, "slowest_by_stage_count": slow}
+
+
+def pac_plan_stage_time(t_f, t_b, mem_fixed, mem_act, mem_budget, x, y, d_first, n):
+    """T(x -> y, {d_first ..}) of Eq. "dp2" and the dispatch that attains it."""
+    L = np.asarray(t_f).shape[1]
+    z = np.zeros(L)
+    prob, keep = _plan_problem(t_f, t_b, mem_fixed, mem_act, mem_budget, z, z, z, 1.0, 1)
+    samples = np.zeros(max(n, 1), dtype=np.int32)
+    t = lib().pac_plan_stage_time(C.byref(prob), x, y, d_first, n, samples.ctypes.data_as(C.c_void_p))
+    return float(t), samples.tolist()
 
 
 def pac_profile_begin(ctx) -> None:

@@ -9,8 +9,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libpac.so")
 OBJ_DIR = os.path.join(_HERE, "_build")
-SOURCES = ["pac_api.hip", "pac_kernels.hip", "pac_gram.hip", "pac_stream.hip", "pac_probe.hip"]
-HEADERS = ["pac_gemm.h", "pac_mma.h", "pac_internal.h", os.path.join("..", "..", "include", "pac.h")]
+SOURCES = ["pac_api.hip", "pac_kernels.hip", "pac_gram.hip", "pac_probe.hip", "pac_plan.hip"]
+HEADERS = ["pac_gemm.h", "pac_mma.h", "pac_internal.h", os.path.join("..", "..", "include", "pac.h"),
+           os.path.join("..", "..", "include", "pac_plan.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
