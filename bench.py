@@ -263,6 +263,49 @@ def cpu_baseline(w, keep_host, lens_all, labels, cpu_ids, seconds):
     return out
 
 
+def bench_first_epoch_storage(torch, pb):
+    """The first epoch's storage side on one backbone-sized projection (4096 x 4096, the LLaMA-7B shape's hidden size):
+    block-wise quantisation (HBM-bound: 4 bytes read + 1 written per weight) and the mixed-precision linear layer on
+    4096 token rows (matrix-bound: 2 M K N flops), each timed with events on the stream it runs on."""
+    dev = torch.device("cuda:0")
+    st = int(torch.cuda.current_stream().cuda_stream)
+    N = K = M = 4096
+    block = 64
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    W = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) / 64.0
+    x = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    y = torch.empty((M, N), dtype=torch.float32, device=dev)
+    consts = torch.empty(N * K // block, dtype=torch.float32, device=dev)
+    out = {}
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    for bits in (8, 4):
+        codes = torch.empty(N * K * bits // 8, dtype=torch.int8, device=dev)
+        tq = timed(lambda: pb.pac_quant_blockwise(W.data_ptr(), N * K, block, bits, codes.data_ptr(), consts.data_ptr(), st), 20)
+        tl = timed(lambda: pb.pac_dequant_linear(x.data_ptr(), M, K, codes.data_ptr(), consts.data_ptr(), N, block, bits,
+                                                 y.data_ptr(), st), 10)
+        qbytes = N * K * (4 + bits / 8) + consts.numel() * 4
+        out[f"int{bits}"] = {
+            "quantise": {"us": tq * 1e6, "bound": "hbm", "achieved": qbytes / tq / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": qbytes / tq / 1e9 / HBM_PEAK_GBS},
+            "linear": {"us": tl * 1e6, "bound": "mfma", "achieved": 2.0 * M * K * N / tl / 1e12,
+                       "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": 2.0 * M * K * N / tl / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        }
+    out["shape"] = f"W {N}x{K} fp32 in blocks of {block}; linear layer on {M} bf16 token rows"
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -321,6 +364,16 @@ def main():
             except Exception as ex:  # the headline stays valid if another configuration cannot run on this machine
                 configs[name] = {"error": f"{type(ex).__name__}: {ex}"}
 
+    extras = {}
+    if not args.no_configs:
+        gc.collect()
+        torch.cuda.empty_cache()
+        try:
+            from paper_2408_10746_amd import binding as pb
+            extras["first_epoch_storage"] = bench_first_epoch_storage(torch, pb)
+        except Exception as ex:
+            extras["first_epoch_storage"] = {"error": f"{type(ex).__name__}: {ex}"}
+
     out = {
         "metric": "adapter-train samples/sec from activation cache",
         "value": head["samples_per_s"],
@@ -337,6 +390,7 @@ def main():
         "whole_step": head["whole_step"],
         "cpu_baseline": cpu,
         "configs": configs,
+        "extras": extras,
     }
     print(json.dumps(out))
 

@@ -30,6 +30,7 @@ EXPORTS = [
     "pac_probe_hbm_read", "pac_probe_mfma_bf16", "pac_probe_mfma_flops",
     "pac_profile_begin", "pac_profile_end", "pac_profile_class_name",
     "pac_plan_hybrid", "pac_plan_stage_time",
+    "pac_quant_blockwise", "pac_dequant_blockwise", "pac_dequant_linear", "pac_dequant_linear_to_cache",
 ]
 PAC_STATIC_WORKSPACE_BYTES = 64 << 20
 
@@ -115,6 +116,14 @@ def lib():
         L.pac_probe_mfma_bf16.argtypes = [i64, vp, vp]
         L.pac_probe_mfma_flops.restype = C.c_double
         L.pac_probe_mfma_flops.argtypes = [i64]
+        L.pac_quant_blockwise.restype = C.c_int
+        L.pac_quant_blockwise.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        L.pac_dequant_blockwise.restype = C.c_int
+        L.pac_dequant_blockwise.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+        L.pac_dequant_linear.restype = C.c_int
+        L.pac_dequant_linear.argtypes = [vp, i32, i32, vp, vp, i32, i32, i32, vp, vp]
+        L.pac_dequant_linear_to_cache.restype = C.c_int
+        L.pac_dequant_linear_to_cache.argtypes = [vp, vp, i64, vp, i32, vp, i32, vp, i32, vp, vp, i32, i32, vp]
         L.pac_plan_hybrid.restype = C.c_int
         L.pac_plan_hybrid.argtypes = [C.POINTER(pac_plan_problem), C.POINTER(pac_plan_result)]
         L.pac_plan_stage_time.restype = C.c_double
@@ -276,6 +285,26 @@ def pac_plan_stage_time(t_f, t_b, mem_fixed, mem_act, mem_budget, x, y, d_first,
     samples = np.zeros(max(n, 1), dtype=np.int32)
     t = lib().pac_plan_stage_time(C.byref(prob), x, y, d_first, n, samples.ctypes.data_as(C.c_void_p))
     return float(t), samples.tolist()
+
+
+def pac_quant_blockwise(x_ptr, n: int, block: int, bits: int, codes_ptr, consts_ptr, stream=0) -> None:
+    _check(lib().pac_quant_blockwise(x_ptr, n, block, bits, codes_ptr, consts_ptr, stream), "pac_quant_blockwise")
+
+
+def pac_dequant_blockwise(codes_ptr, consts_ptr, n: int, block: int, bits: int, out_ptr, stream=0) -> None:
+    _check(lib().pac_dequant_blockwise(codes_ptr, consts_ptr, n, block, bits, out_ptr, stream), "pac_dequant_blockwise")
+
+
+def pac_dequant_linear(x_ptr, M: int, K: int, codes_ptr, consts_ptr, N: int, block: int, bits: int, y_ptr, stream=0) -> None:
+    _check(lib().pac_dequant_linear(x_ptr, M, K, codes_ptr, consts_ptr, N, block, bits, y_ptr, stream), "pac_dequant_linear")
+
+
+def pac_dequant_linear_to_cache(ctx, cache_ptr, cache_bytes, sample_ids, lens, layer: int, x_ptr, K: int, codes_ptr,
+                                consts_ptr, block: int, bits: int, stream=0) -> None:
+    ids = _host_i64(sample_ids)
+    la = _host_i32(lens)
+    _check(lib().pac_dequant_linear_to_cache(ctx, cache_ptr, cache_bytes, _hp(ids), ids.shape[0], _hp(la), layer, x_ptr, K,
+                                             codes_ptr, consts_ptr, block, bits, stream), "pac_dequant_linear_to_cache")
 
 
 def pac_profile_begin(ctx) -> None:

@@ -2,6 +2,7 @@
 // validation, and the hand-off to the kernel launchers.  All checks run on the
 // host before anything is enqueued.
 #include "../../include/pac.h"
+#include "../../include/pac_quant.h"
 #include "pac_internal.h"
 
 #include <cmath>
@@ -208,22 +209,16 @@ pac_status pac_cache_lookup(const pac_ctx *ctx, int64_t sample_id, int64_t *offs
     return PAC_OK;
 }
 
-pac_status pac_cache_fill(pac_ctx *ctx, void *cache, int64_t cache_bytes, const int64_t *sample_ids, int32_t count,
-                          const void *acts, int32_t acts_dtype, const int32_t *lens, void *hip_stream)
+} // extern "C"
+
+// Where the blocks of `count` samples go: a known sample keeps its block (and must keep its length), a new one is
+// appended after the blocks placed so far.  Validates everything and touches nothing; commit_samples records the result.
+static pac_status place_samples(const pac_ctx *ctx, int64_t cache_bytes, const int64_t *sample_ids, int32_t count,
+                                const int32_t *lens, std::vector<int64_t> &new_off, int64_t &next_out)
 {
-    if (!ctx || !cache || !sample_ids || !acts) return PAC_ERR_NULL;
-    if (count < 0) return PAC_ERR_RANGE;
-    if (acts_dtype != PAC_BF16 && acts_dtype != PAC_F32) return PAC_ERR_SHAPE;
-    if (!aligned(cache, 256) || !aligned(acts, 16)) return PAC_ERR_ALIGN;
-    if (count == 0) return PAC_OK;
-    // The launches below are checked with hipGetLastError, which also reports an error left behind
-    // by an earlier, unrelated HIP call of this thread (another library's probe of a host pointer,
-    // say): drop such a leftover first.
-    (void)hipGetLastError();
     const Dims &D = ctx->D;
     const int64_t eb = elem_bytes(D.cache_dtype);
-    // validate everything and lay out new blocks before touching the context
-    std::vector<int64_t> new_off((size_t)count);
+    new_off.assign((size_t)count, 0);
     std::vector<int64_t> sorted(sample_ids, sample_ids + count);
     std::sort(sorted.begin(), sorted.end());
     for (int32_t i = 0; i + 1 < count; ++i)
@@ -243,6 +238,80 @@ pac_status pac_cache_fill(pac_ctx *ctx, void *cache, int64_t cache_bytes, const 
         }
     }
     if (next * eb > cache_bytes) return PAC_ERR_WORKSPACE;
+    next_out = next;
+    return PAC_OK;
+}
+
+static void commit_samples(pac_ctx *ctx, const int64_t *sample_ids, int32_t count, const int32_t *lens,
+                           const std::vector<int64_t> &new_off, int64_t next)
+{
+    for (int32_t i = 0; i < count; ++i) {
+        ctx->off[(size_t)sample_ids[i]] = new_off[(size_t)i];
+        ctx->len[(size_t)sample_ids[i]] = lens ? lens[i] : ctx->D.n_max;
+    }
+    ctx->next_free = next;
+}
+
+extern "C" {
+
+pac_status pac_dequant_linear_to_cache(pac_ctx *ctx, void *cache, int64_t cache_bytes, const int64_t *sample_ids,
+                                       int32_t count, const int32_t *lens, int32_t layer, const void *x, int32_t K,
+                                       const int8_t *codes, const float *consts, int32_t block, int32_t bits,
+                                       void *hip_stream)
+{
+    if (!ctx || !cache || !sample_ids) return PAC_ERR_NULL;
+    if (count < 0) return PAC_ERR_RANGE;
+    const Dims &D = ctx->D;
+    if (layer < 0 || layer >= D.L) return PAC_ERR_RANGE;
+    if (!aligned(cache, 256)) return PAC_ERR_ALIGN;
+    if (count == 0) return PAC_OK;
+    if ((int64_t)count * D.n_max > (int64_t)1 << 30) return PAC_ERR_RANGE;
+    pac_status s = (pac_status)check_dq_linear_args(x, count * D.n_max, K, codes, consts, D.d, block, bits);
+    if (s != PAC_OK) return s;
+    std::vector<int64_t> new_off;
+    int64_t next = 0;
+    s = place_samples(ctx, cache_bytes, sample_ids, count, lens, new_off, next);
+    if (s != PAC_OK) return s;
+    (void)hipGetLastError();
+    const int64_t per_sample_in = (int64_t)D.n_max * K * 2;
+    for (int32_t base = 0; base < count; base += kMaxBatch) {
+        BatchMeta meta{};
+        meta.B = std::min<int32_t>(kMaxBatch, count - base);
+        meta.M = 0;
+        for (int32_t i = 0; i < meta.B; ++i) {
+            meta.len[i] = lens ? lens[base + i] : D.n_max;
+            meta.off[i] = new_off[(size_t)(base + i)];
+            meta.tok_start[i] = meta.M;
+            meta.M += meta.len[i];
+        }
+        meta.tok_start[meta.B] = meta.M;
+        if (launch_dq_linear(static_cast<const char *>(x) + (int64_t)base * per_sample_in, meta.B * D.n_max, K, codes, consts,
+                             D.d, block, bits, nullptr, cache, D.cache_dtype == PAC_F32, D.n_max, layer, &meta,
+                             static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+            return PAC_ERR_DEVICE;
+    }
+    commit_samples(ctx, sample_ids, count, lens, new_off, next);
+    return PAC_OK;
+}
+
+pac_status pac_cache_fill(pac_ctx *ctx, void *cache, int64_t cache_bytes, const int64_t *sample_ids, int32_t count,
+                          const void *acts, int32_t acts_dtype, const int32_t *lens, void *hip_stream)
+{
+    if (!ctx || !cache || !sample_ids || !acts) return PAC_ERR_NULL;
+    if (count < 0) return PAC_ERR_RANGE;
+    if (acts_dtype != PAC_BF16 && acts_dtype != PAC_F32) return PAC_ERR_SHAPE;
+    if (!aligned(cache, 256) || !aligned(acts, 16)) return PAC_ERR_ALIGN;
+    if (count == 0) return PAC_OK;
+    // The launches below are checked with hipGetLastError, which also reports an error left behind
+    // by an earlier, unrelated HIP call of this thread (another library's probe of a host pointer,
+    // say): drop such a leftover first.
+    (void)hipGetLastError();
+    const Dims &D = ctx->D;
+    const int64_t eb = elem_bytes(D.cache_dtype);
+    std::vector<int64_t> new_off;
+    int64_t next = 0;
+    pac_status ps = place_samples(ctx, cache_bytes, sample_ids, count, lens, new_off, next);
+    if (ps != PAC_OK) return ps;
     // enqueue in groups the kernel argument block can describe
     const int64_t per_sample_in = (int64_t)D.L * D.n_max * D.d * elem_bytes(acts_dtype);
     for (int32_t base = 0; base < count; base += kMaxBatch) {
@@ -261,11 +330,7 @@ pac_status pac_cache_fill(pac_ctx *ctx, void *cache, int64_t cache_bytes, const 
                                          ctx->prof.on ? &ctx->prof : nullptr);
         if (e != hipSuccess) return PAC_ERR_DEVICE;
     }
-    for (int32_t i = 0; i < count; ++i) {
-        ctx->off[(size_t)sample_ids[i]] = new_off[(size_t)i];
-        ctx->len[(size_t)sample_ids[i]] = lens ? lens[i] : D.n_max;
-    }
-    ctx->next_free = next;
+    commit_samples(ctx, sample_ids, count, lens, new_off, next);
     return PAC_OK;
 }
 

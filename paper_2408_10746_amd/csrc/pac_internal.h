@@ -133,6 +133,13 @@ hipError_t launch_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &m
 int gram_path_kind(const Dims &D); // a value of WsLayout::use_gram
 void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &offset);
 hipError_t launch_gram_loss_grad(const Dims &D, const WsLayout &W, const BatchMeta &meta, const StepIO &io);
+// mixed-precision linear layer on block-wise quantised weights (pac_quant.hip)
+// (returns a pac_status value)
+int check_dq_linear_args(const void *x, int32_t M, int32_t K, const int8_t *codes, const float *consts, int32_t N,
+                            int32_t block, int32_t bits);
+hipError_t launch_dq_linear(const void *x, int M, int K, const int8_t *codes, const float *consts, int N, int block,
+                            int bits, float *y, void *cache, int cache_f32, int n_max, int layer, const BatchMeta *meta,
+                            hipStream_t st);
 hipError_t launch_adamw(const Dims &D, float *p, float *m, float *v, float *g,
                         const AdamArgs &a, hipStream_t st, Profiler *prof, const Deferred *fin = nullptr);
 

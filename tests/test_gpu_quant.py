@@ -1,0 +1,140 @@
+"""GPU parity of the first epoch's storage side (block-wise quantisation, its inverse, the mixed-precision linear
+layer with and without the fused cache fill) against oracle/quant_oracle.c, through the C ABI.
+
+Bars: integer codes and quantisation constants bit-exact (both sides decide the integer in 32-bit arithmetic);
+dequantised values bit-exact (one 32-bit division); the linear layer within 1e-5 relative L2 of the double-precision
+oracle (fp32 accumulation of exact products is all that differs); values written to a bf16 cache within one bf16
+rounding step of the oracle's value."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from oracle import quant_oracle as qo
+from paper_2408_10746_amd import binding as pb
+from paper_2408_10746_amd import inputs
+from paper_2408_10746_amd.inputs import Workload
+
+pytestmark = pytest.mark.gpu
+
+
+def weights(rng, N, K, outliers=True):
+    """Weights with the heavy-tailed structure that motivates block-wise constants: N(0, 1/K) plus a few large entries."""
+    W = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    if outliers:
+        idx = rng.integers(0, N * K, size=max(1, N * K // 500))
+        W.ravel()[idx] *= 20.0
+    return W
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("n,block", [(64 * 300 + 40, 64), (5000, 128), (7, 64), (4096 * 33, 4096), (1000, 2)])
+def test_quant_and_dequant_bit_exact(n, block, bits):
+    rng = np.random.default_rng(n + bits)
+    x = (rng.standard_normal(n) * np.exp(rng.uniform(-4, 4, size=n))).astype(np.float32)
+    x[:: max(1, n // 7)] = 0.0
+    if n > 200:
+        x[128:192] = 0.0                       # an all-zero block
+        x[200] = np.float32(2.0) ** -130       # a denormal
+    codes_ref, consts_ref = qo.quant(x, block, bits)
+    xd = torch.from_numpy(x).cuda()
+    codes = torch.zeros(codes_ref.size, dtype=torch.int8, device="cuda")
+    consts = torch.zeros(consts_ref.size, dtype=torch.float32, device="cuda")
+    pb.pac_quant_blockwise(xd.data_ptr(), n, block, bits, codes.data_ptr(), consts.data_ptr())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(consts.cpu().numpy().view(np.uint32), consts_ref.view(np.uint32))
+    np.testing.assert_array_equal(codes.cpu().numpy(), codes_ref)
+    out = torch.zeros(n, dtype=torch.float32, device="cuda")
+    pb.pac_dequant_blockwise(codes.data_ptr(), consts.data_ptr(), n, block, bits, out.data_ptr())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy().view(np.uint32), qo.dequant(codes_ref, consts_ref, n, block, bits).view(np.uint32))
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,K,N,block", [(70, 128, 96, 64), (5, 64, 33, 32), (257, 768, 200, 128), (64, 1024, 64, 1024)])
+def test_linear_layer_against_oracle(M, K, N, block, bits):
+    rng = np.random.default_rng(M + K + bits)
+    W = weights(rng, N, K)
+    x16 = torch.from_numpy(rng.standard_normal((M, K)).astype(np.float32)).to(torch.bfloat16)
+    codes_ref, consts_ref = qo.quant(W, block, bits)
+    ref = qo.dequant_linear(x16.float().numpy(), codes_ref, consts_ref, N, block, bits)
+    # the stored form is produced on the device as well (bit-equal to the oracle's, checked above)
+    Wd = torch.from_numpy(W).cuda()
+    codes = torch.zeros(codes_ref.size, dtype=torch.int8, device="cuda")
+    consts = torch.zeros(consts_ref.size, dtype=torch.float32, device="cuda")
+    pb.pac_quant_blockwise(Wd.data_ptr(), N * K, block, bits, codes.data_ptr(), consts.data_ptr())
+    xd = x16.cuda()
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    pb.pac_dequant_linear(xd.data_ptr(), M, K, codes.data_ptr(), consts.data_ptr(), N, block, bits, y.data_ptr())
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), codes_ref)
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    err = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    assert err <= 1e-5, err
+    # element-wise: fp32 accumulation of K exact products, against the sum of their magnitudes
+    mag = np.abs(x16.float().numpy().astype(np.float64)) @ np.abs(
+        qo.dequant(codes_ref, consts_ref, N * K, block, bits).reshape(N, K).astype(np.float64)).T
+    assert np.max(np.abs(got - ref) / mag) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype,bits", [("bf16", 8), ("bf16", 4), ("f32", 8)])
+def test_linear_layer_with_fused_cache_fill(dtype, bits):
+    """Layer by layer, the quantised projection's output goes straight into the cache (ragged samples, two calls,
+    a sample registered by an ordinary fill first); the cache then holds what filling it with the oracle's outputs
+    would hold, to one rounding step of the cache dtype."""
+    w = Workload("qc", L=3, d=96, n_max=21, B=4, r=32, C=2, N=6, cache_dtype=dtype)
+    K, block = 128, 64
+    rng = np.random.default_rng(17)
+    lens = np.array([21, 1, 13, 8, 21, 5], dtype=np.int32)
+    from paper_2408_10746_amd.runtime import Session
+    sess = Session(w, lens=lens)
+    Ws = [weights(rng, w.d, K) for _ in range(w.L)]
+    x16 = torch.from_numpy(rng.standard_normal((w.N, w.L, w.n_max, K)).astype(np.float32)).to(torch.bfloat16)
+    # sample 3 is known before (an ordinary fill of zeros): its block must be reused, not appended again
+    sess.cache_fill([3], np.zeros((1, w.L, w.n_max, w.d), dtype=np.float32), lens[[3]])
+    order = [np.array([0, 3, 5]), np.array([4, 1, 2])]
+    stored = []
+    for l in range(w.L):
+        codes_ref, consts_ref = qo.quant(Ws[l], block, bits)
+        stored.append((codes_ref, consts_ref))
+        codes = torch.from_numpy(codes_ref).cuda()
+        consts = torch.from_numpy(consts_ref).cuda()
+        for ids in order:
+            xd = x16[ids, l].contiguous().cuda()
+            pb.pac_dequant_linear_to_cache(sess.ctx, sess.cache.data_ptr(), sess.cache_bytes, ids, lens[ids], l,
+                                           xd.data_ptr(), K, codes.data_ptr(), consts.data_ptr(), block, bits)
+    torch.cuda.synchronize()
+    # layout: fill order 3, then 0, 5, 4, 1, 2
+    expect_off, pos = {}, 0
+    for sid in [3, 0, 5, 4, 1, 2]:
+        expect_off[sid] = pos
+        pos += w.L * int(lens[sid]) * w.d
+    for sid in range(w.N):
+        off, ln = pb.pac_cache_lookup(sess.ctx, sid)
+        assert off == expect_off[sid] and ln == lens[sid]
+        got = sess.cache_block(sid)
+        for l in range(w.L):
+            ref = qo.dequant_linear(x16[sid, l, :ln].float().numpy(), stored[l][0], stored[l][1], w.d, block, bits)
+            if dtype == "f32":
+                np.testing.assert_allclose(got[l], ref, rtol=0, atol=1e-5 * np.abs(ref).max())
+            else:
+                val = orc.widen(got[l].ravel()).reshape(ln, w.d).astype(np.float64)
+                # one bf16 rounding step: half a unit in the last place of an 8-bit significand, plus the fp32 sum's error
+                assert np.all(np.abs(val - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-5 * np.abs(ref).max())
+                # and most values are the correctly rounded ones
+                exact = np.array([orc.f32_to_bf16_bits(float(v)) for v in ref.ravel()[:500]], dtype=np.uint16)
+                assert np.mean(exact == got[l].ravel()[:500]) > 0.98
+
+
+def test_argument_errors_before_any_launch():
+    lib = pb.lib()
+    dev = 0x7000_0000_0000
+    assert lib.pac_quant_blockwise(None, 10, 64, 8, dev, dev, None) == pb.PAC_ERR_NULL
+    assert lib.pac_quant_blockwise(dev, 10, 64, 5, dev, dev, None) == pb.PAC_ERR_SHAPE
+    assert lib.pac_quant_blockwise(dev, 10, 3, 4, dev, dev, None) == pb.PAC_ERR_RANGE
+    assert lib.pac_quant_blockwise(dev, -1, 64, 8, dev, dev, None) == pb.PAC_ERR_RANGE
+    assert lib.pac_dequant_linear(dev, 4, 100, dev, dev, 8, 32, 8, dev, None) == pb.PAC_ERR_SHAPE
+    assert lib.pac_dequant_linear(dev, 4, 128, dev, dev, 8, 48, 8, dev, None) == pb.PAC_ERR_RANGE
+    assert lib.pac_dequant_linear(dev + 2, 4, 128, dev, dev, 8, 64, 8, dev, None) == pb.PAC_ERR_ALIGN
+    assert lib.pac_dequant_linear(dev, 4, 128, dev, dev, 8, 64, 8, None, None) == pb.PAC_ERR_NULL
