@@ -306,6 +306,44 @@ def bench_first_epoch_storage(torch, pb):
     return out
 
 
+def bench_host_tier(torch, steps=48, warmup=8, N=512):
+    """The T5-Base-shaped step with the cache in pinned host memory: batch k + 1 is reloaded into a device window on a
+    copy stream while batch k trains (paper Sec. 5.2: the cache is reloaded per micro-batch from the larger tier).  Bound
+    by the host link, not by HBM: the figure to read is the reload rate."""
+    import numpy as np
+    from paper_2408_10746_amd import inputs
+    from paper_2408_10746_amd.runtime import TieredSession
+    w = inputs.WORKLOADS["t5base"]
+    dev = torch.device("cuda:0")
+    sess = TieredSession(w, cache_samples=N)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_DATA)
+    for s0 in range(0, N, w.B):
+        a = torch.randn((w.B, w.L, w.n_max, w.d), generator=gen, device=dev, dtype=torch.float32)
+        a = torch.nn.functional.layer_norm(a, (w.d,), eps=1e-5).contiguous()
+        sess.cache_fill(np.arange(s0, s0 + w.B), a)
+    torch.cuda.synchronize()
+    labels = torch.from_numpy(inputs.labels(w)).to(dev)
+    sess.set_params(inputs.init_params(w))
+    plan = [np.arange(w.B) + w.B * (k % (N // w.B)) for k in range(warmup + steps + 1)]
+    labs = [labels[torch.from_numpy(ids).to(dev)].contiguous() for ids in plan]
+    sess.prefetch(0, plan[0])
+    t0 = None
+    for k in range(warmup + steps):
+        if k == warmup:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        sess.prefetch(k + 1, plan[k + 1])
+        sess.step_staged(k, plan[k], labs[k], keep_grads=False)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    slice_bytes = w.L * w.B * w.n_max * w.d * 2
+    return {"workload": f"t5base, {N} samples in pinned host memory ({sess.cache_bytes / 1e9:.2f} GB), two device windows",
+            "ms_per_step": el * 1e3 / steps, "samples_per_s": steps * w.B / el,
+            "reload_GBs": slice_bytes * steps / el / 1e9, "reload_MB_per_step": slice_bytes / 1e6,
+            "final_loss": float(sess.loss.item())}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -373,6 +411,12 @@ def main():
             extras["first_epoch_storage"] = bench_first_epoch_storage(torch, pb)
         except Exception as ex:
             extras["first_epoch_storage"] = {"error": f"{type(ex).__name__}: {ex}"}
+        gc.collect()
+        torch.cuda.empty_cache()
+        try:
+            extras["host_tier"] = bench_host_tier(torch)
+        except Exception as ex:
+            extras["host_tier"] = {"error": f"{type(ex).__name__}: {ex}"}
 
     out = {
         "metric": "adapter-train samples/sec from activation cache",

@@ -31,6 +31,7 @@ EXPORTS = [
     "pac_profile_begin", "pac_profile_end", "pac_profile_class_name",
     "pac_plan_hybrid", "pac_plan_stage_time",
     "pac_quant_blockwise", "pac_dequant_blockwise", "pac_dequant_linear", "pac_dequant_linear_to_cache",
+    "pac_tier_window_bytes", "pac_tier_fill", "pac_tier_stage", "pac_adapter_loss_grad_staged", "pac_adapter_step_staged",
 ]
 PAC_STATIC_WORKSPACE_BYTES = 64 << 20
 
@@ -116,6 +117,16 @@ def lib():
         L.pac_probe_mfma_bf16.argtypes = [i64, vp, vp]
         L.pac_probe_mfma_flops.restype = C.c_double
         L.pac_probe_mfma_flops.argtypes = [i64]
+        L.pac_tier_window_bytes.restype = i64
+        L.pac_tier_window_bytes.argtypes = [vp]
+        L.pac_tier_fill.restype = C.c_int
+        L.pac_tier_fill.argtypes = [vp, vp, i64, vp, i32, vp, i32, vp, vp, i64, vp]
+        L.pac_tier_stage.restype = C.c_int
+        L.pac_tier_stage.argtypes = [vp, vp, vp, i32, vp, i64, vp]
+        L.pac_adapter_loss_grad_staged.restype = C.c_int
+        L.pac_adapter_loss_grad_staged.argtypes = L.pac_adapter_loss_grad.argtypes
+        L.pac_adapter_step_staged.restype = C.c_int
+        L.pac_adapter_step_staged.argtypes = L.pac_adapter_step.argtypes
         L.pac_quant_blockwise.restype = C.c_int
         L.pac_quant_blockwise.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         L.pac_dequant_blockwise.restype = C.c_int
@@ -285,6 +296,40 @@ def pac_plan_stage_time(t_f, t_b, mem_fixed, mem_act, mem_budget, x, y, d_first,
     samples = np.zeros(max(n, 1), dtype=np.int32)
     t = lib().pac_plan_stage_time(C.byref(prob), x, y, d_first, n, samples.ctypes.data_as(C.c_void_p))
     return float(t), samples.tolist()
+
+
+def pac_tier_window_bytes(ctx) -> int:
+    return int(lib().pac_tier_window_bytes(ctx))
+
+
+def pac_tier_fill(ctx, host_ptr, host_bytes, sample_ids, acts_ptr, acts_dtype, lens, window_ptr, window_bytes, stream=0) -> None:
+    ids = _host_i64(sample_ids)
+    la = _host_i32(lens)
+    _check(lib().pac_tier_fill(ctx, host_ptr, host_bytes, _hp(ids), ids.shape[0], acts_ptr, acts_dtype, _hp(la), window_ptr,
+                               window_bytes, stream), "pac_tier_fill")
+
+
+def pac_tier_stage(ctx, host_ptr, sample_ids, window_ptr, window_bytes, stream=0) -> None:
+    ids = _host_i64(sample_ids)
+    _check(lib().pac_tier_stage(ctx, host_ptr, _hp(ids), ids.shape[0], window_ptr, window_bytes, stream), "pac_tier_stage")
+
+
+def pac_adapter_loss_grad_staged(ctx, window_ptr, sample_ids, labels_ptr, params_ptr, ws_ptr, ws_bytes, loss_ptr,
+                                 logits_ptr=None, grads_ptr=None, stream=0) -> None:
+    ids = _host_i64(sample_ids)
+    _check(lib().pac_adapter_loss_grad_staged(ctx, window_ptr, _hp(ids), ids.shape[0], labels_ptr, params_ptr, ws_ptr,
+                                              ws_bytes, loss_ptr, logits_ptr, grads_ptr, stream),
+           "pac_adapter_loss_grad_staged")
+
+
+def pac_adapter_step_staged(ctx, window_ptr, sample_ids, labels_ptr, params_ptr, m_ptr, v_ptr, step: int, hp: pac_adamw,
+                            ws_ptr, ws_bytes, loss_ptr, grads_ptr=None, stream=0) -> int:
+    ids = _host_i64(sample_ids)
+    st = C.c_int64(step)
+    _check(lib().pac_adapter_step_staged(ctx, window_ptr, _hp(ids), ids.shape[0], labels_ptr, params_ptr, m_ptr, v_ptr,
+                                         C.byref(st), C.byref(hp), ws_ptr, ws_bytes, loss_ptr, grads_ptr, stream),
+           "pac_adapter_step_staged")
+    return st.value
 
 
 def pac_quant_blockwise(x_ptr, n: int, block: int, bits: int, codes_ptr, consts_ptr, stream=0) -> None:

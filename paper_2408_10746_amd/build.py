@@ -12,7 +12,8 @@ OBJ_DIR = os.path.join(_HERE, "_build")
 SOURCES = ["pac_api.hip", "pac_kernels.hip", "pac_gram.hip", "pac_probe.hip", "pac_plan.hip", "pac_quant.hip"]
 HEADERS = ["pac_gemm.h", "pac_mma.h", "pac_internal.h", os.path.join("..", "..", "include", "pac.h"),
            os.path.join("..", "..", "include", "pac_plan.h"),
-           os.path.join("..", "..", "include", "pac_quant.h")]
+           os.path.join("..", "..", "include", "pac_quant.h"),
+           os.path.join("..", "..", "include", "pac_tier.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -3,6 +3,7 @@
 // host before anything is enqueued.
 #include "../../include/pac.h"
 #include "../../include/pac_quant.h"
+#include "../../include/pac_tier.h"
 #include "pac_internal.h"
 
 #include <cmath>
@@ -334,7 +335,8 @@ pac_status pac_cache_fill(pac_ctx *ctx, void *cache, int64_t cache_bytes, const 
     return PAC_OK;
 }
 
-static pac_status build_meta(const pac_ctx *ctx, const int64_t *sample_ids, int32_t B, BatchMeta &meta)
+// packed: the blocks sit back to back in batch order (a staged window) instead of at their recorded offsets
+static pac_status build_meta(const pac_ctx *ctx, const int64_t *sample_ids, int32_t B, BatchMeta &meta, bool packed = false)
 {
     const Dims &D = ctx->D;
     if (B < 1 || B > D.B_max) return PAC_ERR_RANGE;
@@ -344,7 +346,7 @@ static pac_status build_meta(const pac_ctx *ctx, const int64_t *sample_ids, int3
         const int64_t id = sample_ids[i];
         if (id < 0 || id >= D.N) return PAC_ERR_RANGE;
         if (ctx->off[(size_t)id] < 0) return PAC_ERR_STATE;
-        meta.off[i] = ctx->off[(size_t)id];
+        meta.off[i] = packed ? (int64_t)D.L * meta.M * D.d : ctx->off[(size_t)id];
         meta.len[i] = ctx->len[(size_t)id];
         meta.tok_start[i] = meta.M;
         meta.M += meta.len[i];
@@ -370,16 +372,16 @@ static pac_status check_common(const pac_ctx *ctx, const void *cache, const int6
     return PAC_OK;
 }
 
-pac_status pac_adapter_loss_grad(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
+static pac_status loss_grad_impl(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
                                  const int32_t *labels, const float *params, void *workspace,
                                  int64_t workspace_bytes, float *loss_out, float *logits_out, float *grads_out,
-                                 void *hip_stream)
+                                 void *hip_stream, bool packed)
 {
     pac_status s = check_common(ctx, cache, sample_ids, labels, params, workspace, workspace_bytes, loss_out);
     if (s != PAC_OK) return s;
     if ((logits_out && !aligned(logits_out, 4)) || (grads_out && !aligned(grads_out, 4))) return PAC_ERR_ALIGN;
     BatchMeta meta;
-    s = build_meta(ctx, sample_ids, B, meta);
+    s = build_meta(ctx, sample_ids, B, meta, packed);
     if (s != PAC_OK) return s;
     StepIO io{cache, labels, params, static_cast<char *>(workspace), loss_out, logits_out, grads_out,
               static_cast<hipStream_t>(hip_stream), ctx->prof.on ? &ctx->prof : nullptr};
@@ -387,11 +389,29 @@ pac_status pac_adapter_loss_grad(pac_ctx *ctx, const void *cache, const int64_t 
     return launch_loss_grad(ctx->D, ctx->W, meta, io) == hipSuccess ? PAC_OK : PAC_ERR_DEVICE;
 }
 
+pac_status pac_adapter_loss_grad(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
+                                 const int32_t *labels, const float *params, void *workspace,
+                                 int64_t workspace_bytes, float *loss_out, float *logits_out, float *grads_out,
+                                 void *hip_stream)
+{
+    return loss_grad_impl(ctx, cache, sample_ids, B, labels, params, workspace, workspace_bytes, loss_out, logits_out,
+                          grads_out, hip_stream, false);
+}
+
+pac_status pac_adapter_loss_grad_staged(pac_ctx *ctx, const void *window, const int64_t *sample_ids, int32_t B,
+                                        const int32_t *labels, const float *params, void *workspace,
+                                        int64_t workspace_bytes, float *loss_out, float *logits_out, float *grads_out,
+                                        void *hip_stream)
+{
+    return loss_grad_impl(ctx, window, sample_ids, B, labels, params, workspace, workspace_bytes, loss_out, logits_out,
+                          grads_out, hip_stream, true);
+}
+
 // The step behind pac_adapter_step and pac_adapter_step_static: forward, loss, backward, AdamW on `workspace`.
 static pac_status step_on_workspace(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
                                     const int32_t *labels, float *params, float *m, float *v, int64_t *step,
                                     const pac_adamw *hp, void *workspace, int64_t workspace_bytes, float *loss_out,
-                                    float *grads_out, void *hip_stream, bool may_profile)
+                                    float *grads_out, void *hip_stream, bool may_profile, bool packed = false)
 {
     pac_status s = check_common(ctx, cache, sample_ids, labels, params, workspace, workspace_bytes, loss_out);
     if (s != PAC_OK) return s;
@@ -402,7 +422,7 @@ static pac_status step_on_workspace(pac_ctx *ctx, const void *cache, const int64
         !(hp->lr >= 0.f) || !(hp->weight_decay >= 0.f))
         return PAC_ERR_RANGE;
     BatchMeta meta;
-    s = build_meta(ctx, sample_ids, B, meta);
+    s = build_meta(ctx, sample_ids, B, meta, packed);
     if (s != PAC_OK) return s;
     char *ws = static_cast<char *>(workspace);
     float *grads = grads_out ? grads_out : reinterpret_cast<float *>(ws + ctx->W.grads);
@@ -430,6 +450,84 @@ pac_status pac_adapter_step(pac_ctx *ctx, const void *cache, const int64_t *samp
 {
     return step_on_workspace(ctx, cache, sample_ids, B, labels, params, m, v, step, hp, workspace, workspace_bytes,
                              loss_out, grads_out, hip_stream, true);
+}
+
+pac_status pac_adapter_step_staged(pac_ctx *ctx, const void *window, const int64_t *sample_ids, int32_t B,
+                                   const int32_t *labels, float *params, float *m, float *v, int64_t *step,
+                                   const pac_adamw *hp, void *workspace, int64_t workspace_bytes, float *loss_out,
+                                   float *grads_out, void *hip_stream)
+{
+    return step_on_workspace(ctx, window, sample_ids, B, labels, params, m, v, step, hp, workspace, workspace_bytes,
+                             loss_out, grads_out, hip_stream, true, true);
+}
+
+int64_t pac_tier_window_bytes(const pac_ctx *ctx)
+{
+    if (!ctx) return -1;
+    const Dims &D = ctx->D;
+    return (int64_t)D.L * D.Mmax * D.d * elem_bytes(D.cache_dtype);
+}
+
+pac_status pac_tier_stage(const pac_ctx *ctx, const void *host_cache, const int64_t *sample_ids, int32_t B, void *window,
+                          int64_t window_bytes, void *copy_stream)
+{
+    if (!ctx || !host_cache || !sample_ids || !window) return PAC_ERR_NULL;
+    if (!aligned(host_cache, 256) || !aligned(window, 256)) return PAC_ERR_ALIGN;
+    BatchMeta meta;
+    pac_status s = build_meta(ctx, sample_ids, B, meta, true);
+    if (s != PAC_OK) return s;
+    const Dims &D = ctx->D;
+    const int64_t eb = elem_bytes(D.cache_dtype);
+    if ((int64_t)D.L * meta.M * D.d * eb > window_bytes) return PAC_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    for (int32_t i = 0; i < B; ++i) {
+        const int64_t bytes = (int64_t)D.L * meta.len[i] * D.d * eb;
+        if (hipMemcpyAsync(static_cast<char *>(window) + meta.off[i] * eb,
+                           static_cast<const char *>(host_cache) + ctx->off[(size_t)sample_ids[i]] * eb, (size_t)bytes,
+                           hipMemcpyHostToDevice, static_cast<hipStream_t>(copy_stream)) != hipSuccess)
+            return PAC_ERR_DEVICE;
+    }
+    return PAC_OK;
+}
+
+pac_status pac_tier_fill(pac_ctx *ctx, void *host_cache, int64_t host_bytes, const int64_t *sample_ids, int32_t count,
+                         const void *acts, int32_t acts_dtype, const int32_t *lens, void *window, int64_t window_bytes,
+                         void *hip_stream)
+{
+    if (!ctx || !host_cache || !sample_ids || !acts || !window) return PAC_ERR_NULL;
+    if (count < 0 || count > ctx->D.B_max) return PAC_ERR_RANGE;
+    if (acts_dtype != PAC_BF16 && acts_dtype != PAC_F32) return PAC_ERR_SHAPE;
+    if (!aligned(host_cache, 256) || !aligned(window, 256) || !aligned(acts, 16)) return PAC_ERR_ALIGN;
+    if (count == 0) return PAC_OK;
+    const Dims &D = ctx->D;
+    const int64_t eb = elem_bytes(D.cache_dtype);
+    std::vector<int64_t> new_off;
+    int64_t next = 0;
+    pac_status s = place_samples(ctx, host_bytes, sample_ids, count, lens, new_off, next);
+    if (s != PAC_OK) return s;
+    BatchMeta meta{};
+    meta.B = count;
+    meta.M = 0;
+    for (int32_t i = 0; i < count; ++i) {
+        meta.len[i] = lens ? lens[i] : D.n_max;
+        meta.off[i] = (int64_t)D.L * meta.M * D.d; // packed in the window
+        meta.tok_start[i] = meta.M;
+        meta.M += meta.len[i];
+    }
+    meta.tok_start[count] = meta.M;
+    if ((int64_t)D.L * meta.M * D.d * eb > window_bytes) return PAC_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (launch_cache_fill(D, window, acts, acts_dtype, meta, st, nullptr) != hipSuccess) return PAC_ERR_DEVICE;
+    for (int32_t i = 0; i < count; ++i) {
+        const int64_t bytes = (int64_t)D.L * meta.len[i] * D.d * eb;
+        if (hipMemcpyAsync(static_cast<char *>(host_cache) + new_off[(size_t)i] * eb,
+                           static_cast<const char *>(window) + meta.off[i] * eb, (size_t)bytes, hipMemcpyDeviceToHost,
+                           st) != hipSuccess)
+            return PAC_ERR_DEVICE;
+    }
+    commit_samples(ctx, sample_ids, count, lens, new_off, next);
+    return PAC_OK;
 }
 
 pac_status pac_adapter_step_static(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
