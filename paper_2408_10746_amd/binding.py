@@ -32,6 +32,7 @@ EXPORTS = [
     "pac_plan_hybrid", "pac_plan_stage_time",
     "pac_quant_blockwise", "pac_dequant_blockwise", "pac_dequant_linear", "pac_dequant_linear_to_cache",
     "pac_tier_window_bytes", "pac_tier_fill", "pac_tier_stage", "pac_adapter_loss_grad_staged", "pac_adapter_step_staged",
+    "pac_ladder_param_count", "pac_ladder_workspace_bytes", "pac_ladder_loss_grad", "pac_ladder_step",
 ]
 PAC_STATIC_WORKSPACE_BYTES = 64 << 20
 
@@ -139,6 +140,15 @@ def lib():
         L.pac_plan_hybrid.argtypes = [C.POINTER(pac_plan_problem), C.POINTER(pac_plan_result)]
         L.pac_plan_stage_time.restype = C.c_double
         L.pac_plan_stage_time.argtypes = [C.POINTER(pac_plan_problem), i32, i32, i32, i32, vp]
+        L.pac_ladder_param_count.restype = i64
+        L.pac_ladder_param_count.argtypes = [vp]
+        L.pac_ladder_workspace_bytes.restype = i64
+        L.pac_ladder_workspace_bytes.argtypes = [vp, i32]
+        L.pac_ladder_loss_grad.restype = C.c_int
+        L.pac_ladder_loss_grad.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp, vp]
+        L.pac_ladder_step.restype = C.c_int
+        L.pac_ladder_step.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, vp, C.POINTER(i64), C.POINTER(pac_adamw), vp, i64,
+                                      vp, vp, vp]
         L.pac_profile_begin.restype = C.c_int
         L.pac_profile_begin.argtypes = [vp]
         L.pac_profile_end.restype = C.c_int
@@ -368,3 +378,28 @@ def pac_profile_end(ctx):
         if launches[i]:
             out[lib().pac_profile_class_name(i).decode()] = (float(ms[i]), int(launches[i]))
     return out
+
+
+def pac_ladder_param_count(ctx) -> int:
+    return int(lib().pac_ladder_param_count(ctx))
+
+
+def pac_ladder_workspace_bytes(ctx, heads: int) -> int:
+    return int(lib().pac_ladder_workspace_bytes(ctx, heads))
+
+
+def pac_ladder_loss_grad(ctx, cache_ptr, sample_ids, labels_ptr, heads, params_ptr, ws_ptr, ws_bytes, loss_ptr,
+                         logits_ptr=None, grads_ptr=None, stream=0) -> None:
+    ids = _host_i64(sample_ids)
+    _check(lib().pac_ladder_loss_grad(ctx, cache_ptr, _hp(ids), ids.shape[0], labels_ptr, heads, params_ptr, ws_ptr,
+                                      ws_bytes, loss_ptr, logits_ptr, grads_ptr, stream), "pac_ladder_loss_grad")
+
+
+def pac_ladder_step(ctx, cache_ptr, sample_ids, labels_ptr, heads, params_ptr, m_ptr, v_ptr, step: int, hp: pac_adamw,
+                    ws_ptr, ws_bytes, loss_ptr, grads_ptr=None, stream=0) -> int:
+    ids = _host_i64(sample_ids)
+    st = C.c_int64(step)
+    _check(lib().pac_ladder_step(ctx, cache_ptr, _hp(ids), ids.shape[0], labels_ptr, heads, params_ptr, m_ptr, v_ptr,
+                                 C.byref(st), C.byref(hp), ws_ptr, ws_bytes, loss_ptr, grads_ptr, stream),
+           "pac_ladder_step")
+    return st.value

@@ -9,11 +9,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libpac.so")
 OBJ_DIR = os.path.join(_HERE, "_build")
-SOURCES = ["pac_api.hip", "pac_kernels.hip", "pac_gram.hip", "pac_probe.hip", "pac_plan.hip", "pac_quant.hip"]
+SOURCES = ["pac_api.hip", "pac_kernels.hip", "pac_gram.hip", "pac_probe.hip", "pac_plan.hip", "pac_quant.hip", "pac_ladder.hip"]
 HEADERS = ["pac_gemm.h", "pac_mma.h", "pac_internal.h", os.path.join("..", "..", "include", "pac.h"),
            os.path.join("..", "..", "include", "pac_plan.h"),
            os.path.join("..", "..", "include", "pac_quant.h"),
-           os.path.join("..", "..", "include", "pac_tier.h")]
+           os.path.join("..", "..", "include", "pac_tier.h"),
+           os.path.join("..", "..", "include", "pac_ladder.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -14,21 +14,14 @@
 
 using namespace pac;
 
-struct pac_ctx {
-    Dims D;
-    WsLayout W;
-    std::vector<int64_t> off; // element offset of each sample's block, -1 = never filled
-    std::vector<int32_t> len;
-    int64_t next_free; // elements
-    Profiler prof;
-};
 
 static const char *const kClassNames[KC_COUNT] = {
     "cache_fill", "setup", "shadows", "fwd_down", "fwd_up", "pool", "head", "head_bwd",
     "bwd_dpre", "bwd_wgrad", "bwd_dx", "reduce", "adamw",
     "g_prep", "g_proj", "g_chain_fwd", "g_head", "g_chain_bwd", "g_tokred", "g_ggsum", "g_post", "g_finish",
     "g_prep.setup", "g_prep.copy", "g_prep.chat", "g_prep.V", "g_proj.U", "g_proj.Q", "g_proj.pb",
-    "g_tokred.E", "g_tokred.G", "g_tokred.vec", "g_post.F", "g_post.W", "g_post.vec"};
+    "g_tokred.E", "g_tokred.G", "g_tokred.vec", "g_post.F", "g_post.W", "g_post.vec",
+    "l_down", "l_row", "l_lin", "l_attn", "l_head", "l_wgrad", "l_reduce"};
 
 static void drop_events(Profiler &p)
 {
@@ -543,3 +536,8 @@ pac_status pac_adapter_step_static(pac_ctx *ctx, const void *cache, const int64_
 }
 
 } // extern "C"
+
+int pac_ctx_build_meta(const pac_ctx *ctx, const int64_t *sample_ids, int32_t B, pac::BatchMeta &meta)
+{
+    return (int)build_meta(ctx, sample_ids, B, meta, false);
+}

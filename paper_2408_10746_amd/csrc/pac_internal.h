@@ -73,6 +73,8 @@ enum KClass {
     // parts of the fused launches, seen only with PAC_FLAG_SPLIT_LAUNCH
     KC_G_PREP_SETUP, KC_G_PREP_COPY, KC_G_PREP_CHAT, KC_G_PREP_V, KC_G_PROJ_U, KC_G_PROJ_Q, KC_G_PROJ_PB,
     KC_G_TOKRED_E, KC_G_TOKRED_G, KC_G_TOKRED_VEC, KC_G_POST_F, KC_G_POST_W, KC_G_POST_VEC,
+    // the ladder architecture (pac_ladder.hip)
+    KC_L_DOWN, KC_L_ROW, KC_L_LIN, KC_L_ATTN, KC_L_HEAD, KC_L_WGRAD, KC_L_REDUCE,
     KC_COUNT
 };
 
@@ -144,3 +146,16 @@ hipError_t launch_adamw(const Dims &D, float *p, float *m, float *v, float *g,
                         const AdamArgs &a, hipStream_t st, Profiler *prof, const Deferred *fin = nullptr);
 
 } // namespace pac
+
+// The host context behind the opaque pac_ctx of the C ABI.
+struct pac_ctx {
+    pac::Dims D;
+    pac::WsLayout W;
+    std::vector<int64_t> off; // element offset of each sample's block, -1 = never filled
+    std::vector<int32_t> len;
+    int64_t next_free; // elements
+    pac::Profiler prof;
+};
+
+// Batch description of `B` filled samples (returns a pac_status value; validates ids and state).
+int pac_ctx_build_meta(const pac_ctx *ctx, const int64_t *sample_ids, int32_t B, pac::BatchMeta &meta);

@@ -1,0 +1,1127 @@
+// The paper's default Parallel-Adapter architecture trained from the activation cache (Sec. 4.1 and
+// Fig. "pa-detail", Sec. 6.1; cached phase Sec. 4.2 / 5.2): the w-wide ladder whose adapter is a reduced
+// transformer layer.  C ABI in include/pac_ladder.h.
+//
+//   u_l = b_l W_down^l + c_down^l            (one batched launch streams the cache once: u does not depend on the ladder)
+//   x_l = lambda_l u_l + (1 - lambda_l) a_{l-1}
+//   a_l = Block_l(x_l): xn = LN1(x); q,k,v = xn W_qkv + b_qkv; o = softmax(q k^T / sqrt(dh)) v per sample and head;
+//                       t = x + o W_o + b_o; tn = LN2(t); a = t + GELU(tn W_1 + b_1) W_2 + b_2
+//   y = b_L + a_L W_up + c_up;  mean over the valid tokens;  classifier;  mean cross-entropy
+//
+// Launch plan of a gradient call (fp32 arithmetic throughout, fp32 matrix instructions through pac_gemm.h):
+//   set-up -> down-projection of every layer (first pass over the cache slice)
+//   per layer, forward : gate + LN1, qkv, attention, output projection (+x), LN2, FFN in (+GELU), FFN out (+t)
+//   head               : token means, logits, loss, dz, the head's gradients, da_L
+//   per layer, backward: FFN out^T (x GELU'), FFN in^T, LN2^T (+da), output projection^T, attention^T, qkv^T,
+//                        LN1^T + gate^T (+dt, gate gradient partials, da_{l-1})
+//   all token contractions of all layers in ONE launch (second pass over the cache slice for dW_down; the bias
+//   gradients are the column sums its right-hand loaders keep), then one ordered reduction into the gradient.
+// Every intermediate the reverse pass needs is kept in the workspace; every reduction runs in a fixed order.
+#include "../../include/pac_ladder.h"
+#include "pac_gemm.h"
+#include "pac_internal.h"
+
+#include <cmath>
+#include <mutex>
+
+namespace pac {
+namespace {
+
+#define LAD_LAUNCH(prof, st, cls, ...)                   \
+    do {                                                 \
+        if (prof) (void)(prof)->mark((st), (cls), true);  \
+        hipLaunchKernelGGL(__VA_ARGS__);                 \
+        if (prof) (void)(prof)->mark((st), (cls), false); \
+    } while (0)
+
+#define LAD_TRY(expr)                    \
+    do {                                 \
+        hipError_t e_ = (expr);          \
+        if (e_ != hipSuccess) return e_; \
+    } while (0)
+
+inline int64_t al256(int64_t x) { return (x + 255) & ~int64_t(255); }
+inline int cdivi(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+using TL = Tile<2, 2, 1, 1, 4>; // 64 x 64 workgroup tile, 64 fp32 values of K per step
+constexpr int kTileLds = tile_lds_bytes<float, TL>();
+constexpr int kLnRows = 32;    // token rows per workgroup of the LayerNorm reverse kernels
+constexpr int kFields = 15;    // tensors of one layer block
+
+// Shapes, parameter offsets (elements) and workspace offsets (bytes).
+struct Lad {
+    int L, d, w, f, nh, dh, C, Bmax, cache_f32;
+    int64_t Mmax;
+    int64_t fo[kFields + 1]; // start of each field inside a layer block; fo[kFields] = block length
+    int64_t PLb, oWup, ocup, oWcls, occls, P;
+    // workspace
+    int64_t rowoff, rowstride, rowsamp, samp_start, samp_len;
+    int64_t U, X, XN, QKV, LSE, O, T, TN, F1, G, A, st1, st2;  // [L][Mmax][...]
+    int64_t DA, DF1, DT, DQKV, DX;                             // [L][Mmax][...]
+    int64_t DTN, DO_, DXN;                                     // [Mmax][w]
+    int64_t ln1p, ln2p, dlamp;                                 // [L][nblk][2][w] x2, [L][nblk]
+    int64_t bmean, abar, pooled, logits, dz, dp, daL, lossp;
+    int64_t part;                                              // [splits][L * PLb]
+    int64_t grads;
+    int64_t total;
+    int nblk, splits, rows_per_split;
+    int items_per_layer, tiles[5][2], item0[6];
+};
+enum Field { F_WD = 0, F_CD, F_G1, F_H1, F_WQKV, F_BQKV, F_WO, F_BO, F_G2, F_H2, F_W1, F_B1, F_W2, F_B2, F_LAM };
+
+// the parameter vector (does not depend on the head count)
+bool lad_shapes(const Dims &D, Lad &a)
+{
+    a.L = D.L; a.d = D.d; a.w = D.r; a.f = 4 * D.r; a.C = D.C; a.Bmax = D.B_max; a.Mmax = D.Mmax;
+    a.cache_f32 = D.cache_dtype != 0;
+    if (a.w % 32 || a.w > 256) return false;
+    const int64_t w = a.w, d = a.d, f = a.f;
+    const int64_t n[kFields] = {d * w, w, w, w, w * 3 * w, 3 * w, w * w, w, w, w, w * f, f, f * w, w, 4};
+    a.fo[0] = 0;
+    for (int i = 0; i < kFields; ++i) a.fo[i + 1] = a.fo[i] + n[i];
+    a.PLb = a.fo[kFields];
+    a.oWup = (int64_t)a.L * a.PLb;
+    a.ocup = a.oWup + w * d;
+    a.oWcls = a.ocup + d;
+    a.occls = a.oWcls + d * a.C;
+    a.P = a.occls + a.C;
+    return true;
+}
+
+bool lad_plan(const Dims &D, int heads, Lad &a)
+{
+    if (!lad_shapes(D, a)) return false;
+    a.nh = heads;
+    if (heads < 1 || a.w % heads) return false;
+    a.dh = a.w / heads;
+    if (a.dh != 4 && a.dh != 8 && a.dh != 16 && a.dh != 32 && a.dh != 64) return false;
+    if ((int64_t)D.n_max * a.dh > 8192) return false;
+    const int64_t w = a.w, d = a.d, f = a.f;
+    int64_t o = 0;
+    auto take = [&](int64_t bytes) { int64_t at = o; o = al256(o + bytes); return at; };
+    const int64_t M = a.Mmax, LM = (int64_t)a.L * M;
+    a.rowoff = take(M * 8); a.rowstride = take(M * 4); a.rowsamp = take(M * 4);
+    a.samp_start = take((kMaxBatch + 1) * 4); a.samp_len = take(kMaxBatch * 4);
+    a.U = take(LM * w * 4); a.X = take(LM * w * 4); a.XN = take(LM * w * 4); a.QKV = take(LM * 3 * w * 4);
+    a.LSE = take(LM * a.nh * 4); a.O = take(LM * w * 4); a.T = take(LM * w * 4); a.TN = take(LM * w * 4);
+    a.F1 = take(LM * f * 4); a.G = take(LM * f * 4); a.A = take(LM * w * 4);
+    a.st1 = take(LM * 2 * 4); a.st2 = take(LM * 2 * 4);
+    a.DA = take(LM * w * 4); a.DF1 = take(LM * f * 4); a.DT = take(LM * w * 4); a.DQKV = take(LM * 3 * w * 4);
+    a.DX = take(LM * w * 4);
+    a.DTN = take(M * w * 4); a.DO_ = take(M * w * 4); a.DXN = take(M * w * 4);
+    a.nblk = cdivi(M, kLnRows);
+    a.ln1p = take((int64_t)a.L * a.nblk * 2 * w * 4); a.ln2p = take((int64_t)a.L * a.nblk * 2 * w * 4);
+    a.dlamp = take((int64_t)a.L * a.nblk * 4);
+    a.bmean = take((int64_t)a.Bmax * d * 4); a.abar = take((int64_t)a.Bmax * w * 4);
+    a.pooled = take((int64_t)a.Bmax * d * 4); a.logits = take((int64_t)a.Bmax * a.C * 4);
+    a.dz = take((int64_t)a.Bmax * a.C * 4); a.dp = take((int64_t)a.Bmax * d * 4);
+    a.daL = take((int64_t)a.Bmax * w * 4); a.lossp = take((int64_t)a.Bmax * 4);
+    // tiles of the five token contractions of one layer: W_down [d][w], W_qkv [w][3w], W_o [w][w], W_1 [w][f], W_2 [f][w]
+    const int rows[5] = {a.d, a.w, a.w, a.w, a.f}, cols[5] = {a.w, 3 * a.w, a.w, a.f, a.w};
+    a.item0[0] = 0;
+    for (int t = 0; t < 5; ++t) {
+        a.tiles[t][0] = cdivi(rows[t], 64);
+        a.tiles[t][1] = cdivi(cols[t], 64);
+        a.item0[t + 1] = a.item0[t] + a.tiles[t][0] * a.tiles[t][1];
+    }
+    a.items_per_layer = a.item0[5];
+    int s = cdivi(1024, (int64_t)a.items_per_layer * a.L);
+    const int by_rows = cdivi(M, 256);
+    if (s > by_rows) s = by_rows;
+    if (s > 16) s = 16;
+    if (s < 1) s = 1;
+    a.rows_per_split = cdivi(cdivi(M, s), 64) * 64;
+    a.splits = cdivi(M, a.rows_per_split);
+    a.part = take((int64_t)a.splits * a.L * a.PLb * 4);
+    a.grads = take(a.P * 4);
+    a.total = o;
+    return true;
+}
+
+// ---------------------------------------------------------------------------
+// set-up: sample ids -> per-token-row cache addresses
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_lsetup(BatchMeta meta, int d, int64_t *rowoff, int32_t *rowstride,
+                                                int32_t *rowsamp, int32_t *samp_start, int32_t *samp_len)
+{
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (blockIdx.x == 0 && (int)threadIdx.x <= meta.B) {
+        samp_start[threadIdx.x] = meta.tok_start[threadIdx.x];
+        if ((int)threadIdx.x < meta.B) samp_len[threadIdx.x] = meta.len[threadIdx.x];
+    }
+    if (m >= meta.M) return;
+    int s = 0;
+    while (s + 1 < meta.B && meta.tok_start[s + 1] <= m) ++s;
+    rowoff[m] = meta.off[s] + (int64_t)(m - meta.tok_start[s]) * d;
+    rowstride[m] = meta.len[s] * d;
+    rowsamp[m] = s;
+}
+
+// ---------------------------------------------------------------------------
+// Cache operands of the fp32 tiles: four consecutive elements of the cache dtype, widened exactly.
+// ---------------------------------------------------------------------------
+template <typename SRC> struct Raw4;
+template <> struct Raw4<float> {
+    typedef u32x4 type;
+    static __device__ __forceinline__ void widen(const type &r, float (&f)[4])
+    {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(r[e]);
+    }
+};
+template <> struct Raw4<bf16_t> {
+    typedef uint2 type;
+    static __device__ __forceinline__ void widen(const type &r, float (&f)[4])
+    {
+        f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+        f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+    }
+};
+
+// operand[row][k] = b_layer[row][k]   (token rows of the batch, K = hidden index)
+template <typename SRC, int ROWS, int KU> struct LoadRowsCache {
+    static constexpr bool kSwizzled = false;
+    using S = Stage<float, KU>;
+    using G = RowsGeom<float, ROWS, KU>;
+    using R = typename Raw4<SRC>::type;
+    const SRC *cache;
+    RowMap map;
+    int layer, klim;
+    const SRC *bp[G::NCH];
+    bool ok[G::NCH];
+    int kpos[2];
+    R reg[2][G::NCH];
+    __device__ void init(int row0)
+    {
+        const int t = threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            const int row = row0 + c / S::CPK;
+            ok[u] = c < G::TOTAL && row < map.M;
+            const int rowc = ok[u] ? row : 0;
+            bp[u] = cache + map.rowoff[rowc] + (int64_t)layer * map.rowstride[rowc] + (c % S::CPK) * 4;
+        }
+    }
+    template <int SLOT> __device__ void fetch(int k0)
+    {
+        kpos[SLOT] = k0;
+        const int t = threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int kc = ((t + kThreads * u) % S::CPK) * 4;
+            // chunks past the end of the row re-read its start (and are stored as zeros)
+            reg[SLOT][u] = *reinterpret_cast<const R *>(bp[u] + (k0 + kc < klim ? k0 : -kc));
+        }
+    }
+    template <int SLOT> __device__ void store(float *lds, bool)
+    {
+        const int t = threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            const bool keep = ok[u] && kpos[SLOT] + (c % S::CPK) * 4 < klim;
+            float f[4];
+            Raw4<SRC>::widen(reg[SLOT][u], f);
+            const f32x4 v = {keep ? f[0] : 0.f, keep ? f[1] : 0.f, keep ? f[2] : 0.f, keep ? f[3] : 0.f};
+            if (c < G::TOTAL) *reinterpret_cast<f32x4 *>(lds + (c / S::CPK) * S::LDP + (c % S::CPK) * 4) = v;
+        }
+    }
+};
+
+// operand[i][k] = b_layer[k][i]   (K = token row: the contraction over the tokens)
+template <typename SRC, int ROWS, int KU> struct LoadColsCache {
+    static constexpr bool kSwizzled = ColsSwizzle<float, KU>::value;
+    using S = Stage<float, KU>;
+    using G = ColsGeom<float, ROWS, KU>;
+    using R = typename Raw4<SRC>::type;
+    const SRC *cache;
+    RowMap map;
+    int layer, ncols, kend, i0;
+    int kpos[2];
+    R reg[2][G::NCH][4];
+    __device__ void init(int i0_) { i0 = i0_; }
+    template <int SLOT> __device__ void fetch(int k0)
+    {
+        kpos[SLOT] = k0;
+        const int t = threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = (t + kThreads * u) % G::TOTAL;
+            const int i = min(i0 + (c % G::IB) * 4, ncols - 4);
+            const int kb = k0 + (c / G::IB) * 4;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int k = min(kb + kk, kend - 1);
+                reg[SLOT][u][kk] = *reinterpret_cast<const R *>(cache + map.rowoff[k] + (int64_t)layer * map.rowstride[k] + i);
+            }
+        }
+    }
+    template <int SLOT> __device__ void store(float *lds, bool)
+    {
+        const int t = threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < G::NCH; ++u) {
+            const int c = t + kThreads * u;
+            const bool icol = i0 + (c % G::IB) * 4 < ncols;
+            const int kb = kpos[SLOT] + (c / G::IB) * 4;
+            Chunk<float> blk[4];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const bool keep = icol && kb + kk < kend && c < G::TOTAL;
+                float f[4];
+                Raw4<SRC>::widen(reg[SLOT][u][kk], f);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) blk[kk].e[e] = keep ? f[e] : 0.f;
+            }
+            if (c < G::TOTAL) cols_store_block<float, ROWS, KU>(lds, c, blk);
+        }
+    }
+};
+
+__device__ __forceinline__ float lgelu(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }
+__device__ __forceinline__ float lgelu_grad(float u)
+{
+    const float Phi = 0.5f * (1.f + erff(u * 0.70710678118654752f));
+    return Phi + u * 0.3989422804014327f * expf(-0.5f * u * u);
+}
+
+// ---------------------------------------------------------------------------
+// u_l = b_l W_down^l + c_down^l for every layer (grid.z = layer)
+// ---------------------------------------------------------------------------
+struct DownArgs {
+    const void *cache;
+    RowMap map;
+    const float *params;
+    int64_t PLb, oWd, ocd;
+    int d, w;
+    float *U; // [L][Mmax][w]
+    int64_t Mmax;
+};
+struct EpiBias {
+    const float *bias;
+    float *out;
+    int ld;
+    __device__ void operator()(int row, int col, float v) const { out[(int64_t)row * ld + col] = v + bias[col]; }
+};
+template <typename SRC> __global__ __launch_bounds__(256) void k_ldown(DownArgs a)
+{
+    __shared__ __attribute__((aligned(16))) char smem[kTileLds];
+    const int l = blockIdx.z;
+    const float *pl = a.params + (int64_t)l * a.PLb;
+    LoadRowsCache<SRC, 64, 4> al;
+    al.cache = static_cast<const SRC *>(a.cache); al.map = a.map; al.layer = l; al.klim = a.d;
+    LoadCols<float, 64, 4, float, false> bl;
+    bl.src = pl + a.oWd; bl.ld = a.w; bl.ncols = a.w; bl.kend = a.d;
+    EpiBias epi{pl + a.ocd, a.U + (int64_t)l * a.Mmax * a.w, a.w};
+    gemm_tile<float, TL>(smem, al, bl, epi, 0, a.d, blockIdx.x * 64, blockIdx.y * 64, a.map.M, a.w);
+}
+
+// ---------------------------------------------------------------------------
+// out = A B (+ ...) for the w-wide activations.  BT false: B is [K][N] (a weight used forward);
+// BT true: B is [N][K] (the same weight used in the reverse pass).
+//   EPI 0: out = acc + bias            1: out = acc + bias + res
+//       2: out = acc + bias, out2 = GELU(out)      3: out = acc * GELU'(aux)      4: out = acc
+// ---------------------------------------------------------------------------
+struct LinArgs {
+    const float *A; int lda;
+    const float *B; int ldb;
+    int M, N, K;
+    const float *bias, *res, *aux;
+    float *out, *out2;
+};
+template <int EPI> struct EpiLin {
+    LinArgs a;
+    __device__ void operator()(int row, int col, float v) const
+    {
+        const int64_t o = (int64_t)row * a.N + col;
+        if (EPI == 0) a.out[o] = v + a.bias[col];
+        if (EPI == 1) a.out[o] = v + a.bias[col] + a.res[o];
+        if (EPI == 2) { const float u = v + a.bias[col]; a.out[o] = u; a.out2[o] = lgelu(u); }
+        if (EPI == 3) a.out[o] = v * lgelu_grad(a.aux[o]);
+        if (EPI == 4) a.out[o] = v;
+    }
+};
+template <bool BT, int EPI> __global__ __launch_bounds__(256) void k_llin(LinArgs a)
+{
+    __shared__ __attribute__((aligned(16))) char smem[kTileLds];
+    LoadRowsTC<float, 64, 4> al;
+    al.src = a.A; al.ld = a.lda; al.nrows = a.M; al.klim = a.K;
+    EpiLin<EPI> epi{a};
+    if (BT) {
+        LoadRowsTC<float, 64, 4> bl;
+        bl.src = a.B; bl.ld = a.ldb; bl.nrows = a.N; bl.klim = a.K;
+        gemm_tile<float, TL>(smem, al, bl, epi, 0, a.K, blockIdx.x * 64, blockIdx.y * 64, a.M, a.N);
+    } else {
+        LoadCols<float, 64, 4, float, false> bl;
+        bl.src = a.B; bl.ld = a.ldb; bl.ncols = a.N; bl.kend = a.K;
+        gemm_tile<float, TL>(smem, al, bl, epi, 0, a.K, blockIdx.x * 64, blockIdx.y * 64, a.M, a.N);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Row kernels (one wavefront per token row, lane owns columns lane, lane + 64, ...; w <= 256)
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// x = lam u + (1 - lam) a_prev (MIX) or x = in (plain); xn = LayerNorm(x; g, h); stats = (mean, 1/sqrt(var + eps))
+struct LnFwdArgs {
+    const float *in, *a_prev, *lam; // a_prev may be null (first layer)
+    const float *g, *h;
+    float *x, *xn, *stats;
+    int M, w;
+};
+template <bool MIX> __global__ __launch_bounds__(256) void k_lln_fwd(LnFwdArgs a)
+{
+    const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.M) return;
+    const float lam = MIX ? *a.lam : 1.f;
+    float x[4], s = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int c = lane + 64 * q;
+        x[q] = 0.f;
+        if (c < a.w) {
+            const int64_t o = (int64_t)row * a.w + c;
+            float v = a.in[o];
+            if (MIX) {
+                v = lam * v + (1.f - lam) * (a.a_prev ? a.a_prev[o] : 0.f);
+                a.x[o] = v;
+            }
+            x[q] = v;
+            s += v;
+        }
+    }
+    const float mu = wave_sum(s) / (float)a.w;
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (lane + 64 * q < a.w) ss += (x[q] - mu) * (x[q] - mu);
+    const float rstd = 1.f / sqrtf(wave_sum(ss) / (float)a.w + 1e-5f);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int c = lane + 64 * q;
+        if (c < a.w) a.xn[(int64_t)row * a.w + c] = (x[q] - mu) * rstd * a.g[c] + a.h[c];
+    }
+    if (lane == 0) { a.stats[2 * row] = mu; a.stats[2 * row + 1] = rstd; }
+}
+
+// Reverse of LayerNorm with the residual path: dx = resid + (1/sigma)(dxh - mean(dxh) - xh mean(dxh xh)),
+// dxh = dy g, xh = (x - mean) / sigma; per-workgroup partial sums of dg = sum dy xh and dh = sum dy.
+// MIX: also the gate's reverse: dlam partial = sum dx (u - a_prev), da_prev = (1 - lam) dx.
+struct LnBwdArgs {
+    const float *dy, *x, *stats, *g, *resid;
+    float *dx;
+    float *part; // [nblk][2][w]
+    const float *u, *a_prev, *lam;
+    float *da_prev;  // null for the first layer
+    float *dlam_part; // [nblk]
+    int M, w;
+};
+template <bool MIX> __global__ __launch_bounds__(256) void k_lln_bwd(LnBwdArgs a)
+{
+    __shared__ float red[4][2][256];
+    __shared__ float redl[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float lam = MIX ? *a.lam : 0.f;
+    float dg[4] = {0.f, 0.f, 0.f, 0.f}, dh[4] = {0.f, 0.f, 0.f, 0.f}, dlam = 0.f;
+    float g[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) g[q] = lane + 64 * q < a.w ? a.g[lane + 64 * q] : 0.f;
+    for (int rr = 0; rr < kLnRows / 4; ++rr) {
+        const int row = blockIdx.x * kLnRows + wave * (kLnRows / 4) + rr;
+        if (row >= a.M) break;
+        const float mu = a.stats[2 * row], rstd = a.stats[2 * row + 1];
+        float xh[4], dxh[4], s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = lane + 64 * q;
+            xh[q] = dxh[q] = 0.f;
+            if (c < a.w) {
+                const int64_t o = (int64_t)row * a.w + c;
+                const float dy = a.dy[o];
+                xh[q] = (a.x[o] - mu) * rstd;
+                dxh[q] = dy * g[q];
+                dg[q] += dy * xh[q];
+                dh[q] += dy;
+                s1 += dxh[q];
+                s2 += dxh[q] * xh[q];
+            }
+        }
+        const float m1 = wave_sum(s1) / (float)a.w, m2 = wave_sum(s2) / (float)a.w;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = lane + 64 * q;
+            if (c < a.w) {
+                const int64_t o = (int64_t)row * a.w + c;
+                const float dx = a.resid[o] + rstd * (dxh[q] - m1 - xh[q] * m2);
+                a.dx[o] = dx;
+                if (MIX) {
+                    dlam += dx * (a.u[o] - (a.a_prev ? a.a_prev[o] : 0.f));
+                    if (a.da_prev) a.da_prev[o] = (1.f - lam) * dx;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { red[wave][0][lane + 64 * q] = dg[q]; red[wave][1][lane + 64 * q] = dh[q]; }
+    if (MIX) {
+        const float t = wave_sum(dlam);
+        if (lane == 0) redl[wave] = t;
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < a.w; c += 256) {
+        float *p = a.part + (int64_t)blockIdx.x * 2 * a.w;
+        p[c] = ((red[0][0][c] + red[1][0][c]) + red[2][0][c]) + red[3][0][c];
+        p[a.w + c] = ((red[0][1][c] + red[1][1][c]) + red[2][1][c]) + red[3][1][c];
+    }
+    if (MIX && threadIdx.x == 0) a.dlam_part[blockIdx.x] = ((redl[0] + redl[1]) + redl[2]) + redl[3];
+}
+
+// ---------------------------------------------------------------------------
+// Attention of one sample and head per workgroup; a thread owns a query row (forward, reverse phase 1)
+// or a key row (reverse phase 2).  K and V (and Q, dO in the reverse pass) of the head sit in LDS.
+// ---------------------------------------------------------------------------
+struct AttnArgs {
+    const float *QKV; // [M][3w]
+    const int32_t *samp_start, *samp_len;
+    float *O;   // [M][w]
+    float *LSE; // [M][nh]
+    const float *dO; // reverse: [M][w]
+    float *dQKV;     // reverse: [M][3w]
+    int w, nh, n_max;
+    float scale;
+};
+template <int DH> __global__ __launch_bounds__(256) void k_lattn_fwd(AttnArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) float lsm[];
+    const int s = blockIdx.x / a.nh, h = blockIdx.x % a.nh;
+    const int m0 = a.samp_start[s], n = a.samp_len[s];
+    const int w3 = 3 * a.w;
+    float *ks = lsm, *vs = lsm + (int64_t)a.n_max * DH;
+    for (int idx = threadIdx.x; idx < n * DH; idx += 256) {
+        const int j = idx / DH, c = idx % DH;
+        const float *row = a.QKV + (int64_t)(m0 + j) * w3 + h * DH + c;
+        ks[idx] = row[a.w];
+        vs[idx] = row[2 * a.w];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += 256) {
+        float q[DH];
+        const float *qp = a.QKV + (int64_t)(m0 + i) * w3 + h * DH;
+#pragma unroll
+        for (int c = 0; c < DH; ++c) q[c] = qp[c] * a.scale;
+        float mx = -INFINITY;
+        for (int j = 0; j < n; ++j) {
+            float sc = 0.f;
+#pragma unroll
+            for (int c = 0; c < DH; ++c) sc += q[c] * ks[j * DH + c];
+            mx = fmaxf(mx, sc);
+        }
+        float l = 0.f, acc[DH];
+#pragma unroll
+        for (int c = 0; c < DH; ++c) acc[c] = 0.f;
+        for (int j = 0; j < n; ++j) {
+            float sc = 0.f;
+#pragma unroll
+            for (int c = 0; c < DH; ++c) sc += q[c] * ks[j * DH + c];
+            const float p = expf(sc - mx);
+            l += p;
+#pragma unroll
+            for (int c = 0; c < DH; ++c) acc[c] += p * vs[j * DH + c];
+        }
+        const float inv = 1.f / l;
+        float *op = a.O + (int64_t)(m0 + i) * a.w + h * DH;
+#pragma unroll
+        for (int c = 0; c < DH; ++c) op[c] = acc[c] * inv;
+        a.LSE[(int64_t)(m0 + i) * a.nh + h] = mx + logf(l);
+    }
+}
+
+template <int DH> __global__ __launch_bounds__(256) void k_lattn_bwd(AttnArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) float lsm[];
+    const int s = blockIdx.x / a.nh, h = blockIdx.x % a.nh;
+    const int m0 = a.samp_start[s], n = a.samp_len[s];
+    const int w3 = 3 * a.w;
+    const int64_t nd = (int64_t)a.n_max * DH;
+    float *qs = lsm, *ks = lsm + nd, *vs = lsm + 2 * nd, *dos = lsm + 3 * nd, *lse = lsm + 4 * nd, *Dr = lse + a.n_max;
+    for (int idx = threadIdx.x; idx < n * DH; idx += 256) {
+        const int j = idx / DH, c = idx % DH;
+        const float *row = a.QKV + (int64_t)(m0 + j) * w3 + h * DH + c;
+        qs[idx] = row[0];
+        ks[idx] = row[a.w];
+        vs[idx] = row[2 * a.w];
+        dos[idx] = a.dO[(int64_t)(m0 + j) * a.w + h * DH + c];
+    }
+    for (int i = threadIdx.x; i < n; i += 256) {
+        lse[i] = a.LSE[(int64_t)(m0 + i) * a.nh + h];
+        const float *op = a.O + (int64_t)(m0 + i) * a.w + h * DH;
+        const float *dp = a.dO + (int64_t)(m0 + i) * a.w + h * DH;
+        float D = 0.f;
+#pragma unroll
+        for (int c = 0; c < DH; ++c) D += op[c] * dp[c];
+        Dr[i] = D;
+    }
+    __syncthreads();
+    // phase 1, query row i: dq_i = scale * sum_j P_ij (dO_i . v_j - D_i) k_j
+    for (int i = threadIdx.x; i < n; i += 256) {
+        float q[DH], go[DH], dq[DH];
+#pragma unroll
+        for (int c = 0; c < DH; ++c) { q[c] = qs[i * DH + c] * a.scale; go[c] = dos[i * DH + c]; dq[c] = 0.f; }
+        const float li = lse[i], Di = Dr[i];
+        for (int j = 0; j < n; ++j) {
+            float sc = 0.f, dpv = 0.f;
+#pragma unroll
+            for (int c = 0; c < DH; ++c) { sc += q[c] * ks[j * DH + c]; dpv += go[c] * vs[j * DH + c]; }
+            const float ds = expf(sc - li) * (dpv - Di);
+#pragma unroll
+            for (int c = 0; c < DH; ++c) dq[c] += ds * ks[j * DH + c];
+        }
+        float *out = a.dQKV + (int64_t)(m0 + i) * w3 + h * DH;
+#pragma unroll
+        for (int c = 0; c < DH; ++c) out[c] = dq[c] * a.scale;
+    }
+    // phase 2, key row j: dv_j = sum_i P_ij dO_i ; dk_j = scale * sum_i P_ij (dO_i . v_j - D_i) q_i
+    for (int j = threadIdx.x; j < n; j += 256) {
+        float k[DH], v[DH], dk[DH], dv[DH];
+#pragma unroll
+        for (int c = 0; c < DH; ++c) { k[c] = ks[j * DH + c] * a.scale; v[c] = vs[j * DH + c]; dk[c] = 0.f; dv[c] = 0.f; }
+        for (int i = 0; i < n; ++i) {
+            float sc = 0.f, dpv = 0.f;
+#pragma unroll
+            for (int c = 0; c < DH; ++c) { sc += qs[i * DH + c] * k[c]; dpv += dos[i * DH + c] * v[c]; }
+            const float p = expf(sc - lse[i]);
+            const float ds = p * (dpv - Dr[i]);
+#pragma unroll
+            for (int c = 0; c < DH; ++c) { dv[c] += p * dos[i * DH + c]; dk[c] += ds * qs[i * DH + c]; }
+        }
+        float *out = a.dQKV + (int64_t)(m0 + j) * w3 + h * DH;
+#pragma unroll
+        for (int c = 0; c < DH; ++c) { out[a.w + c] = dk[c] * a.scale; out[2 * a.w + c] = dv[c]; }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Head: y = b_L + a_L W_up + c_up; its token mean; classifier; cross-entropy; the head's gradients; da_L.
+// ---------------------------------------------------------------------------
+struct HeadArgs {
+    const void *cache;
+    RowMap map;
+    const int32_t *samp_start, *samp_len, *labels;
+    const float *params;
+    int64_t oWup, ocup, oWcls, occls;
+    const float *A_last; // [M][w]
+    float *bmean, *abar, *pooled, *logits, *dz, *dp, *daL, *lossp;
+    float *DA_last; // [M][w]
+    float *loss_out, *logits_out, *grads; // logits_out, grads may be null
+    int B, d, w, C, last_layer;
+};
+
+// token means of b_L (blockIdx.y < column blocks of d) and of a_L (the last blockIdx.y)
+template <typename SRC> __global__ __launch_bounds__(256) void k_lpool(HeadArgs a)
+{
+    const int s = blockIdx.x, m0 = a.samp_start[s], len = a.samp_len[s];
+    const int nbd = (a.d + 255) / 256;
+    if ((int)blockIdx.y < nbd) {
+        const int j = blockIdx.y * 256 + threadIdx.x;
+        if (j >= a.d) return;
+        const SRC *cache = static_cast<const SRC *>(a.cache);
+        float acc = 0.f;
+        for (int t = 0; t < len; ++t) {
+            const int m = m0 + t;
+            acc += to_f32(cache[a.map.rowoff[m] + (int64_t)a.last_layer * a.map.rowstride[m] + j]);
+        }
+        a.bmean[(int64_t)s * a.d + j] = acc / (float)len;
+    } else {
+        const int c = threadIdx.x;
+        if (c >= a.w) return;
+        float acc = 0.f;
+        for (int t = 0; t < len; ++t) acc += a.A_last[(int64_t)(m0 + t) * a.w + c];
+        a.abar[(int64_t)s * a.w + c] = acc / (float)len;
+    }
+}
+
+// one workgroup per sample: pooled, logits, loss term, dz
+__global__ __launch_bounds__(256) void k_lhead_a(HeadArgs a)
+{
+    __shared__ float zpart[256][kMaxClasses];
+    __shared__ float z[kMaxClasses];
+    const int s = blockIdx.x, t = threadIdx.x;
+    const float *Wup = a.params + a.oWup, *cup = a.params + a.ocup, *Wcls = a.params + a.oWcls, *ccls = a.params + a.occls;
+    float zc[kMaxClasses];
+#pragma unroll
+    for (int c = 0; c < kMaxClasses; ++c) zc[c] = 0.f;
+    for (int j = t; j < a.d; j += 256) {
+        float p = a.bmean[(int64_t)s * a.d + j] + cup[j];
+        for (int c = 0; c < a.w; ++c) p += a.abar[(int64_t)s * a.w + c] * Wup[(int64_t)c * a.d + j];
+        a.pooled[(int64_t)s * a.d + j] = p;
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c)
+            if (c < a.C) zc[c] += p * Wcls[(int64_t)j * a.C + c];
+    }
+#pragma unroll
+    for (int c = 0; c < kMaxClasses; ++c) zpart[t][c] = zc[c];
+    __syncthreads();
+    if (t < a.C) {
+        float acc = 0.f;
+        for (int k = 0; k < 256; ++k) acc += zpart[k][t];
+        z[t] = acc + ccls[t];
+    }
+    __syncthreads();
+    if (t == 0) {
+        float mx = z[0];
+        for (int c = 1; c < a.C; ++c) mx = fmaxf(mx, z[c]);
+        float sum = 0.f;
+        for (int c = 0; c < a.C; ++c) sum += expf(z[c] - mx);
+        const float lse = mx + logf(sum);
+        const int y = a.labels[s];
+        a.lossp[s] = lse - z[y];
+        for (int c = 0; c < a.C; ++c) {
+            a.logits[s * a.C + c] = z[c];
+            if (a.logits_out) a.logits_out[s * a.C + c] = z[c];
+            a.dz[s * a.C + c] = (expf(z[c] - lse) - (c == y ? 1.f : 0.f)) / (float)a.B;
+        }
+    }
+}
+
+// thread per hidden column j: dp[s][j], dc_up[j], dW_cls[j][.], dW_up[.][j]; block 0 also the loss and dc_cls
+__global__ __launch_bounds__(256) void k_lhead_b(HeadArgs a)
+{
+    __shared__ float dzs[kMaxBatch * kMaxClasses];
+    for (int q = threadIdx.x; q < a.B * a.C; q += 256) dzs[q] = a.dz[q];
+    __syncthreads();
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        float tot = 0.f;
+        for (int s = 0; s < a.B; ++s) tot += a.lossp[s];
+        *a.loss_out = tot / (float)a.B;
+    }
+    if (!a.grads) return;
+    if (blockIdx.x == 0 && (int)threadIdx.x < a.C) {
+        float acc = 0.f;
+        for (int s = 0; s < a.B; ++s) acc += dzs[s * a.C + threadIdx.x];
+        a.grads[a.occls + threadIdx.x] = acc;
+    }
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= a.d) return;
+    const float *Wcls = a.params + a.oWcls + (int64_t)j * a.C;
+    float wc[kMaxClasses], dwc[kMaxClasses];
+#pragma unroll
+    for (int c = 0; c < kMaxClasses; ++c) { wc[c] = c < a.C ? Wcls[c] : 0.f; dwc[c] = 0.f; }
+    float dcup = 0.f;
+    for (int s = 0; s < a.B; ++s) {
+        float dp = 0.f;
+        const float pl = a.pooled[(int64_t)s * a.d + j];
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c)
+            if (c < a.C) { dp += dzs[s * a.C + c] * wc[c]; dwc[c] += pl * dzs[s * a.C + c]; }
+        a.dp[(int64_t)s * a.d + j] = dp;
+        dcup += dp;
+    }
+    a.grads[a.ocup + j] = dcup;
+#pragma unroll
+    for (int c = 0; c < kMaxClasses; ++c)
+        if (c < a.C) a.grads[a.oWcls + (int64_t)j * a.C + c] = dwc[c];
+    for (int c = 0; c < a.w; ++c) {
+        float acc = 0.f;
+        for (int s = 0; s < a.B; ++s) acc += a.abar[(int64_t)s * a.w + c] * a.dp[(int64_t)s * a.d + j];
+        a.grads[a.oWup + (int64_t)c * a.d + j] = acc;
+    }
+}
+
+// one workgroup per sample: da_L[s][c] = (dp_s . W_up[c][:]) / len_s, written to every token row of the sample
+__global__ __launch_bounds__(256) void k_lhead_c(HeadArgs a)
+{
+    __shared__ float da[256];
+    const int s = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m0 = a.samp_start[s], len = a.samp_len[s];
+    const float *Wup = a.params + a.oWup;
+    for (int c = wave; c < a.w; c += 4) {
+        float acc = 0.f;
+        for (int j = lane; j < a.d; j += 64) acc += a.dp[(int64_t)s * a.d + j] * Wup[(int64_t)c * a.d + j];
+        acc = wave_sum(acc);
+        if (lane == 0) da[c] = acc / (float)len;
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < len * a.w; idx += 256)
+        a.DA_last[(int64_t)(m0 + idx / a.w) * a.w + idx % a.w] = da[idx % a.w];
+}
+
+// ---------------------------------------------------------------------------
+// All contractions over the tokens, one launch: work item = (split, layer, tensor, tile).
+//   W_down: b_l^T dx_l    W_qkv: xn_l^T dqkv_l    W_o: o_l^T dt_l    W_1: tn_l^T df1_l    W_2: g_l^T da_l
+// The right-hand loader of the first row of tiles keeps the column sums: the bias gradients.
+// Results go to part[split] at the tensors' offsets in the parameter vector.
+// ---------------------------------------------------------------------------
+struct WgArgs {
+    const void *cache;
+    RowMap map;
+    const float *XN, *DQKV, *O, *DT, *TN, *DF1, *G, *DA, *DX;
+    float *part;
+    int64_t Mmax, PLb, LP; // LP = L * PLb
+    int64_t fo[kFields + 1];
+    int L, d, w, f, rows_per_split, items_per_layer;
+    int tiles_j[5], item0[6];
+};
+struct EpiSt {
+    float *out;
+    int ld;
+    __device__ void operator()(int row, int col, float v) const { out[(int64_t)row * ld + col] = v; }
+};
+template <class BL> __device__ __forceinline__ void lad_colsums(BL &bl, float *red, float *dst, int ncols, int j0)
+{
+    using G = ColsGeom<float, 64, 4>;
+    __syncthreads();
+    for (int e = 0; e < G::CE; ++e) red[threadIdx.x * G::CE + e] = bl.sums[e];
+    __syncthreads();
+    if ((int)threadIdx.x < 64) {
+        const int col = threadIdx.x, blk = col / G::CE, e = col % G::CE;
+        float acc = 0.f;
+        for (int t = blk; t < kThreads; t += G::IB) acc += red[t * G::CE + e];
+        if (j0 + col < ncols) dst[j0 + col] = acc;
+    }
+}
+template <typename SRC> __global__ __launch_bounds__(256) void k_lwgrad(WgArgs a)
+{
+    __shared__ __attribute__((aligned(16))) char smem[kTileLds];
+    static_assert(kTileLds >= 256 * 4 * 4, "column-sum scratch must fit");
+    int b = blockIdx.x;
+    const int per_split = a.items_per_layer * a.L;
+    const int split = b / per_split;
+    b -= split * per_split;
+    const int l = b / a.items_per_layer, it = b % a.items_per_layer;
+    int t = 0;
+    while (t < 4 && it >= a.item0[t + 1]) ++t;
+    const int ti = (it - a.item0[t]) / a.tiles_j[t], tj = (it - a.item0[t]) % a.tiles_j[t];
+    const int M = a.map.M;
+    const int kbegin = split * a.rows_per_split, kend = min(M, kbegin + a.rows_per_split);
+    float *part = a.part + (int64_t)split * a.LP + (int64_t)l * a.PLb;
+    const int64_t lm = (int64_t)l * a.Mmax;
+    const int w = a.w, f = a.f;
+    // right-hand operand, output field, bias field, shapes
+    const float *Bsrc; int ncolsB; int fieldW, fieldB; const float *Asrc = nullptr; int nrowsA;
+    switch (t) {
+    case 0: Bsrc = a.DX + lm * w; ncolsB = w; fieldW = F_WD; fieldB = F_CD; nrowsA = a.d; break;
+    case 1: Bsrc = a.DQKV + lm * 3 * w; ncolsB = 3 * w; fieldW = F_WQKV; fieldB = F_BQKV; Asrc = a.XN + lm * w; nrowsA = w; break;
+    case 2: Bsrc = a.DT + lm * w; ncolsB = w; fieldW = F_WO; fieldB = F_BO; Asrc = a.O + lm * w; nrowsA = w; break;
+    case 3: Bsrc = a.DF1 + lm * f; ncolsB = f; fieldW = F_W1; fieldB = F_B1; Asrc = a.TN + lm * w; nrowsA = w; break;
+    default: Bsrc = a.DA + lm * w; ncolsB = w; fieldW = F_W2; fieldB = F_B2; Asrc = a.G + lm * f; nrowsA = f; break;
+    }
+    LoadCols<float, 64, 4, float, true> bl;
+    bl.src = Bsrc; bl.ld = ncolsB; bl.ncols = ncolsB; bl.kend = kend;
+    EpiSt epi{part + a.fo[fieldW], ncolsB};
+    if (kbegin >= kend) return; // (no such item: splits are planned from the batch's own row count)
+    if (t == 0) {
+        LoadColsCache<SRC, 64, 4> al;
+        al.cache = static_cast<const SRC *>(a.cache); al.map = a.map; al.layer = l; al.ncols = a.d; al.kend = kend;
+        gemm_tile<float, TL>(smem, al, bl, epi, kbegin, kend, ti * 64, tj * 64, nrowsA, ncolsB);
+    } else {
+        LoadCols<float, 64, 4, float, false> al;
+        al.src = Asrc; al.ld = nrowsA; al.ncols = nrowsA; al.kend = kend;
+        gemm_tile<float, TL>(smem, al, bl, epi, kbegin, kend, ti * 64, tj * 64, nrowsA, ncolsB);
+    }
+    if (ti == 0) lad_colsums(bl, reinterpret_cast<float *>(smem), part + a.fo[fieldB], ncolsB, tj * 64);
+}
+
+// ordered sums into the gradient vector: thread per element of the layer blocks
+struct RedArgs {
+    const float *part, *ln1p, *ln2p, *dlamp, *params;
+    float *grads;
+    int64_t PLb, LP;
+    int64_t fo[kFields + 1];
+    int L, w, splits, nblk;
+};
+__global__ __launch_bounds__(256) void k_lreduce(RedArgs a)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= a.LP) return;
+    const int l = (int)(i / a.PLb);
+    const int64_t o = i - (int64_t)l * a.PLb;
+    int fld = 0;
+    while (fld < kFields - 1 && o >= a.fo[fld + 1]) ++fld;
+    const int c = (int)(o - a.fo[fld]);
+    float acc = 0.f;
+    if (fld == F_G1 || fld == F_H1 || fld == F_G2 || fld == F_H2) {
+        const float *p = ((fld == F_G1 || fld == F_H1) ? a.ln1p : a.ln2p) + (int64_t)l * a.nblk * 2 * a.w +
+                         ((fld == F_H1 || fld == F_H2) ? a.w : 0) + c;
+        for (int k = 0; k < a.nblk; ++k) acc += p[(int64_t)k * 2 * a.w];
+    } else if (fld == F_LAM) {
+        if (c == 0)
+            for (int k = 0; k < a.nblk; ++k) acc += a.dlamp[(int64_t)l * a.nblk + k];
+    } else {
+        for (int s = 0; s < a.splits; ++s) acc += a.part[(int64_t)s * a.LP + i];
+        if (fld == F_WD || fld == F_CD) acc *= a.params[(int64_t)l * a.PLb + a.fo[F_LAM]]; // du = lambda dx
+    }
+    a.grads[i] = acc;
+}
+
+// AdamW over the ladder's parameter vector: decoupled decay on the matrices only
+struct LAdamArgs {
+    float *p, *m, *v;
+    const float *g;
+    int64_t P, PLb, LP, oWup, ocup, oWcls, occls;
+    int64_t fo[kFields + 1];
+    AdamArgs h;
+};
+__global__ __launch_bounds__(256) void k_ladamw(LAdamArgs a)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < a.P; i += (int64_t)gridDim.x * 256) {
+        bool dec;
+        if (i < a.LP) {
+            const int64_t o = i % a.PLb;
+            int fld = 0;
+            while (fld < kFields - 1 && o >= a.fo[fld + 1]) ++fld;
+            dec = fld == F_WD || fld == F_WQKV || fld == F_WO || fld == F_W1 || fld == F_W2;
+        } else {
+            dec = i < a.ocup || (i >= a.oWcls && i < a.occls);
+        }
+        const float g = a.g[i];
+        float p = a.p[i];
+        const float m = a.h.beta1 * a.m[i] + (1.f - a.h.beta1) * g;
+        const float v = a.h.beta2 * a.v[i] + (1.f - a.h.beta2) * g * g;
+        if (dec) p -= a.h.lr * a.h.wd * p;
+        p -= a.h.lr * (m / a.h.bc1) / (sqrtf(v / a.h.bc2) + a.h.eps);
+        a.p[i] = p; a.m[i] = m; a.v[i] = v;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+template <auto Kern> hipError_t lds_once(int bytes)
+{
+    static std::once_flag once;
+    static hipError_t result = hipSuccess;
+    std::call_once(once, [&] {
+        result = hipFuncSetAttribute(reinterpret_cast<const void *>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     160 * 1024);
+    });
+    (void)bytes;
+    return result;
+}
+
+template <int DH> hipError_t launch_attn(bool bwd, const AttnArgs &a, int B, hipStream_t st, Profiler *prof)
+{
+    if (!bwd) {
+        const int lds = 2 * a.n_max * DH * 4;
+        LAD_TRY((lds_once<&k_lattn_fwd<DH>>(lds)));
+        LAD_LAUNCH(prof, st, KC_L_ATTN, (k_lattn_fwd<DH>), dim3(B * a.nh), dim3(256), lds, st, a);
+    } else {
+        const int lds = (4 * a.n_max * DH + 2 * a.n_max) * 4;
+        LAD_TRY((lds_once<&k_lattn_bwd<DH>>(lds)));
+        LAD_LAUNCH(prof, st, KC_L_ATTN, (k_lattn_bwd<DH>), dim3(B * a.nh), dim3(256), lds, st, a);
+    }
+    return hipSuccess;
+}
+
+hipError_t attn(int dh, bool bwd, const AttnArgs &a, int B, hipStream_t st, Profiler *prof)
+{
+    switch (dh) {
+    case 4: return launch_attn<4>(bwd, a, B, st, prof);
+    case 8: return launch_attn<8>(bwd, a, B, st, prof);
+    case 16: return launch_attn<16>(bwd, a, B, st, prof);
+    case 32: return launch_attn<32>(bwd, a, B, st, prof);
+    case 64: return launch_attn<64>(bwd, a, B, st, prof);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <bool BT, int EPI>
+void lin(Profiler *prof, hipStream_t st, int cls, const float *A, int lda, const float *B, int ldb, int M, int N, int K,
+         const float *bias, const float *res, const float *aux, float *out, float *out2)
+{
+    LinArgs a{A, lda, B, ldb, M, N, K, bias, res, aux, out, out2};
+    LAD_LAUNCH(prof, st, cls, (k_llin<BT, EPI>), dim3(cdivi(M, 64), cdivi(N, 64)), dim3(256), 0, st, a);
+}
+
+template <typename SRC>
+hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, const int32_t *labels, const float *params,
+                      char *ws, float *loss_out, float *logits_out, float *grads, hipStream_t st, Profiler *prof)
+{
+    const int M = meta.M, B = meta.B, L = a.L, w = a.w, f = a.f, d = a.d;
+    auto F = [&](int64_t off) { return reinterpret_cast<float *>(ws + off); };
+    int64_t *rowoff = reinterpret_cast<int64_t *>(ws + a.rowoff);
+    int32_t *rowstride = reinterpret_cast<int32_t *>(ws + a.rowstride), *rowsamp = reinterpret_cast<int32_t *>(ws + a.rowsamp);
+    int32_t *samp_start = reinterpret_cast<int32_t *>(ws + a.samp_start), *samp_len = reinterpret_cast<int32_t *>(ws + a.samp_len);
+    const RowMap map{rowoff, rowstride, M};
+    const int64_t Mm = a.Mmax;
+    const int nblk = cdivi(M, kLnRows); // workgroups of the LayerNorm reverse kernels: stride of their partial sums
+    auto lay = [&](int64_t off, int l, int width) { return F(off) + (int64_t)l * Mm * width; };
+
+    LAD_LAUNCH(prof, st, KC_SETUP, k_lsetup, dim3(cdivi(M, 256)), dim3(256), 0, st, meta, d, rowoff, rowstride, rowsamp,
+               samp_start, samp_len);
+    {
+        DownArgs da{cache, map, params, a.PLb, a.fo[F_WD], a.fo[F_CD], d, w, F(a.U), Mm};
+        LAD_LAUNCH(prof, st, KC_L_DOWN, (k_ldown<SRC>), dim3(cdivi(M, 64), cdivi(w, 64), L), dim3(256), 0, st, da);
+    }
+    const float scale = 1.f / sqrtf((float)a.dh);
+    for (int l = 0; l < L; ++l) {
+        const float *pl = params + (int64_t)l * a.PLb;
+        LnFwdArgs n1{lay(a.U, l, w), l ? lay(a.A, l - 1, w) : nullptr, pl + a.fo[F_LAM], pl + a.fo[F_G1], pl + a.fo[F_H1],
+                     lay(a.X, l, w), lay(a.XN, l, w), lay(a.st1, l, 2), M, w};
+        LAD_LAUNCH(prof, st, KC_L_ROW, (k_lln_fwd<true>), dim3(cdivi(M, 4)), dim3(256), 0, st, n1);
+        lin<false, 0>(prof, st, KC_L_LIN, lay(a.XN, l, w), w, pl + a.fo[F_WQKV], 3 * w, M, 3 * w, w, pl + a.fo[F_BQKV],
+                      nullptr, nullptr, lay(a.QKV, l, 3 * w), nullptr);
+        AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), nullptr, nullptr, w,
+                    a.nh, (int)(Mm / a.Bmax), scale};
+        LAD_TRY(attn(a.dh, false, at, B, st, prof));
+        lin<false, 1>(prof, st, KC_L_LIN, lay(a.O, l, w), w, pl + a.fo[F_WO], w, M, w, w, pl + a.fo[F_BO], lay(a.X, l, w),
+                      nullptr, lay(a.T, l, w), nullptr);
+        LnFwdArgs n2{lay(a.T, l, w), nullptr, nullptr, pl + a.fo[F_G2], pl + a.fo[F_H2], nullptr, lay(a.TN, l, w),
+                     lay(a.st2, l, 2), M, w};
+        LAD_LAUNCH(prof, st, KC_L_ROW, (k_lln_fwd<false>), dim3(cdivi(M, 4)), dim3(256), 0, st, n2);
+        lin<false, 2>(prof, st, KC_L_LIN, lay(a.TN, l, w), w, pl + a.fo[F_W1], f, M, f, w, pl + a.fo[F_B1], nullptr, nullptr,
+                      lay(a.F1, l, f), lay(a.G, l, f));
+        lin<false, 1>(prof, st, KC_L_LIN, lay(a.G, l, f), f, pl + a.fo[F_W2], w, M, w, f, pl + a.fo[F_B2], lay(a.T, l, w),
+                      nullptr, lay(a.A, l, w), nullptr);
+    }
+    HeadArgs h{cache, map, samp_start, samp_len, labels, params, a.oWup, a.ocup, a.oWcls, a.occls, lay(a.A, L - 1, w),
+               F(a.bmean), F(a.abar), F(a.pooled), F(a.logits), F(a.dz), F(a.dp), F(a.daL), F(a.lossp),
+               lay(a.DA, L - 1, w), loss_out, logits_out, grads, B, d, w, a.C, L - 1};
+    LAD_LAUNCH(prof, st, KC_L_HEAD, (k_lpool<SRC>), dim3(B, cdivi(d, 256) + 1), dim3(256), 0, st, h);
+    LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_a, dim3(B), dim3(256), 0, st, h);
+    LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_b, dim3(cdivi(d, 256)), dim3(256), 0, st, h);
+    if (!grads) return hipGetLastError();
+    LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_c, dim3(B), dim3(256), 0, st, h);
+
+    for (int l = L - 1; l >= 0; --l) {
+        const float *pl = params + (int64_t)l * a.PLb;
+        float *DA = lay(a.DA, l, w), *DF1 = lay(a.DF1, l, f), *DT = lay(a.DT, l, w), *DQKV = lay(a.DQKV, l, 3 * w);
+        float *DX = lay(a.DX, l, w);
+        // dg = da W_2^T, df1 = dg * GELU'(f1)
+        lin<true, 3>(prof, st, KC_L_LIN, DA, w, pl + a.fo[F_W2], w, M, f, w, nullptr, nullptr, lay(a.F1, l, f), DF1, nullptr);
+        // dtn = df1 W_1^T
+        lin<true, 4>(prof, st, KC_L_LIN, DF1, f, pl + a.fo[F_W1], f, M, w, f, nullptr, nullptr, nullptr, F(a.DTN), nullptr);
+        LnBwdArgs b2{F(a.DTN), lay(a.T, l, w), lay(a.st2, l, 2), pl + a.fo[F_G2], DA, DT,
+                     F(a.ln2p) + (int64_t)l * nblk * 2 * w, nullptr, nullptr, nullptr, nullptr, nullptr, M, w};
+        LAD_LAUNCH(prof, st, KC_L_ROW, (k_lln_bwd<false>), dim3(cdivi(M, kLnRows)), dim3(256), 0, st, b2);
+        // do = dt W_o^T
+        lin<true, 4>(prof, st, KC_L_LIN, DT, w, pl + a.fo[F_WO], w, M, w, w, nullptr, nullptr, nullptr, F(a.DO_), nullptr);
+        AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), F(a.DO_), DQKV, w,
+                    a.nh, (int)(Mm / a.Bmax), scale};
+        LAD_TRY(attn(a.dh, true, at, B, st, prof));
+        // dxn = dqkv W_qkv^T
+        lin<true, 4>(prof, st, KC_L_LIN, DQKV, 3 * w, pl + a.fo[F_WQKV], 3 * w, M, w, 3 * w, nullptr, nullptr, nullptr,
+                     F(a.DXN), nullptr);
+        LnBwdArgs b1{F(a.DXN), lay(a.X, l, w), lay(a.st1, l, 2), pl + a.fo[F_G1], DT, DX,
+                     F(a.ln1p) + (int64_t)l * nblk * 2 * w, lay(a.U, l, w), l ? lay(a.A, l - 1, w) : nullptr,
+                     pl + a.fo[F_LAM], l ? lay(a.DA, l - 1, w) : nullptr, F(a.dlamp) + (int64_t)l * nblk, M, w};
+        LAD_LAUNCH(prof, st, KC_L_ROW, (k_lln_bwd<true>), dim3(cdivi(M, kLnRows)), dim3(256), 0, st, b1);
+    }
+    // token contractions: splits planned for the largest batch, the rows of this batch dealt over them
+    const int rps = cdivi(cdivi(M, a.splits), 64) * 64;
+    const int splits = cdivi(M, rps);
+    WgArgs wg;
+    wg.cache = cache; wg.map = map;
+    wg.XN = F(a.XN); wg.DQKV = F(a.DQKV); wg.O = F(a.O); wg.DT = F(a.DT); wg.TN = F(a.TN); wg.DF1 = F(a.DF1);
+    wg.G = F(a.G); wg.DA = F(a.DA); wg.DX = F(a.DX);
+    wg.part = F(a.part); wg.Mmax = Mm; wg.PLb = a.PLb; wg.LP = (int64_t)L * a.PLb;
+    for (int i = 0; i <= kFields; ++i) wg.fo[i] = a.fo[i];
+    wg.L = L; wg.d = d; wg.w = w; wg.f = f; wg.rows_per_split = rps; wg.items_per_layer = a.items_per_layer;
+    for (int t = 0; t < 5; ++t) wg.tiles_j[t] = a.tiles[t][1];
+    for (int t = 0; t < 6; ++t) wg.item0[t] = a.item0[t];
+    LAD_LAUNCH(prof, st, KC_L_WGRAD, (k_lwgrad<SRC>), dim3(splits * L * a.items_per_layer), dim3(256), 0, st, wg);
+    RedArgs rd;
+    rd.part = F(a.part); rd.ln1p = F(a.ln1p); rd.ln2p = F(a.ln2p); rd.dlamp = F(a.dlamp); rd.params = params;
+    rd.grads = grads; rd.PLb = a.PLb; rd.LP = (int64_t)L * a.PLb;
+    for (int i = 0; i <= kFields; ++i) rd.fo[i] = a.fo[i];
+    rd.L = L; rd.w = w; rd.splits = splits; rd.nblk = nblk;
+    LAD_LAUNCH(prof, st, KC_L_REDUCE, k_lreduce, dim3(cdivi(rd.LP, 256)), dim3(256), 0, st, rd);
+    return hipGetLastError();
+}
+
+pac_status ladder_common(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B, const int32_t *labels,
+                         int32_t heads, const float *params, void *workspace, int64_t workspace_bytes, float *loss_out,
+                         float *logits_out, float *grads, void *hip_stream, Lad &a)
+{
+    if (!ctx || !cache || !sample_ids || !labels || !params || !workspace || !loss_out) return PAC_ERR_NULL;
+    auto al = [](const void *p, uintptr_t n) { return (reinterpret_cast<uintptr_t>(p) & (n - 1)) == 0; };
+    if (!al(cache, 256) || !al(workspace, 256) || !al(params, 16) || !al(labels, 4) || !al(loss_out, 4) ||
+        (logits_out && !al(logits_out, 4)) || (grads && !al(grads, 16)))
+        return PAC_ERR_ALIGN;
+    if (!lad_plan(ctx->D, heads, a)) return PAC_ERR_UNSUPPORTED;
+    if (workspace_bytes < a.total) return PAC_ERR_WORKSPACE;
+    BatchMeta meta;
+    pac_status s = (pac_status)pac_ctx_build_meta(ctx, sample_ids, B, meta);
+    if (s != PAC_OK) return s;
+    (void)hipGetLastError();
+    Profiler *prof = ctx->prof.on ? &ctx->prof : nullptr;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    hipError_t e = a.cache_f32 ? run_ladder<float>(a, meta, cache, labels, params, ws, loss_out, logits_out, grads, st, prof)
+                               : run_ladder<bf16_t>(a, meta, cache, labels, params, ws, loss_out, logits_out, grads, st, prof);
+    return e == hipSuccess ? PAC_OK : PAC_ERR_DEVICE;
+}
+
+} // namespace
+} // namespace pac
+
+using namespace pac;
+
+extern "C" {
+
+int64_t pac_ladder_param_count(const pac_ctx *ctx)
+{
+    if (!ctx) return -1;
+    Lad a;
+    return lad_shapes(ctx->D, a) ? a.P : -1;
+}
+
+int64_t pac_ladder_workspace_bytes(const pac_ctx *ctx, int32_t heads)
+{
+    if (!ctx) return -1;
+    Lad a;
+    return lad_plan(ctx->D, heads, a) ? a.total : -1;
+}
+
+pac_status pac_ladder_loss_grad(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B,
+                                const int32_t *labels, int32_t heads, const float *params, void *workspace,
+                                int64_t workspace_bytes, float *loss_out, float *logits_out, float *grads_out,
+                                void *hip_stream)
+{
+    Lad a;
+    return ladder_common(ctx, cache, sample_ids, B, labels, heads, params, workspace, workspace_bytes, loss_out, logits_out,
+                         grads_out, hip_stream, a);
+}
+
+pac_status pac_ladder_step(pac_ctx *ctx, const void *cache, const int64_t *sample_ids, int32_t B, const int32_t *labels,
+                           int32_t heads, float *params, float *m, float *v, int64_t *step, const pac_adamw *hp,
+                           void *workspace, int64_t workspace_bytes, float *loss_out, float *grads_out, void *hip_stream)
+{
+    if (!m || !v || !step || !hp) return PAC_ERR_NULL;
+    if (*step < 0) return PAC_ERR_RANGE;
+    if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->eps >= 0.f) ||
+        !(hp->lr >= 0.f) || !(hp->weight_decay >= 0.f))
+        return PAC_ERR_RANGE;
+    Lad a;
+    if (!ctx) return PAC_ERR_NULL;
+    if (!lad_plan(ctx->D, heads, a)) return PAC_ERR_UNSUPPORTED;
+    float *grads = grads_out ? grads_out : (workspace ? reinterpret_cast<float *>(static_cast<char *>(workspace) + a.grads) : nullptr);
+    pac_status s = ladder_common(ctx, cache, sample_ids, B, labels, heads, params, workspace, workspace_bytes, loss_out,
+                                 nullptr, grads, hip_stream, a);
+    if (s != PAC_OK) return s;
+    const int64_t t = *step + 1;
+    LAdamArgs aa;
+    aa.p = params; aa.m = m; aa.v = v; aa.g = grads;
+    aa.P = a.P; aa.PLb = a.PLb; aa.LP = (int64_t)a.L * a.PLb; aa.oWup = a.oWup; aa.ocup = a.ocup; aa.oWcls = a.oWcls;
+    aa.occls = a.occls;
+    for (int i = 0; i <= kFields; ++i) aa.fo[i] = a.fo[i];
+    aa.h.lr = hp->lr; aa.h.beta1 = hp->beta1; aa.h.beta2 = hp->beta2; aa.h.eps = hp->eps; aa.h.wd = hp->weight_decay;
+    aa.h.bc1 = (float)(1.0 - pow((double)hp->beta1, (double)t));
+    aa.h.bc2 = (float)(1.0 - pow((double)hp->beta2, (double)t));
+    int blocks = (int)((a.P + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    Profiler *prof = ctx->prof.on ? &ctx->prof : nullptr;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    LAD_LAUNCH(prof, st, KC_ADAMW, k_ladamw, dim3(blocks), dim3(256), 0, st, aa);
+    if (hipGetLastError() != hipSuccess) return PAC_ERR_DEVICE;
+    *step = t;
+    return PAC_OK;
+}
+
+} // extern "C"

@@ -94,6 +94,36 @@ class Session:
         return raw.view(np.uint16 if es == 2 else np.float32).reshape(self.w.L, ln, self.w.d)
 
 
+class LadderSession(Session):
+    """The same cache trained through the paper's default architecture (include/pac_ladder.h): own parameter vector
+    and workspace, the ladder's two calls."""
+
+    def __init__(self, w: Workload, heads: int, cache_samples: int | None = None, lens=None, device: str = "cuda:0"):
+        super().__init__(w, cache_samples=cache_samples, lens=lens, device=device)
+        self.heads = heads
+        self.P = pb.pac_ladder_param_count(self.ctx)
+        self.ws_bytes = pb.pac_ladder_workspace_bytes(self.ctx, heads)
+        if self.P <= 0 or self.ws_bytes <= 0:
+            raise ValueError("configuration not supported by the ladder path")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        self.params = torch.zeros(self.P, dtype=torch.float32, device=self.dev)
+        self.m = torch.zeros(self.P, dtype=torch.float32, device=self.dev)
+        self.v = torch.zeros(self.P, dtype=torch.float32, device=self.dev)
+        self.grads = torch.zeros(self.P, dtype=torch.float32, device=self.dev)
+
+    def loss_grad(self, sample_ids, labels_dev, want_grads: bool = True, want_logits: bool = True) -> None:
+        pb.pac_ladder_loss_grad(self.ctx, self.cache.data_ptr(), sample_ids, labels_dev.data_ptr(), self.heads,
+                                self.params.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self.loss.data_ptr(),
+                                self.logits.data_ptr() if want_logits else None,
+                                self.grads.data_ptr() if want_grads else None, _stream_handle())
+
+    def step(self, sample_ids, labels_dev, keep_grads: bool = True) -> None:
+        self.step_count = pb.pac_ladder_step(
+            self.ctx, self.cache.data_ptr(), sample_ids, labels_dev.data_ptr(), self.heads, self.params.data_ptr(),
+            self.m.data_ptr(), self.v.data_ptr(), self.step_count, self.hp, self.ws.data_ptr(), self.ws_bytes,
+            self.loss.data_ptr(), self.grads.data_ptr() if keep_grads else None, _stream_handle())
+
+
 class TieredSession(Session):
     """The same buffers with the cache in pinned host memory and two device windows: batch k + 1 is reloaded on a
     copy stream while batch k trains on the compute stream (events order the two; default stream priorities)."""
