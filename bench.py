@@ -344,6 +344,64 @@ def bench_host_tier(torch, steps=48, warmup=8, N=512):
             "final_loss": float(sess.loss.item())}
 
 
+def bench_ladder(torch, pb, steps=48, warmup=8, N=1024, heads=12):
+    """The paper's default architecture (the w-wide ladder with a reduced transformer layer per adapter, Sec. 4.1) on the
+    T5-Base-shaped cache: whole training steps, per-kernel-class durations, and the roofline of its two passes over the
+    cache slice (fp32 matrix instructions: 157.3 TFLOP/s peak; the cache stream itself against 8 TB/s)."""
+    import numpy as np
+    from paper_2408_10746_amd import inputs
+    from paper_2408_10746_amd.runtime import LadderSession
+    from oracle import ladder_oracle as lo
+    w = inputs.WORKLOADS["t5base"]
+    dev = torch.device("cuda:0")
+    sess = LadderSession(w, heads, cache_samples=N)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_DATA)
+    for s0 in range(0, N, w.B):
+        a = torch.randn((w.B, w.L, w.n_max, w.d), generator=gen, device=dev, dtype=torch.float32)
+        a = torch.nn.functional.layer_norm(a, (w.d,), eps=1e-5).contiguous()
+        sess.cache_fill(np.arange(s0, s0 + w.B), a)
+    torch.cuda.synchronize()
+    labels = torch.from_numpy(inputs.labels(w)).to(dev)
+    sess.set_params(lo.init_params(lo.LadderDims(w.L, w.d, w.r, heads, w.C), inputs.SEED_PARAMS))
+    plan = [np.arange(w.B) + w.B * (k % (N // w.B)) for k in range(warmup + steps)]
+    labs = [labels[torch.from_numpy(ids).to(dev)].contiguous() for ids in plan]
+    for k in range(warmup):
+        sess.step(plan[k], labs[k], keep_grads=False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(warmup, warmup + steps):
+        sess.step(plan[k], labs[k], keep_grads=False)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    final_loss = float(sess.loss.item())
+    prof_steps = min(steps, 16)
+    pb.pac_profile_begin(sess.ctx)
+    for k in range(warmup, warmup + prof_steps):
+        sess.step(plan[k], labs[k], keep_grads=False)
+    prof = pb.pac_profile_end(sess.ctx)
+    M, wd = w.B * w.n_max, w.r
+    slab = w.L * M * w.d * 2
+    # per token and layer: down-projection 2 d w, qkv 6 w^2, attention 4 n w, output projection 2 w^2, FFN 16 w^2;
+    # the reverse pass costs twice the forward
+    fwd_flops = w.L * M * (2.0 * w.d * wd + 24.0 * wd * wd + 4.0 * w.n_max * wd)
+    act_bytes = w.L * M * wd * 4
+    passes = {}
+    for cls, abytes, aflops in (("l_down", slab + act_bytes, 2.0 * M * w.d * wd * w.L),
+                                ("l_wgrad", slab + 13 * act_bytes, 2.0 * M * w.L * (w.d * wd + 12.0 * wd * wd))):
+        if cls in prof:
+            t = prof[cls][0] * 1e-3 / prof_steps
+            passes[cls] = {"us": t * 1e6, "hbm_GBs": abytes / t / 1e9, "hbm_frac": abytes / t / 1e9 / HBM_PEAK_GBS,
+                           "fp32_mfma_TFLOPs": aflops / t / 1e12, "fp32_mfma_frac": aflops / t / 1e12 / 157.3}
+    sess.close()
+    return {"workload": f"ladder on t5base: L={w.L} d={w.d} seq={w.n_max} B={w.B} w={wd} heads={heads} C={w.C}, "
+                        f"{N} samples resident ({sess.cache_bytes / 1e9:.2f} GB bf16 cache), fp32 arithmetic",
+            "ms_per_step": el * 1e3 / steps, "samples_per_s": steps * w.B / el, "final_loss": final_loss,
+            "algorithmic_GFLOP": 3.0 * fwd_flops / 1e9, "cache_passes": passes,
+            "kernel_ms_per_step": {c: prof[c][0] / prof_steps for c in prof},
+            "launches_per_step": {c: prof[c][1] / prof_steps for c in prof}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -353,6 +411,7 @@ def main():
     ap.add_argument("--samples", type=int, default=0, help="resident samples (0 = the workload's N)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other configurations (headline workload only)")
+    ap.add_argument("--only", default="", help="run one of the extra legs alone and print its JSON (ladder)")
     ap.add_argument("--flags", type=int, default=0, help="pac_config flags (1 per-layer kernels, 2 split launches)")
     ap.add_argument("--cpu-samples", type=int, default=4, help="samples per oracle step")
     ap.add_argument("--cpu-seconds", type=float, default=8.0, help="CPU time per leg of the oracle baseline")
@@ -365,6 +424,10 @@ def main():
     import torch
     from paper_2408_10746_amd import inputs
     torch.cuda.set_device(0)
+    if args.only == "ladder":
+        from paper_2408_10746_amd import binding as pb
+        print(json.dumps(bench_ladder(torch, pb)))
+        return
 
     w = inputs.WORKLOADS[args.workload]
     ncpu = 0 if args.no_cpu_baseline else min(args.cpu_samples, w.B)
@@ -411,6 +474,12 @@ def main():
             extras["first_epoch_storage"] = bench_first_epoch_storage(torch, pb)
         except Exception as ex:
             extras["first_epoch_storage"] = {"error": f"{type(ex).__name__}: {ex}"}
+        gc.collect()
+        torch.cuda.empty_cache()
+        try:
+            extras["ladder"] = bench_ladder(torch, pb)
+        except Exception as ex:
+            extras["ladder"] = {"error": f"{type(ex).__name__}: {ex}"}
         gc.collect()
         torch.cuda.empty_cache()
         try:

@@ -45,7 +45,7 @@ inline int cdivi(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 using TL = Tile<2, 2, 1, 1, 4>; // 64 x 64 workgroup tile, 64 fp32 values of K per step
 constexpr int kTileLds = tile_lds_bytes<float, TL>();
-constexpr int kLnRows = 32;    // token rows per workgroup of the LayerNorm reverse kernels
+constexpr int kLnRows = 16;    // token rows per workgroup of the LayerNorm reverse kernels (four per wavefront)
 constexpr int kFields = 15;    // tensors of one layer block
 
 // Shapes, parameter offsets (elements) and workspace offsets (bytes).
@@ -423,47 +423,78 @@ struct LnBwdArgs {
     float *dlam_part; // [nblk]
     int M, w;
 };
+template <int N> __device__ __forceinline__ void wave_sum_n(float (&v)[N])
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+        for (int k = 0; k < N; ++k) v[k] += __shfl_xor(v[k], o, 64);
+}
+
 template <bool MIX> __global__ __launch_bounds__(256) void k_lln_bwd(LnBwdArgs a)
 {
     __shared__ float red[4][2][256];
     __shared__ float redl[4];
+    constexpr int RB = 4; // rows a wavefront works on at once (independent loads and exchanges in flight)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float lam = MIX ? *a.lam : 0.f;
     float dg[4] = {0.f, 0.f, 0.f, 0.f}, dh[4] = {0.f, 0.f, 0.f, 0.f}, dlam = 0.f;
     float g[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) g[q] = lane + 64 * q < a.w ? a.g[lane + 64 * q] : 0.f;
-    for (int rr = 0; rr < kLnRows / 4; ++rr) {
-        const int row = blockIdx.x * kLnRows + wave * (kLnRows / 4) + rr;
-        if (row >= a.M) break;
-        const float mu = a.stats[2 * row], rstd = a.stats[2 * row + 1];
-        float xh[4], dxh[4], s1 = 0.f, s2 = 0.f;
+    for (int rr = 0; rr < kLnRows / 4; rr += RB) {
+        const int row0 = blockIdx.x * kLnRows + wave * (kLnRows / 4) + rr;
+        if (row0 >= a.M) break;
+        float xh[RB][4], dxh[RB][4], rs[RB][4], dyv[RB][4], sums[2 * RB];
+        float mu[RB], rstd[RB];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int c = lane + 64 * q;
-            xh[q] = dxh[q] = 0.f;
-            if (c < a.w) {
-                const int64_t o = (int64_t)row * a.w + c;
-                const float dy = a.dy[o];
-                xh[q] = (a.x[o] - mu) * rstd;
-                dxh[q] = dy * g[q];
-                dg[q] += dy * xh[q];
-                dh[q] += dy;
-                s1 += dxh[q];
-                s2 += dxh[q] * xh[q];
+        for (int r = 0; r < RB; ++r) {
+            const int row = min(row0 + r, a.M - 1);
+            mu[r] = a.stats[2 * row];
+            rstd[r] = a.stats[2 * row + 1];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = lane + 64 * q;
+                const int64_t o = (int64_t)row * a.w + min(c, a.w - 1);
+                dyv[r][q] = a.dy[o];
+                xh[r][q] = a.x[o];
+                rs[r][q] = a.resid[o];
             }
         }
-        const float m1 = wave_sum(s1) / (float)a.w, m2 = wave_sum(s2) / (float)a.w;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int c = lane + 64 * q;
-            if (c < a.w) {
-                const int64_t o = (int64_t)row * a.w + c;
-                const float dx = a.resid[o] + rstd * (dxh[q] - m1 - xh[q] * m2);
-                a.dx[o] = dx;
-                if (MIX) {
-                    dlam += dx * (a.u[o] - (a.a_prev ? a.a_prev[o] : 0.f));
-                    if (a.da_prev) a.da_prev[o] = (1.f - lam) * dx;
+        for (int r = 0; r < RB; ++r) {
+            const bool rowok = row0 + r < a.M;
+            float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool ok = rowok && lane + 64 * q < a.w;
+                const float dy = ok ? dyv[r][q] : 0.f;
+                xh[r][q] = ok ? (xh[r][q] - mu[r]) * rstd[r] : 0.f;
+                dxh[r][q] = dy * g[q];
+                dg[q] += dy * xh[r][q];
+                dh[q] += dy;
+                s1 += dxh[r][q];
+                s2 += dxh[r][q] * xh[r][q];
+            }
+            sums[2 * r] = s1;
+            sums[2 * r + 1] = s2;
+        }
+        wave_sum_n(sums);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            const int row = row0 + r;
+            const float m1 = sums[2 * r] / (float)a.w, m2 = sums[2 * r + 1] / (float)a.w;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = lane + 64 * q;
+                if (row < a.M && c < a.w) {
+                    const int64_t o = (int64_t)row * a.w + c;
+                    const float dx = rs[r][q] + rstd[r] * (dxh[r][q] - m1 - xh[r][q] * m2);
+                    a.dx[o] = dx;
+                    if (MIX) {
+                        dlam += dx * (a.u[o] - (a.a_prev ? a.a_prev[o] : 0.f));
+                        if (a.da_prev) a.da_prev[o] = (1.f - lam) * dx;
+                    }
                 }
             }
         }
@@ -496,7 +527,21 @@ struct AttnArgs {
     float *dQKV;     // reverse: [M][3w]
     int w, nh, n_max;
     float scale;
+    int tpr; // lanes per row: a power of two, 1 .. 8
 };
+// A row is shared by `tpr` neighbouring lanes (a power of two, chosen so that the sample's rows fill the
+// workgroup); each takes every tpr-th key (query) and the partial results are combined with lane exchanges.
+__device__ __forceinline__ float grp_sum(float v, int tpr)
+{
+    for (int o = 1; o < tpr; o <<= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float grp_max(float v, int tpr)
+{
+    for (int o = 1; o < tpr; o <<= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
 template <int DH> __global__ __launch_bounds__(256) void k_lattn_fwd(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) float lsm[];
@@ -511,35 +556,42 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_fwd(AttnArgs a)
         vs[idx] = row[2 * a.w];
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += 256) {
+    const int tpr = a.tpr, part = threadIdx.x % tpr, rpp = 256 / tpr;
+    // (every lane of a group runs the same number of rounds: the exchanges below need all of them)
+    for (int i0 = 0; i0 < n; i0 += rpp) {
+        const int i = i0 + (int)threadIdx.x / tpr;
+        const bool live = i < n;
+        const int ic = live ? i : n - 1;
         float q[DH];
-        const float *qp = a.QKV + (int64_t)(m0 + i) * w3 + h * DH;
+        const float *qp = a.QKV + (int64_t)(m0 + ic) * w3 + h * DH;
 #pragma unroll
         for (int c = 0; c < DH; ++c) q[c] = qp[c] * a.scale;
-        float mx = -INFINITY;
-        for (int j = 0; j < n; ++j) {
-            float sc = 0.f;
-#pragma unroll
-            for (int c = 0; c < DH; ++c) sc += q[c] * ks[j * DH + c];
-            mx = fmaxf(mx, sc);
-        }
-        float l = 0.f, acc[DH];
+        // running maximum, sum and weighted values over this lane's keys
+        float mx = -INFINITY, l = 0.f, acc[DH];
 #pragma unroll
         for (int c = 0; c < DH; ++c) acc[c] = 0.f;
-        for (int j = 0; j < n; ++j) {
+        for (int j = part; j < n; j += tpr) {
             float sc = 0.f;
 #pragma unroll
             for (int c = 0; c < DH; ++c) sc += q[c] * ks[j * DH + c];
-            const float p = expf(sc - mx);
-            l += p;
+            const float mn = fmaxf(mx, sc);
+            const float corr = expf(mx - mn), p = expf(sc - mn);
+            l = l * corr + p;
 #pragma unroll
-            for (int c = 0; c < DH; ++c) acc[c] += p * vs[j * DH + c];
+            for (int c = 0; c < DH; ++c) acc[c] = acc[c] * corr + p * vs[j * DH + c];
+            mx = mn;
         }
+        const float mall = grp_max(mx, tpr);
+        const float corr = mx == -INFINITY ? 0.f : expf(mx - mall);
+        l = grp_sum(l * corr, tpr);
         const float inv = 1.f / l;
-        float *op = a.O + (int64_t)(m0 + i) * a.w + h * DH;
+        float *op = a.O + (int64_t)(m0 + ic) * a.w + h * DH;
 #pragma unroll
-        for (int c = 0; c < DH; ++c) op[c] = acc[c] * inv;
-        a.LSE[(int64_t)(m0 + i) * a.nh + h] = mx + logf(l);
+        for (int c = 0; c < DH; ++c) {
+            const float v = grp_sum(acc[c] * corr, tpr) * inv;
+            if (live && part == 0) op[c] = v;
+        }
+        if (live && part == 0) a.LSE[(int64_t)(m0 + i) * a.nh + h] = mall + logf(l);
     }
 }
 
@@ -569,13 +621,17 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_bwd(AttnArgs a)
         Dr[i] = D;
     }
     __syncthreads();
+    const int tpr = a.tpr, part = threadIdx.x % tpr, rpp = 256 / tpr;
     // phase 1, query row i: dq_i = scale * sum_j P_ij (dO_i . v_j - D_i) k_j
-    for (int i = threadIdx.x; i < n; i += 256) {
+    for (int i0 = 0; i0 < n; i0 += rpp) {
+        const int i = i0 + (int)threadIdx.x / tpr;
+        const bool live = i < n;
+        const int ic = live ? i : n - 1;
         float q[DH], go[DH], dq[DH];
 #pragma unroll
-        for (int c = 0; c < DH; ++c) { q[c] = qs[i * DH + c] * a.scale; go[c] = dos[i * DH + c]; dq[c] = 0.f; }
-        const float li = lse[i], Di = Dr[i];
-        for (int j = 0; j < n; ++j) {
+        for (int c = 0; c < DH; ++c) { q[c] = qs[ic * DH + c] * a.scale; go[c] = dos[ic * DH + c]; dq[c] = 0.f; }
+        const float li = lse[ic], Di = Dr[ic];
+        for (int j = part; j < n; j += tpr) {
             float sc = 0.f, dpv = 0.f;
 #pragma unroll
             for (int c = 0; c < DH; ++c) { sc += q[c] * ks[j * DH + c]; dpv += go[c] * vs[j * DH + c]; }
@@ -583,16 +639,22 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_bwd(AttnArgs a)
 #pragma unroll
             for (int c = 0; c < DH; ++c) dq[c] += ds * ks[j * DH + c];
         }
-        float *out = a.dQKV + (int64_t)(m0 + i) * w3 + h * DH;
+        float *out = a.dQKV + (int64_t)(m0 + ic) * w3 + h * DH;
 #pragma unroll
-        for (int c = 0; c < DH; ++c) out[c] = dq[c] * a.scale;
+        for (int c = 0; c < DH; ++c) {
+            const float v = grp_sum(dq[c], tpr) * a.scale;
+            if (live && part == 0) out[c] = v;
+        }
     }
     // phase 2, key row j: dv_j = sum_i P_ij dO_i ; dk_j = scale * sum_i P_ij (dO_i . v_j - D_i) q_i
-    for (int j = threadIdx.x; j < n; j += 256) {
+    for (int j0 = 0; j0 < n; j0 += rpp) {
+        const int j = j0 + (int)threadIdx.x / tpr;
+        const bool live = j < n;
+        const int jc = live ? j : n - 1;
         float k[DH], v[DH], dk[DH], dv[DH];
 #pragma unroll
-        for (int c = 0; c < DH; ++c) { k[c] = ks[j * DH + c] * a.scale; v[c] = vs[j * DH + c]; dk[c] = 0.f; dv[c] = 0.f; }
-        for (int i = 0; i < n; ++i) {
+        for (int c = 0; c < DH; ++c) { k[c] = ks[jc * DH + c] * a.scale; v[c] = vs[jc * DH + c]; dk[c] = 0.f; dv[c] = 0.f; }
+        for (int i = part; i < n; i += tpr) {
             float sc = 0.f, dpv = 0.f;
 #pragma unroll
             for (int c = 0; c < DH; ++c) { sc += qs[i * DH + c] * k[c]; dpv += dos[i * DH + c] * v[c]; }
@@ -601,9 +663,12 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_bwd(AttnArgs a)
 #pragma unroll
             for (int c = 0; c < DH; ++c) { dv[c] += p * dos[i * DH + c]; dk[c] += ds * qs[i * DH + c]; }
         }
-        float *out = a.dQKV + (int64_t)(m0 + j) * w3 + h * DH;
+        float *out = a.dQKV + (int64_t)(m0 + jc) * w3 + h * DH;
 #pragma unroll
-        for (int c = 0; c < DH; ++c) { out[a.w + c] = dk[c] * a.scale; out[2 * a.w + c] = dv[c]; }
+        for (int c = 0; c < DH; ++c) {
+            const float gk = grp_sum(dk[c], tpr) * a.scale, gv = grp_sum(dv[c], tpr);
+            if (live && part == 0) { out[a.w + c] = gk; out[2 * a.w + c] = gv; }
+        }
     }
 }
 
@@ -623,44 +688,80 @@ struct HeadArgs {
     int B, d, w, C, last_layer;
 };
 
-// token means of b_L (blockIdx.y < column blocks of d) and of a_L (the last blockIdx.y)
+// token means of b_L (blockIdx.y < column blocks of d) and of a_L (the last blockIdx.y): a lane owns four columns,
+// the four wavefronts take every fourth token and their sums are combined in wavefront order
 template <typename SRC> __global__ __launch_bounds__(256) void k_lpool(HeadArgs a)
 {
+    __shared__ float red[4][256];
     const int s = blockIdx.x, m0 = a.samp_start[s], len = a.samp_len[s];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nbd = (a.d + 255) / 256;
-    if ((int)blockIdx.y < nbd) {
-        const int j = blockIdx.y * 256 + threadIdx.x;
-        if (j >= a.d) return;
-        const SRC *cache = static_cast<const SRC *>(a.cache);
-        float acc = 0.f;
-        for (int t = 0; t < len; ++t) {
-            const int m = m0 + t;
-            acc += to_f32(cache[a.map.rowoff[m] + (int64_t)a.last_layer * a.map.rowstride[m] + j]);
+    const bool from_cache = (int)blockIdx.y < nbd;
+    const int ncols = from_cache ? a.d : a.w;
+    const int c0 = (from_cache ? blockIdx.y * 256 : 0) + lane * 4;
+    const bool live = c0 < ncols; // (d and w are multiples of 4)
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (live) {
+        if (from_cache) {
+            const SRC *cache = static_cast<const SRC *>(a.cache);
+            for (int t = wave; t < len; t += 4) {
+                const int m = m0 + t;
+                float f[4];
+                Raw4<SRC>::widen(*reinterpret_cast<const typename Raw4<SRC>::type *>(
+                                     cache + a.map.rowoff[m] + (int64_t)a.last_layer * a.map.rowstride[m] + c0), f);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += f[e];
+            }
+        } else {
+            for (int t = wave; t < len; t += 4) {
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(a.A_last + (int64_t)(m0 + t) * a.w + c0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += v[e];
+            }
         }
-        a.bmean[(int64_t)s * a.d + j] = acc / (float)len;
-    } else {
-        const int c = threadIdx.x;
-        if (c >= a.w) return;
-        float acc = 0.f;
-        for (int t = 0; t < len; ++t) acc += a.A_last[(int64_t)(m0 + t) * a.w + c];
-        a.abar[(int64_t)s * a.w + c] = acc / (float)len;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[wave][lane * 4 + e] = acc[e];
+    __syncthreads();
+    const int c = (from_cache ? blockIdx.y * 256 : 0) + threadIdx.x;
+    if (c < ncols) {
+        const float tot = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+        (from_cache ? a.bmean + (int64_t)s * a.d : a.abar + (int64_t)s * a.w)[c] = tot / (float)len;
     }
 }
 
-// one workgroup per sample: pooled, logits, loss term, dz
+// pooled[s][j] = mean_t b_L[t][j] + c_up[j] + sum_c mean_t a_L[t][c] W_up[c][j]   (grid: sample x column block)
+__global__ __launch_bounds__(256) void k_lpooled(HeadArgs a)
+{
+    __shared__ float ab[256];
+    const int s = blockIdx.x, j = blockIdx.y * 256 + threadIdx.x;
+    if ((int)threadIdx.x < a.w) ab[threadIdx.x] = a.abar[(int64_t)s * a.w + threadIdx.x];
+    __syncthreads();
+    if (j >= a.d) return;
+    const float *Wup = a.params + a.oWup + j;
+    float p = a.bmean[(int64_t)s * a.d + j] + a.params[a.ocup + j];
+    for (int c0 = 0; c0 < a.w; c0 += 8) { // (w is a multiple of 32)
+        float wv[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) wv[k] = Wup[(int64_t)(c0 + k) * a.d];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) p += ab[c0 + k] * wv[k];
+    }
+    a.pooled[(int64_t)s * a.d + j] = p;
+}
+
+// one workgroup per sample: logits, loss term, dz
 __global__ __launch_bounds__(256) void k_lhead_a(HeadArgs a)
 {
     __shared__ float zpart[256][kMaxClasses];
     __shared__ float z[kMaxClasses];
     const int s = blockIdx.x, t = threadIdx.x;
-    const float *Wup = a.params + a.oWup, *cup = a.params + a.ocup, *Wcls = a.params + a.oWcls, *ccls = a.params + a.occls;
+    const float *Wcls = a.params + a.oWcls, *ccls = a.params + a.occls;
     float zc[kMaxClasses];
 #pragma unroll
     for (int c = 0; c < kMaxClasses; ++c) zc[c] = 0.f;
     for (int j = t; j < a.d; j += 256) {
-        float p = a.bmean[(int64_t)s * a.d + j] + cup[j];
-        for (int c = 0; c < a.w; ++c) p += a.abar[(int64_t)s * a.w + c] * Wup[(int64_t)c * a.d + j];
-        a.pooled[(int64_t)s * a.d + j] = p;
+        const float p = a.pooled[(int64_t)s * a.d + j];
 #pragma unroll
         for (int c = 0; c < kMaxClasses; ++c)
             if (c < a.C) zc[c] += p * Wcls[(int64_t)j * a.C + c];
@@ -690,19 +791,28 @@ __global__ __launch_bounds__(256) void k_lhead_a(HeadArgs a)
     }
 }
 
-// thread per hidden column j: dp[s][j], dc_up[j], dW_cls[j][.], dW_up[.][j]; block 0 also the loss and dc_cls
+// thread per hidden column j (blockIdx.x) and a chunk of kUpChunk rows of W_up (blockIdx.y): dW_up[c][j] for the
+// chunk; the first chunk's blocks also write dp[s][j], dc_up[j], dW_cls[j][.]; block (0, 0) the loss and dc_cls
+constexpr int kUpChunk = 8;
 __global__ __launch_bounds__(256) void k_lhead_b(HeadArgs a)
 {
     __shared__ float dzs[kMaxBatch * kMaxClasses];
+    __shared__ float ab[kMaxBatch * kUpChunk];
+    const bool first = blockIdx.y == 0;
+    const int cbase = blockIdx.y * kUpChunk;
     for (int q = threadIdx.x; q < a.B * a.C; q += 256) dzs[q] = a.dz[q];
+    for (int q = threadIdx.x; q < a.B * kUpChunk; q += 256) {
+        const int sidx = q / kUpChunk, c = cbase + q % kUpChunk;
+        ab[q] = c < a.w ? a.abar[(int64_t)sidx * a.w + c] : 0.f;
+    }
     __syncthreads();
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (first && blockIdx.x == 0 && threadIdx.x == 0) {
         float tot = 0.f;
         for (int s = 0; s < a.B; ++s) tot += a.lossp[s];
         *a.loss_out = tot / (float)a.B;
     }
     if (!a.grads) return;
-    if (blockIdx.x == 0 && (int)threadIdx.x < a.C) {
+    if (first && blockIdx.x == 0 && (int)threadIdx.x < a.C) {
         float acc = 0.f;
         for (int s = 0; s < a.B; ++s) acc += dzs[s * a.C + threadIdx.x];
         a.grads[a.occls + threadIdx.x] = acc;
@@ -713,43 +823,58 @@ __global__ __launch_bounds__(256) void k_lhead_b(HeadArgs a)
     float wc[kMaxClasses], dwc[kMaxClasses];
 #pragma unroll
     for (int c = 0; c < kMaxClasses; ++c) { wc[c] = c < a.C ? Wcls[c] : 0.f; dwc[c] = 0.f; }
-    float dcup = 0.f;
+    float dcup = 0.f, up[kUpChunk];
+#pragma unroll
+    for (int c = 0; c < kUpChunk; ++c) up[c] = 0.f;
     for (int s = 0; s < a.B; ++s) {
         float dp = 0.f;
-        const float pl = a.pooled[(int64_t)s * a.d + j];
 #pragma unroll
         for (int c = 0; c < kMaxClasses; ++c)
-            if (c < a.C) { dp += dzs[s * a.C + c] * wc[c]; dwc[c] += pl * dzs[s * a.C + c]; }
-        a.dp[(int64_t)s * a.d + j] = dp;
-        dcup += dp;
-    }
-    a.grads[a.ocup + j] = dcup;
+            if (c < a.C) dp += dzs[s * a.C + c] * wc[c];
 #pragma unroll
-    for (int c = 0; c < kMaxClasses; ++c)
-        if (c < a.C) a.grads[a.oWcls + (int64_t)j * a.C + c] = dwc[c];
-    for (int c = 0; c < a.w; ++c) {
-        float acc = 0.f;
-        for (int s = 0; s < a.B; ++s) acc += a.abar[(int64_t)s * a.w + c] * a.dp[(int64_t)s * a.d + j];
-        a.grads[a.oWup + (int64_t)c * a.d + j] = acc;
+        for (int c = 0; c < kUpChunk; ++c) up[c] += ab[s * kUpChunk + c] * dp;
+        if (first) {
+            const float pl = a.pooled[(int64_t)s * a.d + j];
+#pragma unroll
+            for (int c = 0; c < kMaxClasses; ++c)
+                if (c < a.C) dwc[c] += pl * dzs[s * a.C + c];
+            a.dp[(int64_t)s * a.d + j] = dp;
+            dcup += dp;
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < kUpChunk; ++c)
+        if (cbase + c < a.w) a.grads[a.oWup + (int64_t)(cbase + c) * a.d + j] = up[c];
+    if (first) {
+        a.grads[a.ocup + j] = dcup;
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c)
+            if (c < a.C) a.grads[a.oWcls + (int64_t)j * a.C + c] = dwc[c];
     }
 }
 
-// one workgroup per sample: da_L[s][c] = (dp_s . W_up[c][:]) / len_s, written to every token row of the sample
+// da_L[s][c] = (dp_s . W_up[c][:]) / len_s for 16 columns c (grid: sample x column chunk), written to every token
+// row of the sample
 __global__ __launch_bounds__(256) void k_lhead_c(HeadArgs a)
 {
-    __shared__ float da[256];
-    const int s = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ float da[16];
+    const int s = blockIdx.x, cb = blockIdx.y * 16, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m0 = a.samp_start[s], len = a.samp_len[s];
     const float *Wup = a.params + a.oWup;
-    for (int c = wave; c < a.w; c += 4) {
-        float acc = 0.f;
-        for (int j = lane; j < a.d; j += 64) acc += a.dp[(int64_t)s * a.d + j] * Wup[(int64_t)c * a.d + j];
-        acc = wave_sum(acc);
-        if (lane == 0) da[c] = acc / (float)len;
+    const float *dp = a.dp + (int64_t)s * a.d;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int j = lane; j < a.d; j += 64) {
+        const float g = dp[j];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] += g * Wup[(int64_t)min(cb + wave * 4 + k, a.w - 1) * a.d + j];
     }
+    wave_sum_n(acc);
+    if (lane < 4) da[wave * 4 + lane] = (lane == 0 ? acc[0] : lane == 1 ? acc[1] : lane == 2 ? acc[2] : acc[3]) / (float)len;
     __syncthreads();
-    for (int idx = threadIdx.x; idx < len * a.w; idx += 256)
-        a.DA_last[(int64_t)(m0 + idx / a.w) * a.w + idx % a.w] = da[idx % a.w];
+    for (int idx = threadIdx.x; idx < len * 16; idx += 256) {
+        const int c = cb + (idx & 15);
+        if (c < a.w) a.DA_last[(int64_t)(m0 + (idx >> 4)) * a.w + c] = da[idx & 15];
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -838,21 +963,40 @@ struct RedArgs {
 };
 __global__ __launch_bounds__(256) void k_lreduce(RedArgs a)
 {
+    const int eblocks = (int)((a.LP + 255) / 256);
+    if ((int)blockIdx.x >= eblocks) {
+        // norm gains / offsets and the gate: one wavefront per element sums the row-block partials (lanes take
+        // every 64th block, then a fixed exchange pattern: the same order on every run)
+        const int lane = threadIdx.x & 63;
+        const int task = ((int)blockIdx.x - eblocks) * 4 + (threadIdx.x >> 6);
+        const int per_layer = 4 * a.w + 1;
+        if (task >= a.L * per_layer) return;
+        const int l = task / per_layer, e = task % per_layer;
+        float acc = 0.f;
+        int64_t dst;
+        if (e == 4 * a.w) {
+            for (int k = lane; k < a.nblk; k += 64) acc += a.dlamp[(int64_t)l * a.nblk + k];
+            dst = a.fo[F_LAM];
+        } else {
+            const int which = e / a.w, c = e % a.w; // 0: ln1 gain, 1: ln1 offset, 2: ln2 gain, 3: ln2 offset
+            const float *p = (which < 2 ? a.ln1p : a.ln2p) + (int64_t)l * a.nblk * 2 * a.w + (which & 1) * a.w + c;
+            for (int k = lane; k < a.nblk; k += 64) acc += p[(int64_t)k * 2 * a.w];
+            dst = a.fo[which == 0 ? F_G1 : which == 1 ? F_H1 : which == 2 ? F_G2 : F_H2] + c;
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) a.grads[(int64_t)l * a.PLb + dst] = acc;
+        return;
+    }
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= a.LP) return;
     const int l = (int)(i / a.PLb);
     const int64_t o = i - (int64_t)l * a.PLb;
     int fld = 0;
     while (fld < kFields - 1 && o >= a.fo[fld + 1]) ++fld;
-    const int c = (int)(o - a.fo[fld]);
+    if (fld == F_G1 || fld == F_H1 || fld == F_G2 || fld == F_H2) return;
     float acc = 0.f;
-    if (fld == F_G1 || fld == F_H1 || fld == F_G2 || fld == F_H2) {
-        const float *p = ((fld == F_G1 || fld == F_H1) ? a.ln1p : a.ln2p) + (int64_t)l * a.nblk * 2 * a.w +
-                         ((fld == F_H1 || fld == F_H2) ? a.w : 0) + c;
-        for (int k = 0; k < a.nblk; ++k) acc += p[(int64_t)k * 2 * a.w];
-    } else if (fld == F_LAM) {
-        if (c == 0)
-            for (int k = 0; k < a.nblk; ++k) acc += a.dlamp[(int64_t)l * a.nblk + k];
+    if (fld == F_LAM) {
+        if (o == a.fo[F_LAM]) return;
     } else {
         for (int s = 0; s < a.splits; ++s) acc += a.part[(int64_t)s * a.LP + i];
         if (fld == F_WD || fld == F_CD) acc *= a.params[(int64_t)l * a.PLb + a.fo[F_LAM]]; // du = lambda dx
@@ -960,6 +1104,10 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
         LAD_LAUNCH(prof, st, KC_L_DOWN, (k_ldown<SRC>), dim3(cdivi(M, 64), cdivi(w, 64), L), dim3(256), 0, st, da);
     }
     const float scale = 1.f / sqrtf((float)a.dh);
+    int nlong = 1; // longest sample of the batch: lanes per attention row so that its rows fill a workgroup
+    for (int i = 0; i < B; ++i) nlong = meta.len[i] > nlong ? meta.len[i] : nlong;
+    int tpr = 1;
+    while (tpr < 8 && 2 * tpr * nlong <= 256) tpr *= 2;
     for (int l = 0; l < L; ++l) {
         const float *pl = params + (int64_t)l * a.PLb;
         LnFwdArgs n1{lay(a.U, l, w), l ? lay(a.A, l - 1, w) : nullptr, pl + a.fo[F_LAM], pl + a.fo[F_G1], pl + a.fo[F_H1],
@@ -968,7 +1116,7 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
         lin<false, 0>(prof, st, KC_L_LIN, lay(a.XN, l, w), w, pl + a.fo[F_WQKV], 3 * w, M, 3 * w, w, pl + a.fo[F_BQKV],
                       nullptr, nullptr, lay(a.QKV, l, 3 * w), nullptr);
         AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), nullptr, nullptr, w,
-                    a.nh, (int)(Mm / a.Bmax), scale};
+                    a.nh, (int)(Mm / a.Bmax), scale, tpr};
         LAD_TRY(attn(a.dh, false, at, B, st, prof));
         lin<false, 1>(prof, st, KC_L_LIN, lay(a.O, l, w), w, pl + a.fo[F_WO], w, M, w, w, pl + a.fo[F_BO], lay(a.X, l, w),
                       nullptr, lay(a.T, l, w), nullptr);
@@ -984,10 +1132,11 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
                F(a.bmean), F(a.abar), F(a.pooled), F(a.logits), F(a.dz), F(a.dp), F(a.daL), F(a.lossp),
                lay(a.DA, L - 1, w), loss_out, logits_out, grads, B, d, w, a.C, L - 1};
     LAD_LAUNCH(prof, st, KC_L_HEAD, (k_lpool<SRC>), dim3(B, cdivi(d, 256) + 1), dim3(256), 0, st, h);
+    LAD_LAUNCH(prof, st, KC_L_HEAD, k_lpooled, dim3(B, cdivi(d, 256)), dim3(256), 0, st, h);
     LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_a, dim3(B), dim3(256), 0, st, h);
-    LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_b, dim3(cdivi(d, 256)), dim3(256), 0, st, h);
+    LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_b, dim3(cdivi(d, 256), grads ? cdivi(w, kUpChunk) : 1), dim3(256), 0, st, h);
     if (!grads) return hipGetLastError();
-    LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_c, dim3(B), dim3(256), 0, st, h);
+    LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_c, dim3(B, cdivi(w, 16)), dim3(256), 0, st, h);
 
     for (int l = L - 1; l >= 0; --l) {
         const float *pl = params + (int64_t)l * a.PLb;
@@ -1003,7 +1152,7 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
         // do = dt W_o^T
         lin<true, 4>(prof, st, KC_L_LIN, DT, w, pl + a.fo[F_WO], w, M, w, w, nullptr, nullptr, nullptr, F(a.DO_), nullptr);
         AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), F(a.DO_), DQKV, w,
-                    a.nh, (int)(Mm / a.Bmax), scale};
+                    a.nh, (int)(Mm / a.Bmax), scale, tpr};
         LAD_TRY(attn(a.dh, true, at, B, st, prof));
         // dxn = dqkv W_qkv^T
         lin<true, 4>(prof, st, KC_L_LIN, DQKV, 3 * w, pl + a.fo[F_WQKV], 3 * w, M, w, 3 * w, nullptr, nullptr, nullptr,
@@ -1031,7 +1180,7 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
     rd.grads = grads; rd.PLb = a.PLb; rd.LP = (int64_t)L * a.PLb;
     for (int i = 0; i <= kFields; ++i) rd.fo[i] = a.fo[i];
     rd.L = L; rd.w = w; rd.splits = splits; rd.nblk = nblk;
-    LAD_LAUNCH(prof, st, KC_L_REDUCE, k_lreduce, dim3(cdivi(rd.LP, 256)), dim3(256), 0, st, rd);
+    LAD_LAUNCH(prof, st, KC_L_REDUCE, k_lreduce, dim3(cdivi(rd.LP, 256) + cdivi((int64_t)L * (4 * w + 1), 4)), dim3(256), 0, st, rd);
     return hipGetLastError();
 }
 
