@@ -121,6 +121,14 @@ def measure_peaks(torch, pb, sess, slice_bytes):
         t = timed(lambda i: pb.pac_probe_hbm_read(base + ((i * 37) % nsl) * sl, sl, sink.data_ptr(), st), 24)
         out["slice_read_GBs"] = sl / t / 1e9
         out["slice_read_bytes"] = sl
+    # the optimizer's access mix (four arrays read, three written back) on arrays of the LLaMA-7B-shaped parameter count,
+    # far larger than any on-chip cache
+    n = 67264548 & ~3
+    arr = [torch.zeros(n, dtype=torch.float32, device=sess.dev) for _ in range(4)]
+    t = timed(lambda i: pb.pac_probe_hbm_update(arr[0].data_ptr(), arr[1].data_ptr(), arr[2].data_ptr(), arr[3].data_ptr(), n, st), 6)
+    out["update_stream_GBs"] = 28.0 * n / t / 1e9
+    out["update_stream_bytes"] = 28 * n
+    del arr
     iters = 20000
     t = timed(lambda i: pb.pac_probe_mfma_bf16(iters, sink.data_ptr(), st), 3)
     out["mfma_bf16_TFLOPs"] = pb.pac_probe_mfma_flops(iters) / t / 1e12

@@ -240,6 +240,10 @@ pac_status pac_adapter_step_static(pac_ctx *ctx, const void *cache /*DEVICE*/,
  *   pac_probe_mfma_bf16  runs `iters` rounds of four independent 32x32x16 bf16 matrix instructions per
  *                        wavefront on register operands, four wavefronts per SIMD on every compute unit:
  *                        pac_probe_mfma_flops(iters) / duration is the matrix rate this chip sustains.
+ *   pac_probe_hbm_update reads four arrays of n floats and writes three of them back (p, m, v in place; g read
+ *                        only), one multiply-add per element: the access mix of the optimizer update (Sec. 5.2's
+ *                        step ends with it) without its arithmetic; 28 n / duration is the rate this chip sustains
+ *                        on that mix, which a read-only figure overstates.  n a multiple of 4, arrays 16-byte aligned.
  * sink: DEVICE, 256 floats, scratch.  The caller times the call with events on the same stream.
  * Errors: NULL, RANGE (bytes or iters not positive, bytes not a multiple of 16), ALIGN (buf not 16-byte
  * aligned), DEVICE.
@@ -247,6 +251,8 @@ pac_status pac_adapter_step_static(pac_ctx *ctx, const void *cache /*DEVICE*/,
 pac_status pac_probe_hbm_read(const void *buf /*DEVICE*/, int64_t bytes, float *sink /*DEVICE*/, void *hip_stream);
 pac_status pac_probe_mfma_bf16(int64_t iters, float *sink /*DEVICE*/, void *hip_stream);
 double pac_probe_mfma_flops(int64_t iters); /* flops one pac_probe_mfma_bf16(iters) call executes */
+pac_status pac_probe_hbm_update(float *p /*DEVICE*/, float *m /*DEVICE*/, float *v /*DEVICE*/, const float *g /*DEVICE*/,
+                                int64_t n, void *hip_stream);
 
 /*
  * Measurement aid (not part of the training path): per-kernel timing with HIP

@@ -27,7 +27,7 @@ EXPORTS = [
     "pac_create", "pac_destroy", "pac_status_str", "pac_param_count", "pac_param_offsets",
     "pac_cache_bytes", "pac_workspace_bytes", "pac_step_path", "pac_cache_fill", "pac_cache_lookup",
     "pac_adapter_loss_grad", "pac_adapter_step", "pac_adapter_step_static",
-    "pac_probe_hbm_read", "pac_probe_mfma_bf16", "pac_probe_mfma_flops",
+    "pac_probe_hbm_read", "pac_probe_mfma_bf16", "pac_probe_mfma_flops", "pac_probe_hbm_update",
     "pac_profile_begin", "pac_profile_end", "pac_profile_class_name",
     "pac_plan_hybrid", "pac_plan_stage_time",
     "pac_quant_blockwise", "pac_dequant_blockwise", "pac_dequant_linear", "pac_dequant_linear_to_cache",
@@ -116,6 +116,8 @@ def lib():
         L.pac_probe_hbm_read.argtypes = [vp, i64, vp, vp]
         L.pac_probe_mfma_bf16.restype = C.c_int
         L.pac_probe_mfma_bf16.argtypes = [i64, vp, vp]
+        L.pac_probe_hbm_update.restype = C.c_int
+        L.pac_probe_hbm_update.argtypes = [vp, vp, vp, vp, i64, vp]
         L.pac_probe_mfma_flops.restype = C.c_double
         L.pac_probe_mfma_flops.argtypes = [i64]
         L.pac_tier_window_bytes.restype = i64
@@ -264,6 +266,10 @@ def pac_probe_hbm_read(buf_ptr, nbytes: int, sink_ptr, stream=0) -> None:
 
 def pac_probe_mfma_bf16(iters: int, sink_ptr, stream=0) -> None:
     _check(lib().pac_probe_mfma_bf16(iters, sink_ptr, stream), "pac_probe_mfma_bf16")
+
+
+def pac_probe_hbm_update(p_ptr, m_ptr, v_ptr, g_ptr, n: int, stream=0) -> None:
+    _check(lib().pac_probe_hbm_update(p_ptr, m_ptr, v_ptr, g_ptr, n, stream), "pac_probe_hbm_update")
 
 
 def pac_probe_mfma_flops(iters: int) -> float:

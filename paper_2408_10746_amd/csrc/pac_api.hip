@@ -431,6 +431,8 @@ static pac_status step_on_workspace(pac_ctx *ctx, const void *cache, const int64
     a.lr = hp->lr; a.beta1 = hp->beta1; a.beta2 = hp->beta2; a.eps = hp->eps; a.wd = hp->weight_decay;
     a.bc1 = (float)(1.0 - pow((double)hp->beta1, (double)t));
     a.bc2 = (float)(1.0 - pow((double)hp->beta2, (double)t));
+    a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)hp->beta1, (double)t)));
+    a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)hp->beta2, (double)t)));
     if (launch_adamw(ctx->D, params, m, v, grads, a, st, prof, &fin) != hipSuccess) return PAC_ERR_DEVICE;
     *step = t;
     return PAC_OK;

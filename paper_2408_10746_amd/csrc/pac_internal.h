@@ -123,7 +123,8 @@ struct Deferred {
 
 struct AdamArgs {
     float lr, beta1, beta2, eps, wd;
-    float bc1, bc2; // 1 - beta^t for the step being applied
+    float bc1, bc2;         // 1 - beta^t for the step being applied
+    float inv_bc1, inv_bc2; // and their reciprocals
 };
 
 void plan_workspace(const Dims &D, WsLayout &W);

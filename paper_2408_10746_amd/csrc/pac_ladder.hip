@@ -1263,8 +1263,11 @@ pac_status pac_ladder_step(pac_ctx *ctx, const void *cache, const int64_t *sampl
     aa.h.lr = hp->lr; aa.h.beta1 = hp->beta1; aa.h.beta2 = hp->beta2; aa.h.eps = hp->eps; aa.h.wd = hp->weight_decay;
     aa.h.bc1 = (float)(1.0 - pow((double)hp->beta1, (double)t));
     aa.h.bc2 = (float)(1.0 - pow((double)hp->beta2, (double)t));
-    int blocks = (int)((a.P + 255) / 256);
-    if (blocks > 4096) blocks = 4096;
+    aa.h.inv_bc1 = (float)(1.0 / (1.0 - pow((double)hp->beta1, (double)t)));
+    aa.h.inv_bc2 = (float)(1.0 / (1.0 - pow((double)hp->beta2, (double)t)));
+    int64_t nb = (a.P + 255) / 256; // one element per thread
+    if (nb > (int64_t)1 << 22) nb = (int64_t)1 << 22;
+    const int blocks = (int)nb;
     Profiler *prof = ctx->prof.on ? &ctx->prof : nullptr;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     LAD_LAUNCH(prof, st, KC_ADAMW, k_ladamw, dim3(blocks), dim3(256), 0, st, aa);

@@ -63,6 +63,20 @@ __global__ __launch_bounds__(256) void k_probe_mfma(int64_t iters, float *sink)
 
 constexpr int kMfmaBlocks = 256 * 4; // four workgroups of four wavefronts per compute unit
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// the optimizer update's access mix: four 16-byte loads and three 16-byte stores per lane and round
+__global__ __launch_bounds__(256) void k_probe_update(f32x4 *__restrict__ p, f32x4 *__restrict__ m, f32x4 *__restrict__ v,
+                                                      const f32x4 *__restrict__ g, int64_t ngroups)
+{
+    for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < ngroups; q += (int64_t)gridDim.x * 256) {
+        const f32x4 gv = g[q];
+        const f32x4 pv = p[q], mv = m[q], vv = v[q];
+        p[q] = pv + 1e-9f * gv;
+        m[q] = mv * 0.9f + gv;
+        v[q] = vv * 0.999f + gv;
+    }
+}
+
 } // namespace
 
 extern "C" {
@@ -87,6 +101,23 @@ pac_status pac_probe_mfma_bf16(int64_t iters, float *sink, void *hip_stream)
     if (iters <= 0) return PAC_ERR_RANGE;
     (void)hipGetLastError();
     hipLaunchKernelGGL(k_probe_mfma, dim3(kMfmaBlocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), iters, sink);
+    return hipGetLastError() == hipSuccess ? PAC_OK : PAC_ERR_DEVICE;
+}
+
+pac_status pac_probe_hbm_update(float *p, float *m, float *v, const float *g, int64_t n, void *hip_stream)
+{
+    if (!p || !m || !v || !g) return PAC_ERR_NULL;
+    if (n <= 0 || n % 4) return PAC_ERR_RANGE;
+    if ((reinterpret_cast<uintptr_t>(p) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(v) |
+         reinterpret_cast<uintptr_t>(g)) & 15)
+        return PAC_ERR_ALIGN;
+    (void)hipGetLastError();
+    const int64_t ngroups = n / 4;
+    int64_t blocks = (ngroups + 255) / 256; // one group per thread, as the optimizer launch
+    if (blocks > (int64_t)1 << 22) blocks = (int64_t)1 << 22;
+    hipLaunchKernelGGL(k_probe_update, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<f32x4 *>(p), reinterpret_cast<f32x4 *>(m), reinterpret_cast<f32x4 *>(v),
+                       reinterpret_cast<const f32x4 *>(g), ngroups);
     return hipGetLastError() == hipSuccess ? PAC_OK : PAC_ERR_DEVICE;
 }
 
