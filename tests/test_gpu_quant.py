@@ -28,7 +28,10 @@ def weights(rng, N, K, outliers=True):
 
 
 @pytest.mark.parametrize("bits", [8, 4])
-@pytest.mark.parametrize("n,block", [(64 * 300 + 40, 64), (5000, 128), (7, 64), (4096 * 33, 4096), (1000, 2)])
+@pytest.mark.parametrize("n,block", [(64 * 300 + 40, 64), (5000, 128), (7, 64), (4096 * 33, 4096), (1000, 2),
+                                     # blocks that tile the tensor exactly: the four-values-per-lane form
+                                     (64 * 1001, 64), (256 * 37, 256), (8 * 1001, 8), (4 * 999, 4), (128 * 513, 128),
+                                     (32 * 70001, 32)])
 def test_quant_and_dequant_bit_exact(n, block, bits):
     rng = np.random.default_rng(n + bits)
     x = (rng.standard_normal(n) * np.exp(rng.uniform(-4, 4, size=n))).astype(np.float32)
