@@ -155,3 +155,43 @@ def test_argument_errors_are_caught_before_any_launch():
             assert isinstance(pb.status_str(s), str) and pb.status_str(s)
     finally:
         pb.pac_destroy(ctx)
+
+
+def test_ladder_argument_errors_are_caught_before_any_launch():
+    """The ladder's calls (include/pac_ladder.h) on fake device addresses: every call must fail on the host."""
+    ctx = pb.pac_create(2, 64, 16, 32, 3, 4, 8, pb.PAC_BF16)
+    lib = pb.lib()
+    dev = 0x7000_0000_0000
+    ids = np.array([0, 1], dtype=np.int64)
+    idp = ids.ctypes.data_as(C.c_void_p)
+    try:
+        w, d, f, L, Cc = 32, 64, 128, 2, 3
+        per_layer = d * w + w + 2 * w + 3 * w * w + 3 * w + w * w + w + 2 * w + w * f + f + f * w + w + 4
+        assert pb.pac_ladder_param_count(ctx) == L * per_layer + w * d + d + d * Cc + Cc
+        assert lib.pac_ladder_param_count(None) == -1
+        assert pb.pac_ladder_workspace_bytes(ctx, 3) == -1        # 32 / 3 is not a whole head width
+        assert pb.pac_ladder_workspace_bytes(ctx, 16) == -1       # head width 2 is not supported
+        ws = pb.pac_ladder_workspace_bytes(ctx, 4)
+        assert ws > 0 and ws % 256 == 0
+        call = lambda **k: lib.pac_ladder_loss_grad(
+            ctx, k.get("cache", dev), k.get("ids", idp), k.get("B", 2), k.get("labels", dev), k.get("heads", 4),
+            k.get("params", dev), k.get("ws", dev), k.get("ws_bytes", ws), k.get("loss", dev), None, None, None)
+        assert call(cache=None) == pb.PAC_ERR_NULL and call(loss=None) == pb.PAC_ERR_NULL
+        assert call(params=dev + 4) == pb.PAC_ERR_ALIGN and call(ws=dev + 16) == pb.PAC_ERR_ALIGN
+        assert call(heads=3) == pb.PAC_ERR_UNSUPPORTED
+        assert call(ws_bytes=ws - 1) == pb.PAC_ERR_WORKSPACE
+        assert call(B=0) == pb.PAC_ERR_RANGE and call(B=5) == pb.PAC_ERR_RANGE
+        assert call() == pb.PAC_ERR_STATE                         # samples 0 and 1 were never filled
+        hp = pb.pac_adamw(1e-3, 0.9, 0.999, 1e-8, 0.01)
+        st = C.c_int64(0)
+        step = lambda hp_, st_, m_=dev: lib.pac_ladder_step(ctx, dev, idp, 2, dev, 4, dev, m_, dev, st_, hp_, dev, ws, dev,
+                                                            None, None)
+        assert step(None, C.byref(st)) == pb.PAC_ERR_NULL and step(C.byref(hp), C.byref(st), None) == pb.PAC_ERR_NULL
+        assert step(C.byref(pb.pac_adamw(1e-3, 0.9, 1.0, 1e-8, 0.0)), C.byref(st)) == pb.PAC_ERR_RANGE
+        assert step(C.byref(hp), C.byref(C.c_int64(-1))) == pb.PAC_ERR_RANGE
+        assert step(C.byref(hp), C.byref(st)) == pb.PAC_ERR_STATE and st.value == 0
+        assert lib.pac_probe_hbm_update(dev, dev, dev, None, 1024, None) == pb.PAC_ERR_NULL
+        assert lib.pac_probe_hbm_update(dev, dev, dev, dev, 1022, None) == pb.PAC_ERR_RANGE
+        assert lib.pac_probe_hbm_update(dev, dev + 8, dev, dev, 1024, None) == pb.PAC_ERR_ALIGN
+    finally:
+        pb.pac_destroy(ctx)
