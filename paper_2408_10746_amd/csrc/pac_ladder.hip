@@ -43,7 +43,7 @@ namespace {
 inline int64_t al256(int64_t x) { return (x + 255) & ~int64_t(255); }
 inline int cdivi(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
-using TL = Tile<2, 2, 1, 1, 4>; // 64 x 64 workgroup tile, 64 fp32 values of K per step
+using TL = Tile<2, 2, 1, 1, 4, 2>; // 64 x 64 workgroup tile, 64 fp32 values of K per step, two steps in flight
 constexpr int kTileLds = tile_lds_bytes<float, TL>();
 constexpr int kLnRows = 16;    // token rows per workgroup of the LayerNorm reverse kernels (four per wavefront)
 constexpr int kFields = 15;    // tensors of one layer block
