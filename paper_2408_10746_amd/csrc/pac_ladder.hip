@@ -527,7 +527,8 @@ struct AttnArgs {
     float *dQKV;     // reverse: [M][3w]
     int w, nh, n_max;
     float scale;
-    int tpr; // lanes per row: a power of two, 1 .. 8
+    int tpr;    // lanes per row: a power of two, 1 .. 8
+    int nchunk; // workgroups per sample and head (blockIdx.y): each takes a contiguous share of the rows
 };
 // A row is shared by `tpr` neighbouring lanes (a power of two, chosen so that the sample's rows fill the
 // workgroup); each takes every tpr-th key (query) and the partial results are combined with lane exchanges.
@@ -557,10 +558,11 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_fwd(AttnArgs a)
     }
     __syncthreads();
     const int tpr = a.tpr, part = threadIdx.x % tpr, rpp = 256 / tpr;
+    const int rpc = (n + a.nchunk - 1) / a.nchunk, r_lo = blockIdx.y * rpc, r_hi = min(n, r_lo + rpc);
     // (every lane of a group runs the same number of rounds: the exchanges below need all of them)
-    for (int i0 = 0; i0 < n; i0 += rpp) {
+    for (int i0 = r_lo; i0 < r_hi; i0 += rpp) {
         const int i = i0 + (int)threadIdx.x / tpr;
-        const bool live = i < n;
+        const bool live = i < r_hi;
         const int ic = live ? i : n - 1;
         float q[DH];
         const float *qp = a.QKV + (int64_t)(m0 + ic) * w3 + h * DH;
@@ -622,10 +624,11 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_bwd(AttnArgs a)
     }
     __syncthreads();
     const int tpr = a.tpr, part = threadIdx.x % tpr, rpp = 256 / tpr;
+    const int rpc = (n + a.nchunk - 1) / a.nchunk, r_lo = blockIdx.y * rpc, r_hi = min(n, r_lo + rpc);
     // phase 1, query row i: dq_i = scale * sum_j P_ij (dO_i . v_j - D_i) k_j
-    for (int i0 = 0; i0 < n; i0 += rpp) {
+    for (int i0 = r_lo; i0 < r_hi; i0 += rpp) {
         const int i = i0 + (int)threadIdx.x / tpr;
-        const bool live = i < n;
+        const bool live = i < r_hi;
         const int ic = live ? i : n - 1;
         float q[DH], go[DH], dq[DH];
 #pragma unroll
@@ -647,9 +650,9 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_bwd(AttnArgs a)
         }
     }
     // phase 2, key row j: dv_j = sum_i P_ij dO_i ; dk_j = scale * sum_i P_ij (dO_i . v_j - D_i) q_i
-    for (int j0 = 0; j0 < n; j0 += rpp) {
+    for (int j0 = r_lo; j0 < r_hi; j0 += rpp) {
         const int j = j0 + (int)threadIdx.x / tpr;
-        const bool live = j < n;
+        const bool live = j < r_hi;
         const int jc = live ? j : n - 1;
         float k[DH], v[DH], dk[DH], dv[DH];
 #pragma unroll
@@ -1054,11 +1057,11 @@ template <int DH> hipError_t launch_attn(bool bwd, const AttnArgs &a, int B, hip
     if (!bwd) {
         const int lds = 2 * a.n_max * DH * 4;
         LAD_TRY((lds_once<&k_lattn_fwd<DH>>(lds)));
-        LAD_LAUNCH(prof, st, KC_L_ATTN, (k_lattn_fwd<DH>), dim3(B * a.nh), dim3(256), lds, st, a);
+        LAD_LAUNCH(prof, st, KC_L_ATTN, (k_lattn_fwd<DH>), dim3(B * a.nh, a.nchunk), dim3(256), lds, st, a);
     } else {
         const int lds = (4 * a.n_max * DH + 2 * a.n_max) * 4;
         LAD_TRY((lds_once<&k_lattn_bwd<DH>>(lds)));
-        LAD_LAUNCH(prof, st, KC_L_ATTN, (k_lattn_bwd<DH>), dim3(B * a.nh), dim3(256), lds, st, a);
+        LAD_LAUNCH(prof, st, KC_L_ATTN, (k_lattn_bwd<DH>), dim3(B * a.nh, a.nchunk), dim3(256), lds, st, a);
     }
     return hipSuccess;
 }
@@ -1106,8 +1109,12 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
     const float scale = 1.f / sqrtf((float)a.dh);
     int nlong = 1; // longest sample of the batch: lanes per attention row so that its rows fill a workgroup
     for (int i = 0; i < B; ++i) nlong = meta.len[i] > nlong ? meta.len[i] : nlong;
+    // several workgroups per sample and head (about 32 rows each), the rows of one shared by up to 8 lanes
+    int nchunk = nlong / 32;
+    nchunk = nchunk < 1 ? 1 : (nchunk > 8 ? 8 : nchunk);
+    const int rows_per_wg = (nlong + nchunk - 1) / nchunk;
     int tpr = 1;
-    while (tpr < 8 && 2 * tpr * nlong <= 256) tpr *= 2;
+    while (tpr < 8 && 2 * tpr * rows_per_wg <= 256) tpr *= 2;
     for (int l = 0; l < L; ++l) {
         const float *pl = params + (int64_t)l * a.PLb;
         LnFwdArgs n1{lay(a.U, l, w), l ? lay(a.A, l - 1, w) : nullptr, pl + a.fo[F_LAM], pl + a.fo[F_G1], pl + a.fo[F_H1],
@@ -1116,7 +1123,7 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
         lin<false, 0>(prof, st, KC_L_LIN, lay(a.XN, l, w), w, pl + a.fo[F_WQKV], 3 * w, M, 3 * w, w, pl + a.fo[F_BQKV],
                       nullptr, nullptr, lay(a.QKV, l, 3 * w), nullptr);
         AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), nullptr, nullptr, w,
-                    a.nh, (int)(Mm / a.Bmax), scale, tpr};
+                    a.nh, (int)(Mm / a.Bmax), scale, tpr, nchunk};
         LAD_TRY(attn(a.dh, false, at, B, st, prof));
         lin<false, 1>(prof, st, KC_L_LIN, lay(a.O, l, w), w, pl + a.fo[F_WO], w, M, w, w, pl + a.fo[F_BO], lay(a.X, l, w),
                       nullptr, lay(a.T, l, w), nullptr);
@@ -1152,7 +1159,7 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
         // do = dt W_o^T
         lin<true, 4>(prof, st, KC_L_LIN, DT, w, pl + a.fo[F_WO], w, M, w, w, nullptr, nullptr, nullptr, F(a.DO_), nullptr);
         AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), F(a.DO_), DQKV, w,
-                    a.nh, (int)(Mm / a.Bmax), scale, tpr};
+                    a.nh, (int)(Mm / a.Bmax), scale, tpr, nchunk};
         LAD_TRY(attn(a.dh, true, at, B, st, prof));
         // dxn = dqkv W_qkv^T
         lin<true, 4>(prof, st, KC_L_LIN, DQKV, 3 * w, pl + a.fo[F_WQKV], 3 * w, M, w, 3 * w, nullptr, nullptr, nullptr,
