@@ -114,6 +114,18 @@ def test_more_rows_than_one_split_and_many_layers():
     run_case(w, 8, inputs.lengths(w), seed=7, what="lad_m")
 
 
+def test_long_ragged_sequences_several_attention_chunks():
+    """Samples of up to 1024 tokens (eight attention workgroups per sample and head, rows not shared between lanes) next
+    to short ones in the same batch; fp32 cache."""
+    w = Workload("lad_l", L=2, d=64, n_max=1024, B=3, r=64, C=2, N=3, cache_dtype="f32")
+    run_case(w, 8, np.array([1024, 37, 700], dtype=np.int32), seed=21, what="lad_l")
+
+
+def test_largest_batch_of_short_samples():
+    w = Workload("lad_x", L=2, d=96, n_max=20, B=64, r=32, C=5, N=64, cache_dtype="bf16", len_lo=1)
+    run_case(w, 2, inputs.lengths(w), seed=22, what="lad_x")
+
+
 def test_training_steps_follow_the_oracle():
     from paper_2408_10746_amd.runtime import LadderSession
     w = Workload("lad_t", L=2, d=64, n_max=16, B=4, r=32, C=3, N=8, cache_dtype="bf16")
