@@ -706,20 +706,35 @@ template <typename SRC> __global__ __launch_bounds__(256) void k_lpool(HeadArgs 
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     if (live) {
         if (from_cache) {
-            const SRC *cache = static_cast<const SRC *>(a.cache);
-            for (int t = wave; t < len; t += 4) {
-                const int m = m0 + t;
-                float f[4];
-                Raw4<SRC>::widen(*reinterpret_cast<const typename Raw4<SRC>::type *>(
-                                     cache + a.map.rowoff[m] + (int64_t)a.last_layer * a.map.rowstride[m] + c0), f);
+            // the tokens of a sample are consecutive rows of one cache block: one table look-up gives them all;
+            // eight rows are requested per round
+            const SRC *base = static_cast<const SRC *>(a.cache) + a.map.rowoff[m0] + (int64_t)a.last_layer * a.map.rowstride[m0] + c0;
+            for (int t0 = wave; t0 < len; t0 += 32) {
+                typename Raw4<SRC>::type raw[8];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[e] += f[e];
+                for (int u = 0; u < 8; ++u)
+                    raw[u] = *reinterpret_cast<const typename Raw4<SRC>::type *>(base + (int64_t)min(t0 + 4 * u, len - 1) * a.d);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (t0 + 4 * u < len) {
+                        float f[4];
+                        Raw4<SRC>::widen(raw[u], f);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[e] += f[e];
+                    }
             }
         } else {
-            for (int t = wave; t < len; t += 4) {
-                const f32x4 v = *reinterpret_cast<const f32x4 *>(a.A_last + (int64_t)(m0 + t) * a.w + c0);
+            for (int t0 = wave; t0 < len; t0 += 32) {
+                f32x4 v[8];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[e] += v[e];
+                for (int u = 0; u < 8; ++u)
+                    v[u] = *reinterpret_cast<const f32x4 *>(a.A_last + (int64_t)(m0 + min(t0 + 4 * u, len - 1)) * a.w + c0);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (t0 + 4 * u < len) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[e] += v[u][e];
+                    }
             }
         }
     }
@@ -829,6 +844,7 @@ __global__ __launch_bounds__(256) void k_lhead_b(HeadArgs a)
     float dcup = 0.f, up[kUpChunk];
 #pragma unroll
     for (int c = 0; c < kUpChunk; ++c) up[c] = 0.f;
+#pragma unroll 4
     for (int s = 0; s < a.B; ++s) {
         float dp = 0.f;
 #pragma unroll
