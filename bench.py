@@ -235,7 +235,7 @@ def run_workload(name, N, steps, warmup, flags, keep_cpu_samples=0, want_peaks=F
     return res, keep_host, lens_all, labels
 
 
-def cpu_baseline(w, keep_host, lens_all, labels, cpu_ids, seconds):
+def cpu_baseline(w, keep_host, lens_all, labels, cpu_ids, seconds, one_core=True):
     """The CPU oracle as it stands on a bounded sample of the workload: whole training steps on the same few
     samples, once on all host cores and once on one core."""
     import numpy as np
@@ -266,7 +266,38 @@ def cpu_baseline(w, keep_host, lens_all, labels, cpu_ids, seconds):
                           f"of the {w.name} workload, cache already in host memory; {c2 - c1:.1f} s"}
 
     out = leg(all_cores, seconds)
-    out["single_core"] = leg(1, seconds)
+    if one_core:
+        out["single_core"] = leg(1, seconds)
+    orc.set_num_threads(all_cores)
+    return out
+
+
+def cpu_baseline_tiny():
+    """The oracle on the whole Tiny run (3 epochs x 8 steps on 64 samples, fp32 cache), all cores and one core."""
+    import numpy as np
+    from paper_2408_10746_amd import inputs
+    from oracle import oracle as orc
+    w = inputs.WORKLOADS["tiny"]
+    dims = orc.Dims(w.L, w.d, w.r, w.C)
+    acts = inputs.batch_acts(w, range(w.N))
+    labels = inputs.labels(w)
+    cache, off, lens = orc.cache_fill(acts, as_bf16=False)
+    hp = orc.AdamW()
+    all_cores = orc.num_threads()
+    out = {}
+    for name, threads in (("all_cores", all_cores), ("single_core", 1)):
+        orc.set_num_threads(threads)
+        p = inputs.init_params(w).astype(np.float64)
+        m, v, t = np.zeros(dims.P), np.zeros(dims.P), 0
+        c1 = time.perf_counter()
+        for e in range(w.epochs):
+            order = inputs.epoch_order(w, e)
+            for b in range(w.N // w.B):
+                ids = order[b * w.B:(b + 1) * w.B]
+                _, _, t = orc.step(dims, cache, off[ids], lens[ids], labels[ids], p, m, v, t, hp)
+        el = time.perf_counter() - c1
+        out[name] = {"value": t * w.B / el, "unit": "samples/s", "cores": threads, "kind": "oracle",
+                     "sample": f"the whole Tiny run: {t} training steps of {w.B} samples; {el:.2f} s"}
     orc.set_num_threads(all_cores)
     return out
 
@@ -458,6 +489,8 @@ def main():
     cpu = None
     if ncpu:
         cpu = cpu_baseline(w, keep_host, lens_all, labels, list(range(ncpu)), args.cpu_seconds)
+        if args.workload == "t5base" and not args.no_configs:
+            cpu["tiny"] = cpu_baseline_tiny()
     del keep_host
 
     configs = {}
@@ -466,10 +499,17 @@ def main():
             gc.collect()
             torch.cuda.empty_cache()
             try:
-                res, _, _, _ = run_workload(name, 0, steps, warmup, 0)
+                wl = inputs.WORKLOADS[name]
+                ncpu_cfg = wl.B if (name == "llama7b" and not args.no_cpu_baseline) else 0
+                res, kh, la, lb = run_workload(name, 0, steps, warmup, 0, keep_cpu_samples=ncpu_cfg)
                 configs[name] = {k: res[k] for k in ("workload", "N_resident", "N_config", "tokens_per_step", "formulation",
                                                      "steps", "ms_per_step", "samples_per_s", "cache_fill_s",
                                                      "roofline", "cache_passes", "whole_step")}
+                if ncpu_cfg:
+                    # one whole step of this configuration in the oracle on all host cores (1.65 TFLOP: tens of seconds;
+                    # the one-core leg would take minutes and is left out)
+                    configs[name]["cpu_baseline"] = cpu_baseline(wl, kh, la, lb, list(range(ncpu_cfg)), 0.5, one_core=False)
+                del kh
             except Exception as ex:  # the headline stays valid if another configuration cannot run on this machine
                 configs[name] = {"error": f"{type(ex).__name__}: {ex}"}
 
