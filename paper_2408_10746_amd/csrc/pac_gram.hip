@@ -124,13 +124,16 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.g_QpN = take(q_bytes);
     W.g_QpT = take(q_bytes);
     W.chain_group = 1;
-    W.g_P = W.g_ghat = 0;
+    W.g_P = W.g_ghat = W.g_QgN = W.g_QgT = 0;
     if (W.use_gram == 2) {
         // layers per group of the layer-by-layer chains: about 1024 columns per wide contraction
         const int g = 1024 / D.r;
         W.chain_group = g < 1 ? 1 : (g > 8 ? 8 : g);
         W.g_P = take(D.Mmax * (int64_t)W.chain_group * D.r * 4);
         W.g_ghat = take((int64_t)D.B_max * Lr * 4);
+        const int64_t in_group = (int64_t)cdiv(D.L, W.chain_group) * (W.chain_group * (W.chain_group - 1) / 2);
+        W.g_QgN = take((in_group + 1) * D.r * D.r * 2);
+        W.g_QgT = take((in_group + 1) * D.r * D.r * 2);
     }
     W.g_DP = take(D.Mmax * Lr * 2);
     W.g_Gp = take(D.Mmax * Lr * 2);
@@ -403,6 +406,8 @@ struct ProjArgs {
     int64_t PL;
     float *U;          // [L][M][r]
     bf16_t *QpN, *QpT; // [pairs][r][r] in fragment-major order (EpiQ), or (q_full) [L*r][L*r] each (EpiQFull)
+    bf16_t *QgN, *QgT; // q_full: the pairs inside a group of chain_group layers once more, fragment-major
+    int chain_group;
     const int32_t *samp_start, *samp_len;
     float *pb; // [B][d]
     int C;
@@ -446,9 +451,20 @@ struct EpiQFull {
     float one_minus_lam;
     int k, l;
     int64_t Lr;
+    bf16_t *gn, *gt; // this pair's fragment-major blocks when both layers are in one group, else null
     __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
     {
         if (col >= ncols) return;
+        if (gt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = epi_row(row_base, v);
+                if (row < nrows) {
+                    gn[frag_index(row, col, r)] = static_cast<bf16_t>(one_minus_lam * acc[v]); // backward: B[n=row][kk=col]
+                    gt[frag_index(col, row, r)] = static_cast<bf16_t>(acc[v]);                 // forward:  B[n=col][kk=row]
+                }
+            }
+        }
         bf16_t *qt_row = qt + ((int64_t)l * r + col) * Lr + (int64_t)k * r;
         bf16_t *qn_col = qn + (int64_t)k * r * Lr + (int64_t)l * r + col;
 #pragma unroll
@@ -555,7 +571,17 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(NT > 4 ? 512 
         auto brow = [&](int c) { return Wd + (int64_t)c * d; };
         const float oml = 1.f - a.params[(int64_t)l * a.PL + a.PL - 1];
         if constexpr (QFULL) {
-            EpiQFull epi{a.QpN, a.QpT, a.r, oml, k, l, (int64_t)a.L * a.r};
+            // slot of an in-group pair: the forward chain reaches it at step (l - l0, k - l0) of its group, the
+            // backward chain at step (l1 - 1 - k, l1 - 1 - l); slot of step (q, j) = q (q - 1) / 2 + j
+            const int g = a.chain_group, gi = l / g;
+            bf16_t *gn = nullptr, *gt = nullptr;
+            if (k / g == gi) {
+                const int l0 = gi * g, l1 = min(l0 + g, a.L), pg = g * (g - 1) / 2;
+                const int qf = l - l0, jf = k - l0, qb = l1 - 1 - k, jb = l1 - 1 - l;
+                gt = a.QgT + ((int64_t)gi * pg + qf * (qf - 1) / 2 + jf) * a.r * a.r;
+                gn = a.QgN + ((int64_t)gi * pg + qb * (qb - 1) / 2 + jb) * a.r * a.r;
+            }
+            EpiQFull epi{a.QpN, a.QpT, a.r, oml, k, l, (int64_t)a.L * a.r, gn, gt};
             gemm_nt<TQ, true>(smem, arow, brow, epi, 0, a.d, (idx / tqn) * TQ::BM, (idx % tqn) * TQ::BN, a.r, a.r);
         } else {
             EpiQ epi{a.QpN + (int64_t)p * a.r * a.r, a.QpT + (int64_t)p * a.r * a.r, a.r, oml};
@@ -1035,10 +1061,12 @@ template <bool FWD, int NT, int CMAX = kMaxClasses> __global__ __launch_bounds__
 //
 // The layers are taken in groups of g.  What the layers before a group contribute to all g layers of
 // the group is one wide contraction (K = all earlier layers, N = g*r: enough 128 x 128 tiles to fill
-// the chip without splitting K).  Inside the group each layer is a short contraction over the group's
-// earlier layers whose epilogue adds the wide contraction's result and applies the nonlinearity, so
-// that no partial sums travel through memory more than once.  The per-tile column sums the later
-// launches need are taken from the finished bf16 arrays in one pass per direction.
+// the chip without splitting K).  Inside the group each layer contracts over the group's earlier layers
+// and then adds the wide contraction's result and applies the nonlinearity, so that no partial sums
+// travel through memory more than once: up to r = 256 one launch walks all layers of the group per
+// 16-token tile (k_gseq_group), above that each layer is a short tiled contraction of its own
+// (k_gseq_layer).  The per-tile column sums the later launches need are taken from the finished bf16
+// arrays in one pass per direction.
 // ---------------------------------------------------------------------------
 struct SeqBigArgs {
     const bf16_t *A;  // H or DP [M][L*r]
@@ -1150,6 +1178,256 @@ template <bool FWD, int BK> __global__ __launch_bounds__(256) void k_gseq_layer(
                          a.Hg + (int64_t)l * r, Lr, r, pl[a.PL - 1], a.chat + (int64_t)l * r, pl + (int64_t)a.d * r,
                          FWD ? nullptr : a.ghat + (int64_t)l * r, a.rowsamp};
     gemm_nt<TL>(smem, arow, brow, epi, a.kbegin, a.kend, rt * TL::BM, ct * TL::BN, a.M, r);
+}
+
+// All layers of a group in one launch.  The chain is a recurrence per token, so a workgroup that owns 16 token rows
+// can walk the group's layers by itself: h (or dpre) of the group's finished layers stays in LDS as the operand of
+// the later ones, and the r x r operands stream from fragment-major copies of the group's pairs through a register
+// FIFO that runs ahead across layer boundaries (they depend on nothing computed here).
+//
+// Contracting wavefronts (one per 32 columns of r) issue nothing but those operand requests: on this target loads
+// and stores complete in order per wavefront, so a per-token load or a store between two operand requests would
+// make every later operand wait for it.  Four helper wavefronts (four token rows each) do all per-token global
+// traffic instead: they request the next layer's inputs one step ahead, fold them into the one tile the epilogue
+// needs (forward t = lambda U + (1-lambda)(P + chat) + c_down; backward t = ghat + P and GELU'), put that into an
+// LDS ring, and write the finished layer's tiles out while the next layer is contracted.
+//
+// The matrix instructions take the r x r fragment as their first operand and the token fragment as the second:
+// lane (i, g4) then holds columns n0 + 16 cb + 4 g4 .. + 3 of token row i, four consecutive values per access.
+struct SeqGroupArgs {
+    SeqLayerArgs la;  // l, Bq, kbegin, kend, ctiles, pcol0 unused
+    int l0, l1;       // the group's layers
+    const bf16_t *Qg; // the group's pairs, fragment-major: block q (q - 1) / 2 + j for step q's operand of step j
+};
+constexpr int kGroupHelpers = 4;
+constexpr int kGroupDepth = 8;   // K blocks of operands requested ahead per contracting wavefront
+constexpr int kGroupMaxR = 256;  // eight contracting wavefronts
+// LDS of the group kernel (T = kChainRows):
+//   Hs   [layers][T][r + 8] bf16   h or dpre of the group's layers
+//   ring [2][T][r + 4] fp32        the epilogue's per-token input t
+//   xst  [2][T][r + 8] bf16        GELU': the backward chain's input, the forward chain's output on its way out
+//   vecS [layers][r] fp32, lamS [layers] fp32
+static size_t group_lds(int layers, int r)
+{
+    return (size_t)layers * kChainRows * (r + kChainPad) * 2 + (size_t)2 * kChainRows * (r + 4) * 4 +
+           (size_t)2 * kChainRows * (r + kChainPad) * 2 + (size_t)layers * r * 4 + (size_t)((layers + 3) / 4 * 4) * 4;
+}
+
+template <bool FWD> __global__ __launch_bounds__(64 * (kGroupMaxR / 32 + kGroupHelpers)) void k_gseq_group(SeqGroupArgs ga)
+{
+    extern __shared__ __attribute__((aligned(16))) char dyn_smem[];
+    const SeqLayerArgs &a = ga.la;
+    constexpr int T = kChainRows, D = kGroupDepth;
+    const int r = a.r, RP = r + kChainPad, RF = r + 4, KB = r >> 5, NWV = r >> 5, M = a.M;
+    const int gl = ga.l1 - ga.l0;
+    bf16_t *Hs = reinterpret_cast<bf16_t *>(dyn_smem);
+    float *ring = reinterpret_cast<float *>(Hs + (size_t)gl * T * RP);
+    bf16_t *xst = reinterpret_cast<bf16_t *>(ring + (size_t)2 * T * RF);
+    float *vecS = reinterpret_cast<float *>(xst + (size_t)2 * T * RP);
+    float *lamS = vecS + (size_t)gl * r;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m0 = blockIdx.x * T;
+    const int64_t Lr = (int64_t)a.L * r, Mr = (int64_t)M * r;
+    const int nthreads = 64 * (NWV + kGroupHelpers);
+    auto layer_at = [&](int q) { return FWD ? ga.l0 + q : ga.l1 - 1 - q; };
+    auto per_layer_vectors = [&]() {
+        for (int c = threadIdx.x; c < gl * r; c += nthreads) {
+            const int q = c / r, n = c - q * r, l = layer_at(q);
+            const float *pl = a.params + (int64_t)l * a.PL;
+            vecS[c] = FWD ? (1.f - pl[a.PL - 1]) * a.chat[(int64_t)l * r + n] + pl[(int64_t)a.d * r + n] : 0.f;
+            if (n == 0) lamS[q] = pl[a.PL - 1];
+        }
+    };
+
+    if (wave >= NWV) {
+        // ---- helper wavefronts: rows 4 h .. 4 h + 3 of the tile ----
+        __builtin_amdgcn_s_setprio(3);
+        const int h = wave - NWV;
+        const int cpr = r >> 2, nc = 4 * cpr; // 4-column chunks per row, chunks of this wavefront's four rows (<= 256)
+        // element offsets of this lane's chunks in a layer of U / Gp, in P, in ghat (all below 2^31: at most 65536 token
+        // rows of at most 1024 columns), and their row and column in the tile.  Chunks past the end repeat the last one.
+        int off_u[4], off_p[4], off_g[4], trow[4], tcol[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = min(lane + 64 * u, nc - 1);
+            const int row = 4 * h + c / cpr, col = 4 * (c % cpr);
+            const int m = min(m0 + row, M - 1);
+            off_u[u] = m * r + col;
+            off_p[u] = m * a.ldp + col;
+            off_g[u] = FWD ? 0 : a.rowsamp[m] * (int)Lr + col;
+            trow[u] = row;
+            tcol[u] = col;
+        }
+        // two tiles in registers (even steps in set 0, odd steps in set 1), each requested two steps before it is needed
+        struct Regs {
+            f32x4 ru[4], rp[4];
+            bf16x4 rx[4];
+        };
+        Regs ra, rb;
+        auto fetch = [&](int s, Regs &g) {
+            if (s >= gl) return;
+            const int l = layer_at(s);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (FWD) {
+                    g.ru[u] = *reinterpret_cast<const f32x4 *>(a.U + (int64_t)l * Mr + off_u[u]);
+                } else {
+                    g.ru[u] = *reinterpret_cast<const f32x4 *>(a.ghat + (int64_t)l * r + off_g[u]);
+                    g.rx[u] = *reinterpret_cast<const bf16x4 *>(a.Gp + (int64_t)l * Mr + off_u[u]);
+                }
+                g.rp[u] = a.P ? *reinterpret_cast<const f32x4 *>(a.P + (int64_t)(l - ga.l0) * r + off_p[u])
+                              : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        };
+        auto put = [&](int s, const Regs &g) {
+            if (s >= gl) return;
+            float *rt = ring + (size_t)(s & 1) * T * RF;
+            bf16_t *xt = xst + (size_t)(s & 1) * T * RP;
+            const float lam = lamS[s];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                f32x4 t;
+                if (FWD) {
+                    const f32x4 cv = *reinterpret_cast<const f32x4 *>(vecS + s * r + tcol[u]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[e] = lam * g.ru[u][e] + (1.f - lam) * g.rp[u][e] + cv[e];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[e] = g.ru[u][e] + g.rp[u][e];
+                    *reinterpret_cast<bf16x4 *>(xt + trow[u] * RP + tcol[u]) = g.rx[u];
+                }
+                *reinterpret_cast<f32x4 *>(rt + trow[u] * RF + tcol[u]) = t;
+            }
+        };
+        // tiles of a finished step, LDS -> global: h or dpre, and (forward) GELU'
+        auto drain = [&](int s) {
+            if (s < 0 || s >= gl) return;
+            const int l = layer_at(s);
+            const int cp8 = r >> 3; // 16-byte chunks per row
+            const bf16_t *hq = Hs + (size_t)s * T * RP, *xq = xst + (size_t)(s & 1) * T * RP;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int c = lane + 64 * u;
+                const int row = 4 * h + c / cp8, cc = c % cp8, m = m0 + row;
+                if (c < 4 * cp8 && m < M) {
+                    *reinterpret_cast<u32x4 *>(a.Hg + (int64_t)m * Lr + (int64_t)l * r + cc * 8) =
+                        *reinterpret_cast<const u32x4 *>(hq + row * RP + cc * 8);
+                    if (FWD)
+                        *reinterpret_cast<u32x4 *>(a.Gp + (int64_t)l * Mr + (int64_t)m * r + cc * 8) =
+                            *reinterpret_cast<const u32x4 *>(xq + row * RP + cc * 8);
+                }
+            }
+        };
+        fetch(0, ra);
+        fetch(1, rb);
+        per_layer_vectors();
+        __syncthreads(); // vectors
+        put(0, ra);
+        fetch(2, ra);
+        __syncthreads(); // the first step's tile is in the ring
+        for (int s = 0; s < gl; s += 2) {
+            // during step s: the tile of step s+1 (requested two steps ago) goes into the ring slot step s-1 has left,
+            // the tiles step s-1 produced go out, and the inputs of step s+3 are requested into the registers just freed
+            put(s + 1, rb);
+            drain(s - 1);
+            fetch(s + 3, rb);
+            __syncthreads();
+            if (s + 1 < gl) {
+                put(s + 2, ra);
+                drain(s);
+                fetch(s + 4, ra);
+                __syncthreads();
+            }
+        }
+        drain(gl - 1);
+        return;
+    }
+
+    // ---- contracting wavefronts ----
+    const int i = lane & 15, g4 = lane >> 4;
+    const int n0 = 32 * wave;
+    const int64_t rr = (int64_t)r * r;
+    const bf16_t *Bl = ga.Qg + ((int64_t)2 * wave * KB * 64 + lane) * 8; // this lane's 16 bytes of a fragment
+    const int total = gl * (gl - 1) / 2 * KB;
+    // next request: (layer step, earlier step, K block).  Every FIFO slot is requested on every path; past the end
+    // the last block is requested again and never used.
+    int iq = 1, ik = 0, ib = 0;
+    auto issue = [&](bf16x8(&bq)[2]) {
+        const bool live = iq < gl;
+        const int q = live ? iq : gl - 1, k = live ? ik : gl - 2, b = live ? ib : KB - 1;
+        const bf16_t *p = Bl + (q * (q - 1) / 2 + k) * rr + b * 512;
+        bq[0] = *reinterpret_cast<const bf16x8 *>(p);
+        bq[1] = *reinterpret_cast<const bf16x8 *>(p + KB * 512);
+        if (live && ++ib >= KB) {
+            ib = 0;
+            if (++ik >= iq) {
+                ik = 0;
+                ++iq;
+            }
+        }
+    };
+    bf16x8 fifo[D][2];
+    if (total > 0) {
+#pragma unroll
+        for (int slot = 0; slot < D; ++slot) issue(fifo[slot]);
+    }
+    per_layer_vectors();
+    const bool live_row = m0 + i < M;
+    f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    auto contract = [&](const bf16x8(&bq)[2], int k, int b) {
+        const bf16x8 av = *reinterpret_cast<const bf16x8 *>(Hs + ((size_t)k * T + i) * RP + 32 * b + 8 * g4);
+        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bq[0], av, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bq[1], av, acc[1], 0, 0, 0);
+    };
+    auto finish_layer = [&](int q) { // the rest of the layer, its tiles to LDS, barrier
+        const float lam = lamS[q];
+        const float *rt = ring + ((size_t)(q & 1) * T + i) * RF;
+        bf16_t *xt = xst + ((size_t)(q & 1) * T + i) * RP;
+        bf16_t *Hq = Hs + ((size_t)q * T + i) * RP;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const int col = n0 + 16 * cb + 4 * g4;
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(rt + col);
+            bf16x4 o, gq;
+            if (!FWD) gq = *reinterpret_cast<const bf16x4 *>(xt + col);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float out;
+                if (FWD) {
+                    float gp;
+                    gelu_pair(t[v] + (1.f - lam) * acc[cb][v], out, gp);
+                    gq[v] = static_cast<bf16_t>(gp);
+                } else {
+                    out = (t[v] + acc[cb][v]) * to_f32(gq[v]);
+                }
+                o[v] = static_cast<bf16_t>(live_row ? out : 0.f);
+                acc[cb][v] = 0.f;
+            }
+            *reinterpret_cast<bf16x4 *>(Hq + col) = o;
+            if (FWD) *reinterpret_cast<bf16x4 *>(xt + col) = gq;
+        }
+        __syncthreads();
+    };
+    __syncthreads(); // vectors
+    __syncthreads(); // the first step's tile is in the ring
+    finish_layer(0); // the group's first layer has nothing to contract inside the group
+    int cq = 1, ck = 0, cb_ = 0; // block being contracted
+    for (int p0 = 0; p0 < total; p0 += D) {
+#pragma unroll
+        for (int slot = 0; slot < D; ++slot) {
+            if (p0 + slot < total) {
+                contract(fifo[slot], ck, cb_);
+                if (++cb_ >= KB) {
+                    cb_ = 0;
+                    if (++ck >= cq) {
+                        finish_layer(cq++);
+                        ck = 0;
+                    }
+                }
+            }
+            issue(fifo[slot]);
+        }
+    }
 }
 
 // part[tile][kk] = sum over the tile's valid rows of X[row][kk]   (X = H or DP, bf16 [M][L*r])
@@ -1886,6 +2164,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.nb_C = L * cdiv(r, 64);
         a.cusum = cusum; a.chat = chat; a.params = io.params; a.PL = D.PL;
         a.WdT = WdT; a.Wu = Wu; a.U = pre; a.QpN = QpN; a.QpT = QpT;
+        a.QgN = (bf16_t *)(ws + W.g_QgN); a.QgT = (bf16_t *)(ws + W.g_QgT); a.chain_group = W.chain_group;
         a.samp_start = samp_start; a.samp_len = samp_len; a.pb = pb; a.C = C; a.zpbp = zpb;
         const int counts[4] = {a.nb_U, a.nb_Q, a.nb_C, B * cdiv(d, 256)};
         const int classes[4] = {KC_G_PROJ_U, KC_G_PROJ_Q, KC_G_PROJ_Q, KC_G_PROJ_PB};
@@ -1938,12 +2217,14 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             return hipErrorInvalidValue;
         }
     } else {
-        // groups of W.chain_group layers: one wide contraction per group, one short one per layer
+        // groups of W.chain_group layers: one wide contraction per group, then the group's own layers
         const bool k64 = r % 64 == 0;
         const int big_lds = k64 ? SeqShapes<64>::TB::LDS_BYTES : SeqShapes<32>::TB::LDS_BYTES;
         const int small_lds = k64 ? SeqShapes<64>::TS::LDS_BYTES : SeqShapes<32>::TS::LDS_BYTES;
         PAC_HIP_TRY((allow_lds_once<&k_gseq_big<64>>(SeqShapes<64>::TB::LDS_BYTES)));
         PAC_HIP_TRY((allow_lds_once<&k_gseq_big<32>>(SeqShapes<32>::TB::LDS_BYTES)));
+        PAC_HIP_TRY((allow_lds_once<&k_gseq_group<true>>(160 * 1024)));
+        PAC_HIP_TRY((allow_lds_once<&k_gseq_group<false>>(160 * 1024)));
         float *P = (float *)(ws + W.g_P), *ghat = (float *)(ws + W.g_ghat);
         const int g = W.chain_group, ldp = g * r;
         const int rt128 = cdiv(M, kSeqTile), rt64 = cdiv(M, 64), ct64 = cdiv(r, 64);
@@ -1959,6 +2240,23 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             if (have_big) {
                 if (k64) PAC_LAUNCH(prof, st, cls, k_gseq_big<64>, dim3(rt128 * ba.ctiles), dim3(256), big_lds, st, ba);
                 else PAC_LAUNCH(prof, st, cls, k_gseq_big<32>, dim3(rt128 * ba.ctiles), dim3(256), big_lds, st, ba);
+            }
+            if (r <= kGroupMaxR) {
+                // one launch for the group's layers (wider adapters: one launch per layer, below)
+                SeqGroupArgs ga;
+                SeqLayerArgs &la = ga.la;
+                la.A = ba.A; la.Bq = ba.Bq; la.P = have_big ? P : nullptr; la.ldp = ldp; la.pcol0 = 0;
+                la.l = l0; la.L = L; la.r = r; la.M = M; la.d = d;
+                la.kbegin = 0; la.kend = 0; la.ctiles = 0;
+                la.U = pre; la.Gp = ca.Gp; la.chat = chat; la.params = io.params; la.PL = D.PL;
+                la.Hg = fwd ? H : DP; la.ghat = ghat; la.rowsamp = rowsamp;
+                ga.l0 = l0; ga.l1 = l1;
+                ga.Qg = (const bf16_t *)(ws + (fwd ? W.g_QgT : W.g_QgN)) + (int64_t)(l0 / g) * (g * (g - 1) / 2) * r * r;
+                const int lds = (int)group_lds(l1 - l0, r);
+                const dim3 grid(cdiv(M, kChainRows)), block(64 * (r / 32 + kGroupHelpers));
+                if (fwd) PAC_LAUNCH(prof, st, cls, (k_gseq_group<true>), grid, block, lds, st, ga);
+                else PAC_LAUNCH(prof, st, cls, (k_gseq_group<false>), grid, block, lds, st, ga);
+                return;
             }
             for (int q = 0; q < l1 - l0; ++q) {
                 const int l = fwd ? l0 + q : l1 - 1 - q;

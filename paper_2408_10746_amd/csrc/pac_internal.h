@@ -44,6 +44,7 @@ struct WsLayout {
     int64_t g_WuTs, g_Wds;          // bf16 [d][L*r] stacked projection copies
     int64_t g_cusum, g_chat, g_V;   // f32 [L+1][d], [L][r], [L*r][C]
     int64_t g_QpN, g_QpT;           // bf16 [pairs][r][r], both orientations (use_gram 2: [L*r][L*r] each)
+    int64_t g_QgN, g_QgT;           // use_gram 2: bf16 [groups][g (g - 1) / 2][r][r], the pairs inside a group, fragment-major
     int64_t g_DP;                   // bf16 [Mmax][L*r]
     int64_t g_HSpart, g_cspart;     // f32 [max_tiles][L][r]
     int64_t g_zpart, g_zpb;         // f32 [max_tiles][C], [B_max][C]: shares of the logits
