@@ -302,7 +302,17 @@ struct EpiBias {
     const float *bias;
     float *out;
     int ld;
-    __device__ void operator()(int row, int col, float v) const { out[(int64_t)row * ld + col] = v + bias[col]; }
+    static constexpr bool kBatched = true; // the bias is read once, before the stores
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
+    {
+        const float b = bias[min(col, ncols - 1)];
+        if (col >= ncols) return;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = epi_row(row_base, v);
+            if (row < nrows) out[(int64_t)row * ld + col] = acc[v] + b;
+        }
+    }
 };
 template <typename SRC> __global__ __launch_bounds__(256) void k_ldown(DownArgs a)
 {
@@ -331,15 +341,33 @@ struct LinArgs {
     float *out, *out2;
 };
 template <int EPI> struct EpiLin {
+    // every value the epilogue reads is requested (from clamped indices) before the first store: element by element
+    // each load would have to wait behind the store before it, which may alias it as far as the compiler knows
+    static constexpr bool kBatched = true;
     LinArgs a;
-    __device__ void operator()(int row, int col, float v) const
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
     {
-        const int64_t o = (int64_t)row * a.N + col;
-        if (EPI == 0) a.out[o] = v + a.bias[col];
-        if (EPI == 1) a.out[o] = v + a.bias[col] + a.res[o];
-        if (EPI == 2) { const float u = v + a.bias[col]; a.out[o] = u; a.out2[o] = lgelu(u); }
-        if (EPI == 3) a.out[o] = v * lgelu_grad(a.aux[o]);
-        if (EPI == 4) a.out[o] = v;
+        const int cc = min(col, ncols - 1);
+        const float bias = (EPI <= 2) ? a.bias[cc] : 0.f;
+        float x[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t o = (int64_t)min(epi_row(row_base, v), nrows - 1) * a.N + cc;
+            x[v] = EPI == 1 ? a.res[o] : EPI == 3 ? a.aux[o] : 0.f;
+        }
+        if (col >= ncols) return;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = epi_row(row_base, v);
+            if (row < nrows) {
+                const int64_t o = (int64_t)row * a.N + col;
+                if (EPI == 0) a.out[o] = acc[v] + bias;
+                if (EPI == 1) a.out[o] = acc[v] + bias + x[v];
+                if (EPI == 2) { const float u = acc[v] + bias; a.out[o] = u; a.out2[o] = lgelu(u); }
+                if (EPI == 3) a.out[o] = acc[v] * lgelu_grad(x[v]);
+                if (EPI == 4) a.out[o] = acc[v];
+            }
+        }
     }
 };
 template <bool BT, int EPI> __global__ __launch_bounds__(256) void k_llin(LinArgs a)
