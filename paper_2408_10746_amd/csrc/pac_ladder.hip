@@ -369,7 +369,106 @@ template <int EPI> struct EpiLin {
             }
         }
     }
+    // the same for a 16 x 16 block: rows row_base .. row_base + 3 of column col
+    __device__ void batch4(int row_base, int col, const f32x4 &acc, int nrows, int ncols) const
+    {
+        const int cc = min(col, ncols - 1);
+        const float bias = (EPI <= 2) ? a.bias[cc] : 0.f;
+        float x[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int64_t o = (int64_t)min(row_base + v, nrows - 1) * a.N + cc;
+            x[v] = EPI == 1 ? a.res[o] : EPI == 3 ? a.aux[o] : 0.f;
+        }
+        if (col >= ncols) return;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = row_base + v;
+            if (row < nrows) {
+                const int64_t o = (int64_t)row * a.N + col;
+                if (EPI == 0) a.out[o] = acc[v] + bias;
+                if (EPI == 1) a.out[o] = acc[v] + bias + x[v];
+                if (EPI == 2) { const float u = acc[v] + bias; a.out[o] = u; a.out2[o] = lgelu(u); }
+                if (EPI == 3) a.out[o] = acc[v] * lgelu_grad(x[v]);
+                if (EPI == 4) a.out[o] = acc[v];
+            }
+        }
+    }
 };
+
+// The same contraction on a 32 x 32 workgroup tile of 2 x 2 blocks of 16 x 16, one per wavefront (16x16x4 fp32 matrix
+// instructions): four times as many blocks as the 32 x 32 form.  For outputs as narrow as the ladder (N = w): there the
+// 32 x 32 blocks number a third of the SIMDs and a launch with K = 4 w spends 12 k cycles in one block's instructions.
+// A lane reads four consecutive K values of its row and feeds one to each of four instructions (both operands use the
+// same assignment, so the order of K inside a step does not matter).
+constexpr int kTile16Lds = 64 * Stage<float, 4>::LDP * 4;
+template <class ALoad, class BLoad, class Epi>
+__device__ __forceinline__ void gemm_tile16(void *lds, ALoad &al, BLoad &bl, Epi &epi, int kbegin, int kend, int row0,
+                                            int col0, int nrows, int ncols)
+{
+    using S = Stage<float, 4>;
+    float *As = reinterpret_cast<float *>(lds);
+    float *Bs = As + 32 * S::LDP;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1, i = lane & 15, g4 = lane >> 4;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    al.init(row0);
+    bl.init(col0);
+    const int nsteps = (kend - kbegin + S::BK - 1) / S::BK;
+    auto mma = [&]() {
+        const float *ap = As + (wm * 16 + i) * S::LDP + 4 * g4;
+        const float *bp = Bs + (wn * 16 + i) * S::LDP + 4 * g4;
+#pragma unroll
+        for (int kk = 0; kk < S::BK / 16; ++kk) {
+            const f32x4 a4 = *reinterpret_cast<const f32x4 *>(ap + 16 * kk);
+            const f32x4 b4 = *reinterpret_cast<const f32x4 *>(bp + 16 * kk);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[j], b4[j], acc, 0, 0, 0);
+        }
+    };
+    if (nsteps > 0) { // two K steps in flight, as in gemm_tile
+        const int klast = kbegin + (nsteps - 1) * S::BK;
+        al.template fetch<0>(kbegin);
+        bl.template fetch<0>(kbegin);
+        al.template fetch<1>(min(kbegin + S::BK, klast));
+        bl.template fetch<1>(min(kbegin + S::BK, klast));
+        for (int st = 0; st < nsteps; st += 2) {
+            const int k0 = kbegin + st * S::BK;
+            al.template store<0>(As, true);
+            bl.template store<0>(Bs, true);
+            __syncthreads();
+            al.template fetch<0>(min(k0 + 2 * S::BK, klast));
+            bl.template fetch<0>(min(k0 + 2 * S::BK, klast));
+            mma();
+            __syncthreads();
+            const bool live = st + 1 < nsteps;
+            al.template store<1>(As, live);
+            bl.template store<1>(Bs, live);
+            __syncthreads();
+            al.template fetch<1>(min(k0 + 3 * S::BK, klast));
+            bl.template fetch<1>(min(k0 + 3 * S::BK, klast));
+            if (live) mma();
+            __syncthreads();
+        }
+    }
+    epi.batch4(row0 + wm * 16 + 4 * g4, col0 + wn * 16 + i, acc, nrows, ncols);
+}
+template <bool BT, int EPI> __global__ __launch_bounds__(256) void k_llin16(LinArgs a)
+{
+    __shared__ __attribute__((aligned(16))) char smem[kTile16Lds];
+    LoadRowsTC<float, 32, 4> al;
+    al.src = a.A; al.ld = a.lda; al.nrows = a.M; al.klim = a.K;
+    EpiLin<EPI> epi{a};
+    if (BT) {
+        LoadRowsTC<float, 32, 4> bl;
+        bl.src = a.B; bl.ld = a.ldb; bl.nrows = a.N; bl.klim = a.K;
+        gemm_tile16(smem, al, bl, epi, 0, a.K, blockIdx.x * 32, blockIdx.y * 32, a.M, a.N);
+    } else {
+        LoadCols<float, 32, 4, float, false> bl;
+        bl.src = a.B; bl.ld = a.ldb; bl.ncols = a.N; bl.kend = a.K;
+        gemm_tile16(smem, al, bl, epi, 0, a.K, blockIdx.x * 32, blockIdx.y * 32, a.M, a.N);
+    }
+}
 template <bool BT, int EPI> __global__ __launch_bounds__(256) void k_llin(LinArgs a)
 {
     __shared__ __attribute__((aligned(16))) char smem[kTileLds];
@@ -1127,6 +1226,10 @@ void lin(Profiler *prof, hipStream_t st, int cls, const float *A, int lda, const
          const float *bias, const float *res, const float *aux, float *out, float *out2)
 {
     LinArgs a{A, lda, B, ldb, M, N, K, bias, res, aux, out, out2};
+    if (N <= 128 && K > 128) { // narrow output, long contraction: 16 x 16 blocks
+        LAD_LAUNCH(prof, st, cls, (k_llin16<BT, EPI>), dim3(cdivi(M, 32), cdivi(N, 32)), dim3(256), 0, st, a);
+        return;
+    }
     LAD_LAUNCH(prof, st, cls, (k_llin<BT, EPI>), dim3(cdivi(M, 64), cdivi(N, 64)), dim3(256), 0, st, a);
 }
 
