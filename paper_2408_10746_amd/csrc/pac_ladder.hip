@@ -657,6 +657,11 @@ struct AttnArgs {
     int tpr;    // lanes per row: a power of two, 1 .. 8
     int nchunk; // workgroups per sample and head (blockIdx.y): each takes a contiguous share of the rows
 };
+// Probabilities are formed as 2^(score - max) with the scores scaled by log2(e) beforehand (folded into the query's
+// scale): the hardware's exponential is base 2, so a natural exponential costs a multiply and range fix-ups per call,
+// and these kernels are bound by their vector arithmetic.  Results below the normal range flush to zero.
+constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+__device__ __forceinline__ float lexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 // A row is shared by `tpr` neighbouring lanes (a power of two, chosen so that the sample's rows fill the
 // workgroup); each takes every tpr-th key (query) and the partial results are combined with lane exchanges.
 __device__ __forceinline__ float grp_sum(float v, int tpr)
@@ -694,7 +699,7 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_fwd(AttnArgs a)
         float q[DH];
         const float *qp = a.QKV + (int64_t)(m0 + ic) * w3 + h * DH;
 #pragma unroll
-        for (int c = 0; c < DH; ++c) q[c] = qp[c] * a.scale;
+        for (int c = 0; c < DH; ++c) q[c] = qp[c] * (a.scale * kLog2e); // scores in units of ln 2: one exp2 instruction each
         // running maximum, sum and weighted values over this lane's keys
         float mx = -INFINITY, l = 0.f, acc[DH];
 #pragma unroll
@@ -704,14 +709,14 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_fwd(AttnArgs a)
 #pragma unroll
             for (int c = 0; c < DH; ++c) sc += q[c] * ks[j * DH + c];
             const float mn = fmaxf(mx, sc);
-            const float corr = expf(mx - mn), p = expf(sc - mn);
+            const float corr = lexp2(mx - mn), p = lexp2(sc - mn);
             l = l * corr + p;
 #pragma unroll
             for (int c = 0; c < DH; ++c) acc[c] = acc[c] * corr + p * vs[j * DH + c];
             mx = mn;
         }
         const float mall = grp_max(mx, tpr);
-        const float corr = mx == -INFINITY ? 0.f : expf(mx - mall);
+        const float corr = mx == -INFINITY ? 0.f : lexp2(mx - mall);
         l = grp_sum(l * corr, tpr);
         const float inv = 1.f / l;
         float *op = a.O + (int64_t)(m0 + ic) * a.w + h * DH;
@@ -720,7 +725,7 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_fwd(AttnArgs a)
             const float v = grp_sum(acc[c] * corr, tpr) * inv;
             if (live && part == 0) op[c] = v;
         }
-        if (live && part == 0) a.LSE[(int64_t)(m0 + i) * a.nh + h] = mall + logf(l);
+        if (live && part == 0) a.LSE[(int64_t)(m0 + i) * a.nh + h] = mall * kLn2 + logf(l); // natural logarithm
     }
 }
 
@@ -741,7 +746,7 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_bwd(AttnArgs a)
         dos[idx] = a.dO[(int64_t)(m0 + j) * a.w + h * DH + c];
     }
     for (int i = threadIdx.x; i < n; i += 256) {
-        lse[i] = a.LSE[(int64_t)(m0 + i) * a.nh + h];
+        lse[i] = a.LSE[(int64_t)(m0 + i) * a.nh + h] * kLog2e;
         const float *op = a.O + (int64_t)(m0 + i) * a.w + h * DH;
         const float *dp = a.dO + (int64_t)(m0 + i) * a.w + h * DH;
         float D = 0.f;
@@ -759,13 +764,13 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_bwd(AttnArgs a)
         const int ic = live ? i : n - 1;
         float q[DH], go[DH], dq[DH];
 #pragma unroll
-        for (int c = 0; c < DH; ++c) { q[c] = qs[ic * DH + c] * a.scale; go[c] = dos[ic * DH + c]; dq[c] = 0.f; }
+        for (int c = 0; c < DH; ++c) { q[c] = qs[ic * DH + c] * (a.scale * kLog2e); go[c] = dos[ic * DH + c]; dq[c] = 0.f; }
         const float li = lse[ic], Di = Dr[ic];
         for (int j = part; j < n; j += tpr) {
             float sc = 0.f, dpv = 0.f;
 #pragma unroll
             for (int c = 0; c < DH; ++c) { sc += q[c] * ks[j * DH + c]; dpv += go[c] * vs[j * DH + c]; }
-            const float ds = expf(sc - li) * (dpv - Di);
+            const float ds = lexp2(sc - li) * (dpv - Di);
 #pragma unroll
             for (int c = 0; c < DH; ++c) dq[c] += ds * ks[j * DH + c];
         }
@@ -783,12 +788,12 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_bwd(AttnArgs a)
         const int jc = live ? j : n - 1;
         float k[DH], v[DH], dk[DH], dv[DH];
 #pragma unroll
-        for (int c = 0; c < DH; ++c) { k[c] = ks[jc * DH + c] * a.scale; v[c] = vs[jc * DH + c]; dk[c] = 0.f; dv[c] = 0.f; }
+        for (int c = 0; c < DH; ++c) { k[c] = ks[jc * DH + c] * (a.scale * kLog2e); v[c] = vs[jc * DH + c]; dk[c] = 0.f; dv[c] = 0.f; }
         for (int i = part; i < n; i += tpr) {
             float sc = 0.f, dpv = 0.f;
 #pragma unroll
             for (int c = 0; c < DH; ++c) { sc += qs[i * DH + c] * k[c]; dpv += dos[i * DH + c] * v[c]; }
-            const float p = expf(sc - lse[i]);
+            const float p = lexp2(sc - lse[i]);
             const float ds = p * (dpv - Dr[i]);
 #pragma unroll
             for (int c = 0; c < DH; ++c) { dv[c] += p * dos[i * DH + c]; dk[c] += ds * qs[i * DH + c]; }
