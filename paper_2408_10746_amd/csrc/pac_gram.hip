@@ -103,7 +103,10 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     W.se = se < 1 ? 1 : (se > 16 ? 16 : se);
     if (cdiv(W.max_tiles, W.se) > kMaxSplitTiles) W.se = cdiv(W.max_tiles, kMaxSplitTiles); // LDS tile table of k_gtokred
     const int tg = cdiv(Lr, 128);
-    int sg = cdiv(256, (int64_t)tg * (tg + 1) / 2);
+    // Token splits of the Gram matrix: about 128 of its workgroups (they run beside E's; at the T5-Base shape four
+    // splits of 45 tiles measured 2 us faster in this launch than eight, and the ordered sum afterwards reads half the
+    // partials).
+    int sg = cdiv(128, (int64_t)tg * (tg + 1) / 2);
     // A power of two: the Gram tiles are numbered with the split fastest and dealt round-robin over the eight
     // dies, so a die then only ever reads the token rows of its own split(s) of H and DP (with six splits
     // every die fetched most of both matrices: 63 MB over the fabric for 19 MB of operands).
