@@ -96,8 +96,8 @@ void plan_gram_workspace(const Dims &D, WsLayout &W, int64_t &o)
     const int e_tiles = D.L * cdiv(D.d, kETileCols) * cdiv(D.r, 128);
     // Token splits of E (measured): with few tiles (T5-Base-shaped: 72) E's workgroups and the Gram tiles that
     // run beside them should all be resident at once, two per compute unit; with more tiles than that anyway
-    // (Large-shaped: 192) shorter E workgroups balance better.
-    int se = cdiv(e_tiles >= 128 ? 432 : 288, e_tiles);
+    // (Large-shaped: 192) two splits measured best (113 us for the launch against 117 with three, 152 with one).
+    int se = cdiv(e_tiles >= 128 ? 384 : 288, e_tiles);
     const int max_by_rows = (int)((D.Mmax + 127) / 128);
     if (se > max_by_rows) se = max_by_rows;
     W.se = se < 1 ? 1 : (se > 16 ? 16 : se);
