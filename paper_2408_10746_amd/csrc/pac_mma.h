@@ -147,6 +147,7 @@ __device__ __forceinline__ void gemm_nt(char *lds /* TL::LDS_BYTES, 1 KB aligned
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     if (ks + 1 < KS) rd(ks + 1);
+                    __builtin_amdgcn_sched_barrier(0); // the next sub-step's reads stay ahead of this one's matrix instructions
 #pragma unroll
                     for (int q = ks * TL::NI / KS; q < (ks + 1) * TL::NI / KS; ++q)
                         dma16(gp[q] + k0n, lds + nslot * TL::STAGE_BYTES + ldso[q]);
