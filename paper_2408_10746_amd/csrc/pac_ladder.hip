@@ -487,6 +487,190 @@ template <bool BT, int EPI> __global__ __launch_bounds__(256) void k_llin(LinArg
 }
 
 // ---------------------------------------------------------------------------
+// The forward tail of a ladder layer in one launch (w <= 128): output projection + x, LayerNorm 2, FFN in + GELU,
+// FFN out + t, for 16 token rows per workgroup.  Everything a later kernel reads is written exactly as the separate
+// launches write it (T, TN, the LayerNorm statistics, F1, G, A); between the four steps the tile stays in LDS.
+// Matrix instructions: 16x16x4 fp32, A operand = the tile's activations (lane (i, g4): token row i), B operand = the
+// weight as stored ([K][N], N contiguous), read straight from global memory (L2): a lane takes two neighbouring
+// columns 32 p + 2 i, + 1 per load, one for each of two accumulators, so that loads and stores are 8 bytes wide and
+// rows of 128 bytes; K is walked in blocks of 8 (lane g4 takes k = 2 g4 + s of a block for its s-th instruction, the
+// same assignment on both operands).  The two contractions with a narrow output (N = w) split K over the four
+// wavefronts and meet in LDS; FFN in splits its 4 w columns over them.
+// ---------------------------------------------------------------------------
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+struct MlpArgs {
+    const float *O, *X; // [M][w]: attention output, the layer's input (residual)
+    const float *Wo, *bo, *g2, *h2, *W1, *b1, *W2, *b2;
+    float *T, *TN, *st2, *F1, *G, *A;
+    int M;
+};
+// A chunk of WB blocks of 8 K values of a weight, in registers: rows kbeg + 8 (c WB + b) + 2 g4 + s, columns
+// n0 + 32 p + 2 i, + 1.  Weights depend on nothing computed here, so a chunk is requested well before it is used
+// (the first chunks of the next contraction while the tile is still in the previous step's epilogue); the scheduling
+// barriers keep the compiler from moving the requests down to their uses.
+template <int WB> struct WChunk {
+    f32x2 r[WB][2][WB];
+    __device__ __forceinline__ void load(const float *W, int ldw, int kbeg, int n0, int c, int i, int g4)
+    {
+#pragma unroll
+        for (int b = 0; b < WB; ++b)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int pq = 0; pq < WB; ++pq)
+                    r[b][s2][pq] = *reinterpret_cast<const f32x2 *>(W + (int64_t)(kbeg + 8 * (c * WB + b) + 2 * g4 + s2) * ldw + n0 + 32 * pq + 2 * i);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // acc += Alds[16][the chunk's K values] (chunk)
+    __device__ __forceinline__ void mul(const float *Alds, int pitch, int kbeg, int c, f32x4 (&acc)[2 * WB], int i, int g4) const
+    {
+#pragma unroll
+        for (int b = 0; b < WB; ++b) {
+            const f32x2 av = *reinterpret_cast<const f32x2 *>(Alds + i * pitch + kbeg + 8 * (c * WB + b) + 2 * g4);
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int pq = 0; pq < WB; ++pq) {
+                    acc[2 * pq] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s2], r[b][s2][pq][0], acc[2 * pq], 0, 0, 0);
+                    acc[2 * pq + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s2], r[b][s2][pq][1], acc[2 * pq + 1], 0, 0, 0);
+                }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+};
+template <int WB> constexpr int mlp_lds_bytes() { return (96 * (32 * WB + 4) + 16 * (128 * WB + 4)) * 4; }
+
+template <int WB> __global__ __launch_bounds__(256) void k_lmlp_fwd(MlpArgs a)
+{
+    constexpr int w = 32 * WB, f = 4 * w, NB = 2 * WB, PW = w + 4, PF = f + 4, T = 16;
+    extern __shared__ __attribute__((aligned(16))) float msm[];
+    float *bufA = msm, *bufT = bufA + T * PW, *bufG = bufT + T * PW, *part = bufG + T * PF; // part [4][T][PW]
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, i = lane & 15, g4 = lane >> 4;
+    const int m0 = blockIdx.x * T, M = a.M;
+    WChunk<WB> c0, c1;
+    c0.load(a.Wo, w, wave * (w / 4), 0, 0, i, g4);
+    for (int idx = t; idx < T * (w / 4); idx += 256) {
+        const int row = idx / (w / 4), c4 = idx % (w / 4), m = min(m0 + row, M - 1);
+        *reinterpret_cast<f32x4 *>(bufA + row * PW + 4 * c4) = *reinterpret_cast<const f32x4 *>(a.O + (int64_t)m * w + 4 * c4);
+    }
+    __syncthreads();
+    f32x4 acc[NB];
+    auto zero = [&]() {
+#pragma unroll
+        for (int q = 0; q < NB; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto to_part = [&]() { // this wavefront's share of K: rows 4 g4 + v, columns 32 p + 2 i, + 1
+        float *pp = part + (size_t)wave * T * PW;
+#pragma unroll
+        for (int pq = 0; pq < WB; ++pq)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                *reinterpret_cast<f32x2 *>(pp + (4 * g4 + v) * PW + 32 * pq + 2 * i) = f32x2{acc[2 * pq][v], acc[2 * pq + 1][v]};
+    };
+    // ---- t = o W_o + b_o + x ----
+    zero();
+    c0.mul(bufA, PW, wave * (w / 4), 0, acc, i, g4);
+    c0.load(a.W1, f, 0, wave * w, 0, i, g4); // the first half of W_1's share, used after the LayerNorm
+    c1.load(a.W1, f, 0, wave * w, 1, i, g4);
+    to_part();
+    __syncthreads();
+    for (int idx = t; idx < T * (w / 2); idx += 256) {
+        const int row = idx / (w / 2), col = 2 * (idx % (w / 2)), m = m0 + row, mc = min(m, M - 1);
+        const f32x2 xr = *reinterpret_cast<const f32x2 *>(a.X + (int64_t)mc * w + col);
+        f32x2 v = {a.bo[col] + xr[0], a.bo[col + 1] + xr[1]};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x2 pv = *reinterpret_cast<const f32x2 *>(part + ((size_t)q * T + row) * PW + col);
+            v[0] += pv[0];
+            v[1] += pv[1];
+        }
+        *reinterpret_cast<f32x2 *>(bufT + row * PW + col) = v;
+        if (m < M) *reinterpret_cast<f32x2 *>(a.T + (int64_t)m * w + col) = v;
+    }
+    __syncthreads();
+    // ---- LayerNorm 2: sixteen threads per row ----
+    {
+        const int row = t >> 4, sub = t & 15, m = m0 + row;
+        float x[NB], sum = 0.f;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            x[q] = bufT[row * PW + sub + 16 * q];
+            sum += x[q];
+        }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
+        const float mu = sum / (float)w;
+        float ss = 0.f;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) ss += (x[q] - mu) * (x[q] - mu);
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) ss += __shfl_xor(ss, o, 64);
+        const float rstd = 1.f / sqrtf(ss / (float)w + 1e-5f);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int c = sub + 16 * q;
+            const float y = (x[q] - mu) * rstd * a.g2[c] + a.h2[c];
+            bufA[row * PW + c] = y;
+            if (m < M) a.TN[(int64_t)m * w + c] = y;
+        }
+        if (sub == 0 && m < M) {
+            a.st2[2 * (int64_t)m] = mu;
+            a.st2[2 * (int64_t)m + 1] = rstd;
+        }
+    }
+    __syncthreads();
+    // ---- f1 = tn W_1 + b_1, g = GELU(f1): this wavefront's w columns ----
+    zero();
+    c0.mul(bufA, PW, 0, 0, acc, i, g4);
+    c0.load(a.W1, f, 0, wave * w, 2, i, g4);
+    c1.mul(bufA, PW, 0, 1, acc, i, g4);
+    c1.load(a.W1, f, 0, wave * w, 3, i, g4);
+    c0.mul(bufA, PW, 0, 2, acc, i, g4);
+    c0.load(a.W2, w, wave * w, 0, 0, i, g4); // W_2's first half, used after the GELU
+    c1.mul(bufA, PW, 0, 3, acc, i, g4);
+    c1.load(a.W2, w, wave * w, 0, 1, i, g4);
+#pragma unroll
+    for (int pq = 0; pq < WB; ++pq) {
+        const int col = wave * w + 32 * pq + 2 * i;
+        const f32x2 bb = *reinterpret_cast<const f32x2 *>(a.b1 + col);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = 4 * g4 + v, m = m0 + row;
+            const f32x2 u = {acc[2 * pq][v] + bb[0], acc[2 * pq + 1][v] + bb[1]};
+            const f32x2 gl = {lgelu(u[0]), lgelu(u[1])};
+            *reinterpret_cast<f32x2 *>(bufG + row * PF + col) = gl;
+            if (m < M) {
+                *reinterpret_cast<f32x2 *>(a.F1 + (int64_t)m * f + col) = u;
+                *reinterpret_cast<f32x2 *>(a.G + (int64_t)m * f + col) = gl;
+            }
+        }
+    }
+    __syncthreads();
+    // ---- a = g W_2 + b_2 + t ----
+    zero();
+    c0.mul(bufG, PF, wave * w, 0, acc, i, g4);
+    c0.load(a.W2, w, wave * w, 0, 2, i, g4);
+    c1.mul(bufG, PF, wave * w, 1, acc, i, g4);
+    c1.load(a.W2, w, wave * w, 0, 3, i, g4);
+    c0.mul(bufG, PF, wave * w, 2, acc, i, g4);
+    c1.mul(bufG, PF, wave * w, 3, acc, i, g4);
+    to_part();
+    __syncthreads();
+    for (int idx = t; idx < T * (w / 2); idx += 256) {
+        const int row = idx / (w / 2), col = 2 * (idx % (w / 2)), m = m0 + row;
+        const f32x2 tr = *reinterpret_cast<const f32x2 *>(bufT + row * PW + col);
+        f32x2 v = {a.b2[col] + tr[0], a.b2[col + 1] + tr[1]};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x2 pv = *reinterpret_cast<const f32x2 *>(part + ((size_t)q * T + row) * PW + col);
+            v[0] += pv[0];
+            v[1] += pv[1];
+        }
+        if (m < M) *reinterpret_cast<f32x2 *>(a.A + (int64_t)m * w + col) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Row kernels (one wavefront per token row, lane owns columns lane, lane + 64, ...; w <= 256)
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v)
@@ -1277,6 +1461,21 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
         AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), nullptr, nullptr, w,
                     a.nh, (int)(Mm / a.Bmax), scale, tpr, nchunk};
         LAD_TRY(attn(a.dh, false, at, B, st, prof));
+        if (w <= 128) { // the rest of the layer in one launch
+            MlpArgs ma{lay(a.O, l, w), lay(a.X, l, w), pl + a.fo[F_WO], pl + a.fo[F_BO], pl + a.fo[F_G2], pl + a.fo[F_H2],
+                       pl + a.fo[F_W1], pl + a.fo[F_B1], pl + a.fo[F_W2], pl + a.fo[F_B2], lay(a.T, l, w), lay(a.TN, l, w),
+                       lay(a.st2, l, 2), lay(a.F1, l, f), lay(a.G, l, f), lay(a.A, l, w), M};
+            const dim3 grid(cdivi(M, 16));
+            switch (w / 32) {
+            case 1: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lmlp_fwd<1>), grid, dim3(256), mlp_lds_bytes<1>(), st, ma); break;
+            case 2: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lmlp_fwd<2>), grid, dim3(256), mlp_lds_bytes<2>(), st, ma); break;
+            case 3: LAD_TRY((lds_once<&k_lmlp_fwd<3>>(mlp_lds_bytes<3>())));
+                    LAD_LAUNCH(prof, st, KC_L_LIN, (k_lmlp_fwd<3>), grid, dim3(256), mlp_lds_bytes<3>(), st, ma); break;
+            default: LAD_TRY((lds_once<&k_lmlp_fwd<4>>(mlp_lds_bytes<4>())));
+                    LAD_LAUNCH(prof, st, KC_L_LIN, (k_lmlp_fwd<4>), grid, dim3(256), mlp_lds_bytes<4>(), st, ma); break;
+            }
+            continue;
+        }
         lin<false, 1>(prof, st, KC_L_LIN, lay(a.O, l, w), w, pl + a.fo[F_WO], w, M, w, w, pl + a.fo[F_BO], lay(a.X, l, w),
                       nullptr, lay(a.T, l, w), nullptr);
         LnFwdArgs n2{lay(a.T, l, w), nullptr, nullptr, pl + a.fo[F_G2], pl + a.fo[F_H2], nullptr, lay(a.TN, l, w),
