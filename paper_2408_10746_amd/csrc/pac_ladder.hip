@@ -59,6 +59,7 @@ struct Lad {
     int64_t U, X, XN, QKV, LSE, O, T, TN, F1, G, A, st1, st2;  // [L][Mmax][...]
     int64_t DA, DF1, DT, DQKV, DX;                             // [L][Mmax][...]
     int64_t DTN, DO_, DXN;                                     // [Mmax][w]
+    int64_t WT;                                                // [L][2 w f + w w]: W_2^T, W_1^T, W_o^T
     int64_t ln1p, ln2p, dlamp;                                 // [L][nblk][2][w] x2, [L][nblk]
     int64_t bmean, abar, pooled, logits, dz, dp, daL, lossp;
     int64_t part;                                              // [splits][L * PLb]
@@ -109,6 +110,7 @@ bool lad_plan(const Dims &D, int heads, Lad &a)
     a.DA = take(LM * w * 4); a.DF1 = take(LM * f * 4); a.DT = take(LM * w * 4); a.DQKV = take(LM * 3 * w * 4);
     a.DX = take(LM * w * 4);
     a.DTN = take(M * w * 4); a.DO_ = take(M * w * 4); a.DXN = take(M * w * 4);
+    a.WT = take((int64_t)a.L * (2 * w * f + w * w) * 4); // transposed copies for the fused reverse tail
     a.nblk = cdivi(M, kLnRows);
     a.ln1p = take((int64_t)a.L * a.nblk * 2 * w * 4); a.ln2p = take((int64_t)a.L * a.nblk * 2 * w * 4);
     a.dlamp = take((int64_t)a.L * a.nblk * 4);
@@ -667,6 +669,159 @@ template <int WB> __global__ __launch_bounds__(256) void k_lmlp_fwd(MlpArgs a)
             v[1] += pv[1];
         }
         if (m < M) *reinterpret_cast<f32x2 *>(a.A + (int64_t)m * w + col) = v;
+    }
+}
+
+// The reverse of that tail in one launch: dg = da W_2^T, df1 = dg GELU'(f1), dtn = df1 W_1^T, the reverse of
+// LayerNorm 2 (dt, with its partial sums for the gain and offset gradients of this 16-row block), do = dt W_o^T.
+// The three weights are read from transposed copies made once per step (k_ltrans): contracted along their contiguous
+// index straight from the parameter vector, a load instruction touched sixteen rows of 32 bytes and the launch took
+// as long as the four it replaces.
+// WT[l] = [W_2^T (w x 4w) | W_1^T (4w x w) | W_o^T (w x w)] of every layer
+__global__ __launch_bounds__(256) void k_ltrans(const float *params, int64_t PLb, int64_t oW2, int64_t oW1, int64_t oWo, int w,
+                                               float *WT)
+{
+    const int f = 4 * w, per = 2 * w * f + w * w, l = blockIdx.y;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= per) return;
+    const float *pl = params + (int64_t)l * PLb;
+    float v;
+    if (e < w * f) v = pl[oW2 + (int64_t)(e % f) * w + e / f];                                 // W_2 [4w][w]
+    else if (e < 2 * w * f) v = pl[oW1 + (int64_t)((e - w * f) % w) * f + (e - w * f) / w];    // W_1 [w][4w]
+    else v = pl[oWo + (int64_t)((e - 2 * w * f) % w) * w + (e - 2 * w * f) / w];               // W_o [w][w]
+    WT[(int64_t)l * per + e] = v;
+}
+struct MlpBwdArgs {
+    const float *DA;                 // [M][w]: gradient of the layer's output (also the residual path of LayerNorm 2)
+    const float *F1, *T, *st2;       // saved by the forward tail
+    const float *W2T, *W1T, *WoT, *g2; // [w][4w], [4w][w], [w][w]
+    float *DF1, *DT, *DO;            // [M][4w], [M][w], [M][w]
+    float *ln2p;                     // this layer's [blocks][2][w] partial sums
+    int M;
+};
+template <int WB> constexpr int mlp_bwd_lds_bytes() { return (112 * (32 * WB + 4) + 16 * (128 * WB + 4)) * 4; }
+
+template <int WB> __global__ __launch_bounds__(256) void k_lmlp_bwd(MlpBwdArgs a)
+{
+    constexpr int w = 32 * WB, f = 4 * w, NB = 2 * WB, PW = w + 4, PF = f + 4, T = 16;
+    extern __shared__ __attribute__((aligned(16))) float msm[];
+    float *bufD = msm, *bufA = bufD + T * PW, *bufT = bufA + T * PW, *bufG = bufT + T * PW, *part = bufG + T * PF; // part [4][T][PW]
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, i = lane & 15, g4 = lane >> 4;
+    const int m0 = blockIdx.x * T, M = a.M;
+    WChunk<WB> c0, c1;
+    // dg: this wavefront's w columns of 4 w, K = w = four chunks
+    c0.load(a.W2T, f, 0, wave * w, 0, i, g4);
+    c1.load(a.W2T, f, 0, wave * w, 1, i, g4);
+    for (int idx = t; idx < T * (w / 4); idx += 256) {
+        const int row = idx / (w / 4), c4 = idx % (w / 4), m = min(m0 + row, M - 1);
+        *reinterpret_cast<f32x4 *>(bufD + row * PW + 4 * c4) = *reinterpret_cast<const f32x4 *>(a.DA + (int64_t)m * w + 4 * c4);
+    }
+    // f1 of this lane's outputs: rows 4 g4 + v, columns wave w + 32 p + 2 i, + 1
+    f32x2 f1v[WB][4];
+#pragma unroll
+    for (int pq = 0; pq < WB; ++pq)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            f1v[pq][v] = *reinterpret_cast<const f32x2 *>(a.F1 + (int64_t)min(m0 + 4 * g4 + v, M - 1) * f + wave * w + 32 * pq + 2 * i);
+    __syncthreads();
+    f32x4 acc[NB];
+    auto zero = [&]() {
+#pragma unroll
+        for (int q = 0; q < NB; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto to_part = [&]() {
+        float *pp = part + (size_t)wave * T * PW;
+#pragma unroll
+        for (int pq = 0; pq < WB; ++pq)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                *reinterpret_cast<f32x2 *>(pp + (4 * g4 + v) * PW + 32 * pq + 2 * i) = f32x2{acc[2 * pq][v], acc[2 * pq + 1][v]};
+    };
+    zero();
+    c0.mul(bufD, PW, 0, 0, acc, i, g4);
+    c0.load(a.W2T, f, 0, wave * w, 2, i, g4);
+    c1.mul(bufD, PW, 0, 1, acc, i, g4);
+    c1.load(a.W2T, f, 0, wave * w, 3, i, g4);
+    c0.mul(bufD, PW, 0, 2, acc, i, g4);
+    c0.load(a.W1T, w, wave * w, 0, 0, i, g4); // dtn: K = 4 w split over the wavefronts
+    c1.mul(bufD, PW, 0, 3, acc, i, g4);
+    c1.load(a.W1T, w, wave * w, 0, 1, i, g4);
+#pragma unroll
+    for (int pq = 0; pq < WB; ++pq)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = 4 * g4 + v, m = m0 + row, col = wave * w + 32 * pq + 2 * i;
+            const f32x2 d = {acc[2 * pq][v] * lgelu_grad(f1v[pq][v][0]), acc[2 * pq + 1][v] * lgelu_grad(f1v[pq][v][1])};
+            *reinterpret_cast<f32x2 *>(bufG + row * PF + col) = d;
+            if (m < M) *reinterpret_cast<f32x2 *>(a.DF1 + (int64_t)m * f + col) = d;
+        }
+    __syncthreads();
+    zero();
+    c0.mul(bufG, PF, wave * w, 0, acc, i, g4);
+    c0.load(a.W1T, w, wave * w, 0, 2, i, g4);
+    c1.mul(bufG, PF, wave * w, 1, acc, i, g4);
+    c1.load(a.W1T, w, wave * w, 0, 3, i, g4);
+    c0.mul(bufG, PF, wave * w, 2, acc, i, g4);
+    c0.load(a.WoT, w, wave * (w / 4), 0, 0, i, g4); // do: K = w split over the wavefronts
+    c1.mul(bufG, PF, wave * w, 3, acc, i, g4);
+    to_part();
+    __syncthreads();
+    for (int idx = t; idx < T * w; idx += 256) {
+        const int row = idx / w, col = idx % w;
+        bufA[row * PW + col] = ((part[((size_t)0 * T + row) * PW + col] + part[((size_t)1 * T + row) * PW + col]) +
+                                part[((size_t)2 * T + row) * PW + col]) + part[((size_t)3 * T + row) * PW + col];
+    }
+    __syncthreads();
+    // ---- reverse of LayerNorm 2: sixteen threads per row; dy xh and dy of every row go to `part` for the block sums ----
+    {
+        const int row = t >> 4, sub = t & 15, m = m0 + row, mc = min(m, M - 1);
+        const bool rowok = m < M;
+        const float mu = a.st2[2 * (int64_t)mc], rstd = a.st2[2 * (int64_t)mc + 1];
+        float xh[NB], dxh[NB], s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int c = sub + 16 * q;
+            const float dy = rowok ? bufA[row * PW + c] : 0.f;
+            xh[q] = rowok ? (a.T[(int64_t)mc * w + c] - mu) * rstd : 0.f;
+            dxh[q] = dy * a.g2[c];
+            part[(size_t)row * PW + c] = dy * xh[q];
+            part[((size_t)T + row) * PW + c] = dy;
+            s1 += dxh[q];
+            s2 += dxh[q] * xh[q];
+        }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+            s1 += __shfl_xor(s1, o, 64);
+            s2 += __shfl_xor(s2, o, 64);
+        }
+        const float m1 = s1 / (float)w, m2 = s2 / (float)w;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int c = sub + 16 * q;
+            const float dx = bufD[row * PW + c] + rstd * (dxh[q] - m1 - xh[q] * m2);
+            bufT[row * PW + c] = dx;
+            if (rowok) a.DT[(int64_t)m * w + c] = dx;
+        }
+    }
+    __syncthreads();
+    for (int c = t; c < 2 * w; c += 256) {
+        const int which = c / w, col = c % w;
+        float sum = 0.f;
+#pragma unroll
+        for (int row = 0; row < T; ++row) sum += part[((size_t)which * T + row) * PW + col];
+        a.ln2p[(int64_t)blockIdx.x * 2 * w + c] = sum;
+    }
+    __syncthreads();
+    // ---- do = dt W_o^T ----
+    zero();
+    c0.mul(bufT, PW, wave * (w / 4), 0, acc, i, g4);
+    to_part();
+    __syncthreads();
+    for (int idx = t; idx < T * w; idx += 256) {
+        const int row = idx / w, col = idx % w, m = m0 + row;
+        if (m < M)
+            a.DO[(int64_t)m * w + col] = ((part[((size_t)0 * T + row) * PW + col] + part[((size_t)1 * T + row) * PW + col]) +
+                                          part[((size_t)2 * T + row) * PW + col]) + part[((size_t)3 * T + row) * PW + col];
     }
 }
 
@@ -1496,10 +1651,27 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
     if (!grads) return hipGetLastError();
     LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_c, dim3(B, cdivi(w, 16)), dim3(256), 0, st, h);
 
+    if (w <= 128)
+        LAD_LAUNCH(prof, st, KC_SETUP, k_ltrans, dim3(cdivi(2 * w * f + w * w, 256), L), dim3(256), 0, st, params, a.PLb,
+                   a.fo[F_W2], a.fo[F_W1], a.fo[F_WO], w, F(a.WT));
     for (int l = L - 1; l >= 0; --l) {
         const float *pl = params + (int64_t)l * a.PLb;
         float *DA = lay(a.DA, l, w), *DF1 = lay(a.DF1, l, f), *DT = lay(a.DT, l, w), *DQKV = lay(a.DQKV, l, 3 * w);
         float *DX = lay(a.DX, l, w);
+        if (w <= 128) { // the reverse of the layer's tail in one launch
+            const float *wt = F(a.WT) + (int64_t)l * (2 * w * f + w * w);
+            MlpBwdArgs mb{DA, lay(a.F1, l, f), lay(a.T, l, w), lay(a.st2, l, 2), wt, wt + (int64_t)w * f, wt + (int64_t)2 * w * f,
+                          pl + a.fo[F_G2], DF1, DT, F(a.DO_), F(a.ln2p) + (int64_t)l * nblk * 2 * w, M};
+            const dim3 grid(cdivi(M, 16));
+            switch (w / 32) {
+            case 1: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lmlp_bwd<1>), grid, dim3(256), mlp_bwd_lds_bytes<1>(), st, mb); break;
+            case 2: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lmlp_bwd<2>), grid, dim3(256), mlp_bwd_lds_bytes<2>(), st, mb); break;
+            case 3: LAD_TRY((lds_once<&k_lmlp_bwd<3>>(mlp_bwd_lds_bytes<3>())));
+                    LAD_LAUNCH(prof, st, KC_L_LIN, (k_lmlp_bwd<3>), grid, dim3(256), mlp_bwd_lds_bytes<3>(), st, mb); break;
+            default: LAD_TRY((lds_once<&k_lmlp_bwd<4>>(mlp_bwd_lds_bytes<4>())));
+                    LAD_LAUNCH(prof, st, KC_L_LIN, (k_lmlp_bwd<4>), grid, dim3(256), mlp_bwd_lds_bytes<4>(), st, mb); break;
+            }
+        } else {
         // dg = da W_2^T, df1 = dg * GELU'(f1)
         lin<true, 3>(prof, st, KC_L_LIN, DA, w, pl + a.fo[F_W2], w, M, f, w, nullptr, nullptr, lay(a.F1, l, f), DF1, nullptr);
         // dtn = df1 W_1^T
@@ -1509,6 +1681,7 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
         LAD_LAUNCH(prof, st, KC_L_ROW, (k_lln_bwd<false>), dim3(cdivi(M, kLnRows)), dim3(256), 0, st, b2);
         // do = dt W_o^T
         lin<true, 4>(prof, st, KC_L_LIN, DT, w, pl + a.fo[F_WO], w, M, w, w, nullptr, nullptr, nullptr, F(a.DO_), nullptr);
+        }
         AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), F(a.DO_), DQKV, w,
                     a.nh, (int)(Mm / a.Bmax), scale, tpr, nchunk};
         LAD_TRY(attn(a.dh, true, at, B, st, prof));
