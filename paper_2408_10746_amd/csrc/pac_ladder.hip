@@ -59,7 +59,7 @@ struct Lad {
     int64_t U, X, XN, QKV, LSE, O, T, TN, F1, G, A, st1, st2;  // [L][Mmax][...]
     int64_t DA, DF1, DT, DQKV, DX;                             // [L][Mmax][...]
     int64_t DTN, DO_, DXN;                                     // [Mmax][w]
-    int64_t WT;                                                // [L][2 w f + w w]: W_2^T, W_1^T, W_o^T
+    int64_t WT;                                                // [L][2 w f + 4 w w]: W_2^T, W_1^T, W_o^T, W_qkv^T
     int64_t ln1p, ln2p, dlamp;                                 // [L][nblk][2][w] x2, [L][nblk]
     int64_t bmean, abar, pooled, logits, dz, dp, daL, lossp;
     int64_t part;                                              // [splits][L * PLb]
@@ -110,7 +110,7 @@ bool lad_plan(const Dims &D, int heads, Lad &a)
     a.DA = take(LM * w * 4); a.DF1 = take(LM * f * 4); a.DT = take(LM * w * 4); a.DQKV = take(LM * 3 * w * 4);
     a.DX = take(LM * w * 4);
     a.DTN = take(M * w * 4); a.DO_ = take(M * w * 4); a.DXN = take(M * w * 4);
-    a.WT = take((int64_t)a.L * (2 * w * f + w * w) * 4); // transposed copies for the fused reverse tail
+    a.WT = take((int64_t)a.L * (2 * w * f + 4 * w * w) * 4); // transposed copies for the fused reverse kernels
     a.nblk = cdivi(M, kLnRows);
     a.ln1p = take((int64_t)a.L * a.nblk * 2 * w * 4); a.ln2p = take((int64_t)a.L * a.nblk * 2 * w * 4);
     a.dlamp = take((int64_t)a.L * a.nblk * 4);
@@ -677,18 +677,19 @@ template <int WB> __global__ __launch_bounds__(256) void k_lmlp_fwd(MlpArgs a)
 // The three weights are read from transposed copies made once per step (k_ltrans): contracted along their contiguous
 // index straight from the parameter vector, a load instruction touched sixteen rows of 32 bytes and the launch took
 // as long as the four it replaces.
-// WT[l] = [W_2^T (w x 4w) | W_1^T (4w x w) | W_o^T (w x w)] of every layer
-__global__ __launch_bounds__(256) void k_ltrans(const float *params, int64_t PLb, int64_t oW2, int64_t oW1, int64_t oWo, int w,
-                                               float *WT)
+// WT[l] = [W_2^T (w x 4w) | W_1^T (4w x w) | W_o^T (w x w) | W_qkv^T (3w x w)] of every layer
+__global__ __launch_bounds__(256) void k_ltrans(const float *params, int64_t PLb, int64_t oW2, int64_t oW1, int64_t oWo,
+                                               int64_t oWqkv, int w, float *WT)
 {
-    const int f = 4 * w, per = 2 * w * f + w * w, l = blockIdx.y;
+    const int f = 4 * w, per = 2 * w * f + 4 * w * w, l = blockIdx.y;
     const int e = blockIdx.x * 256 + threadIdx.x;
     if (e >= per) return;
     const float *pl = params + (int64_t)l * PLb;
     float v;
     if (e < w * f) v = pl[oW2 + (int64_t)(e % f) * w + e / f];                                 // W_2 [4w][w]
     else if (e < 2 * w * f) v = pl[oW1 + (int64_t)((e - w * f) % w) * f + (e - w * f) / w];    // W_1 [w][4w]
-    else v = pl[oWo + (int64_t)((e - 2 * w * f) % w) * w + (e - 2 * w * f) / w];               // W_o [w][w]
+    else if (e < 2 * w * f + w * w) v = pl[oWo + (int64_t)((e - 2 * w * f) % w) * w + (e - 2 * w * f) / w]; // W_o [w][w]
+    else v = pl[oWqkv + (int64_t)((e - 2 * w * f - w * w) % w) * 3 * w + (e - 2 * w * f - w * w) / w];        // W_qkv [w][3w]
     WT[(int64_t)l * per + e] = v;
 }
 struct MlpBwdArgs {
@@ -823,6 +824,177 @@ template <int WB> __global__ __launch_bounds__(256) void k_lmlp_bwd(MlpBwdArgs a
             a.DO[(int64_t)m * w + col] = ((part[((size_t)0 * T + row) * PW + col] + part[((size_t)1 * T + row) * PW + col]) +
                                           part[((size_t)2 * T + row) * PW + col]) + part[((size_t)3 * T + row) * PW + col];
     }
+}
+
+// The head of a ladder layer in one launch (w <= 128): gate mix x = lambda u + (1 - lambda) a_prev, LayerNorm 1 and the
+// fused q, k, v projection for 16 token rows; three wavefronts take w of the 3 w output columns each.
+struct QkvArgs {
+    const float *U, *Aprev, *lam; // Aprev null in the first layer
+    const float *g1, *h1, *Wqkv, *bqkv;
+    float *X, *XN, *st1, *QKV;
+    int M;
+};
+template <int WB> __global__ __launch_bounds__(256) void k_lqkv_fwd(QkvArgs a)
+{
+    constexpr int w = 32 * WB, NB = 2 * WB, PW = w + 4, T = 16;
+    __shared__ __attribute__((aligned(16))) float bufA[T * PW];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, i = lane & 15, g4 = lane >> 4;
+    const int m0 = blockIdx.x * T, M = a.M;
+    WChunk<WB> c0, c1;
+    if (wave < 3) {
+        c0.load(a.Wqkv, 3 * w, 0, wave * w, 0, i, g4);
+        c1.load(a.Wqkv, 3 * w, 0, wave * w, 1, i, g4);
+    }
+    {
+        const int row = t >> 4, sub = t & 15, m = m0 + row, mc = min(m, M - 1);
+        const float lam = *a.lam;
+        float x[NB], sum = 0.f;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int64_t o = (int64_t)mc * w + sub + 16 * q;
+            x[q] = lam * a.U[o] + (1.f - lam) * (a.Aprev ? a.Aprev[o] : 0.f);
+            if (m < M) a.X[o] = x[q];
+            sum += x[q];
+        }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
+        const float mu = sum / (float)w;
+        float ss = 0.f;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) ss += (x[q] - mu) * (x[q] - mu);
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) ss += __shfl_xor(ss, o, 64);
+        const float rstd = 1.f / sqrtf(ss / (float)w + 1e-5f);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int c = sub + 16 * q;
+            const float y = (x[q] - mu) * rstd * a.g1[c] + a.h1[c];
+            bufA[row * PW + c] = y;
+            if (m < M) a.XN[(int64_t)m * w + c] = y;
+        }
+        if (sub == 0 && m < M) {
+            a.st1[2 * (int64_t)m] = mu;
+            a.st1[2 * (int64_t)m + 1] = rstd;
+        }
+    }
+    __syncthreads();
+    if (wave >= 3) return;
+    f32x4 acc[NB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    c0.mul(bufA, PW, 0, 0, acc, i, g4);
+    c0.load(a.Wqkv, 3 * w, 0, wave * w, 2, i, g4);
+    c1.mul(bufA, PW, 0, 1, acc, i, g4);
+    c1.load(a.Wqkv, 3 * w, 0, wave * w, 3, i, g4);
+    c0.mul(bufA, PW, 0, 2, acc, i, g4);
+    c1.mul(bufA, PW, 0, 3, acc, i, g4);
+#pragma unroll
+    for (int pq = 0; pq < WB; ++pq) {
+        const int col = wave * w + 32 * pq + 2 * i;
+        const f32x2 bb = *reinterpret_cast<const f32x2 *>(a.bqkv + col);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int m = m0 + 4 * g4 + v;
+            if (m < M) *reinterpret_cast<f32x2 *>(a.QKV + (int64_t)m * 3 * w + col) = f32x2{acc[2 * pq][v] + bb[0], acc[2 * pq + 1][v] + bb[1]};
+        }
+    }
+}
+
+// Its reverse: dxn = dqkv W_qkv^T (K = 3 w split over the four wavefronts, transposed copy of the weight), the reverse
+// of LayerNorm 1 with the residual path dt, and the reverse of the gate (its partial sum for this block, da_prev).
+struct QkvBwdArgs {
+    const float *DQKV, *WqkvT; // [M][3w], [3w][w]
+    const float *X, *st1, *g1, *DT, *U, *Aprev, *lam;
+    float *DX, *DAprev; // DAprev null in the first layer
+    float *ln1p, *dlamp; // this layer's [blocks][2][w] and [blocks]
+    int M;
+};
+template <int WB> constexpr int qkv_bwd_lds_bytes() { return (16 * (96 * WB + 4) + 80 * (32 * WB + 4) + 4) * 4; }
+template <int WB> __global__ __launch_bounds__(256) void k_lqkv_bwd(QkvBwdArgs a)
+{
+    constexpr int w = 32 * WB, NB = 2 * WB, PW = w + 4, P3 = 3 * w + 4, T = 16;
+    extern __shared__ __attribute__((aligned(16))) float msm[];
+    float *bufQ = msm, *bufA = bufQ + T * P3, *part = bufA + T * PW, *redl = part + 4 * T * PW; // part [4][T][PW], redl [4]
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, i = lane & 15, g4 = lane >> 4;
+    const int m0 = blockIdx.x * T, M = a.M;
+    const int kb = wave * (3 * w / 4); // this wavefront's share of K: three chunks
+    WChunk<WB> c0, c1;
+    c0.load(a.WqkvT, w, kb, 0, 0, i, g4);
+    c1.load(a.WqkvT, w, kb, 0, 1, i, g4);
+    for (int idx = t; idx < T * (3 * w / 4); idx += 256) {
+        const int row = idx / (3 * w / 4), c4 = idx % (3 * w / 4), m = min(m0 + row, M - 1);
+        *reinterpret_cast<f32x4 *>(bufQ + row * P3 + 4 * c4) = *reinterpret_cast<const f32x4 *>(a.DQKV + (int64_t)m * 3 * w + 4 * c4);
+    }
+    __syncthreads();
+    f32x4 acc[NB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    c0.mul(bufQ, P3, kb, 0, acc, i, g4);
+    c0.load(a.WqkvT, w, kb, 0, 2, i, g4);
+    c1.mul(bufQ, P3, kb, 1, acc, i, g4);
+    c0.mul(bufQ, P3, kb, 2, acc, i, g4);
+    {
+        float *pp = part + (size_t)wave * T * PW;
+#pragma unroll
+        for (int pq = 0; pq < WB; ++pq)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                *reinterpret_cast<f32x2 *>(pp + (4 * g4 + v) * PW + 32 * pq + 2 * i) = f32x2{acc[2 * pq][v], acc[2 * pq + 1][v]};
+    }
+    __syncthreads();
+    for (int idx = t; idx < T * w; idx += 256) {
+        const int row = idx / w, col = idx % w;
+        bufA[row * PW + col] = ((part[((size_t)0 * T + row) * PW + col] + part[((size_t)1 * T + row) * PW + col]) +
+                                part[((size_t)2 * T + row) * PW + col]) + part[((size_t)3 * T + row) * PW + col];
+    }
+    __syncthreads();
+    {
+        const int row = t >> 4, sub = t & 15, m = m0 + row, mc = min(m, M - 1);
+        const bool rowok = m < M;
+        const float lam = *a.lam;
+        const float mu = a.st1[2 * (int64_t)mc], rstd = a.st1[2 * (int64_t)mc + 1];
+        float xh[NB], dxh[NB], s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int c = sub + 16 * q;
+            const float dy = rowok ? bufA[row * PW + c] : 0.f;
+            xh[q] = rowok ? (a.X[(int64_t)mc * w + c] - mu) * rstd : 0.f;
+            dxh[q] = dy * a.g1[c];
+            part[(size_t)row * PW + c] = dy * xh[q];
+            part[((size_t)T + row) * PW + c] = dy;
+            s1 += dxh[q];
+            s2 += dxh[q] * xh[q];
+        }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+            s1 += __shfl_xor(s1, o, 64);
+            s2 += __shfl_xor(s2, o, 64);
+        }
+        const float m1 = s1 / (float)w, m2 = s2 / (float)w;
+        float dlam = 0.f;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int64_t o = (int64_t)mc * w + sub + 16 * q;
+            const float dx = a.DT[o] + rstd * (dxh[q] - m1 - xh[q] * m2);
+            if (rowok) {
+                a.DX[o] = dx;
+                dlam += dx * (a.U[o] - (a.Aprev ? a.Aprev[o] : 0.f));
+                if (a.DAprev) a.DAprev[o] = (1.f - lam) * dx;
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) dlam += __shfl_xor(dlam, o, 64);
+        if (lane == 0) redl[wave] = dlam;
+    }
+    __syncthreads();
+    for (int c = t; c < 2 * w; c += 256) {
+        const int which = c / w, col = c % w;
+        float sum = 0.f;
+#pragma unroll
+        for (int row = 0; row < T; ++row) sum += part[((size_t)which * T + row) * PW + col];
+        a.ln1p[(int64_t)blockIdx.x * 2 * w + c] = sum;
+    }
+    if (t == 0) a.dlamp[blockIdx.x] = ((redl[0] + redl[1]) + redl[2]) + redl[3];
 }
 
 // ---------------------------------------------------------------------------
@@ -1608,11 +1780,24 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
     while (tpr < 8 && 2 * tpr * rows_per_wg <= 256) tpr *= 2;
     for (int l = 0; l < L; ++l) {
         const float *pl = params + (int64_t)l * a.PLb;
+        if (w <= 128) { // gate, LayerNorm 1 and the q, k, v projection in one launch
+            QkvArgs qa{lay(a.U, l, w), l ? lay(a.A, l - 1, w) : nullptr, pl + a.fo[F_LAM], pl + a.fo[F_G1], pl + a.fo[F_H1],
+                       pl + a.fo[F_WQKV], pl + a.fo[F_BQKV], lay(a.X, l, w), lay(a.XN, l, w), lay(a.st1, l, 2),
+                       lay(a.QKV, l, 3 * w), M};
+            const dim3 grid(cdivi(M, 16));
+            switch (w / 32) {
+            case 1: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lqkv_fwd<1>), grid, dim3(256), 0, st, qa); break;
+            case 2: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lqkv_fwd<2>), grid, dim3(256), 0, st, qa); break;
+            case 3: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lqkv_fwd<3>), grid, dim3(256), 0, st, qa); break;
+            default: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lqkv_fwd<4>), grid, dim3(256), 0, st, qa); break;
+            }
+        } else {
         LnFwdArgs n1{lay(a.U, l, w), l ? lay(a.A, l - 1, w) : nullptr, pl + a.fo[F_LAM], pl + a.fo[F_G1], pl + a.fo[F_H1],
                      lay(a.X, l, w), lay(a.XN, l, w), lay(a.st1, l, 2), M, w};
         LAD_LAUNCH(prof, st, KC_L_ROW, (k_lln_fwd<true>), dim3(cdivi(M, 4)), dim3(256), 0, st, n1);
         lin<false, 0>(prof, st, KC_L_LIN, lay(a.XN, l, w), w, pl + a.fo[F_WQKV], 3 * w, M, 3 * w, w, pl + a.fo[F_BQKV],
                       nullptr, nullptr, lay(a.QKV, l, 3 * w), nullptr);
+        }
         AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), nullptr, nullptr, w,
                     a.nh, (int)(Mm / a.Bmax), scale, tpr, nchunk};
         LAD_TRY(attn(a.dh, false, at, B, st, prof));
@@ -1652,14 +1837,14 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
     LAD_LAUNCH(prof, st, KC_L_HEAD, k_lhead_c, dim3(B, cdivi(w, 16)), dim3(256), 0, st, h);
 
     if (w <= 128)
-        LAD_LAUNCH(prof, st, KC_SETUP, k_ltrans, dim3(cdivi(2 * w * f + w * w, 256), L), dim3(256), 0, st, params, a.PLb,
-                   a.fo[F_W2], a.fo[F_W1], a.fo[F_WO], w, F(a.WT));
+        LAD_LAUNCH(prof, st, KC_SETUP, k_ltrans, dim3(cdivi(2 * w * f + 4 * w * w, 256), L), dim3(256), 0, st, params, a.PLb,
+                   a.fo[F_W2], a.fo[F_W1], a.fo[F_WO], a.fo[F_WQKV], w, F(a.WT));
     for (int l = L - 1; l >= 0; --l) {
         const float *pl = params + (int64_t)l * a.PLb;
         float *DA = lay(a.DA, l, w), *DF1 = lay(a.DF1, l, f), *DT = lay(a.DT, l, w), *DQKV = lay(a.DQKV, l, 3 * w);
         float *DX = lay(a.DX, l, w);
         if (w <= 128) { // the reverse of the layer's tail in one launch
-            const float *wt = F(a.WT) + (int64_t)l * (2 * w * f + w * w);
+            const float *wt = F(a.WT) + (int64_t)l * (2 * w * f + 4 * w * w);
             MlpBwdArgs mb{DA, lay(a.F1, l, f), lay(a.T, l, w), lay(a.st2, l, 2), wt, wt + (int64_t)w * f, wt + (int64_t)2 * w * f,
                           pl + a.fo[F_G2], DF1, DT, F(a.DO_), F(a.ln2p) + (int64_t)l * nblk * 2 * w, M};
             const dim3 grid(cdivi(M, 16));
@@ -1685,6 +1870,21 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
         AttnArgs at{lay(a.QKV, l, 3 * w), samp_start, samp_len, lay(a.O, l, w), lay(a.LSE, l, a.nh), F(a.DO_), DQKV, w,
                     a.nh, (int)(Mm / a.Bmax), scale, tpr, nchunk};
         LAD_TRY(attn(a.dh, true, at, B, st, prof));
+        if (w <= 128) { // dxn, the reverse of LayerNorm 1 and of the gate in one launch
+            const float *wt = F(a.WT) + (int64_t)l * (2 * w * f + 4 * w * w) + (int64_t)2 * w * f + (int64_t)w * w;
+            QkvBwdArgs qb{DQKV, wt, lay(a.X, l, w), lay(a.st1, l, 2), pl + a.fo[F_G1], DT, lay(a.U, l, w),
+                          l ? lay(a.A, l - 1, w) : nullptr, pl + a.fo[F_LAM], DX, l ? lay(a.DA, l - 1, w) : nullptr,
+                          F(a.ln1p) + (int64_t)l * nblk * 2 * w, F(a.dlamp) + (int64_t)l * nblk, M};
+            const dim3 grid(cdivi(M, 16));
+            switch (w / 32) {
+            case 1: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lqkv_bwd<1>), grid, dim3(256), qkv_bwd_lds_bytes<1>(), st, qb); break;
+            case 2: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lqkv_bwd<2>), grid, dim3(256), qkv_bwd_lds_bytes<2>(), st, qb); break;
+            case 3: LAD_LAUNCH(prof, st, KC_L_LIN, (k_lqkv_bwd<3>), grid, dim3(256), qkv_bwd_lds_bytes<3>(), st, qb); break;
+            default: LAD_TRY((lds_once<&k_lqkv_bwd<4>>(qkv_bwd_lds_bytes<4>())));
+                    LAD_LAUNCH(prof, st, KC_L_LIN, (k_lqkv_bwd<4>), grid, dim3(256), qkv_bwd_lds_bytes<4>(), st, qb); break;
+            }
+            continue;
+        }
         // dxn = dqkv W_qkv^T
         lin<true, 4>(prof, st, KC_L_LIN, DQKV, 3 * w, pl + a.fo[F_WQKV], 3 * w, M, w, 3 * w, nullptr, nullptr, nullptr,
                      F(a.DXN), nullptr);
