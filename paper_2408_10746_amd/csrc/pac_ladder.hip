@@ -1772,8 +1772,9 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
     const float scale = 1.f / sqrtf((float)a.dh);
     int nlong = 1; // longest sample of the batch: lanes per attention row so that its rows fill a workgroup
     for (int i = 0; i < B; ++i) nlong = meta.len[i] > nlong ? meta.len[i] : nlong;
-    // several workgroups per sample and head (about 32 rows each), the rows of one shared by up to 8 lanes
-    int nchunk = nlong / 32;
+    // several workgroups per sample and head (about 64 rows each: measured against 32 and 128 at 128-token samples),
+    // the rows of one shared by up to 8 lanes
+    int nchunk = nlong / 64;
     nchunk = nchunk < 1 ? 1 : (nchunk > 8 ? 8 : nchunk);
     const int rows_per_wg = (nlong + nchunk - 1) / nchunk;
     int tpr = 1;
