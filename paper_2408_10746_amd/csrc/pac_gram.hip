@@ -444,6 +444,39 @@ struct EpiQ {
     }
 };
 
+// All products Q_{kl} of the single-launch chains from ONE contraction over the stacked projections: row (k, j) of the
+// stacked up-projections against column (l, n) of the stacked down-projections; only k < l is kept.
+struct EpiQStacked {
+    static constexpr bool kBatched = true;
+    static constexpr int kLayers = 6; // column layers one 128-column tile can touch (r >= 32)
+    bf16_t *qn, *qt; // [pair][r x r], fragment-major (frag_index)
+    int r, l0;       // first column layer of the tile
+    float one_minus_lam[kLayers]; // of layers l0 .., read before the first store (a load behind a store waits for it)
+    // r is a multiple of 32, so a 32 x 32 block of the stacked product lies inside one pair (k, l)
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
+    {
+        if (col >= ncols || row_base >= nrows) return;
+        const int k = row_base / r, l = col / r;
+        if (k >= l) return;
+        const int jb = row_base - k * r, n = col - l * r;
+        float oml = one_minus_lam[0];
+#pragma unroll
+        for (int i = 1; i < kLayers; ++i) oml = l - l0 == i ? one_minus_lam[i] : oml;
+        bf16_t *pn = qn + (int64_t)pair_index(k, l) * r * r, *pt = qt + (int64_t)pair_index(k, l) * r * r;
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+            const int j = jb + 8 * vg; // four consecutive rows j .. j+3, j a multiple of 4
+            bf16_t t4[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                pn[frag_index(j + w, n, r)] = static_cast<bf16_t>(oml * acc[4 * vg + w]); // backward: B[n=row][kk=col]
+                t4[w] = static_cast<bf16_t>(acc[4 * vg + w]);
+            }
+            __builtin_memcpy(pt + frag_index(n, j, r), t4, 8); // forward: B[n=col][kk=row], kk = j .. j+3 adjacent
+        }
+    }
+};
+
 // The layer-by-layer chains read Q from two [L*r][L*r] matrices whose row (layer, n) holds, K-contiguous
 // over (layer', j), the second operand of their contractions:
 //   qt[(l, col)][(k, row)] = Q_{kl}[row][col]  and  qn[(k, row)][(l, col)] = (1-lambda_l) Q_{kl}[row][col].
@@ -499,12 +532,13 @@ using T64K = Tile<2, 2, 1, 1, 4>; // 128-token K step for the token contractions
 
 // Stage counts are kept small on purpose: more workgroups per compute unit hide the memory latency
 // better than deeper rings in fewer workgroups (measured both ways).
-template <int NT, int BK> struct ProjShapes {
+template <int NT, int BK, bool QFULL = false> struct ProjShapes {
     static constexpr bool BIG = NT > 4;
+    static constexpr bool QSTACK = !BIG && !QFULL; // Q as one contraction over the stacked projections
     // r > 128: 128 x 256 tiles (all of r), eight wavefronts, three stages, interleaved sub-steps; one workgroup per CU
     using TBig = NtTile<2, 4, 2, 2, BK, 3>;
     using TU = typename std::conditional<BIG, TBig, NtTile<4, 1, 1, (BIG ? 1 : NT), BK, 2>>::type; // 128 token rows x r
-    using TQ = typename std::conditional<BIG, TBig, NtTile<2, 2, 1, 1, BK, 3>>::type;              // 64 x 64 (or 128 x 256)
+    using TQ = typename std::conditional<BIG, TBig, typename std::conditional<QSTACK, NtTile<2, 2, 2, 2, BK, 2>, NtTile<2, 2, 1, 1, BK, 3>>::type>::type; // 128 x 128 of the stacked product, 64 x 64 of a pair, or 128 x 256
     static constexpr int kThreadsPerBlock = BIG ? 512 : 256;
     using TC = Tile<2, 2, 1, 1, BK / 32>;   // the one-row chat contraction (staged through registers)
     static constexpr int kA = TU::LDS_BYTES > TQ::LDS_BYTES ? TU::LDS_BYTES : TQ::LDS_BYTES;
@@ -514,14 +548,17 @@ template <int NT, int BK> struct ProjShapes {
 
 template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(NT > 4 ? 512 : 256) void k_gproj(ProjArgs a)
 {
-    using SH = ProjShapes<NT, BK>;
+    using SH = ProjShapes<NT, BK, QFULL>;
     using TU = typename SH::TU;
     using TQ = typename SH::TQ;
     constexpr int KU = BK / 32;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    // workgroups are numbered with the big streaming part first but dispatched in reverse: the small
-    // latency-bound parts start at once and run alongside it
-    const int b = (int)(gridDim.x - 1 - blockIdx.x) + a.blk_off;
+    // Workgroups are numbered with the big streaming part first.  Where Q is one stacked contraction (few tiles) they
+    // are dispatched in that order: every U tile starts at once, the few Q tiles take the slots left over, and Q is
+    // the last thing written before the chain that reads it (time stamps: with Q as four 64 x 64 tiles per pair,
+    // dispatched first, the median U tile waited 7 us for a slot).  The wide shapes dispatch in reverse: their small
+    // latency-bound parts start at once and run alongside the stream.
+    const int b = (SH::QSTACK ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x)) + a.blk_off;
     if (b < a.nb_U) {
         // (layer, row tile, column tile), the column tiles of a row tile next to each other
         // Wide shapes: the tiles of a layer go to one die, which then fetches that layer's projection once (numbered
@@ -541,6 +578,23 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(NT > 4 ? 512 
     }
     const int tqm = (a.r + TQ::BM - 1) / TQ::BM, tqn = (a.r + TQ::BN - 1) / TQ::BN, tq2 = tqm * tqn, tc64 = (a.r + 63) / 64;
     if (b < a.nb_U + a.nb_Q) {
+        if constexpr (SH::QSTACK) {
+            // tile (ti, tj) of [L r] x [L r]; needed where some row layer is below some column layer
+            const int Lr = a.L * a.r, tq = (Lr + TQ::BN - 1) / TQ::BN;
+            const int idx = b - a.nb_U, ti = idx / tq, tj = idx % tq;
+            if ((ti * TQ::BM) / a.r >= min(Lr - 1, tj * TQ::BN + TQ::BN - 1) / a.r) return;
+            const bf16_t *Wu = a.Wu, *Wd = a.WdT;
+            const int d = a.d;
+            auto arow = [&](int row) { return Wu + (int64_t)row * d; };
+            auto brow = [&](int c) { return Wd + (int64_t)c * d; };
+            EpiQStacked epi;
+            epi.qn = a.QpN; epi.qt = a.QpT; epi.r = a.r; epi.l0 = (tj * TQ::BN) / a.r;
+#pragma unroll
+            for (int i = 0; i < EpiQStacked::kLayers; ++i)
+                epi.one_minus_lam[i] = 1.f - a.params[(int64_t)min(epi.l0 + i, a.L - 1) * a.PL + a.PL - 1];
+            gemm_nt<TQ>(smem, arow, brow, epi, 0, a.d, ti * TQ::BM, tj * TQ::BN, Lr, Lr);
+            return;
+        }
         int idx, k, l, p;
         if constexpr (SH::BIG) {
             // Blocks of 4 x 4 layer pairs (k in 4 kb.., l in 4 lb.., kb <= lb), one block per die at a time: its tiles
@@ -2160,6 +2214,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         constexpr int kProjThreads = NT > 4 ? 512 : 256;
         a.row_tiles = cdiv(M, 128); a.nb_U = a.row_tiles * L * (NT > 4 ? cdiv(r, 256) : 1);
         a.nb_Q = W.pairs * cdiv(r, kQRows) * cdiv(r, kQCols);
+        if (NT <= 4 && W.use_gram != 2) a.nb_Q = L > 1 ? cdiv(Lr, 128) * cdiv(Lr, 128) : 0; // ProjShapes::QSTACK
         if (NT > 4) { // blocks of 4 x 4 layer pairs, see k_gproj
             const int nlb = cdiv(L, 4);
             a.nb_Q = L > 1 ? nlb * (nlb + 1) / 2 * 16 * cdiv(r, kQRows) * cdiv(r, kQCols) : 0;
@@ -2176,11 +2231,11 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         };
         const bool q_full = W.use_gram == 2;
         if (d % 64 == 0) {
-            constexpr int lds = ProjShapes<NT, 64>::kLds;
+            constexpr int lds = ProjShapes<NT, 64, true>::kLds > ProjShapes<NT, 64, false>::kLds ? ProjShapes<NT, 64, true>::kLds : ProjShapes<NT, 64, false>::kLds;
             if (q_full) { PAC_HIP_TRY((allow_lds_once<&k_gproj<NT, 64, true>>(lds))); launch_proj(&k_gproj<NT, 64, true>, lds); }
             else { PAC_HIP_TRY((allow_lds_once<&k_gproj<NT, 64, false>>(lds))); launch_proj(&k_gproj<NT, 64, false>, lds); }
         } else {
-            constexpr int lds = ProjShapes<NT, 32>::kLds;
+            constexpr int lds = ProjShapes<NT, 32, true>::kLds > ProjShapes<NT, 32, false>::kLds ? ProjShapes<NT, 32, true>::kLds : ProjShapes<NT, 32, false>::kLds;
             if (q_full) { PAC_HIP_TRY((allow_lds_once<&k_gproj<NT, 32, true>>(lds))); launch_proj(&k_gproj<NT, 32, true>, lds); }
             else { PAC_HIP_TRY((allow_lds_once<&k_gproj<NT, 32, false>>(lds))); launch_proj(&k_gproj<NT, 32, false>, lds); }
         }
