@@ -541,7 +541,9 @@ template <int NT, int BK, bool QFULL = false> struct ProjShapes {
     using TQ = typename std::conditional<BIG, TBig, typename std::conditional<QSTACK, NtTile<2, 2, 2, 2, BK, 2>, NtTile<2, 2, 1, 1, BK, 3>>::type>::type; // 128 x 128 of the stacked product, 64 x 64 of a pair, or 128 x 256
     static constexpr int kThreadsPerBlock = BIG ? 512 : 256;
     using TC = Tile<2, 2, 1, 1, BK / 32>;   // the one-row chat contraction (staged through registers)
-    static constexpr int kA = TU::LDS_BYTES > TQ::LDS_BYTES ? TU::LDS_BYTES : TQ::LDS_BYTES;
+    static constexpr int kUStages = 3; // the small shapes' U tile: three stages of cache rows, two of the projection
+    static constexpr int kULds = BIG ? TU::LDS_BYTES : nt_deepA_lds<TU, kUStages>();
+    static constexpr int kA = kULds > TQ::LDS_BYTES ? kULds : TQ::LDS_BYTES;
     static constexpr int kB = tile_lds_bytes<bf16_t, TC>() > 8 * 256 * 4 ? tile_lds_bytes<bf16_t, TC>() : 8 * 256 * 4;
     static constexpr int kLds = kA > kB ? kA : kB;
 };
@@ -573,7 +575,8 @@ template <int NT, int BK, bool QFULL> __global__ __launch_bounds__(NT > 4 ? 512 
         auto arow = [&](int m) { return cache + map.rowoff[m] + (int64_t)l * map.rowstride[m]; };
         auto brow = [&](int c) { return W + (int64_t)c * d; };
         EpiStoreF32 epi{a.U + (int64_t)l * a.map.M * a.r, a.r};
-        gemm_nt<TU, SH::BIG>(smem, arow, brow, epi, 0, a.d, mt * TU::BM, ct * TU::BN, a.map.M, a.r);
+        if constexpr (SH::BIG) gemm_nt<TU, true>(smem, arow, brow, epi, 0, a.d, mt * TU::BM, ct * TU::BN, a.map.M, a.r);
+        else gemm_nt_deepA<TU, SH::kUStages>(smem, arow, brow, epi, 0, a.d, mt * TU::BM, ct * TU::BN, a.map.M, a.r);
         return;
     }
     const int tqm = (a.r + TQ::BM - 1) / TQ::BM, tqn = (a.r + TQ::BN - 1) / TQ::BN, tq2 = tqm * tqn, tc64 = (a.r + 63) / 64;

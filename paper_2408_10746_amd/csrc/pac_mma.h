@@ -189,6 +189,111 @@ __device__ __forceinline__ void gemm_nt(char *lds /* TL::LDS_BYTES, 1 KB aligned
     tile_epilogue<TL>(acc, epi, wm, wn, lane, row0, col0, nrows, ncols);
 }
 
+// gemm_nt with rings of different depth for the two operands: SA stages for A (rows streamed from HBM once: the
+// deeper ring keeps two stages of them in flight), SB = SA - 1 for B (rows shared by many tiles and found in L2).
+// Per step the transfers of B for step st + SB - 1 are issued before those of A for step st + SA - 1, so that at the
+// top of a step everything but the newest A stage has to have landed: one counted wait, as in gemm_nt.
+template <class TL, int SA, class ARow, class BRow, class Epi>
+__device__ __forceinline__ void gemm_nt_deepA(char *lds /* nt_deepA_lds<TL, SA>() bytes, 1 KB aligned */, const ARow &arow,
+                                              const BRow &brow, Epi &epi, int kbegin, int kend, int row0, int col0,
+                                              int nrows, int ncols)
+{
+    constexpr int SB = SA - 1;
+    constexpr int A_I = TL::BM / TL::RPI, B_I = TL::BN / TL::RPI; // transfer instructions per stage
+    static_assert(SB >= 2, "at least two stages of B");
+    constexpr int NA = (A_I + TL::NW - 1) / TL::NW, NB = (B_I + TL::NW - 1) / TL::NW; // (the last ones may repeat a row group)
+    constexpr int A_STAGE = TL::BM * TL::BK * 2, B_STAGE = TL::BN * TL::BK * 2;
+    static_assert((NA + NB) * SB + NA < 64, "transfers in flight must fit the counter");
+    char *ldsA = lds, *ldsB = lds + SA * A_STAGE;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / TL::WN, wn = wave % TL::WN;
+    f32x16 acc[TL::WTM][TL::WTN];
+#pragma unroll
+    for (int x = 0; x < TL::WTM; ++x)
+#pragma unroll
+        for (int y = 0; y < TL::WTN; ++y)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
+
+    const int nsteps = (kend - kbegin) / TL::BK;
+    if (nsteps > 0) {
+        const bf16_t *gpa[NA], *gpb[NB];
+        int offa[NA], offb[NB];
+#pragma unroll
+        for (int q = 0; q < NA; ++q) {
+            const int ii = min(wave + TL::NW * q, A_I - 1);
+            const int lr = ii * TL::RPI + lane / TL::CPR;
+            gpa[q] = arow(min(row0 + lr, nrows - 1)) + ((lane % TL::CPR) ^ nt_swz<TL::BK>(lr)) * 8;
+            offa[q] = ii * 1024;
+        }
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int ii = min(wave + TL::NW * q, B_I - 1);
+            const int lr = ii * TL::RPI + lane / TL::CPR;
+            gpb[q] = brow(min(col0 + lr, ncols - 1)) + ((lane % TL::CPR) ^ nt_swz<TL::BK>(lr)) * 8;
+            offb[q] = ii * 1024;
+        }
+        auto issueA = [&](int step) {
+            const int k0 = kbegin + min(step, nsteps - 1) * TL::BK; // past the end: repeat the last step, never used
+            char *dst = ldsA + (step % SA) * A_STAGE;
+#pragma unroll
+            for (int q = 0; q < NA; ++q) dma16(gpa[q] + k0, dst + offa[q]);
+        };
+        auto issueB = [&](int step) {
+            const int k0 = kbegin + min(step, nsteps - 1) * TL::BK;
+            char *dst = ldsB + (step % SB) * B_STAGE;
+#pragma unroll
+            for (int q = 0; q < NB; ++q) dma16(gpb[q] + k0, dst + offb[q]);
+        };
+#pragma unroll
+        for (int s = 0; s < SB - 1; ++s) { issueA(s); issueB(s); }
+        issueA(SB - 1);
+        const int i = lane & 31, g = lane >> 5;
+        int arow_b[TL::WTM], brow_b[TL::WTN], asw[TL::WTM], bsw[TL::WTN];
+#pragma unroll
+        for (int x = 0; x < TL::WTM; ++x) {
+            const int lr = (wm * TL::WTM + x) * 32 + i;
+            arow_b[x] = lr * TL::BK * 2;
+            asw[x] = nt_swz<TL::BK>(lr);
+        }
+#pragma unroll
+        for (int y = 0; y < TL::WTN; ++y) {
+            const int lr = (wn * TL::WTN + y) * 32 + i;
+            brow_b[y] = lr * TL::BK * 2;
+            bsw[y] = nt_swz<TL::BK>(lr);
+        }
+        for (int st = 0; st < nsteps; ++st) {
+            wait_vm<NA>();   // all but the newest A stage have landed (this wavefront's share)
+            __syncthreads(); // ... and everybody else's; the stages of step st - 1 are free
+            issueB(st + SB - 1);
+            issueA(st + SA - 1);
+            const char *sa = ldsA + (st % SA) * A_STAGE, *sb = ldsB + (st % SB) * B_STAGE;
+            bf16x8 a[TL::BK / 16][TL::WTM], b[TL::BK / 16][TL::WTN];
+#pragma unroll
+            for (int ks = 0; ks < TL::BK / 16; ++ks) {
+#pragma unroll
+                for (int x = 0; x < TL::WTM; ++x)
+                    a[ks][x] = *reinterpret_cast<const bf16x8 *>(sa + arow_b[x] + (((2 * ks + g) ^ asw[x]) << 4));
+#pragma unroll
+                for (int y = 0; y < TL::WTN; ++y)
+                    b[ks][y] = *reinterpret_cast<const bf16x8 *>(sb + brow_b[y] + (((2 * ks + g) ^ bsw[y]) << 4));
+            }
+            __builtin_amdgcn_sched_barrier(0); // keep the scheduler from sinking the reads to their uses
+#pragma unroll
+            for (int ks = 0; ks < TL::BK / 16; ++ks)
+#pragma unroll
+                for (int x = 0; x < TL::WTM; ++x)
+#pragma unroll
+                    for (int y = 0; y < TL::WTN; ++y)
+                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][x], b[ks][y], acc[x][y], 0, 0, 0);
+        }
+        wait_vm<0>(); // the repeated transfers of the last steps must not outlive this use of the LDS
+        __syncthreads();
+    }
+    tile_epilogue<TL>(acc, epi, wm, wn, lane, row0, col0, nrows, ncols);
+}
+template <class TL, int SA> constexpr int nt_deepA_lds() { return SA * TL::BM * TL::BK * 2 + (SA - 1) * TL::BN * TL::BK * 2; }
+
 // ---------------------------------------------------------------------------
 // Contractions over the token index: C[i][n] = sum_t A[t][i] * B[t][n], both operands row-major
 // over tokens.  A stage holds KT token rows of BM columns of A and BN columns of B as 64-column
