@@ -423,6 +423,37 @@ struct EpiStoreF32 {
     __device__ void operator()(int row, int col, float v) const { out[(int64_t)row * ld + col] = v; }
 };
 
+// The Gram matrix straight from the token contraction where the tokens are not split: the two bf16 copies the
+// gradient launch contracts (GG transposed; GG with column layer l scaled by 1 - lambda_l), for the 32 x 32 blocks
+// with a row layer below a column layer, exactly what the ordered sum of the partials writes otherwise.
+struct EpiGramDirect {
+    static constexpr bool kBatched = true;
+    bf16_t *ggt, *ggsc;
+    int64_t Lr;
+    int r;
+    const float *params;
+    int64_t PL;
+    __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
+    {
+        if (col >= ncols) return;
+        if ((row_base & ~31) / r >= ((col & ~31) + 31) / r) return;
+        const float oml = 1.f - params[(int64_t)(col / r) * PL + PL - 1]; // read before the first store
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+            const int row = row_base + 8 * vg; // four consecutive rows; nrows is a multiple of 4
+            if (row < nrows) {
+                bf16_t t4[4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    ggsc[(int64_t)(row + w) * Lr + col] = static_cast<bf16_t>(oml * acc[4 * vg + w]);
+                    t4[w] = static_cast<bf16_t>(acc[4 * vg + w]);
+                }
+                __builtin_memcpy(ggt + (int64_t)col * Lr + row, t4, 8);
+            }
+        }
+    }
+};
+
 // Q is stored twice, each time in the order the chain kernels' matrix instructions consume it
 // ("fragment-major"): for the contraction sum_kk A[.][kk] B[n][kk] in 16-column x 32-deep operand
 // fragments, element B[n][kk] sits at
@@ -1556,6 +1587,8 @@ struct TokRedArgs {
     const float *params;
     int64_t PL;
     float *GGpart;        // [sg][L*r][L*r]
+    bf16_t *GGT, *GGsc;   // written directly where sg == 1 (gg_direct)
+    int gg_direct;
     int ntiles, B, C;
     const float *cspart, *HSpart, *dz;
     const int32_t *tile_samp, *samp_len;
@@ -1650,8 +1683,13 @@ template <int NT> __global__ __launch_bounds__(TokRedShapes<NT>::kThreadsPerBloc
             const int k = kbegin + step * kTokKT + grp * 8 + r8;
             return k < kend ? DP + (int64_t)k * Lr : nullptr;
         };
-        EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
-        gemm_tn<TG, true>(smem, atok, btok, a.zeros, epi, (kend - kbegin + kTokKT - 1) / kTokKT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
+        if (a.gg_direct) {
+            EpiGramDirect epi{a.GGT, a.GGsc, Lr, a.r, a.params, a.PL};
+            gemm_tn<TG, true>(smem, atok, btok, a.zeros, epi, (kend - kbegin + kTokKT - 1) / kTokKT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
+        } else {
+            EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
+            gemm_tn<TG, true>(smem, atok, btok, a.zeros, epi, (kend - kbegin + kTokKT - 1) / kTokKT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
+        }
         return;
     }
     // cs[kk] = sum over the tiles of their column sums of dpre ;
@@ -2372,6 +2410,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.reverse = NT <= 4 && L * a.e_tiles >= 128;
         a.nb_G = L > 1 ? a.tg * a.tgn * a.sg : 0;
         a.H = H; a.DP = DP; a.Epart = Epart; a.GGpart = GGpart;
+        // tokens not split: the Gram tiles write the two bf16 copies themselves, and E needs no sum either
+        a.gg_direct = a.sg == 1; a.GGT = GGT; a.GGsc = GGsc; a.params = io.params; a.PL = D.PL;
         a.ntiles = ntiles; a.B = B; a.C = C; a.cspart = cspart; a.HSpart = HSpart; a.dz = dz;
         a.tile_samp = tile_samp; a.samp_len = samp_len; a.cs = cs; a.Z = Z; a.dzsum = dzsum;
         {
@@ -2380,12 +2420,14 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
             launch_parts(prof, st, split, k_gtokred<NT>, a, 3, counts, classes, KC_G_TOKRED, TokRedShapes<NT>::kThreadsPerBlock, TokRedShapes<NT>::kLds);
         }
         {
-            const int nb_GG = L > 1 ? (Lr / 32) * (Lr / 32) : 0;
-            const int64_t e_elems = (int64_t)L * d * r;
+            const int nb_GG = L > 1 && !a.gg_direct ? (Lr / 32) * (Lr / 32) : 0;
+            const int64_t e_elems = a.se > 1 ? (int64_t)L * d * r : 0;
             float *E = (float *)(ws + W.g_E);
-            PAC_LAUNCH(prof, st, KC_G_GGSUM, k_ggsum, dim3(nb_GG + cdiv(e_elems / 4, 256)), dim3(256), 0, st, L, r, a.sg,
-                       GGpart, io.params, D.PL, GGT, GGsc, nb_GG, a.se, e_elems, Epart, E);
+            if (nb_GG + e_elems > 0)
+                PAC_LAUNCH(prof, st, KC_G_GGSUM, k_ggsum, dim3(nb_GG + cdiv(e_elems / 4, 256)), dim3(256), 0, st, L, r, a.sg,
+                           GGpart, io.params, D.PL, GGT, GGsc, nb_GG, a.se, e_elems, Epart, E);
         }
+        const float *Esum = a.se > 1 ? (const float *)(ws + W.g_E) : Epart;
         PostArgs pa;
         pa.L = L; pa.d = d; pa.r = r; pa.C = C; pa.B = B; pa.se = 1;
         constexpr bool BIG = NT > 4, XW = NT > 8;
@@ -2395,7 +2437,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         pa.nb_F = L * cdiv(d, kFRows) * cdiv(r, kFCols); pa.nb_W = L * cdiv(r, kWRows) * cdiv(d, kWCols);
         pa.nb_vec = cdiv(d, (256 / NH) / L) + 1;
         pa.params = io.params; pa.PL = D.PL; pa.WuTs = WuTs; pa.Wds = Wds; pa.GGT = GGT; pa.GGsc = GGsc;
-        pa.Epart = (const float *)(ws + W.g_E); pa.cusum = cusum; pa.cs = cs; pa.Z = Z; pa.dzsum = dzsum; pa.dz = dz; pa.pb = pb;
+        pa.Epart = Esum; pa.cusum = cusum; pa.cs = cs; pa.Z = Z; pa.dzsum = dzsum; pa.dz = dz; pa.pb = pb;
         pa.grads = io.grads; pa.dlam_part = dlam_part;
         pa.slots = cdiv(d, kFRows) * cdiv(r, kFCols);
         {
