@@ -1600,12 +1600,15 @@ constexpr int kTokKT = 32;    // tokens per stage of the token contractions (a m
 template <int NT> struct TokRedShapes {
     static constexpr bool BIG = NT > 4;
     // r > 128: 128 x 256 tiles, eight wavefronts, three stages (E then covers all of r: the cache is read once)
+    // r = 96: 64 tokens per stage in a two-stage ring (same LDS; half the barriers: 37.5 -> 36.9 us on the T5-Base-shaped
+    // step; at r = 128, L = 24 the same measured 2 us slower and is not used)
+    static constexpr int KT = NT == 3 ? 64 : kTokKT, ST = NT == 3 ? 2 : kTokStages;
     using TBig = TnTile<2, 4, 2, 2, kTokKT, 3>;
     // r = 96, 128: the same 128 x 128 tile as 4 x 2 wavefronts of 32 x 64 (eight wavefronts issue the transfers of a
     // stage in half the time each; measured 42 -> 39 us on the T5-Base-shaped step)
     static constexpr bool W8 = NT == 3 || NT == 4;
-    using TE = typename std::conditional<BIG, TBig, typename std::conditional<W8, TnTile<4, 2, 1, 2, kTokKT, kTokStages>, TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), kTokKT, kTokStages>>::type>::type;
-    using TG = typename std::conditional<BIG, TBig, typename std::conditional<W8, TnTile<4, 2, 1, 2, kTokKT, kTokStages>, TnTile<2, 2, 2, 2, kTokKT, kTokStages>>::type>::type; // tile of the Gram matrix
+    using TE = typename std::conditional<BIG, TBig, typename std::conditional<W8, TnTile<4, 2, 1, 2, KT, ST>, TnTile<2, 2, kETileCols / 64, (NT > 2 ? 2 : 1), kTokKT, kTokStages>>::type>::type;
+    using TG = typename std::conditional<BIG, TBig, typename std::conditional<W8, TnTile<4, 2, 1, 2, KT, ST>, TnTile<2, 2, 2, 2, kTokKT, kTokStages>>::type>::type; // tile of the Gram matrix
     static constexpr int kThreadsPerBlock = (BIG || W8) ? 512 : 256;
     static constexpr int kVecLds = 256 * (1 + kMaxClasses) * 4 + kMaxTiles * 4 + kMaxBatch * kMaxClasses * 4; // + tile and sample tables
     static constexpr int kTileLds = TE::LDS_BYTES > TG::LDS_BYTES ? TE::LDS_BYTES : TG::LDS_BYTES;
@@ -1616,6 +1619,7 @@ template <int NT> __global__ __launch_bounds__(TokRedShapes<NT>::kThreadsPerBloc
 {
     using TE = typename TokRedShapes<NT>::TE;
     using TG = typename TokRedShapes<NT>::TG;
+    constexpr int KT = TokRedShapes<NT>::KT;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     __shared__ int64_t t_aoff[kMaxSplitTiles]; // cache offset of the tile's first row in this layer
     __shared__ int32_t t_m0[kMaxSplitTiles], t_rows[kMaxSplitTiles];
@@ -1649,17 +1653,17 @@ template <int NT> __global__ __launch_bounds__(TokRedShapes<NT>::kThreadsPerBloc
         const bf16_t *dp = a.DP + (int64_t)l * a.r;
         const int d = a.d;
         auto atok = [&](int step, int grp, int r8) -> const bf16_t * {
-            const int tl = step * (kTokKT / 16) + (grp >> 1), row = (grp & 1) * 8 + r8;
+            const int tl = step * (KT / 16) + (grp >> 1), row = (grp & 1) * 8 + r8;
             if (tl >= ntl || row >= t_rows[tl]) return nullptr;
             return cache + t_aoff[tl] + (int64_t)row * d;
         };
         auto btok = [&](int step, int grp, int r8) -> const bf16_t * {
-            const int tl = step * (kTokKT / 16) + (grp >> 1), row = (grp & 1) * 8 + r8;
+            const int tl = step * (KT / 16) + (grp >> 1), row = (grp & 1) * 8 + r8;
             if (tl >= ntl || row >= t_rows[tl]) return nullptr;
             return dp + (int64_t)(t_m0[tl] + row) * Lr;
         };
         EpiStoreF32 epi{a.Epart + ((int64_t)split * a.L + l) * a.d * a.r, a.r};
-        gemm_tn<TE, true>(smem, atok, btok, a.zeros, epi, (ntl * 16 + kTokKT - 1) / kTokKT, it * TE::BM, ct * TE::BN, a.d, a.r, a.d, a.r);
+        gemm_tn<TE, true>(smem, atok, btok, a.zeros, epi, (ntl * 16 + KT - 1) / KT, it * TE::BM, ct * TE::BN, a.d, a.r, a.d, a.r);
         return;
     }
     if (b < a.nb_E + a.nb_G) {
@@ -1676,19 +1680,19 @@ template <int NT> __global__ __launch_bounds__(TokRedShapes<NT>::kThreadsPerBloc
         const int kend = min(M, kbegin + a.rows_per_sg);
         const bf16_t *H = a.H, *DP = a.DP;
         auto atok = [&](int step, int grp, int r8) -> const bf16_t * {
-            const int k = kbegin + step * kTokKT + grp * 8 + r8;
+            const int k = kbegin + step * KT + grp * 8 + r8;
             return k < kend ? H + (int64_t)k * Lr : nullptr;
         };
         auto btok = [&](int step, int grp, int r8) -> const bf16_t * {
-            const int k = kbegin + step * kTokKT + grp * 8 + r8;
+            const int k = kbegin + step * KT + grp * 8 + r8;
             return k < kend ? DP + (int64_t)k * Lr : nullptr;
         };
         if (a.gg_direct) {
             EpiGramDirect epi{a.GGT, a.GGsc, Lr, a.r, a.params, a.PL};
-            gemm_tn<TG, true>(smem, atok, btok, a.zeros, epi, (kend - kbegin + kTokKT - 1) / kTokKT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
+            gemm_tn<TG, true>(smem, atok, btok, a.zeros, epi, (kend - kbegin + KT - 1) / KT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
         } else {
             EpiStoreF32 epi{a.GGpart + (int64_t)split * Lr * Lr, Lr};
-            gemm_tn<TG, true>(smem, atok, btok, a.zeros, epi, (kend - kbegin + kTokKT - 1) / kTokKT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
+            gemm_tn<TG, true>(smem, atok, btok, a.zeros, epi, (kend - kbegin + KT - 1) / KT, ti * TG::BM, tj * TG::BN, Lr, Lr, Lr, Lr);
         }
         return;
     }
@@ -2398,7 +2402,7 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         {
             // W.se is fixed by the configuration (the partial buffers are sized for it)
             if (cdiv(ntiles, W.se) > kMaxSplitTiles) return hipErrorInvalidValue;
-            a.tiles_per_se = cdiv(cdiv(ntiles, W.se), kTokKT / 16) * (kTokKT / 16);
+            a.tiles_per_se = cdiv(cdiv(ntiles, W.se), TokRedShapes<NT>::KT / 16) * (TokRedShapes<NT>::KT / 16);
             a.se = cdiv(ntiles, a.tiles_per_se);
         }
         a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.zeros = ws + W.g_zero;
