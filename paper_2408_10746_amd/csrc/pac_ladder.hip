@@ -18,7 +18,7 @@
 //   gradients are the column sums its right-hand loaders keep), then one ordered reduction into the gradient.
 // Every intermediate the reverse pass needs is kept in the workspace; every reduction runs in a fixed order.
 #include "../../include/pac_ladder.h"
-#include "pac_gemm.h"
+#include "pac_mma.h"
 #include "pac_internal.h"
 
 #include <cmath>
@@ -60,6 +60,7 @@ struct Lad {
     int64_t DA, DF1, DT, DQKV, DX;                             // [L][Mmax][...]
     int64_t DTN, DO_, DXN;                                     // [Mmax][w]
     int64_t WT;                                                // [L][2 w f + 4 w w]: W_2^T, W_1^T, W_o^T, W_qkv^T
+    int64_t Wsp;                                               // [L][3][w][d] bf16: W_down^T as three bf16 terms, or -1
     int64_t ln1p, ln2p, dlamp;                                 // [L][nblk][2][w] x2, [L][nblk]
     int64_t bmean, abar, pooled, logits, dz, dp, daL, lossp;
     int64_t part;                                              // [splits][L * PLb]
@@ -111,6 +112,7 @@ bool lad_plan(const Dims &D, int heads, Lad &a)
     a.DX = take(LM * w * 4);
     a.DTN = take(M * w * 4); a.DO_ = take(M * w * 4); a.DXN = take(M * w * 4);
     a.WT = take((int64_t)a.L * (2 * w * f + 4 * w * w) * 4); // transposed copies for the fused reverse kernels
+    a.Wsp = (!a.cache_f32 && w <= 128 && d % 32 == 0) ? take((int64_t)a.L * 3 * w * d * 2) : -1; // see k_ldown3
     a.nblk = cdivi(M, kLnRows);
     a.ln1p = take((int64_t)a.L * a.nblk * 2 * w * 4); a.ln2p = take((int64_t)a.L * a.nblk * 2 * w * 4);
     a.dlamp = take((int64_t)a.L * a.nblk * 4);
@@ -316,6 +318,61 @@ struct EpiBias {
         }
     }
 };
+// The same on the bf16 matrix units, for a bf16 cache: W_down^l as three bf16 terms, transposed ([3][w][d], k_lsplit,
+// once per step), one workgroup per 128 token rows and layer (gemm_nt_fold3).  The cache values are exactly bf16, so
+// every product is exact in fp32 and only the order of the additions differs from the fp32 contraction.
+__global__ __launch_bounds__(256) void k_lsplit(const float *params, int64_t PLb, int64_t oWd, int d, int w, bf16_t *Wsp)
+{
+    __shared__ float tile[64][33]; // 64 rows x 32 columns of W_down^l ([d][w])
+    const int l = blockIdx.y, c0 = blockIdx.x * 64, n0 = blockIdx.z * 32;
+    const float *W = params + (int64_t)l * PLb + oWd;
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int e = threadIdx.x + 256 * q, c = e >> 5, n = e & 31;
+        v[q] = c0 + c < d ? W[(int64_t)(c0 + c) * w + n0 + n] : 0.f;
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int e = threadIdx.x + 256 * q;
+        tile[e >> 5][e & 31] = v[q];
+    }
+    __syncthreads();
+    bf16_t *out = Wsp + (int64_t)l * 3 * w * d;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int e = threadIdx.x + 256 * q, n = e >> 6, c = e & 63;
+        if (c0 + c >= d) continue;
+        const float x = tile[c][n];
+        const bf16_t hi = static_cast<bf16_t>(x);
+        const float r1 = x - to_f32(hi);       // exact
+        const bf16_t mid = static_cast<bf16_t>(r1);
+        const float r2 = r1 - to_f32(mid);     // exact
+        const bf16_t lo = static_cast<bf16_t>(r2);
+        out[((int64_t)0 * w + n0 + n) * d + c0 + c] = hi;
+        out[((int64_t)1 * w + n0 + n) * d + c0 + c] = mid;
+        out[((int64_t)2 * w + n0 + n) * d + c0 + c] = lo;
+    }
+}
+// K steps of 32 in a two-stage ring: 53 KB of LDS at w = 96, every tile of the launch resident at once (measured:
+// K steps of 64, one workgroup per compute unit, 57 us; these 43 us; a third stage 45 us)
+template <int WB> struct Down3Shapes { using TL = NtTile<4, 1, 1, 3 * WB, 32, 2>; };
+template <int WB> __global__ __launch_bounds__(256) void k_ldown3(DownArgs a, const bf16_t *Wsp)
+{
+    using TL = typename Down3Shapes<WB>::TL;
+    extern __shared__ __attribute__((aligned(1024))) char dsm[];
+    const int l = blockIdx.y;
+    const float *pl = a.params + (int64_t)l * a.PLb;
+    const bf16_t *cache = static_cast<const bf16_t *>(a.cache);
+    const RowMap map = a.map;
+    const bf16_t *Wl = Wsp + (int64_t)l * 3 * a.w * a.d;
+    const int d = a.d;
+    auto arow = [&](int m) { return cache + map.rowoff[m] + (int64_t)l * map.rowstride[m]; };
+    auto brow = [&](int c) { return Wl + (int64_t)c * d; };
+    EpiBias epi{pl + a.ocd, a.U + (int64_t)l * a.Mmax * a.w, a.w};
+    gemm_nt_fold3<TL>(dsm, arow, brow, epi, 0, a.d, blockIdx.x * TL::BM, a.map.M, a.w);
+}
+
 template <typename SRC> __global__ __launch_bounds__(256) void k_ldown(DownArgs a)
 {
     __shared__ __attribute__((aligned(16))) char smem[kTileLds];
@@ -1767,7 +1824,19 @@ hipError_t run_ladder(const Lad &a, const BatchMeta &meta, const void *cache, co
                samp_start, samp_len);
     {
         DownArgs da{cache, map, params, a.PLb, a.fo[F_WD], a.fo[F_CD], d, w, F(a.U), Mm};
-        LAD_LAUNCH(prof, st, KC_L_DOWN, (k_ldown<SRC>), dim3(cdivi(M, 64), cdivi(w, 64), L), dim3(256), 0, st, da);
+        if (std::is_same<SRC, bf16_t>::value && a.Wsp >= 0) {
+            bf16_t *Wsp = reinterpret_cast<bf16_t *>(ws + a.Wsp);
+            LAD_LAUNCH(prof, st, KC_L_DOWN, k_lsplit, dim3(cdivi(d, 64), L, w / 32), dim3(256), 0, st, params, a.PLb, a.fo[F_WD], d, w, Wsp);
+            const dim3 grid(cdivi(M, 128), L);
+            switch (w / 32) {
+            case 1: LAD_TRY((lds_once<&k_ldown3<1>>(0))); LAD_LAUNCH(prof, st, KC_L_DOWN, (k_ldown3<1>), grid, dim3(256), Down3Shapes<1>::TL::LDS_BYTES, st, da, Wsp); break;
+            case 2: LAD_TRY((lds_once<&k_ldown3<2>>(0))); LAD_LAUNCH(prof, st, KC_L_DOWN, (k_ldown3<2>), grid, dim3(256), Down3Shapes<2>::TL::LDS_BYTES, st, da, Wsp); break;
+            case 3: LAD_TRY((lds_once<&k_ldown3<3>>(0))); LAD_LAUNCH(prof, st, KC_L_DOWN, (k_ldown3<3>), grid, dim3(256), Down3Shapes<3>::TL::LDS_BYTES, st, da, Wsp); break;
+            default: LAD_TRY((lds_once<&k_ldown3<4>>(0))); LAD_LAUNCH(prof, st, KC_L_DOWN, (k_ldown3<4>), grid, dim3(256), Down3Shapes<4>::TL::LDS_BYTES, st, da, Wsp); break;
+            }
+        } else {
+            LAD_LAUNCH(prof, st, KC_L_DOWN, (k_ldown<SRC>), dim3(cdivi(M, 64), cdivi(w, 64), L), dim3(256), 0, st, da);
+        }
     }
     const float scale = 1.f / sqrtf((float)a.dh);
     int nlong = 1; // longest sample of the batch: lanes per attention row so that its rows fill a workgroup

@@ -189,6 +189,93 @@ __device__ __forceinline__ void gemm_nt(char *lds /* TL::LDS_BYTES, 1 KB aligned
     tile_epilogue<TL>(acc, epi, wm, wn, lane, row0, col0, nrows, ncols);
 }
 
+// gemm_nt whose B operand holds THREE row groups that all contribute to the same output columns:
+//   C[row][col] = sum_k A[row][k] * (B[col][k] + B[ncols + col][k] + B[2 ncols + col][k]).
+// It serves a product with an fp32 matrix written as three bf16 terms (value = hi + mid + lo, exact to 2^-24 of the
+// value): with A exactly bf16 every product is exact in fp32 and the result differs from an fp32 contraction by the
+// order of the additions only, at the bf16 matrix rate.  TL::BN is the stage's B row count (3 x the output tile's
+// columns); brow(i) returns row i of the [3 ncols][K] operand; ncols = TL::BN / 3 must be the whole output width or the
+// caller passes col0 = 0 only (one column tile).
+template <class TL, class ARow, class BRow, class Epi>
+__device__ __forceinline__ void gemm_nt_fold3(char *lds /* TL::LDS_BYTES, 1 KB aligned */, const ARow &arow, const BRow &brow,
+                                              Epi &epi, int kbegin, int kend, int row0, int nrows, int ncols)
+{
+    static_assert(TL::WN == 1 && TL::WTN % 3 == 0, "three row groups of B per wavefront");
+    constexpr int WTO = TL::WTN / 3; // output blocks per wavefront
+    using TO = NtTile<TL::WM, 1, TL::WTM, WTO, TL::BK, TL::STAGES>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave;
+    f32x16 acc[TL::WTM][WTO];
+#pragma unroll
+    for (int x = 0; x < TL::WTM; ++x)
+#pragma unroll
+        for (int y = 0; y < WTO; ++y)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
+    const int nsteps = (kend - kbegin) / TL::BK;
+    if (nsteps > 0) {
+        const bf16_t *gp[TL::NI];
+        int ldso[TL::NI];
+#pragma unroll
+        for (int q = 0; q < TL::NI; ++q) {
+            const int ii = min(wave + TL::NW * q, TL::TOTAL_I - 1);
+            const int lr = ii * TL::RPI + lane / TL::CPR;
+            const int lc = (lane % TL::CPR) ^ nt_swz<TL::BK>(lr);
+            // B row of the stage: group t = (lr - BM) / (BN / 3), column n inside it; columns past ncols repeat the last one
+            const int br = lr - TL::BM, t = br / (TL::BN / 3), n = br - t * (TL::BN / 3);
+            gp[q] = (lr < TL::BM ? arow(min(row0 + lr, nrows - 1)) : brow(t * ncols + min(n, ncols - 1))) + lc * 8;
+            ldso[q] = ii * 1024;
+        }
+        auto issue = [&](int slot, int step) {
+            const int k0 = kbegin + min(step, nsteps - 1) * TL::BK; // past the end: repeat the last step, never used
+#pragma unroll
+            for (int q = 0; q < TL::NI; ++q) dma16(gp[q] + k0, lds + slot * TL::STAGE_BYTES + ldso[q]);
+        };
+#pragma unroll
+        for (int s = 0; s < TL::STAGES - 1; ++s) issue(s, s);
+        const int i = lane & 31, g = lane >> 5;
+        int arow_b[TL::WTM], brow_b[TL::WTN], asw[TL::WTM], bsw[TL::WTN];
+#pragma unroll
+        for (int x = 0; x < TL::WTM; ++x) {
+            const int lr = (wm * TL::WTM + x) * 32 + i;
+            arow_b[x] = lr * TL::BK * 2;
+            asw[x] = nt_swz<TL::BK>(lr);
+        }
+#pragma unroll
+        for (int y = 0; y < TL::WTN; ++y) {
+            const int lr = TL::BM + y * 32 + i;
+            brow_b[y] = lr * TL::BK * 2;
+            bsw[y] = nt_swz<TL::BK>(lr);
+        }
+        int slot = 0;
+        for (int st = 0; st < nsteps; ++st) {
+            wait_vm<TL::NI * (TL::STAGES - 2)>();
+            __syncthreads();
+            const char *sb = lds + slot * TL::STAGE_BYTES;
+            issue(slot == 0 ? TL::STAGES - 1 : slot - 1, st + TL::STAGES - 1);
+#pragma unroll
+            for (int ks = 0; ks < TL::BK / 16; ++ks) {
+                bf16x8 a[TL::WTM], b[TL::WTN];
+#pragma unroll
+                for (int x = 0; x < TL::WTM; ++x)
+                    a[x] = *reinterpret_cast<const bf16x8 *>(sb + arow_b[x] + (((2 * ks + g) ^ asw[x]) << 4));
+#pragma unroll
+                for (int y = 0; y < TL::WTN; ++y)
+                    b[y] = *reinterpret_cast<const bf16x8 *>(sb + brow_b[y] + (((2 * ks + g) ^ bsw[y]) << 4));
+#pragma unroll
+                for (int x = 0; x < TL::WTM; ++x)
+#pragma unroll
+                    for (int y = 0; y < TL::WTN; ++y)
+                        acc[x][y % WTO] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b[y], acc[x][y % WTO], 0, 0, 0);
+            }
+            slot = slot + 1 == TL::STAGES ? 0 : slot + 1;
+        }
+        wait_vm<0>();
+        __syncthreads();
+    }
+    tile_epilogue<TO>(acc, epi, wm, 0, lane, row0, 0, nrows, ncols);
+}
+
 // gemm_nt with rings of different depth for the two operands: SA stages for A (rows streamed from HBM once: the
 // deeper ring keeps two stages of them in flight), SB = SA - 1 for B (rows shared by many tiles and found in L2).
 // Per step the transfers of B for step st + SB - 1 are issued before those of A for step st + SA - 1, so that at the
