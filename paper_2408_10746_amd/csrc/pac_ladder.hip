@@ -1272,15 +1272,31 @@ template <int DH> __global__ __launch_bounds__(256) void k_lattn_fwd(AttnArgs a)
         float mx = -INFINITY, l = 0.f, acc[DH];
 #pragma unroll
         for (int c = 0; c < DH; ++c) acc[c] = 0.f;
-        for (int j = part; j < n; j += tpr) {
-            float sc = 0.f;
+        // four keys per round: one rescaling of the running sums per round instead of one per key
+        for (int j0 = part; j0 < n; j0 += 4 * tpr) {
+            float sc[4];
 #pragma unroll
-            for (int c = 0; c < DH; ++c) sc += q[c] * ks[j * DH + c];
-            const float mn = fmaxf(mx, sc);
-            const float corr = lexp2(mx - mn), p = lexp2(sc - mn);
-            l = l * corr + p;
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u * tpr;
+                const float *kr = ks + min(j, n - 1) * DH;
+                float t = 0.f;
 #pragma unroll
-            for (int c = 0; c < DH; ++c) acc[c] = acc[c] * corr + p * vs[j * DH + c];
+                for (int c = 0; c < DH; ++c) t += q[c] * kr[c];
+                sc[u] = j < n ? t : -INFINITY;
+            }
+            const float mn = fmaxf(fmaxf(mx, fmaxf(sc[0], sc[1])), fmaxf(sc[2], sc[3])); // sc[0] is always a key: finite
+            const float corr = lexp2(mx - mn);
+            l *= corr;
+#pragma unroll
+            for (int c = 0; c < DH; ++c) acc[c] *= corr;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float p = lexp2(sc[u] - mn); // 0 for the slots past the last key
+                const float *vr = vs + min(j0 + u * tpr, n - 1) * DH;
+                l += p;
+#pragma unroll
+                for (int c = 0; c < DH; ++c) acc[c] += p * vr[c];
+            }
             mx = mn;
         }
         const float mall = grp_max(mx, tpr);
