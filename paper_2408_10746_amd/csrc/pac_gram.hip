@@ -435,21 +435,40 @@ struct EpiGramDirect {
     int64_t PL;
     __device__ void batch(int row_base, int col, const f32x16 &acc, int nrows, int ncols) const
     {
-        if (col >= ncols) return;
+        // (every condition below is the same for the two lanes lane and lane ^ 32, which hold the same column and the
+        // two interleaved halves of the block's 32 rows: the exchange further down needs both)
+        if (col >= ncols || (row_base & ~31) >= nrows) return; // nrows is a multiple of 32
         if ((row_base & ~31) / r >= ((col & ~31) + 31) / r) return;
         const float oml = 1.f - params[(int64_t)(col / r) * PL + PL - 1]; // read before the first store
+        uint32_t t[4][2]; // this lane's rows 8 vg + 4 g .. + 3 of the block as bf16 pairs
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
-            const int row = row_base + 8 * vg; // four consecutive rows; nrows is a multiple of 4
-            if (row < nrows) {
-                bf16_t t4[4];
+            const int row = row_base + 8 * vg;
+            bf16_t t4[4];
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    ggsc[(int64_t)(row + w) * Lr + col] = static_cast<bf16_t>(oml * acc[4 * vg + w]);
-                    t4[w] = static_cast<bf16_t>(acc[4 * vg + w]);
-                }
-                __builtin_memcpy(ggt + (int64_t)col * Lr + row, t4, 8);
+            for (int w = 0; w < 4; ++w) {
+                ggsc[(int64_t)(row + w) * Lr + col] = static_cast<bf16_t>(oml * acc[4 * vg + w]);
+                t4[w] = static_cast<bf16_t>(acc[4 * vg + w]);
             }
+            __builtin_memcpy(t[vg], t4, 8);
+        }
+        // Transposed copy: a column's 32 rows are 64 contiguous bytes, of which this lane holds every other 8.  The
+        // lane pair swaps two of its four pieces so that each lane stores two 16-byte pieces instead of four of 8.
+        const int g = (threadIdx.x >> 5) & 1;
+        uint32_t recv[2][2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) recv[u][h] = __shfl_xor(g ? t[2 * u][h] : t[2 * u + 1][h], 32, 64);
+        bf16_t *dst = ggt + (int64_t)col * Lr + (row_base & ~31);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            // g = 0: rows 16 u .. 16 u + 7 = own piece 2 u, then the partner's; g = 1: rows 16 u + 8 .. + 15 = the
+            // partner's piece 2 u + 1, then own
+            u32x4 v;
+            if (g == 0) { v[0] = t[2 * u][0]; v[1] = t[2 * u][1]; v[2] = recv[u][0]; v[3] = recv[u][1]; }
+            else { v[0] = recv[u][0]; v[1] = recv[u][1]; v[2] = t[2 * u + 1][0]; v[3] = t[2 * u + 1][1]; }
+            *reinterpret_cast<u32x4 *>(dst + 16 * u + 8 * g) = v;
         }
     }
 };
