@@ -218,6 +218,7 @@ struct PrepArgs {
     int64_t PL;
     int L, d, r, C;
     int nb_setup, nb_shadow, nb_chat;
+    int tile64; // the copy part works on 64 x 64 tiles (d, r multiples of 64; TPB = 4): every store a full 128-byte line
     int64_t *rowoff;
     int32_t *rowstride, *rowsamp, *samp_start, *samp_len;
     int32_t *tile_row0, *tile_rows, *tile_samp, *samp_tile0;
@@ -266,6 +267,44 @@ template <int TPB, int RPW> __global__ __launch_bounds__(256) void k_gprep(PrepA
         a.rowoff[m] = meta.off[s] + (int64_t)(m - meta.tok_start[s]) * d;
         a.rowstride[m] = meta.len[s] * d;
         a.rowsamp[m] = s;
+        return;
+    }
+    if (TPB == 4 && a.tile64 && b < a.nb_setup + a.nb_shadow) {
+        // One 64 x 64 tile of W_down^k (which = 0, [d][r]) or W_up^k (which = 1, [r][d]).  A wavefront stores 64
+        // neighbouring bf16 values at a time, a whole 128-byte line, in the straight copy and in the transposed one:
+        // with 32 x 32 tiles every store was half a line whose other half came from another workgroup much later, and
+        // the launch fetched 1.75 x the parameter bytes.
+        const int per_mat = (d / 64) * (r / 64);
+        int idx = b - a.nb_setup;
+        const int which = idx / (per_mat * L);
+        idx -= which * per_mat * L;
+        const int kk = idx / per_mat;
+        idx -= kk * per_mat;
+        const int cols = which == 0 ? r : d, tiles_c = cols / 64;
+        const int r0 = (idx / tiles_c) * 64, c0 = (idx % tiles_c) * 64;
+        const int tx = t & 63, ty = t >> 6;
+        const float *src = a.params + (int64_t)kk * a.PL + (which == 0 ? 0 : (int64_t)d * r + r);
+        float v[16];
+#pragma unroll
+        for (int yi = 0; yi < 16; ++yi) v[yi] = src[(int64_t)(r0 + ty + 4 * yi) * cols + c0 + tx];
+        float(*tile)[65] = reinterpret_cast<float(*)[65]>(sh); // 64 x 65 floats = TPB * 32 * 33 * 4 bytes or less
+        static_assert(TPB != 4 || 64 * 65 <= TPB * 32 * 33, "LDS of the 64 x 64 tile");
+#pragma unroll
+        for (int yi = 0; yi < 16; ++yi) {
+            const int y = ty + 4 * yi, row = r0 + y, col = c0 + tx;
+            tile[y][tx] = v[yi];
+            if (which == 0) a.Wds[(int64_t)row * Lr + (int64_t)kk * r + col] = static_cast<bf16_t>(v[yi]);
+            else a.Wu[((int64_t)kk * r + row) * d + col] = static_cast<bf16_t>(v[yi]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int yi = 0; yi < 16; ++yi) {
+            // element (row = r0 + tx, col = c0 + y) written at the transposed position
+            const int y = ty + 4 * yi, row = r0 + tx, col = c0 + y;
+            const bf16_t w = static_cast<bf16_t>(tile[tx][y]);
+            if (which == 0) a.WdT[((int64_t)kk * r + col) * d + row] = w;
+            else a.WuTs[(int64_t)col * Lr + (int64_t)kk * r + row] = w;
+        }
         return;
     }
     if (b < a.nb_setup + a.nb_shadow) {
@@ -2259,6 +2298,8 @@ template <int NT> static hipError_t run_gram(const Dims &D, const WsLayout &W, c
         a.nb_setup = cdiv(M, 256); // several weight tiles per workgroup only where that still leaves thousands of workgroups
         const int tpb = (int64_t)(d / 32) * (r / 32) * L * 2 >= 8192 * kPrepTiles ? kPrepTiles : 1;
         a.nb_shadow = cdiv((int64_t)(d / 32) * (r / 32) * L * 2, tpb); a.nb_chat = cdiv(d, 256);
+        a.tile64 = tpb == kPrepTiles && d % 64 == 0 && r % 64 == 0;
+        if (a.tile64) a.nb_shadow = (d / 64) * (r / 64) * L * 2;
         a.rowoff = rowoff; a.rowstride = rowstride; a.rowsamp = rowsamp; a.samp_start = samp_start;
         a.samp_len = samp_len; a.tile_row0 = tile_row0; a.tile_rows = tile_rows; a.tile_samp = tile_samp; a.samp_tile0 = samp_tile0;
         a.WdT = WdT; a.Wu = Wu; a.WuTs = WuTs; a.Wds = Wds; a.cusum = cusum; a.V = V;
